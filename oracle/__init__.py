@@ -1,0 +1,188 @@
+"""ctypes front-end of the plain CPU oracle of Dictionary Annealing (``da_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: the product path never imports this package.  Callers are the
+tests, the smoke check and the benchmark's ``cpu_baseline`` leg.
+
+State is kept in float64 NumPy arrays (``C[M][K][D]``, ``r[N][D]``) and uint8 codes
+``[N][M]``; every function mutates its arrays in place like the C routines do.  See the
+header of ``da_oracle.c`` for the passages of the paper (arXiv 1509.05194, Sec. 3.1-3.3)
+each routine follows.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "da_oracle.c")
+_LIB = os.path.join(_HERE, "libda_oracle.so")
+_lib = None
+
+
+def build(force=True):
+    """Compile the oracle with gcc: -O2, OpenMP, no fast-math, no FP contraction."""
+    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+        return _LIB
+    cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+           "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_f64p = ctypes.POINTER(ctypes.c_double)
+_f32p = ctypes.POINTER(ctypes.c_float)
+_u8p = ctypes.POINTER(ctypes.c_uint8)
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_i64 = ctypes.c_int64
+_int = ctypes.c_int
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build(force=False)
+    lib = ctypes.CDLL(_LIB)
+    lib.da_oracle_threads.restype = _int
+    lib.da_oracle_set_threads.argtypes = [_int]
+    lib.da_heat.argtypes = [_f64p, _u8p, _f64p, _i64, _int, _int, _int, _int]
+    lib.da_cool.argtypes = [_f64p, _u8p, _f64p, _i64, _int, _int, _int, _int]
+    lib.da_assign.argtypes = [_f64p, _f64p, _i64, _int, _int, _int, _int, _u8p, _f64p, _f64p, _i32p]
+    lib.da_dist_to.argtypes = [_f64p, _f64p, _i64, _int, _int, _int, _int]
+    lib.da_dist_to.restype = ctypes.c_double
+    lib.da_update.argtypes = [_f64p, _u8p, _f64p, _i64, _int, _int, _int, _int, _i64p]
+    lib.da_update.restype = _int
+    lib.da_quant_error.argtypes = [_f64p, _i64, _int]
+    lib.da_quant_error.restype = ctypes.c_double
+    lib.da_encode.argtypes = [_f32p, _f64p, _i64, _int, _int, _int, _u8p, _f64p]
+    lib.da_anneal_stage.argtypes = [_int, _f64p, _u8p, _f64p, _i64, _int, _int, _int, _int, _i64p, _f64p]
+    lib.da_anneal_stage.restype = ctypes.c_double
+    lib.da_sweep.argtypes = [_f64p, _u8p, _f64p, _i64, _int, _int, _int, _int, _i64p, _f64p]
+    lib.da_reconstruct.argtypes = [_f64p, _u8p, _i64, _int, _int, _int, _f64p]
+    _lib = lib
+    return lib
+
+
+def _chk(a, dtype, shape=None):
+    assert isinstance(a, np.ndarray) and a.dtype == dtype and a.flags["C_CONTIGUOUS"], \
+        "expected a C-contiguous %s array" % np.dtype(dtype).name
+    if shape is not None:
+        assert tuple(a.shape) == tuple(shape), "shape %s, expected %s" % (a.shape, shape)
+    return a
+
+
+def _p(a, ptype):
+    return None if a is None else a.ctypes.data_as(ptype)
+
+
+def _dims(C, codes, r):
+    M, K, D = C.shape
+    N = r.shape[0]
+    _chk(C, np.float64)
+    _chk(codes, np.uint8, (N, M))
+    _chk(r, np.float64, (N, D))
+    return N, D, M, K
+
+
+def threads():
+    return _load().da_oracle_threads()
+
+
+def set_threads(t):
+    _load().da_oracle_set_threads(int(t))
+
+
+def heat(r, codes, C, m):
+    N, D, M, K = _dims(C, codes, r)
+    _load().da_heat(_p(r, _f64p), _p(codes, _u8p), _p(C, _f64p), N, D, M, K, m)
+
+
+def cool(xp, codes, C, m):
+    N, D, M, K = _dims(C, codes, xp)
+    _load().da_cool(_p(xp, _f64p), _p(codes, _u8p), _p(C, _f64p), N, D, M, K, m)
+
+
+def assign(xp, C, codes, m, top2=False):
+    """Nearest codeword of dictionary m; writes codes[:, m].
+    With top2=True also returns (d1, d2, i2): best / second-best squared distance and the
+    index of the second best."""
+    N, D, M, K = _dims(C, codes, xp)
+    if top2:
+        d1 = np.empty(N, np.float64)
+        d2 = np.empty(N, np.float64)
+        i2 = np.empty(N, np.int32)
+    else:
+        d1 = d2 = i2 = None
+    _load().da_assign(_p(xp, _f64p), _p(C, _f64p), N, D, M, K, m, _p(codes, _u8p),
+                      _p(d1, _f64p), _p(d2, _f64p), _p(i2, _i32p))
+    return (d1, d2, i2) if top2 else None
+
+
+def dist_to(xp, C, n, m, k):
+    M, K, D = C.shape
+    return _load().da_dist_to(_p(xp, _f64p), _p(C, _f64p), int(n), D, K, m, int(k))
+
+
+def update(xp, codes, C, m):
+    """Centroid update of dictionary m in place; returns (counts[K] int64, n_empty)."""
+    N, D, M, K = _dims(C, codes, xp)
+    counts = np.zeros(K, np.int64)
+    empty = _load().da_update(_p(xp, _f64p), _p(codes, _u8p), _p(C, _f64p), N, D, M, K, m,
+                              _p(counts, _i64p))
+    return counts, empty
+
+
+def quant_error(r):
+    _chk(r, np.float64)
+    N, D = r.shape
+    return _load().da_quant_error(_p(r, _f64p), N, D)
+
+
+def encode(X, C):
+    """Greedy (single-path) residual encoding.  Returns (codes uint8 [N][M], r float64 [N][D])."""
+    _chk(X, np.float32)
+    _chk(C, np.float64)
+    N, D = X.shape
+    M, K, D2 = C.shape
+    assert D == D2
+    codes = np.zeros((N, M), np.uint8)
+    r = np.empty((N, D), np.float64)
+    _load().da_encode(_p(X, _f32p), _p(C, _f64p), N, D, M, K, _p(codes, _u8p), _p(r, _f64p))
+    return codes, r
+
+
+def anneal_stage(m, C, codes, r, T, init_idx=None, trace=False):
+    """One DA iteration on dictionary m, in place.  Returns E after the stage, or (E, J)
+    with the 2T+2 objective values when trace=True."""
+    N, D, M, K = _dims(C, codes, r)
+    if init_idx is not None:
+        init_idx = np.ascontiguousarray(init_idx, np.int64)
+        assert init_idx.shape == (K,) and init_idx.min() >= 0 and init_idx.max() < N
+    J = np.zeros(2 * T + 2, np.float64) if trace else None
+    E = _load().da_anneal_stage(m, _p(C, _f64p), _p(codes, _u8p), _p(r, _f64p), N, D, M, K, T,
+                                _p(init_idx, _i64p), _p(J, _f64p))
+    return (E, J) if trace else E
+
+
+def sweep(C, codes, r, T, init_idx=None):
+    """Stages m = 0..M-1 in order, in place.  Returns E after each stage (float64[M])."""
+    N, D, M, K = _dims(C, codes, r)
+    if init_idx is not None:
+        init_idx = np.ascontiguousarray(init_idx, np.int64)
+        assert init_idx.shape == (M, K) and init_idx.min() >= 0 and init_idx.max() < N
+    err = np.zeros(M, np.float64)
+    _load().da_sweep(_p(C, _f64p), _p(codes, _u8p), _p(r, _f64p), N, D, M, K, T,
+                     _p(init_idx, _i64p), _p(err, _f64p))
+    return err
+
+
+def reconstruct(C, codes):
+    _chk(C, np.float64)
+    M, K, D = C.shape
+    N = codes.shape[0]
+    _chk(codes, np.uint8, (N, M))
+    xhat = np.empty((N, D), np.float64)
+    _load().da_reconstruct(_p(C, _f64p), _p(codes, _u8p), N, D, M, K, _p(xhat, _f64p))
+    return xhat

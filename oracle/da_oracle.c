@@ -1,0 +1,267 @@
+/*
+ * Dictionary Annealing (DA) -- plain CPU oracle.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement of what
+ * the GPU library computes.  It shares no code, header, table or helper with the HIP
+ * path; only tests, the smoke check and the benchmark's cpu_baseline leg may call it.
+ *
+ * Paper: "HCLAE: High Capacity Locally Aggregating Encodings for Approximate Nearest
+ * Neighbor Search" (arXiv 1509.05194).  Passages followed:
+ *   - Sec. 3.1 (Dictionary Annealing): heat  x' = e_x + c_m(i_m(x));  cool = refit C_m to
+ *     {x'}; one dictionary per iteration, then re-encode to get the next residue; learning
+ *     from scratch = DA on all-zero dictionaries (footnote: then x' equals the residue).
+ *   - Sec. 3.2: the previously learned dictionary is the initial point of the k-means
+ *     that cools (plain full-dimension Lloyd here; the PCA / dimension-adding variant is
+ *     not part of this oracle).
+ *   - Sec. 3.3, Eq. 1 first line: E = || x - sum_m c_m(i_m(x)) ||^2 ; Eq. 3 with L = 1 is
+ *     greedy residual encoding.
+ *   - Table 1 magnitudes fix E as the mean over vectors of the squared residual norm.
+ *
+ * Readings where the paper is silent: fixed number T of Lloyd iterations per cool-down;
+ * argmin ties go to the lowest index (ascending k, strict <); an empty cluster keeps its
+ * previous codeword; a stage re-encodes only its own code column; an all-zero dictionary
+ * is seeded with K rows of x' picked by caller-supplied indices.
+ *
+ * Arithmetic: IEEE double everywhere, every sum in ascending index order, distances in
+ * the direct form sum_d (x_d - c_d)^2.  Build WITHOUT fast-math and without FP contraction.
+ * OpenMP is used only across vectors, where results do not depend on the thread count;
+ * the centroid sums are accumulated serially in vector order.
+ *
+ * Layouts (row-major): r, xp: double[N][D]; C: double[M][K][D]; codes: uint8[N][M].
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#include <math.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int da_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void da_oracle_set_threads(int t)
+{
+#ifdef _OPENMP
+    if (t > 0) omp_set_num_threads(t);
+#else
+    (void)t;
+#endif
+}
+
+/* Sec. 3.1, heat-up: x'_n = e_n + c_m(i_m(n)), in place over r. */
+void da_heat(double *r, const uint8_t *codes, const double *C,
+             int64_t N, int D, int M, int K, int m)
+{
+    const double *Cm = C + (size_t)m * K * D;
+    #pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        const double *c = Cm + (size_t)codes[n * M + m] * D;
+        double *rn = r + (size_t)n * D;
+        for (int d = 0; d < D; ++d) rn[d] = rn[d] + c[d];
+    }
+}
+
+/* Sec. 3.1, "obtain the new residue": e_n = x'_n - c_m(i_m(n)), in place over xp. */
+void da_cool(double *xp, const uint8_t *codes, const double *C,
+             int64_t N, int D, int M, int K, int m)
+{
+    const double *Cm = C + (size_t)m * K * D;
+    #pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        const double *c = Cm + (size_t)codes[n * M + m] * D;
+        double *xn = xp + (size_t)n * D;
+        for (int d = 0; d < D; ++d) xn[d] = xn[d] - c[d];
+    }
+}
+
+/*
+ * Nearest codeword of dictionary m for every x'_n (the assignment half of the k-means
+ * that cools, Sec. 3.1/3.2; also the L = 1 case of Eq. 3).
+ * Writes codes[n][m].  Optional outputs (may be NULL):
+ *   d1[n]  smallest squared distance, d2[n] second smallest (+inf when K == 1),
+ *   i2[n]  index attaining d2 (-1 when K == 1).
+ */
+void da_assign(const double *xp, const double *C, int64_t N, int D, int M, int K, int m,
+               uint8_t *codes, double *d1, double *d2, int32_t *i2)
+{
+    const double *Cm = C + (size_t)m * K * D;
+    #pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        const double *x = xp + (size_t)n * D;
+        double best = INFINITY, second = INFINITY;
+        int ibest = 0, isecond = -1;
+        for (int k = 0; k < K; ++k) {
+            const double *c = Cm + (size_t)k * D;
+            double s = 0.0;
+            for (int d = 0; d < D; ++d) {
+                double t = x[d] - c[d];
+                s = s + t * t;
+            }
+            if (k == 0 || s < best) {
+                if (k != 0) { second = best; isecond = ibest; }
+                best = s; ibest = k;
+            } else if (s < second) {
+                second = s; isecond = k;
+            }
+        }
+        codes[n * M + m] = (uint8_t)ibest;
+        if (d1) d1[n] = best;
+        if (d2) d2[n] = second;
+        if (i2) i2[n] = isecond;
+    }
+}
+
+/* Squared distance from x'_n to one given codeword k of dictionary m (test helper for
+ * judging a code that differs from the oracle's own choice). */
+double da_dist_to(const double *xp, const double *C, int64_t n, int D, int K, int m, int k)
+{
+    const double *x = xp + (size_t)n * D;
+    const double *c = C + ((size_t)m * K + k) * D;
+    double s = 0.0;
+    for (int d = 0; d < D; ++d) {
+        double t = x[d] - c[d];
+        s = s + t * t;
+    }
+    return s;
+}
+
+/*
+ * Centroid half of the k-means that cools: c_m(k) <- mean of the x'_n assigned to k;
+ * a codeword with no member is left as it was.  counts[K] (may be NULL) receives n_k.
+ * Returns the number of empty clusters.
+ */
+int da_update(const double *xp, const uint8_t *codes, double *C,
+              int64_t N, int D, int M, int K, int m, int64_t *counts)
+{
+    double *Cm = C + (size_t)m * K * D;
+    double *S = (double *)calloc((size_t)K * D, sizeof(double));
+    int64_t *cnt = (int64_t *)calloc((size_t)K, sizeof(int64_t));
+    for (int64_t n = 0; n < N; ++n) {
+        int k = codes[n * M + m];
+        const double *x = xp + (size_t)n * D;
+        double *s = S + (size_t)k * D;
+        for (int d = 0; d < D; ++d) s[d] = s[d] + x[d];
+        cnt[k] += 1;
+    }
+    int empty = 0;
+    for (int k = 0; k < K; ++k) {
+        if (cnt[k] > 0) {
+            for (int d = 0; d < D; ++d)
+                Cm[(size_t)k * D + d] = S[(size_t)k * D + d] / (double)cnt[k];
+        } else {
+            ++empty;
+        }
+        if (counts) counts[k] = cnt[k];
+    }
+    free(S);
+    free(cnt);
+    return empty;
+}
+
+/* Eq. 1, first line, averaged over the vectors: E = (1/N) sum_n ||e_n||^2. */
+double da_quant_error(const double *r, int64_t N, int D)
+{
+    double total = 0.0;
+    for (int64_t n = 0; n < N; ++n) {
+        const double *rn = r + (size_t)n * D;
+        double s = 0.0;
+        for (int d = 0; d < D; ++d) s = s + rn[d] * rn[d];
+        total = total + s;
+    }
+    return N > 0 ? total / (double)N : 0.0;
+}
+
+/*
+ * Greedy residual encoding = multi-path encoding with a single path (Eq. 3, L = 1):
+ * r <- x; for m = 1..M: i_m = argmin_k ||r - c_m(k)||^2, r <- r - c_m(i_m).
+ * X is the fp32 input, widened exactly.
+ */
+void da_encode(const float *X, const double *C, int64_t N, int D, int M, int K,
+               uint8_t *codes, double *r)
+{
+    for (size_t i = 0; i < (size_t)N * D; ++i) r[i] = (double)X[i];
+    for (int m = 0; m < M; ++m) {
+        da_assign(r, C, N, D, M, K, m, codes, NULL, NULL, NULL);
+        da_cool(r, codes, C, N, D, M, K, m);
+    }
+}
+
+/*
+ * One DA iteration on dictionary m (Sec. 3.1): heat, optional seeding of an all-zero
+ * dictionary from rows of x' (init_idx[K], may be NULL), T x (assign, update), a final
+ * assign against the final C_m (the stage-local re-encode), cool.
+ * Precondition: r == x - sum_j C_j[codes[:,j]].
+ * J (may be NULL) receives 2T+2 values of (1/N) sum ||x' - C_m[i]||^2: at stage entry,
+ * after every assign and every update, and after the final assign.
+ * Returns E after the stage.
+ */
+double da_anneal_stage(int m, double *C, uint8_t *codes, double *r,
+                       int64_t N, int D, int M, int K, int T,
+                       const int64_t *init_idx, double *J)
+{
+    double *Cm = C + (size_t)m * K * D;
+    int j = 0;
+    if (J) J[j++] = da_quant_error(r, N, D);
+    da_heat(r, codes, C, N, D, M, K, m);               /* r now holds x' */
+    if (init_idx) {
+        for (int k = 0; k < K; ++k)
+            memcpy(Cm + (size_t)k * D, r + (size_t)init_idx[k] * D, sizeof(double) * D);
+    }
+    for (int t = 0; t < T; ++t) {
+        da_assign(r, C, N, D, M, K, m, codes, NULL, NULL, NULL);
+        if (J) {
+            da_cool(r, codes, C, N, D, M, K, m);
+            J[j++] = da_quant_error(r, N, D);
+            da_heat(r, codes, C, N, D, M, K, m);
+        }
+        da_update(r, codes, C, N, D, M, K, m, NULL);
+        if (J) {
+            da_cool(r, codes, C, N, D, M, K, m);
+            J[j++] = da_quant_error(r, N, D);
+            da_heat(r, codes, C, N, D, M, K, m);
+        }
+    }
+    da_assign(r, C, N, D, M, K, m, codes, NULL, NULL, NULL);
+    da_cool(r, codes, C, N, D, M, K, m);               /* r holds the residue again */
+    double E = da_quant_error(r, N, D);
+    if (J) J[j++] = E;
+    return E;
+}
+
+/*
+ * One sweep: DA iteration on m = 0..M-1 in order (Sec. 3.1, "multiple iterations").
+ * init_idx: NULL or int64[M][K].  err_per_stage: NULL or double[M].
+ */
+void da_sweep(double *C, uint8_t *codes, double *r,
+              int64_t N, int D, int M, int K, int T,
+              const int64_t *init_idx, double *err_per_stage)
+{
+    for (int m = 0; m < M; ++m) {
+        double E = da_anneal_stage(m, C, codes, r, N, D, M, K, T,
+                                   init_idx ? init_idx + (size_t)m * K : NULL, NULL);
+        if (err_per_stage) err_per_stage[m] = E;
+    }
+}
+
+/* x_hat_n = sum_m c_m(i_m(n)) (used to check x = x_hat + r). */
+void da_reconstruct(const double *C, const uint8_t *codes, int64_t N, int D, int M, int K,
+                    double *xhat)
+{
+    #pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        double *o = xhat + (size_t)n * D;
+        for (int d = 0; d < D; ++d) o[d] = 0.0;
+        for (int m = 0; m < M; ++m) {
+            const double *c = C + ((size_t)m * K + codes[n * M + m]) * D;
+            for (int d = 0; d < D; ++d) o[d] = o[d] + c[d];
+        }
+    }
+}
