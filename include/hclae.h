@@ -1,0 +1,139 @@
+/*
+ * libhclae -- Dictionary Annealing (DA) sweep on one AMD MI355X (gfx950).
+ *
+ * Method: "HCLAE: High Capacity Locally Aggregating Encodings for Approximate Nearest
+ * Neighbor Search", arXiv 1509.05194.  The library implements the data-parallel part of
+ * Sec. 3.1 (Dictionary Annealing) with the single-path case of Sec. 3.3 (Eq. 3, L = 1)
+ * as its encoder and Eq. 1 (first line) as its error measure.
+ *
+ * Notation (the paper's, with 0-based indices):
+ *   N vectors x in R^D;  M dictionaries C_m of K codewords c_m(k);  code i_m(x) in [0,K);
+ *   residue e_x = x - sum_m c_m(i_m(x));  intermediate vector x' = e_x + c_m(i_m(x)).
+ *
+ * Layouts (all row-major, all DEVICE memory unless marked HOST):
+ *   X, residue : float   [N][D]      (D % 4 == 0, base 16-byte aligned)
+ *   C          : float   [M][K][D]
+ *   codes      : uint8_t [N][M]      (the paper's M-byte code; K <= 256)
+ *
+ * Ownership: every data pointer is caller-owned; the library neither allocates nor frees
+ * them and keeps no pointer after a call returns.  An hclae_ctx owns scratch memory only.
+ *
+ * Ordering: all work is enqueued on the HIP stream given to hclae_create.  Calls return
+ * after enqueueing, except where a HOST output is requested (stats, err_per_stage, out):
+ * those synchronise that stream before returning.  One ctx must not be used from two
+ * threads at once.
+ *
+ * Errors: every entry point returns HCLAE_OK or a negative code.  Arguments are checked
+ * before any HIP call; on HCLAE_EINVAL nothing was enqueued and no state changed.
+ * A failing HIP call gives HCLAE_EHIP; hclae_last_error(ctx) then holds its text.
+ * Argmin ties go to the lowest index.  A codeword whose cluster is empty keeps its value.
+ */
+#ifndef HCLAE_H
+#define HCLAE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hclae_ctx hclae_ctx;
+
+enum {
+    HCLAE_OK     = 0,
+    HCLAE_EINVAL = -1,   /* bad argument (null pointer, size out of range, shape mismatch) */
+    HCLAE_ENOMEM = -2,   /* scratch allocation failed                                       */
+    HCLAE_EHIP   = -3,   /* a HIP runtime call failed                                       */
+    HCLAE_ESTATE = -4    /* call exceeds what the ctx was created for                       */
+};
+
+/* Limits checked by every entry point. */
+#define HCLAE_MAX_K 256
+#define HCLAE_MAX_D 4096
+#define HCLAE_MAX_M 256
+
+typedef struct {
+    double  err_before;      /* (1/N) sum ||e_x||^2 at stage entry                          */
+    double  err_after;       /* same at stage exit                                          */
+    int64_t codes_changed;   /* vectors whose i_m differs from its value at stage entry     */
+    int64_t refined;         /* vectors of the final assign decided by the fp64 re-check    */
+    int32_t empty_clusters;  /* codewords with no member at the last centroid update        */
+    int32_t iters_run;       /* Lloyd iterations executed                                   */
+} hclae_stage_stats;
+
+/* Shape check shared by all entry points: HCLAE_OK iff 0 <= N < 2^31, 4 <= D <= HCLAE_MAX_D
+ * with D % 4 == 0, 1 <= M <= HCLAE_MAX_M, 1 <= K <= HCLAE_MAX_K.  Needs no device. */
+int hclae_check_shape(int64_t N, int D, int M, int K);
+
+/* Create a context whose scratch fits calls with N <= N_max and exactly this D, M, K.
+ * hip_stream: a hipStream_t (NULL = the default stream).  The current device is used. */
+int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_stream);
+int hclae_destroy(hclae_ctx *ctx);
+/* Text of the last error of this ctx (never NULL; valid until the next call on it).
+ * With ctx == NULL: text of the last error of a failed hclae_create on this thread. */
+const char *hclae_last_error(const hclae_ctx *ctx);
+
+/*
+ * Sec. 3.3, Eq. 3 with one path (greedy residual encoding) under the objective of Eq. 1:
+ *   r <- x;  for m = 0..M-1:  i_m = argmin_k ||r - c_m(k)||^2,  r <- r - c_m(i_m).
+ * Reads X and C; writes codes[N][M] and residue[N][D] (residue may not alias X).
+ */
+int hclae_encode(hclae_ctx *ctx, const float *X, int64_t N, int D,
+                 const float *C, int M, int K, uint8_t *codes, float *residue);
+
+/*
+ * Sec. 3.1, one DA iteration on dictionary m:
+ *   heat   x' = e_x + c_m(i_m(x))                              (in place over residue)
+ *   [seed  c_m(k) <- x'[init_idx[k]] : the "all-zeros dictionary" start, where x' = e_x]
+ *   cool   iters x ( i_m = argmin_k ||x' - c_m(k)||^2 ;  c_m(k) <- mean of its members )
+ *   re-encode  i_m = argmin_k ||x' - c_m(k)||^2 ;  e_x = x' - c_m(i_m)
+ * Updates C[m], column m of codes and residue in place.
+ * Precondition: residue == X - sum_j C[j][codes[:,j]].
+ * init_idx: HOST int64[K] of row indices in [0,N), or NULL.  stats: HOST, or NULL.
+ */
+int hclae_anneal_stage(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M, int K,
+                       uint8_t *codes, float *residue, int iters,
+                       const int64_t *init_idx, hclae_stage_stats *stats);
+
+/*
+ * Sec. 3.1, "multiple iterations": hclae_anneal_stage for m = 0..M-1 in order.
+ * reencode_mode 0: each stage re-encodes only its own column (keeps E non-increasing).
+ * reencode_mode 1: after each stage all M parts are re-encoded greedily from X
+ *                  (hclae_encode); X must then be non-NULL.
+ * init_idx: HOST int64[M][K] or NULL.  err_per_stage: HOST double[M] or NULL
+ * (mean ||e_x||^2 after each stage).
+ */
+int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int M, int K,
+                uint8_t *codes, float *residue, int iters, int reencode_mode,
+                const int64_t *init_idx, double *err_per_stage);
+
+/* Eq. 1, first line, averaged over the vectors (Table 1 reports such means):
+ *   *out = (1/N) sum_n ||residue_n||^2, accumulated in fp64.  out: HOST.  N == 0 gives 0. */
+int hclae_quant_error(hclae_ctx *ctx, const float *residue, int64_t N, int D, double *out);
+
+/* ---- single steps of a stage (Sec. 3.1), exported so each can be checked on its own ---- */
+
+/* heat: residue_n += C[m][codes[n][m]] */
+int hclae_heat(hclae_ctx *ctx, int m, int64_t N, int D, const float *C, int M, int K,
+               const uint8_t *codes, float *residue);
+/* new residue: xp_n -= C[m][codes[n][m]] */
+int hclae_cool(hclae_ctx *ctx, int m, int64_t N, int D, const float *C, int M, int K,
+               const uint8_t *codes, float *xp);
+/* assignment half of the cooling k-means: codes[n][m] = argmin_k ||xp_n - C[m][k]||^2.
+ * dmin: DEVICE float[N] or NULL; receives ||xp_n - C[m][codes[n][m]]||^2 (direct form). */
+int hclae_assign(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, const float *C,
+                 int M, int K, uint8_t *codes, float *dmin);
+/* centroid half: C[m][k] = mean of xp_n with codes[n][m] == k (unchanged when empty).
+ * counts: DEVICE int32[K] or NULL; receives the cluster sizes. */
+int hclae_update(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, float *C,
+                 int M, int K, const uint8_t *codes, int32_t *counts);
+
+/* Number of vectors the last hclae_assign (or the last assign inside a stage / encode) sent
+ * to the fp64 re-check because their two best fp32 scores were closer than the rounding
+ * bound of the fp32 contraction.  Synchronises the stream.  out: HOST. */
+int hclae_last_refined(hclae_ctx *ctx, int64_t *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HCLAE_H */

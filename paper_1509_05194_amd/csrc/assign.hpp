@@ -1,0 +1,351 @@
+// Nearest-codeword assignment (the assignment half of the k-means that cools a dictionary,
+// Sec. 3.1/3.2; equally the per-dictionary step of Eq. 3 with one path).
+//
+// argmin_k ||x' - c_k||^2 = argmax_k ( x'.c_k - ||c_k||^2/2 ).  The right-hand score is a dense
+// K x D by D x N contraction and runs on the fp32 matrix cores (v_mfma_f32_32x32x2_f32), with
+// the accumulators started at -||c_k||^2/2.  The product is oriented codewords x vectors, so a
+// lane ends up holding scores of many codewords for ONE vector and the argmax never leaves
+// the wave (one exchange between lane l and lane l+32 at the end).
+//
+// fp32 rounding of the expanded form can reorder two codewords whose distances differ by less
+// than the rounding error, which is far larger than the error of the direct form.  Each wave
+// therefore bounds that error rigorously, collects every codeword whose score is within the
+// bound of the best, and when more than one remains hands the vector to k_refine, which decides
+// among the candidates with direct-form distances in fp64 (lowest index on exact ties).
+#pragma once
+#include "common.hpp"
+
+namespace hclae {
+
+constexpr int kAssignThreads = 512;                 // 8 waves: 2 per SIMD
+constexpr int kAssignWaves = kAssignThreads / kWave;
+constexpr int kTileVec = 32;                        // vectors per wave tile (N side of the MFMA)
+constexpr int kChunkD = 64;                         // dims per register-resident chunk of x'
+
+// One entry of the re-check list.
+struct RefineItem {
+    uint32_t n;       // vector index
+    uint32_t span;    // lo | hi << 8 | (exactly two candidates) << 16
+};
+
+// -||c_k||^2 / 2 in fp32 (computed in fp64) for k < K, -inf for the padding rows up to kpad.
+// One wave per codeword.  Also resets the re-check counter for the assign that follows.
+__global__ __launch_bounds__(256) void k_codeword_norms(
+    const float *__restrict__ Cm, int K, int D, int kpad, float *__restrict__ hneg,
+    unsigned *__restrict__ refine_count)
+{
+    const int lane = lane_id();
+    const int k = blockIdx.x * (256 / kWave) + (threadIdx.x >> 6);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *refine_count = 0u;
+    if (k >= kpad) return;
+    if (k >= K) {
+        if (lane == 0) hneg[k] = -__builtin_inff();
+        return;
+    }
+    const float *c = Cm + (size_t)k * D;
+    double s = 0.0;
+    for (int d = lane; d < D; d += kWave) s += (double)c[d] * (double)c[d];
+    s = wave_sum(s);
+    if (lane == 0) hneg[k] = -(float)(0.5 * s);
+}
+
+// LDS image of the codebook in MFMA operand order.  For row block b (32 codewords), k-step s
+// (8 dims) and lane l = 32*h + r, the float4 at index (b*S + s)*64 + l holds
+// C[32b + r][8s + 4h .. 8s + 4h + 3]; a wave's ds_read_b128 of one (b, s) is one contiguous
+// kilobyte (no bank conflicts), and component j of it is the A operand of the MFMA that
+// contracts dims {8s + j, 8s + 4 + j}.
+__device__ __forceinline__ void stage_codebook(
+    float4 *lds, const float *__restrict__ Cm, int K, int D, int kb, int S)
+{
+    const int total = kb * S * kWave;
+    for (int e = threadIdx.x; e < total; e += blockDim.x) {
+        const int l = e & 63;
+        const int bs = e >> 6;
+        const int s = bs % S;
+        const int b = bs / S;
+        const int row = 32 * b + (l & 31);
+        const int col = 8 * s + 4 * (l >> 5);
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row < K && col < D) v = *reinterpret_cast<const float4 *>(Cm + (size_t)row * D + col);
+        lds[e] = v;
+    }
+}
+
+// Loads the 64-dim chunk q of the wave's 32-vector tile into B-operand order:
+// lane (h, r) gets x'[row r][64q + 8s + 4h .. +3] for s = 0..7.
+__device__ __forceinline__ void load_x_chunk(
+    float4 (&x)[8], const float *__restrict__ xrow, int q, int h, int D)
+{
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        const int col = kChunkD * q + 8 * s + 4 * h;
+        x[s] = (col < D) ? *reinterpret_cast<const float4 *>(xrow + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
+template <int KB>
+__device__ __forceinline__ void mfma_chunk(
+    floatx16 (&acc)[KB], const float4 (&x)[8], const float4 *__restrict__ lds, int q, int S, int lane,
+    float &xsq)
+{
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        float4 a[KB];
+#pragma unroll
+        for (int b = 0; b < KB; ++b) a[b] = lds[(b * S + 8 * q + s) * kWave + lane];
+        const float4 xv = x[s];
+        xsq = fmaf(xv.x, xv.x, xsq);
+        xsq = fmaf(xv.y, xv.y, xsq);
+        xsq = fmaf(xv.z, xv.z, xsq);
+        xsq = fmaf(xv.w, xv.w, xsq);
+#pragma unroll
+        for (int b = 0; b < KB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[b].x, xv.x, acc[b], 0, 0, 0);
+#pragma unroll
+        for (int b = 0; b < KB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[b].y, xv.y, acc[b], 0, 0, 0);
+#pragma unroll
+        for (int b = 0; b < KB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[b].z, xv.z, acc[b], 0, 0, 0);
+#pragma unroll
+        for (int b = 0; b < KB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[b].w, xv.w, acc[b], 0, 0, 0);
+    }
+}
+
+// Accumulator start: element v of block b in lane (h, r) belongs to codeword
+// 32b + 8(v/4) + 4h + v%4 (the 32x32 fp32 MFMA result layout).
+template <int KB>
+__device__ __forceinline__ void init_acc(floatx16 (&acc)[KB], const float *hneg_lds, int h)
+{
+#pragma unroll
+    for (int b = 0; b < KB; ++b) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float4 t = *reinterpret_cast<const float4 *>(hneg_lds + 32 * b + 8 * g + 4 * h);
+            acc[b][4 * g + 0] = t.x;
+            acc[b][4 * g + 1] = t.y;
+            acc[b][4 * g + 2] = t.z;
+            acc[b][4 * g + 3] = t.w;
+        }
+    }
+}
+
+// Per-vector decision from the wave's scores.  `eps` * (hmax + ||x'|| * cmax) bounds twice the
+// rounding error of any score, so the true nearest codeword is among those within that
+// margin of the best score.
+template <int KB>
+__device__ __forceinline__ void decide(
+    const floatx16 (&acc)[KB], float xsq, float eps, float hmax, float cmax, int lane,
+    int64_t n, int64_t N, int M, int m, uint8_t *__restrict__ codes,
+    RefineItem *__restrict__ list, unsigned *__restrict__ refine_count)
+{
+    const int h = lane >> 5;
+    float mx = -__builtin_inff();
+#pragma unroll
+    for (int b = 0; b < KB; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[b][v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    const float x2 = xsq + __shfl_xor(xsq, 32, kWave);
+    const float thr = mx - eps * (hmax + sqrtf(x2) * cmax);
+
+    constexpr int NW = (KB + 1) / 2;
+    uint32_t mk[NW];
+#pragma unroll
+    for (int i = 0; i < NW; ++i) mk[i] = 0u;
+#pragma unroll
+    for (int b = 0; b < KB; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            if (acc[b][v] >= thr) mk[b >> 1] |= 1u << ((b & 1) * 16 + v);
+
+    // bit p of word i is codeword 64 i + 8 (p >> 2) + 4 h + (p & 3): ascending in (i, p)
+    int cnt = 0, lo = 0x7fffffff, hi = -1;
+#pragma unroll
+    for (int i = NW - 1; i >= 0; --i)
+        if (mk[i]) {
+            const int p = __ffs(mk[i]) - 1;
+            lo = 64 * i + 8 * (p >> 2) + 4 * h + (p & 3);
+        }
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        cnt += __popc(mk[i]);
+        if (mk[i]) {
+            const int p = 31 - __clz(mk[i]);
+            hi = 64 * i + 8 * (p >> 2) + 4 * h + (p & 3);
+        }
+    }
+    cnt += __shfl_xor(cnt, 32, kWave);
+    lo = min(lo, __shfl_xor(lo, 32, kWave));
+    hi = max(hi, __shfl_xor(hi, 32, kWave));
+
+    if (h == 0 && n < N) {
+        if (cnt == 0) { lo = 0; }                 // only with non-finite input
+        codes[n * M + m] = (uint8_t)lo;
+        if (cnt >= 2) {
+            const unsigned slot = atomicAdd(refine_count, 1u);
+            RefineItem it;
+            it.n = (uint32_t)n;
+            it.span = (uint32_t)lo | ((uint32_t)hi << 8) | ((cnt == 2) ? (1u << 16) : 0u);
+            list[slot] = it;
+        }
+    }
+}
+
+// Assignment with the whole (padded) codebook resident in LDS: D <= 64 * NC_max dims such that
+// 32*KB * 64*NC floats fit.  Each wave owns tiles of 32 vectors, streams them from HBM straight
+// into B-operand registers in 64-dim chunks (two register sets, the next chunk in flight while
+// the current one is contracted) and keeps all 32*KB scores of a vector in accumulators.
+template <int KB>
+__global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
+    const float *__restrict__ xp, const float *__restrict__ Cm, const float *__restrict__ hneg,
+    int64_t N, int D, int K, int M, int m, int NC, float eps,
+    uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count)
+{
+    extern __shared__ float4 smem4[];
+    const int S = 8 * NC;
+    float4 *lds_c = smem4;                                          // KB * S * 64 float4
+    float *lds_h = reinterpret_cast<float *>(smem4 + KB * S * kWave);   // 32*KB floats + 2
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int h = lane >> 5;
+    const int r = lane & 31;
+
+    stage_codebook(lds_c, Cm, K, D, KB, S);
+    for (int k = threadIdx.x; k < 32 * KB; k += blockDim.x) lds_h[k] = hneg[k];
+    __syncthreads();
+    // largest ||c||^2/2 over the real codewords (every thread computes the same value)
+    float hmax = 0.f;
+    for (int k = 0; k < K; ++k) hmax = fmaxf(hmax, -lds_h[k]);
+    const float cmax = sqrtf(2.f * hmax) * 1.000001f;
+
+    const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
+    const int64_t tstride = (int64_t)gridDim.x * kAssignWaves;
+    const int64_t t0 = (int64_t)blockIdx.x * kAssignWaves + wave;
+    if (t0 >= ntiles) return;
+    const int64_t my_tiles = (ntiles - t0 + tstride - 1) / tstride;
+    const int64_t G = my_tiles * NC;                                // (tile, chunk) steps of this wave
+
+    auto row_ptr = [&](int64_t tile) {
+        int64_t n = tile * kTileVec + r;
+        if (n >= N) n = N - 1;                                      // tail rows re-read the last vector
+        return xp + n * D;
+    };
+
+    floatx16 acc[KB];
+    float4 xa[8], xb[8];
+    float xsq = 0.f;
+    int64_t tile = t0;
+    int q = 0;
+    load_x_chunk(xa, row_ptr(tile), 0, h, D);
+    // Steps come in pairs so that the two register sets alternate with static names.
+    for (int64_t g = 0; g < G; g += 2) {
+        // ---- step g on xa; prefetch step g+1 into xb
+        int64_t tile1 = tile;
+        int q1 = q + 1;
+        if (q1 == NC) { q1 = 0; tile1 = tile + tstride; }
+        if (g + 1 < G) load_x_chunk(xb, row_ptr(tile1), q1, h, D);
+        if (q == 0) { init_acc<KB>(acc, lds_h, h); xsq = 0.f; }
+        mfma_chunk<KB>(acc, xa, lds_c, q, S, lane, xsq);
+        if (q == NC - 1)
+            decide<KB>(acc, xsq, eps, hmax, cmax, lane, tile * kTileVec + r, N, M, m, codes, list, refine_count);
+        if (g + 1 >= G) break;
+        // ---- step g+1 on xb; prefetch step g+2 into xa
+        int64_t tile2 = tile1;
+        int q2 = q1 + 1;
+        if (q2 == NC) { q2 = 0; tile2 = tile1 + tstride; }
+        if (g + 2 < G) load_x_chunk(xa, row_ptr(tile2), q2, h, D);
+        if (q1 == 0) { init_acc<KB>(acc, lds_h, h); xsq = 0.f; }
+        mfma_chunk<KB>(acc, xb, lds_c, q1, S, lane, xsq);
+        if (q1 == NC - 1)
+            decide<KB>(acc, xsq, eps, hmax, cmax, lane, tile1 * kTileVec + r, N, M, m, codes, list, refine_count);
+        tile = tile2;
+        q = q2;
+    }
+}
+
+// Assignment for dimensions whose codebook does not fit LDS: the block walks the D axis in
+// 64-dim chunks, restaging that slice of the codebook for every tile of 8 x 32 vectors; the
+// accumulators persist across chunks.
+template <int KB>
+__global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
+    const float *__restrict__ xp, const float *__restrict__ Cm, const float *__restrict__ hneg,
+    int64_t N, int D, int K, int M, int m, int NC, float eps,
+    uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count)
+{
+    extern __shared__ float4 smem4[];
+    constexpr int S = 8;                                            // one chunk resident
+    float4 *lds_c = smem4;                                          // KB * 8 * 64 float4
+    float *lds_h = reinterpret_cast<float *>(smem4 + KB * S * kWave);
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int h = lane >> 5;
+    const int r = lane & 31;
+
+    for (int k = threadIdx.x; k < 32 * KB; k += blockDim.x) lds_h[k] = hneg[k];
+    __syncthreads();
+    float hmax = 0.f;
+    for (int k = 0; k < K; ++k) hmax = fmaxf(hmax, -lds_h[k]);
+    const float cmax = sqrtf(2.f * hmax) * 1.000001f;
+
+    const int64_t nbt = (N + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);   // block tiles
+    for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
+        const int64_t n_raw = (bt * kAssignWaves + wave) * kTileVec + r;
+        const int64_t n = n_raw < N ? n_raw : N - 1;
+        const float *xrow = xp + n * D;
+        floatx16 acc[KB];
+        float4 x[8];
+        float xsq = 0.f;
+        init_acc<KB>(acc, lds_h, h);
+        for (int q = 0; q < NC; ++q) {
+            load_x_chunk(x, xrow, q, h, D);
+            __syncthreads();                                        // previous chunk fully consumed
+            // slice [64q, 64q+64) of the codebook, as chunk 0 of an S = 8 image
+            for (int e = threadIdx.x; e < KB * S * kWave; e += blockDim.x) {
+                const int l = e & 63;
+                const int bs = e >> 6;
+                const int s = bs & 7;
+                const int b = bs >> 3;
+                const int row = 32 * b + (l & 31);
+                const int col = kChunkD * q + 8 * s + 4 * (l >> 5);
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (row < K && col < D) v = *reinterpret_cast<const float4 *>(Cm + (size_t)row * D + col);
+                lds_c[e] = v;
+            }
+            __syncthreads();
+            mfma_chunk<KB>(acc, x, lds_c, 0, S, lane, xsq);
+        }
+        decide<KB>(acc, xsq, eps, hmax, cmax, lane, n_raw, N, M, m, codes, list, refine_count);
+    }
+}
+
+// fp64 re-check of the vectors whose fp32 scores were too close to call: direct-form squared
+// distances, candidates in ascending index order, strict '<' (ties keep the lowest index).
+// One wave per list entry; lanes split the D axis.
+__global__ __launch_bounds__(256) void k_refine(
+    const float *__restrict__ xp, const float *__restrict__ Cm, int D, int M, int m,
+    uint8_t *__restrict__ codes, const RefineItem *__restrict__ list,
+    const unsigned *__restrict__ refine_count)
+{
+    const int lane = lane_id();
+    const unsigned count = *refine_count;
+    const unsigned wpg = gridDim.x * (256 / kWave);
+    for (unsigned i = blockIdx.x * (256 / kWave) + (threadIdx.x >> 6); i < count; i += wpg) {
+        const RefineItem it = list[i];
+        const int lo = it.span & 255, hi = (it.span >> 8) & 255;
+        const int step = (it.span >> 16) & 1 ? (hi - lo) : 1;       // pair: visit lo and hi only
+        const float *x = xp + (size_t)it.n * D;
+        double best = 0.0;
+        int ibest = lo;
+        for (int k = lo; k <= hi; k += step) {
+            const float *c = Cm + (size_t)k * D;
+            double s = 0.0;
+            for (int d = lane; d < D; d += kWave) {
+                const double t = (double)x[d] - (double)c[d];
+                s += t * t;
+            }
+            s = wave_sum(s);
+            if (k == lo || s < best) { best = s; ibest = k; }
+        }
+        if (lane == 0) codes[(size_t)it.n * M + m] = (uint8_t)ibest;
+    }
+}
+
+}  // namespace hclae

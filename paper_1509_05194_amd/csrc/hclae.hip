@@ -1,0 +1,537 @@
+// C ABI of libhclae: argument checks, scratch ownership and kernel sequencing for the
+// Dictionary Annealing sweep (arXiv 1509.05194, Sec. 3.1; encoder: Eq. 3 with one path;
+// error: Eq. 1 first line).  All arithmetic of the method happens in the kernels included
+// below; this file only validates, sizes launches and orders them on one stream.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+#include <new>
+
+#include "../../include/hclae.h"
+#include "assign.hpp"
+#include "stream.hpp"
+#include "update.hpp"
+
+using namespace hclae;
+
+namespace {
+
+constexpr int kMaxParts = 4096;          // upper bound on blocks of a streaming pass
+constexpr int kLdsBudget = 160 * 1024;   // LDS per workgroup on gfx950
+
+thread_local char g_create_error[256] = "";
+
+}  // namespace
+
+struct hclae_ctx {
+    int64_t N_max;
+    int D, M, K;
+    int kb;                  // 32-codeword blocks of the padded codebook: 1, 2, 4 or 8
+    int NC;                  // 64-dim chunks of the padded D
+    bool resident;           // whole padded codebook fits LDS
+    int cus;
+    hipStream_t stream;
+    int device;
+    // scratch (device)
+    float *hneg;             // [32*kb]
+    unsigned *refine_count;
+    RefineItem *refine_list; // [N_max]
+    uint8_t *old_codes;      // [N_max]
+    float *partial;          // [upd_blocks][K][D]
+    int *pcount;             // [upd_blocks][K]
+    int *nk;                 // [K]
+    int64_t *seed_idx;       // [K]
+    double *part_a, *part_b; // [kMaxParts]
+    long long *part_chg;     // [kMaxParts]
+    StageRecord *rec;        // [M]
+    // host
+    StageRecord *rec_host;   // pinned [M]
+    int upd_blocks;
+    char err[256];
+};
+
+namespace {
+
+int fail(hclae_ctx *ctx, int code, const char *what, hipError_t e = hipSuccess)
+{
+    char *dst = ctx ? ctx->err : g_create_error;
+    if (e != hipSuccess) snprintf(dst, 256, "%s: %s", what, hipGetErrorString(e));
+    else snprintf(dst, 256, "%s", what);
+    return code;
+}
+
+#define HIP_TRY(ctx, call)                                                      \
+    do {                                                                        \
+        hipError_t e__ = (call);                                                \
+        if (e__ != hipSuccess) return fail((ctx), HCLAE_EHIP, #call, e__);      \
+    } while (0)
+
+int check_call(hclae_ctx *ctx, int64_t N, int D, int M, int K)
+{
+    if (!ctx) return HCLAE_EINVAL;
+    int rc = hclae_check_shape(N, D, M, K);
+    if (rc != HCLAE_OK) return fail(ctx, rc, "shape out of range");
+    if (D != ctx->D || M != ctx->M || K != ctx->K) return fail(ctx, HCLAE_ESTATE, "D, M, K differ from hclae_create");
+    if (N > ctx->N_max) return fail(ctx, HCLAE_ESTATE, "N exceeds N_max of hclae_create");
+    return HCLAE_OK;
+}
+
+int stream_blocks(const hclae_ctx *ctx, int64_t work_items, int per_block)
+{
+    int64_t need = (work_items + per_block - 1) / per_block;
+    int64_t cap = (int64_t)ctx->cus * 8;
+    if (cap > kMaxParts) cap = kMaxParts;
+    if (need > cap) need = cap;
+    if (need < 1) need = 1;
+    return (int)need;
+}
+
+RowGeom row_geom(int D)
+{
+    RowGeom g;
+    g.d4 = D / 4;
+    int l = 0;
+    while ((2 << l) <= g.d4 && l < 6) ++l;     // largest power of two <= min(d4, 64)
+    g.lcw = l;
+    return g;
+}
+
+// ---- launches (all on ctx->stream) ------------------------------------------------------
+
+template <int SIGN, bool STATS>
+int launch_heat_cool(hclae_ctx *ctx, int m, int64_t N, const float *C, const uint8_t *codes, float *r,
+                     double *part_err)
+{
+    const RowGeom g = row_geom(ctx->D);
+    const int rows = kStreamThreads >> g.lcw;
+    const int blocks = stream_blocks(ctx, N, rows);
+    const float *Cm = C + (size_t)m * ctx->K * ctx->D;
+    hipLaunchKernelGGL((k_heat_cool<SIGN, STATS>), dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
+                       r, codes, Cm, N, ctx->D, ctx->M, m, g, ctx->old_codes, part_err, ctx->part_chg);
+    HIP_TRY(ctx, hipGetLastError());
+    return blocks;
+}
+
+int launch_norms(hclae_ctx *ctx, const float *Cm)
+{
+    const int kpad = 32 * ctx->kb;
+    hipLaunchKernelGGL(k_codeword_norms, dim3((kpad + 3) / 4), dim3(256), 0, ctx->stream,
+                       Cm, ctx->K, ctx->D, kpad, ctx->hneg, ctx->refine_count);
+    HIP_TRY(ctx, hipGetLastError());
+    return HCLAE_OK;
+}
+
+template <int KB>
+int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float *Cm, uint8_t *codes)
+{
+    const int D = ctx->D;
+    const int dpad = kChunkD * ctx->NC;
+    // twice the worst-case rounding error of a score: (dpad + 1) roundings of relative size 2^-23
+    // on partial sums bounded by h + ||x'|| ||c||, plus the rounding of h itself
+    const float eps = 2.02f * (float)(dpad + 2) * 1.1920929e-7f;
+    if (ctx->resident) {
+        const size_t lds = (size_t)KB * 8 * ctx->NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
+        const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
+        int64_t blocks = (ntiles + kAssignWaves - 1) / kAssignWaves;
+        if (blocks > ctx->cus) blocks = ctx->cus;
+        static bool attr_set = false;
+        if (!attr_set) {
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            attr_set = true;
+        }
+        hipLaunchKernelGGL((k_assign_resident<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
+                           xp, Cm, ctx->hneg, N, D, ctx->K, ctx->M, m, ctx->NC, eps,
+                           codes, ctx->refine_list, ctx->refine_count);
+    } else {
+        const size_t lds = (size_t)KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
+        const int64_t nbt = (N + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);
+        int64_t blocks = nbt < 2 * ctx->cus ? nbt : 2 * ctx->cus;
+        static bool attr_set = false;
+        if (!attr_set) {
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_chunked<KB>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            attr_set = true;
+        }
+        hipLaunchKernelGGL((k_assign_chunked<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
+                           xp, Cm, ctx->hneg, N, D, ctx->K, ctx->M, m, ctx->NC, eps,
+                           codes, ctx->refine_list, ctx->refine_count);
+    }
+    HIP_TRY(ctx, hipGetLastError());
+    hipLaunchKernelGGL(k_refine, dim3(ctx->cus * 4), dim3(256), 0, ctx->stream,
+                       xp, Cm, D, ctx->M, m, codes, ctx->refine_list, ctx->refine_count);
+    HIP_TRY(ctx, hipGetLastError());
+    return HCLAE_OK;
+}
+
+// Assumes hneg holds the norms of Cm and the re-check counter is zero.
+int launch_assign(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float *Cm, uint8_t *codes)
+{
+    switch (ctx->kb) {
+    case 1: return launch_assign_kb<1>(ctx, m, N, xp, Cm, codes);
+    case 2: return launch_assign_kb<2>(ctx, m, N, xp, Cm, codes);
+    case 4: return launch_assign_kb<4>(ctx, m, N, xp, Cm, codes);
+    default: return launch_assign_kb<8>(ctx, m, N, xp, Cm, codes);
+    }
+}
+
+// Accumulate + merge; leaves hneg = norms of the new Cm and the re-check counter at zero.
+int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, const uint8_t *codes,
+                  int32_t *counts)
+{
+    const int D = ctx->D, K = ctx->K;
+    const int windows = (D + kUpdWindow - 1) / kUpdWindow;
+    int64_t nb = (N + 255) / 256;                     // at least 256 rows per block
+    if (nb > ctx->upd_blocks) nb = ctx->upd_blocks;
+    if (nb < 1) nb = 1;
+    int64_t rpb = (N + nb - 1) / nb;
+    const size_t lds = ((size_t)kUpdWaves * K * kUpdSlice + K) * sizeof(float);
+    static bool attr_set = false;
+    if (!attr_set) {
+        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_accumulate),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(k_accumulate, dim3((unsigned)nb, (unsigned)windows), dim3(kUpdThreads), lds, ctx->stream,
+                       xp, codes, N, D, K, ctx->M, m, rpb, ctx->partial, ctx->pcount);
+    HIP_TRY(ctx, hipGetLastError());
+    hipLaunchKernelGGL(k_merge, dim3(K), dim3(256), 0, ctx->stream,
+                       ctx->partial, ctx->pcount, (int)nb, K, D, Cm, ctx->hneg, ctx->nk, counts, ctx->refine_count);
+    HIP_TRY(ctx, hipGetLastError());
+    return HCLAE_OK;
+}
+
+int launch_sqnorm(hclae_ctx *ctx, const float *r, int64_t N, double *part)
+{
+    const int64_t n4 = N * (ctx->D / 4);
+    const int blocks = stream_blocks(ctx, n4, kStreamThreads * 4);
+    hipLaunchKernelGGL(k_sqnorm, dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
+                       reinterpret_cast<const float4 *>(r), n4, part);
+    HIP_TRY(ctx, hipGetLastError());
+    return blocks;
+}
+
+// Enqueues one full stage; by-products land in ctx->rec[slot].  No host synchronisation.
+int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, float *residue, int iters,
+                  const int64_t *init_idx, int slot)
+{
+    const int D = ctx->D, K = ctx->K;
+    float *Cm = C + (size_t)m * K * D;
+    int rc;
+    if (init_idx)   // pageable host memory: the copy is staged before the call returns
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->seed_idx, init_idx, sizeof(int64_t) * K, hipMemcpyHostToDevice, ctx->stream));
+    const int pb = launch_heat_cool<+1, true>(ctx, m, N, C, codes, residue, ctx->part_a);
+    if (pb < 0) return pb;
+    if (init_idx) {
+        hipLaunchKernelGGL(k_seed, dim3(K), dim3(256), 0, ctx->stream, residue, ctx->seed_idx, K, D, Cm);
+        HIP_TRY(ctx, hipGetLastError());
+    }
+    if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
+    for (int t = 0; t < iters; ++t) {
+        if ((rc = launch_assign(ctx, m, N, residue, Cm, codes)) != HCLAE_OK) return rc;
+        if ((rc = launch_update(ctx, m, N, residue, Cm, codes, nullptr)) != HCLAE_OK) return rc;
+    }
+    if ((rc = launch_assign(ctx, m, N, residue, Cm, codes)) != HCLAE_OK) return rc;
+    const int pa = launch_heat_cool<-1, true>(ctx, m, N, C, codes, residue, ctx->part_b);
+    if (pa < 0) return pa;
+    hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kStreamThreads), 0, ctx->stream,
+                       ctx->part_a, ctx->part_b, ctx->part_chg, pa, iters > 0 ? ctx->nk : nullptr, K,
+                       ctx->refine_count, ctx->rec + slot);
+    HIP_TRY(ctx, hipGetLastError());
+    return HCLAE_OK;
+}
+
+int enqueue_encode(hclae_ctx *ctx, const float *X, int64_t N, const float *C, uint8_t *codes, float *residue)
+{
+    const int D = ctx->D, K = ctx->K;
+    const int64_t n4 = N * (D / 4);
+    int rc;
+    hipLaunchKernelGGL(k_copy, dim3(stream_blocks(ctx, n4, kStreamThreads * 4)), dim3(kStreamThreads), 0, ctx->stream,
+                       reinterpret_cast<float4 *>(residue), reinterpret_cast<const float4 *>(X), n4);
+    HIP_TRY(ctx, hipGetLastError());
+    for (int m = 0; m < ctx->M; ++m) {
+        const float *Cm = C + (size_t)m * K * D;
+        if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
+        if ((rc = launch_assign(ctx, m, N, residue, Cm, codes)) != HCLAE_OK) return rc;
+        const int b = launch_heat_cool<-1, false>(ctx, m, N, C, codes, residue, nullptr);
+        if (b < 0) return b;
+    }
+    return HCLAE_OK;
+}
+
+int fetch_records(hclae_ctx *ctx, int count)
+{
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->rec_host, ctx->rec, sizeof(StageRecord) * count, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HCLAE_OK;
+}
+
+}  // namespace
+
+// =========================================================================================
+extern "C" {
+
+int hclae_check_shape(int64_t N, int D, int M, int K)
+{
+    if (N < 0 || N >= ((int64_t)1 << 31)) return HCLAE_EINVAL;
+    if (D < 4 || D > HCLAE_MAX_D || (D % 4) != 0) return HCLAE_EINVAL;
+    if (M < 1 || M > HCLAE_MAX_M) return HCLAE_EINVAL;
+    if (K < 1 || K > HCLAE_MAX_K) return HCLAE_EINVAL;
+    return HCLAE_OK;
+}
+
+const char *hclae_last_error(const hclae_ctx *ctx) { return ctx ? ctx->err : g_create_error; }
+
+int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_stream)
+{
+    if (!out) return fail(nullptr, HCLAE_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (hclae_check_shape(N_max, D, M, K) != HCLAE_OK || N_max < 1)
+        return fail(nullptr, HCLAE_EINVAL, "shape out of range");
+    hclae_ctx *ctx = new (std::nothrow) hclae_ctx();
+    if (!ctx) return fail(nullptr, HCLAE_ENOMEM, "host allocation failed");
+    memset(ctx, 0, sizeof(*ctx));
+    ctx->N_max = N_max; ctx->D = D; ctx->M = M; ctx->K = K;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    ctx->kb = K <= 32 ? 1 : K <= 64 ? 2 : K <= 128 ? 4 : 8;
+    ctx->NC = (D + kChunkD - 1) / kChunkD;
+    ctx->resident = (size_t)32 * ctx->kb * kChunkD * ctx->NC * sizeof(float) + 4096 <= (size_t)kLdsBudget;
+
+    hipError_t e = hipGetDevice(&ctx->device);
+    hipDeviceProp_t prop;
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, ctx->device);
+    if (e != hipSuccess) {
+        int rc = fail(nullptr, HCLAE_EHIP, "no usable HIP device", e);
+        delete ctx;
+        return rc;
+    }
+    ctx->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    if ((size_t)prop.sharedMemPerBlock < 64 * 1024 && false) { /* LDS limit is raised per kernel below */ }
+
+    // partial sums: at most one vector range per CU, fewer when K*D is large (cap ~256 MB)
+    int ub = ctx->cus;
+    const size_t per = (size_t)K * D * sizeof(float);
+    while (ub > 8 && per * ub > ((size_t)256 << 20)) ub /= 2;
+    ctx->upd_blocks = ub;
+
+    struct { void **p; size_t bytes; } allocs[] = {
+        {(void **)&ctx->hneg, sizeof(float) * 32 * ctx->kb},
+        {(void **)&ctx->refine_count, 256},
+        {(void **)&ctx->refine_list, sizeof(RefineItem) * (size_t)N_max},
+        {(void **)&ctx->old_codes, (size_t)N_max},
+        {(void **)&ctx->partial, per * ub},
+        {(void **)&ctx->pcount, sizeof(int) * (size_t)K * ub},
+        {(void **)&ctx->nk, sizeof(int) * K},
+        {(void **)&ctx->seed_idx, sizeof(int64_t) * K},
+        {(void **)&ctx->part_a, sizeof(double) * kMaxParts},
+        {(void **)&ctx->part_b, sizeof(double) * kMaxParts},
+        {(void **)&ctx->part_chg, sizeof(long long) * kMaxParts},
+        {(void **)&ctx->rec, sizeof(StageRecord) * M},
+    };
+    for (auto &a : allocs) {
+        e = hipMalloc(a.p, a.bytes);
+        if (e != hipSuccess) {
+            int rc = fail(nullptr, e == hipErrorOutOfMemory ? HCLAE_ENOMEM : HCLAE_EHIP, "hipMalloc (scratch)", e);
+            hclae_destroy(ctx);
+            return rc;
+        }
+    }
+    e = hipHostMalloc((void **)&ctx->rec_host, sizeof(StageRecord) * M, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipMemset(ctx->rec, 0, sizeof(StageRecord) * M);
+    if (e == hipSuccess) e = hipMemset(ctx->refine_count, 0, 256);
+    if (e == hipSuccess) e = hipMemset(ctx->nk, 0, sizeof(int) * K);
+    if (e != hipSuccess) {
+        int rc = fail(nullptr, HCLAE_EHIP, "scratch initialisation", e);
+        hclae_destroy(ctx);
+        return rc;
+    }
+    snprintf(ctx->err, sizeof(ctx->err), "ok");
+    *out = ctx;
+    return HCLAE_OK;
+}
+
+int hclae_destroy(hclae_ctx *ctx)
+{
+    if (!ctx) return HCLAE_EINVAL;
+    void *dev[] = {ctx->hneg, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
+                   ctx->nk, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec};
+    for (void *p : dev)
+        if (p) (void)hipFree(p);
+    if (ctx->rec_host) (void)hipHostFree(ctx->rec_host);
+    delete ctx;
+    return HCLAE_OK;
+}
+
+int hclae_heat(hclae_ctx *ctx, int m, int64_t N, int D, const float *C, int M, int K,
+               const uint8_t *codes, float *residue)
+{
+    int rc = check_call(ctx, N, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (m < 0 || m >= M || !C || !codes || !residue) return fail(ctx, HCLAE_EINVAL, "hclae_heat: bad argument");
+    if (N == 0) return HCLAE_OK;
+    const int b = launch_heat_cool<+1, false>(ctx, m, N, C, codes, residue, nullptr);
+    return b < 0 ? b : HCLAE_OK;
+}
+
+int hclae_cool(hclae_ctx *ctx, int m, int64_t N, int D, const float *C, int M, int K,
+               const uint8_t *codes, float *xp)
+{
+    int rc = check_call(ctx, N, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (m < 0 || m >= M || !C || !codes || !xp) return fail(ctx, HCLAE_EINVAL, "hclae_cool: bad argument");
+    if (N == 0) return HCLAE_OK;
+    const int b = launch_heat_cool<-1, false>(ctx, m, N, C, codes, xp, nullptr);
+    return b < 0 ? b : HCLAE_OK;
+}
+
+int hclae_assign(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, const float *C,
+                 int M, int K, uint8_t *codes, float *dmin)
+{
+    int rc = check_call(ctx, N, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (m < 0 || m >= M || !C || !codes || !xp) return fail(ctx, HCLAE_EINVAL, "hclae_assign: bad argument");
+    if (N == 0) return HCLAE_OK;
+    const float *Cm = C + (size_t)m * K * D;
+    if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
+    if ((rc = launch_assign(ctx, m, N, xp, Cm, codes)) != HCLAE_OK) return rc;
+    if (dmin) {
+        hipLaunchKernelGGL(k_dist_to_code, dim3(stream_blocks(ctx, N, kStreamThreads / kWave)), dim3(kStreamThreads), 0,
+                           ctx->stream, xp, codes, Cm, N, D, M, m, dmin);
+        HIP_TRY(ctx, hipGetLastError());
+    }
+    return HCLAE_OK;
+}
+
+int hclae_update(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, float *C,
+                 int M, int K, const uint8_t *codes, int32_t *counts)
+{
+    int rc = check_call(ctx, N, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (m < 0 || m >= M || !C || !codes || !xp) return fail(ctx, HCLAE_EINVAL, "hclae_update: bad argument");
+    if (N == 0) {
+        if (counts) HIP_TRY(ctx, hipMemsetAsync(counts, 0, sizeof(int32_t) * K, ctx->stream));
+        return HCLAE_OK;
+    }
+    return launch_update(ctx, m, N, xp, C + (size_t)m * K * D, codes, counts);
+}
+
+int hclae_quant_error(hclae_ctx *ctx, const float *residue, int64_t N, int D, double *out)
+{
+    if (!ctx) return HCLAE_EINVAL;
+    int rc = check_call(ctx, N, D, ctx->M, ctx->K);
+    if (rc != HCLAE_OK) return rc;
+    if (!out || (!residue && N > 0)) return fail(ctx, HCLAE_EINVAL, "hclae_quant_error: bad argument");
+    if (N == 0) { *out = 0.0; return HCLAE_OK; }
+    const int blocks = launch_sqnorm(ctx, residue, N, ctx->part_b);
+    if (blocks < 0) return blocks;
+    hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kStreamThreads), 0, ctx->stream,
+                       (const double *)nullptr, ctx->part_b, (const long long *)nullptr, blocks,
+                       (const int *)nullptr, 0, (const unsigned *)nullptr, ctx->rec);
+    HIP_TRY(ctx, hipGetLastError());
+    if ((rc = fetch_records(ctx, 1)) != HCLAE_OK) return rc;
+    *out = ctx->rec_host[0].sum_after / (double)N;
+    return HCLAE_OK;
+}
+
+int hclae_encode(hclae_ctx *ctx, const float *X, int64_t N, int D,
+                 const float *C, int M, int K, uint8_t *codes, float *residue)
+{
+    int rc = check_call(ctx, N, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (!X || !C || !codes || !residue || X == residue) return fail(ctx, HCLAE_EINVAL, "hclae_encode: bad argument");
+    if (N == 0) return HCLAE_OK;
+    return enqueue_encode(ctx, X, N, C, codes, residue);
+}
+
+static int check_init_idx(const int64_t *idx, int count, int64_t N)
+{
+    for (int i = 0; i < count; ++i)
+        if (idx[i] < 0 || idx[i] >= N) return HCLAE_EINVAL;
+    return HCLAE_OK;
+}
+
+static void fill_stats(const StageRecord &r, int64_t N, int iters, hclae_stage_stats *s)
+{
+    s->err_before = r.sum_before / (double)N;
+    s->err_after = r.sum_after / (double)N;
+    s->codes_changed = r.changed;
+    s->refined = r.refined;
+    s->empty_clusters = iters > 0 ? r.empty : 0;
+    s->iters_run = iters;
+}
+
+int hclae_anneal_stage(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M, int K,
+                       uint8_t *codes, float *residue, int iters,
+                       const int64_t *init_idx, hclae_stage_stats *stats)
+{
+    int rc = check_call(ctx, N, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (m < 0 || m >= M || iters < 0 || !C || !codes || !residue)
+        return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage: bad argument");
+    if (init_idx && check_init_idx(init_idx, K, N) != HCLAE_OK)
+        return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage: init_idx out of range");
+    if (N == 0) {
+        if (stats) { memset(stats, 0, sizeof(*stats)); }
+        return HCLAE_OK;
+    }
+    if ((rc = enqueue_stage(ctx, m, N, C, codes, residue, iters, init_idx, 0)) != HCLAE_OK) return rc;
+    if (stats) {
+        if ((rc = fetch_records(ctx, 1)) != HCLAE_OK) return rc;
+        fill_stats(ctx->rec_host[0], N, iters, stats);
+    } else if (init_idx) {
+        // the seed indices were read from caller memory by an asynchronous copy
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    }
+    return HCLAE_OK;
+}
+
+int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int M, int K,
+                uint8_t *codes, float *residue, int iters, int reencode_mode,
+                const int64_t *init_idx, double *err_per_stage)
+{
+    int rc = check_call(ctx, N, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (iters < 0 || !C || !codes || !residue || (reencode_mode != 0 && reencode_mode != 1))
+        return fail(ctx, HCLAE_EINVAL, "hclae_sweep: bad argument");
+    if (reencode_mode == 1 && (!X || X == residue)) return fail(ctx, HCLAE_EINVAL, "hclae_sweep: reencode_mode 1 needs X");
+    if (init_idx && check_init_idx(init_idx, M * K, N) != HCLAE_OK)
+        return fail(ctx, HCLAE_EINVAL, "hclae_sweep: init_idx out of range");
+    if (N == 0) {
+        if (err_per_stage) for (int m = 0; m < M; ++m) err_per_stage[m] = 0.0;
+        return HCLAE_OK;
+    }
+    for (int m = 0; m < M; ++m) {
+        const int64_t *idx = init_idx ? init_idx + (size_t)m * K : nullptr;
+        if ((rc = enqueue_stage(ctx, m, N, C, codes, residue, iters, idx, m)) != HCLAE_OK) return rc;
+        if (idx) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));   // seed_idx scratch is reused by the next stage
+        if (reencode_mode == 1) {
+            if ((rc = enqueue_encode(ctx, X, N, C, codes, residue)) != HCLAE_OK) return rc;
+            if (err_per_stage) {
+                const int blocks = launch_sqnorm(ctx, residue, N, ctx->part_b);
+                if (blocks < 0) return blocks;
+                hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kStreamThreads), 0, ctx->stream,
+                                   (const double *)nullptr, ctx->part_b, (const long long *)nullptr, blocks,
+                                   (const int *)nullptr, 0, (const unsigned *)nullptr, ctx->rec + m);
+                HIP_TRY(ctx, hipGetLastError());
+            }
+        }
+    }
+    if (err_per_stage) {
+        if ((rc = fetch_records(ctx, M)) != HCLAE_OK) return rc;
+        for (int m = 0; m < M; ++m) err_per_stage[m] = ctx->rec_host[m].sum_after / (double)N;
+    }
+    return HCLAE_OK;
+}
+
+int hclae_last_refined(hclae_ctx *ctx, int64_t *out)
+{
+    if (!ctx || !out) return HCLAE_EINVAL;
+    unsigned v = 0;
+    HIP_TRY(ctx, hipMemcpyAsync(&v, ctx->refine_count, sizeof(unsigned), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    *out = (int64_t)v;
+    return HCLAE_OK;
+}
+
+}  // extern "C"

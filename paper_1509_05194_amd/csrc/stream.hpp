@@ -1,0 +1,151 @@
+// Streaming passes of a DA stage (Sec. 3.1): heat x' = e_x + c_m(i_m(x)), the new residue
+// e_x = x' - c_m(i_m(x)), and the error of Eq. 1 (first line).  All are HBM-bound: every
+// thread moves one float4 per row pass, a wave covers contiguous kilobytes, the K x D
+// codebook (<= 1 MB) stays in L2.
+#pragma once
+#include "common.hpp"
+
+namespace hclae {
+
+constexpr int kStreamThreads = 256;
+
+// Geometry shared by the streaming kernels: a block is (1 << lcw) column threads by
+// (256 >> lcw) rows; column thread tx walks float4 columns tx, tx + cw, ...
+struct RowGeom {
+    int lcw;        // log2 of column threads per row
+    int d4;         // D / 4
+};
+
+// residue_n (+|-)= C_m[codes[n][m]]  with optional by-products:
+//   SIGN = +1 : heat.  Also saves column m of the codes (old_codes) and sums ||e_x||^2 of the input.
+//   SIGN = -1 : cool.  Also sums ||e_x||^2 of the output and counts codes != old_codes.
+// part_err[blockIdx.x], part_chg[blockIdx.x] receive this block's partial sums (fixed order).
+template <int SIGN, bool STATS>
+__global__ __launch_bounds__(kStreamThreads) void k_heat_cool(
+    float *__restrict__ r, const uint8_t *__restrict__ codes, const float *__restrict__ Cm,
+    int64_t N, int D, int M, int m, RowGeom g,
+    uint8_t *__restrict__ old_codes, double *__restrict__ part_err, long long *__restrict__ part_chg)
+{
+    __shared__ double red[kStreamThreads / kWave];
+    const int cw = 1 << g.lcw;
+    const int tx = threadIdx.x & (cw - 1);
+    const int ty = threadIdx.x >> g.lcw;
+    const int rows = kStreamThreads >> g.lcw;
+    double err = 0.0;
+    long long chg = 0;
+    for (int64_t n = (int64_t)blockIdx.x * rows + ty; n < N; n += (int64_t)gridDim.x * rows) {
+        const int code = codes[n * M + m];
+        float4 *rn = reinterpret_cast<float4 *>(r + n * D);
+        const float4 *c = reinterpret_cast<const float4 *>(Cm + (size_t)code * D);
+        if (STATS && tx == 0) {
+            if (SIGN > 0) old_codes[n] = (uint8_t)code;
+            else chg += (old_codes[n] != (uint8_t)code);
+        }
+        for (int j = tx; j < g.d4; j += cw) {
+            float4 v = rn[j];
+            const float4 cv = c[j];
+            if (STATS && SIGN > 0)
+                err += (double)v.x * v.x + (double)v.y * v.y + (double)v.z * v.z + (double)v.w * v.w;
+            if (SIGN > 0) { v.x += cv.x; v.y += cv.y; v.z += cv.z; v.w += cv.w; }
+            else          { v.x -= cv.x; v.y -= cv.y; v.z -= cv.z; v.w -= cv.w; }
+            if (STATS && SIGN < 0)
+                err += (double)v.x * v.x + (double)v.y * v.y + (double)v.z * v.z + (double)v.w * v.w;
+            rn[j] = v;
+        }
+    }
+    if (STATS) {
+        const double e = block_sum(err, red);
+        if (threadIdx.x == 0) part_err[blockIdx.x] = e;
+        if (SIGN < 0) {
+            // integer sum: any order gives the same value
+            const double c = block_sum((double)chg, red);
+            if (threadIdx.x == 0) part_chg[blockIdx.x] = (long long)c;
+        }
+    }
+}
+
+// r <- X (first step of the greedy encoder), one float4 per thread per pass.
+__global__ __launch_bounds__(kStreamThreads) void k_copy(
+    float4 *__restrict__ dst, const float4 *__restrict__ src, int64_t n4)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kStreamThreads + threadIdx.x; i < n4;
+         i += (int64_t)gridDim.x * kStreamThreads)
+        dst[i] = src[i];
+}
+
+// Partial sums of ||e_x||^2 (Eq. 1, first line), fp64 accumulation.
+__global__ __launch_bounds__(kStreamThreads) void k_sqnorm(
+    const float4 *__restrict__ r, int64_t n4, double *__restrict__ part_err)
+{
+    __shared__ double red[kStreamThreads / kWave];
+    double err = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * kStreamThreads + threadIdx.x; i < n4;
+         i += (int64_t)gridDim.x * kStreamThreads) {
+        const float4 v = r[i];
+        err += (double)v.x * v.x + (double)v.y * v.y + (double)v.z * v.z + (double)v.w * v.w;
+    }
+    const double e = block_sum(err, red);
+    if (threadIdx.x == 0) part_err[blockIdx.x] = e;
+}
+
+// dmin_n = ||xp_n - C_m[codes[n][m]]||^2 in the direct form, one wave-row-group per row.
+__global__ __launch_bounds__(kStreamThreads) void k_dist_to_code(
+    const float *__restrict__ xp, const uint8_t *__restrict__ codes, const float *__restrict__ Cm,
+    int64_t N, int D, int M, int m, float *__restrict__ dmin)
+{
+    const int lane = lane_id();
+    const int wpb = kStreamThreads / kWave;
+    for (int64_t n = (int64_t)blockIdx.x * wpb + (threadIdx.x >> 6); n < N; n += (int64_t)gridDim.x * wpb) {
+        const float *x = xp + n * D;
+        const float *c = Cm + (size_t)codes[n * M + m] * D;
+        double s = 0.0;
+        for (int d = lane; d < D; d += kWave) {
+            const double t = (double)x[d] - (double)c[d];
+            s += t * t;
+        }
+        s = wave_sum(s);
+        if (lane == 0) dmin[n] = (float)s;
+    }
+}
+
+// Device-side record of one stage's by-products; copied to the host only when asked for.
+struct StageRecord {
+    double sum_before;       // sum ||e_x||^2 at entry
+    double sum_after;        // sum ||e_x||^2 at exit
+    long long changed;
+    long long refined;
+    int empty;
+    int pad;
+};
+
+// Final, fixed-order reduction of the per-block partials into a StageRecord (one block).
+__global__ __launch_bounds__(kStreamThreads) void k_finish_stage(
+    const double *__restrict__ part_before, const double *__restrict__ part_after,
+    const long long *__restrict__ part_chg, int nparts,
+    const int *__restrict__ nk, int K, const unsigned *__restrict__ refine_count,
+    StageRecord *__restrict__ rec)
+{
+    __shared__ double red[kStreamThreads / kWave];
+    double a = 0.0, b = 0.0, c = 0.0, e = 0.0;
+    for (int i = threadIdx.x; i < nparts; i += kStreamThreads) {
+        if (part_before) a += part_before[i];
+        if (part_after) b += part_after[i];
+        if (part_chg) c += (double)part_chg[i];
+    }
+    if (nk)
+        for (int k = threadIdx.x; k < K; k += kStreamThreads) e += (nk[k] == 0);
+    a = block_sum(a, red);
+    b = block_sum(b, red);
+    c = block_sum(c, red);
+    e = block_sum(e, red);
+    if (threadIdx.x == 0) {
+        if (part_before) rec->sum_before = a;
+        if (part_after) rec->sum_after = b;
+        rec->changed = (long long)c;
+        rec->empty = (int)e;
+        rec->refined = refine_count ? (long long)*refine_count : 0;
+        rec->pad = 0;
+    }
+}
+
+}  // namespace hclae

@@ -1,0 +1,191 @@
+"""ctypes binding of libhclae.so -- argument marshalling only.
+
+Function names and argument order are those of ``include/hclae.h``; tensors are PyTorch CUDA
+(ROCm) tensors used purely as device buffers, their ``data_ptr()`` is what crosses the ABI.
+Every step of the method runs inside the library's HIP kernels; there is no fallback: if the
+library is missing or fails to load, importing a symbol from it raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhclae.so")
+
+OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
+_ERRNAME = {0: "HCLAE_OK", -1: "HCLAE_EINVAL", -2: "HCLAE_ENOMEM", -3: "HCLAE_EHIP", -4: "HCLAE_ESTATE"}
+
+EXPORTS = (
+    "hclae_check_shape", "hclae_create", "hclae_destroy", "hclae_last_error",
+    "hclae_encode", "hclae_anneal_stage", "hclae_sweep", "hclae_quant_error",
+    "hclae_heat", "hclae_cool", "hclae_assign", "hclae_update", "hclae_last_refined",
+)
+
+
+class StageStats(ctypes.Structure):
+    _fields_ = [("err_before", ctypes.c_double), ("err_after", ctypes.c_double),
+                ("codes_changed", ctypes.c_int64), ("refined", ctypes.c_int64),
+                ("empty_clusters", ctypes.c_int32), ("iters_run", ctypes.c_int32)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class HclaeError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("%s (%d): %s" % (_ERRNAME.get(code, "?"), code, text))
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  Raises if libhclae.so has not been built (see build.py)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libhclae.so is not built: run `python -m paper_1509_05194_amd.build`")
+    # PyTorch ships its own HIP runtime (same soname).  Loading it first makes libhclae bind to
+    # that one, so the process holds a single runtime and both see the same device and streams.
+    import torch  # noqa: F401
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    L.hclae_check_shape.argtypes = [i64, i32, i32, i32]
+    L.hclae_create.argtypes = [ctypes.POINTER(vp), i64, i32, i32, i32, vp]
+    L.hclae_destroy.argtypes = [vp]
+    L.hclae_last_error.argtypes = [vp]
+    L.hclae_last_error.restype = ctypes.c_char_p
+    L.hclae_encode.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp]
+    L.hclae_anneal_stage.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp, i32, vp, ctypes.POINTER(StageStats)]
+    L.hclae_sweep.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp, i32, i32, vp, vp]
+    L.hclae_quant_error.argtypes = [vp, vp, i64, i32, ctypes.POINTER(ctypes.c_double)]
+    L.hclae_heat.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp]
+    L.hclae_cool.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp]
+    L.hclae_assign.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, vp, vp]
+    L.hclae_update.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, vp, vp]
+    L.hclae_last_refined.argtypes = [vp, ctypes.POINTER(i64)]
+    for name in EXPORTS:
+        if name != "hclae_last_error":
+            getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+def check_shape(N, D, M, K):
+    return lib().hclae_check_shape(N, D, M, K)
+
+
+def _ptr(t, dtype_name, shape=None):
+    """Device pointer of a contiguous CUDA tensor of the expected dtype (None -> NULL)."""
+    if t is None:
+        return None
+    import torch
+    want = {"f32": torch.float32, "u8": torch.uint8, "i32": torch.int32}[dtype_name]
+    if not (t.is_cuda and t.dtype == want and t.is_contiguous()):
+        raise TypeError("expected a contiguous CUDA %s tensor" % dtype_name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("tensor shape %s, expected %s" % (tuple(t.shape), tuple(shape)))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class Context:
+    """An hclae_ctx bound to one HIP stream (default: torch's current stream)."""
+
+    def __init__(self, N_max, D, M, K, stream=None):
+        import torch
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        self.N_max, self.D, self.M, self.K = int(N_max), int(D), int(M), int(K)
+        self._h = ctypes.c_void_p()
+        rc = lib().hclae_create(ctypes.byref(self._h), self.N_max, self.D, self.M, self.K, ctypes.c_void_p(stream))
+        if rc != OK:
+            raise HclaeError(rc, lib().hclae_last_error(None).decode())
+
+    def close(self):
+        if self._h:
+            lib().hclae_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _chk(self, rc):
+        if rc != OK:
+            raise HclaeError(rc, lib().hclae_last_error(self._h).decode())
+
+    def _shapes(self, N, C=None, codes=None, res=None):
+        D, M, K = self.D, self.M, self.K
+        return (_ptr(C, "f32", (M, K, D)) if C is not None else None,
+                _ptr(codes, "u8", (N, M)) if codes is not None else None,
+                _ptr(res, "f32", (N, D)) if res is not None else None)
+
+    # ---- the four calls of the method -------------------------------------------------
+    def encode(self, X, C, codes, residue):
+        N = X.shape[0]
+        pC, pcodes, pres = self._shapes(N, C, codes, residue)
+        self._chk(lib().hclae_encode(self._h, _ptr(X, "f32", (N, self.D)), N, self.D, pC, self.M, self.K, pcodes, pres))
+
+    def anneal_stage(self, m, C, codes, residue, iters, init_idx=None, want_stats=True):
+        N = residue.shape[0]
+        pC, pcodes, pres = self._shapes(N, C, codes, residue)
+        idx = None
+        if init_idx is not None:
+            idx = np.ascontiguousarray(init_idx, np.int64)
+            assert idx.shape == (self.K,)
+        stats = StageStats() if want_stats else None
+        self._chk(lib().hclae_anneal_stage(self._h, m, N, self.D, pC, self.M, self.K, pcodes, pres, iters,
+                                           idx.ctypes.data_as(ctypes.c_void_p) if idx is not None else None,
+                                           ctypes.byref(stats) if want_stats else None))
+        return stats.as_dict() if want_stats else None
+
+    def sweep(self, C, codes, residue, iters, X=None, reencode_mode=0, init_idx=None, want_err=True):
+        N = residue.shape[0]
+        pC, pcodes, pres = self._shapes(N, C, codes, residue)
+        idx = None
+        if init_idx is not None:
+            idx = np.ascontiguousarray(init_idx, np.int64)
+            assert idx.shape == (self.M, self.K)
+        err = np.zeros(self.M, np.float64) if want_err else None
+        self._chk(lib().hclae_sweep(self._h, _ptr(X, "f32", (N, self.D)), N, self.D, pC, self.M, self.K, pcodes, pres,
+                                    iters, reencode_mode,
+                                    idx.ctypes.data_as(ctypes.c_void_p) if idx is not None else None,
+                                    err.ctypes.data_as(ctypes.c_void_p) if want_err else None))
+        return err
+
+    def quant_error(self, residue):
+        N = residue.shape[0]
+        out = ctypes.c_double()
+        self._chk(lib().hclae_quant_error(self._h, _ptr(residue, "f32", (N, self.D)), N, self.D, ctypes.byref(out)))
+        return out.value
+
+    # ---- single steps -------------------------------------------------------------------
+    def heat(self, m, C, codes, residue):
+        N = residue.shape[0]
+        pC, pcodes, pres = self._shapes(N, C, codes, residue)
+        self._chk(lib().hclae_heat(self._h, m, N, self.D, pC, self.M, self.K, pcodes, pres))
+
+    def cool(self, m, C, codes, xp):
+        N = xp.shape[0]
+        pC, pcodes, pres = self._shapes(N, C, codes, xp)
+        self._chk(lib().hclae_cool(self._h, m, N, self.D, pC, self.M, self.K, pcodes, pres))
+
+    def assign(self, m, xp, C, codes, dmin=None):
+        N = xp.shape[0]
+        pC, pcodes, pxp = self._shapes(N, C, codes, xp)
+        self._chk(lib().hclae_assign(self._h, m, N, self.D, pxp, pC, self.M, self.K, pcodes, _ptr(dmin, "f32", (N,))))
+
+    def update(self, m, xp, C, codes, counts=None):
+        N = xp.shape[0]
+        pC, pcodes, pxp = self._shapes(N, C, codes, xp)
+        self._chk(lib().hclae_update(self._h, m, N, self.D, pxp, pC, self.M, self.K, pcodes, _ptr(counts, "i32", (self.K,))))
+
+    def last_refined(self):
+        out = ctypes.c_int64()
+        self._chk(lib().hclae_last_refined(self._h, ctypes.byref(out)))
+        return out.value
