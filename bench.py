@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the Dictionary Annealing sweep (arXiv 1509.05194, Sec. 3.1) on one MI355X.
+
+One step = one pass of the whole hot path over the SIFT-shaped workload: a full DA sweep
+(heat, T Lloyd iterations of assign + centroid update, re-encode, new residue, for each of
+the M dictionaries) over N resident vectors, plus greedy encoding of 10,000 held-out queries.
+Prints ONE JSON line.  Inputs are seeded synthetic stand-ins shaped like 128-d SIFT
+descriptors (integer-valued in [0,255], ~30 % zeros), already in HBM when timing starts.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0             # MI355X HBM3E peak
+
+# HBM bytes per launch of the assign kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# scaled by a copy kernel of known size; None until measured (see profiles/).
+ASSIGN_TRAFFIC_BYTES = None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--n", type=int, default=1_000_000)
+    ap.add_argument("--m", type=int, default=8)
+    ap.add_argument("--iters", type=int, default=10, help="Lloyd iterations T per cool-down")
+    ap.add_argument("--queries", type=int, default=10_000)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-breakdown", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    from paper_1509_05194_amd import hclae, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    N, D, M, K, T, Q = args.n, 128, args.m, 256, args.iters, args.queries
+
+    t_gen = time.perf_counter()
+    X = synth.sift_like(N, D=D)
+    Xq = synth.sift_like(Q, D=D, seed=synth.SEED_HELDOUT)
+    idx = synth.init_indices(N, M, K)
+    t_gen = time.perf_counter() - t_gen
+
+    Xg = torch.from_numpy(X).to(dev)
+    Xqg = torch.from_numpy(Xq).to(dev)
+    C = torch.zeros((M, K, D), dtype=torch.float32, device=dev)
+    codes = torch.zeros((N, M), dtype=torch.uint8, device=dev)
+    r = Xg.clone()                       # all-zero dictionaries: residue = x
+    qcodes = torch.zeros((Q, M), dtype=torch.uint8, device=dev)
+    qres = torch.empty((Q, D), dtype=torch.float32, device=dev)
+    ctx = hclae.Context(N, D, M, K)
+
+    def step(first):
+        ctx.timing_enable(["assign"])
+        ctx.sweep(C, codes, r, T, init_idx=idx if first else None, want_err=False)
+        ctx.timing_enable([])
+        ctx.encode(Xqg, C, qcodes, qres)
+
+    # warm-up: the first step learns the dictionaries from scratch, later ones anneal them
+    first = True
+    for _ in range(max(args.warmup, 1)):
+        step(first)
+        first = False
+    torch.cuda.synchronize()
+    ctx.timing_read()
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(False)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    times = ctx.timing_read()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = N * M / ((t1 - t0) / args.steps)              # vectors/s per stage
+    a_ms, a_n = times["assign"]
+    assign_ms = a_ms / max(a_n, 1)
+    flops = 2.0 * N * K * D                               # algorithmic flops of one assign launch
+    achieved = flops / (assign_ms * 1e-3) / 1e12
+    E_final = ctx.quant_error(r)
+
+    out = {
+        "metric": "DA sweep vectors/sec per stage (D=128,K=256)",
+        "value": value,
+        "unit": "vectors/s per stage",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": max(args.warmup, 1),
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "SIFT-shaped: N=%d, D=128, M=%d, K=256, T=%d Lloyd iterations per stage; "
+                               "one DA sweep + greedy encode of %d held-out queries per step" % (N, M, T, Q),
+                   "N": N, "D": D, "M": M, "K": K, "iters": T, "queries": Q,
+                   "quant_error_after": E_final},
+        "roofline": {"bound": "mfma", "kernel": "k_assign_resident<8> (fp32 MFMA distance contraction + argmin)",
+                     "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": ASSIGN_TRAFFIC_BYTES,
+                     "avg_launch_ms": assign_ms, "launches": a_n, "flops_per_launch": flops},
+    }
+
+    if not args.no_breakdown:
+        # one more sweep, outside the timed region, with every kernel class bracketed by events
+        ctx.timing_enable(hclae.KERNEL_CLASSES)
+        ctx.sweep(C, codes, r, T, want_err=False)
+        ctx.timing_enable([])
+        bt = ctx.timing_read()
+        alg_bytes = {"heat": N * (8 * D + 1 + 1), "cool": N * (8 * D + 1 + 1), "accumulate": N * (4 * D + 1),
+                     "error": N * 4 * D}
+        kernels = {}
+        for cls, (ms, n) in bt.items():
+            if n == 0:
+                continue
+            e = {"avg_ms": ms / n, "launches": n}
+            if cls in alg_bytes:
+                gbs = alg_bytes[cls] / (ms / n * 1e-3) / 1e9
+                e.update(achieved_GBs=gbs, frac_hbm=gbs / PEAK_HBM_GBS)
+            if cls == "assign":
+                tf = flops / (ms / n * 1e-3) / 1e12
+                e.update(achieved_TFLOPs=tf, frac_mfma=tf / PEAK_FP32_MFMA_TFLOPS)
+            kernels[cls] = e
+        out["kernels"] = kernels
+
+    if not args.no_cpu_baseline:
+        import oracle
+        Ns = min(N, 200_000)
+        Xs = np.ascontiguousarray(X[:Ns])
+        Co = np.zeros((M, K, D), np.float64)
+        co = np.zeros((Ns, M), np.uint8)
+        ro = Xs.astype(np.float64)
+        idx_s = synth.init_indices(Ns, M, K)
+        tc = time.perf_counter()
+        oracle.anneal_stage(0, Co, co, ro, T, idx_s[0])
+        tc = time.perf_counter() - tc
+        out["cpu_baseline"] = {"value": Ns / tc, "unit": "vectors/s per stage", "cores": oracle.threads(),
+                               "kind": "oracle",
+                               "sample": "one DA stage (m=0, T=%d, K=256) of the fp64 oracle on the first %d "
+                                         "vectors of the same workload, %.1f s" % (T, Ns, tc)}
+    out["host_gen_s"] = t_gen
+    print(json.dumps(out))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -26,6 +26,7 @@
  * Errors: every entry point returns HCLAE_OK or a negative code.  Arguments are checked
  * before any HIP call; on HCLAE_EINVAL nothing was enqueued and no state changed.
  * A failing HIP call gives HCLAE_EHIP; hclae_last_error(ctx) then holds its text.
+ * With N == 0 every call is a no-op that returns HCLAE_OK (data pointers may then be NULL).
  * Argmin ties go to the lowest index.  A codeword whose cluster is empty keeps its value.
  */
 #ifndef HCLAE_H
@@ -132,6 +133,32 @@ int hclae_update(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, float
  * to the fp64 re-check because their two best fp32 scores were closer than the rounding
  * bound of the fp32 contraction.  Synchronises the stream.  out: HOST. */
 int hclae_last_refined(hclae_ctx *ctx, int64_t *out);
+
+/* ---- measurement: per-kernel durations from HIP events on the ctx's stream ------------- */
+
+enum {
+    HCLAE_T_HEAT = 0,   /* heat pass (Sec. 3.1, x' = e_x + c)                              */
+    HCLAE_T_COOL,       /* new-residue pass                                                 */
+    HCLAE_T_ASSIGN,     /* fp32-MFMA distance contraction + argmin                          */
+    HCLAE_T_REFINE,     /* fp64 re-check of near-ties                                       */
+    HCLAE_T_ACCUM,      /* centroid sums and counts                                         */
+    HCLAE_T_MERGE,      /* merge of the block partials, division, codeword norms            */
+    HCLAE_T_NORMS,      /* codeword norms alone                                             */
+    HCLAE_T_ERROR,      /* Eq. 1 reduction alone                                            */
+    HCLAE_T_COUNT
+};
+
+typedef struct {
+    double  ms[HCLAE_T_COUNT];        /* summed event time per kernel class, milliseconds   */
+    int64_t launches[HCLAE_T_COUNT];  /* launches those sums cover                          */
+} hclae_kernel_times;
+
+/* Bracket every later launch whose class bit (1 << HCLAE_T_*) is set in class_mask with a
+ * pair of events; 0 switches timing off (recorded launches are kept until read).  At most
+ * 4096 launches are kept between reads; later ones go untimed. */
+int hclae_timing_enable(hclae_ctx *ctx, uint32_t class_mask);
+/* Synchronise the stream, sum the recorded launches per class into *out (HOST), forget them. */
+int hclae_timing_read(hclae_ctx *ctx, hclae_kernel_times *out);
 
 #ifdef __cplusplus
 }

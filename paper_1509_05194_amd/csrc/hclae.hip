@@ -19,6 +19,7 @@ namespace {
 
 constexpr int kMaxParts = 4096;          // upper bound on blocks of a streaming pass
 constexpr int kLdsBudget = 160 * 1024;   // LDS per workgroup on gfx950
+constexpr int kMaxTimed = 4096;          // event pairs kept between two hclae_timing_read calls
 
 thread_local char g_create_error[256] = "";
 
@@ -48,6 +49,11 @@ struct hclae_ctx {
     // host
     StageRecord *rec_host;   // pinned [M]
     int upd_blocks;
+    // optional per-kernel timing (HIP events on ctx->stream)
+    uint32_t t_mask;
+    int t_used;
+    hipEvent_t *t_beg, *t_end;   // [kMaxTimed] each, created on first enable
+    uint8_t *t_cls;
     char err[256];
 };
 
@@ -60,6 +66,25 @@ int fail(hclae_ctx *ctx, int code, const char *what, hipError_t e = hipSuccess)
     else snprintf(dst, 256, "%s", what);
     return code;
 }
+
+// Scope guard: brackets the launches issued during its lifetime with two events.
+struct Timed {
+    hclae_ctx *c;
+    int slot;
+    Timed(hclae_ctx *ctx, int cls) : c(ctx), slot(-1)
+    {
+        if ((c->t_mask >> cls) & 1u) {
+            if (c->t_used < kMaxTimed && hipEventRecord(c->t_beg[c->t_used], c->stream) == hipSuccess) {
+                slot = c->t_used;
+                c->t_cls[slot] = (uint8_t)cls;
+            }
+        }
+    }
+    ~Timed()
+    {
+        if (slot >= 0 && hipEventRecord(c->t_end[slot], c->stream) == hipSuccess) c->t_used = slot + 1;
+    }
+};
 
 #define HIP_TRY(ctx, call)                                                      \
     do {                                                                        \
@@ -107,6 +132,7 @@ int launch_heat_cool(hclae_ctx *ctx, int m, int64_t N, const float *C, const uin
     const int rows = kStreamThreads >> g.lcw;
     const int blocks = stream_blocks(ctx, N, rows);
     const float *Cm = C + (size_t)m * ctx->K * ctx->D;
+    Timed t_(ctx, SIGN > 0 ? HCLAE_T_HEAT : HCLAE_T_COOL);
     hipLaunchKernelGGL((k_heat_cool<SIGN, STATS>), dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
                        r, codes, Cm, N, ctx->D, ctx->M, m, g, ctx->old_codes, part_err, ctx->part_chg);
     HIP_TRY(ctx, hipGetLastError());
@@ -116,6 +142,7 @@ int launch_heat_cool(hclae_ctx *ctx, int m, int64_t N, const float *C, const uin
 int launch_norms(hclae_ctx *ctx, const float *Cm)
 {
     const int kpad = 32 * ctx->kb;
+    Timed t_(ctx, HCLAE_T_NORMS);
     hipLaunchKernelGGL(k_codeword_norms, dim3((kpad + 3) / 4), dim3(256), 0, ctx->stream,
                        Cm, ctx->K, ctx->D, kpad, ctx->hneg, ctx->refine_count);
     HIP_TRY(ctx, hipGetLastError());
@@ -130,6 +157,8 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
     // twice the worst-case rounding error of a score: (dpad + 1) roundings of relative size 2^-23
     // on partial sums bounded by h + ||x'|| ||c||, plus the rounding of h itself
     const float eps = 2.02f * (float)(dpad + 2) * 1.1920929e-7f;
+    {
+    Timed t_(ctx, HCLAE_T_ASSIGN);
     if (ctx->resident) {
         const size_t lds = (size_t)KB * 8 * ctx->NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
@@ -158,7 +187,9 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
                            xp, Cm, ctx->hneg, N, D, ctx->K, ctx->M, m, ctx->NC, eps,
                            codes, ctx->refine_list, ctx->refine_count);
     }
+    }
     HIP_TRY(ctx, hipGetLastError());
+    Timed t_(ctx, HCLAE_T_REFINE);
     hipLaunchKernelGGL(k_refine, dim3(ctx->cus * 4), dim3(256), 0, ctx->stream,
                        xp, Cm, D, ctx->M, m, codes, ctx->refine_list, ctx->refine_count);
     HIP_TRY(ctx, hipGetLastError());
@@ -193,9 +224,13 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
         attr_set = true;
     }
-    hipLaunchKernelGGL(k_accumulate, dim3((unsigned)nb, (unsigned)windows), dim3(kUpdThreads), lds, ctx->stream,
-                       xp, codes, N, D, K, ctx->M, m, rpb, ctx->partial, ctx->pcount);
+    {
+        Timed t_(ctx, HCLAE_T_ACCUM);
+        hipLaunchKernelGGL(k_accumulate, dim3((unsigned)nb, (unsigned)windows), dim3(kUpdThreads), lds, ctx->stream,
+                           xp, codes, N, D, K, ctx->M, m, rpb, ctx->partial, ctx->pcount);
+    }
     HIP_TRY(ctx, hipGetLastError());
+    Timed t_(ctx, HCLAE_T_MERGE);
     hipLaunchKernelGGL(k_merge, dim3(K), dim3(256), 0, ctx->stream,
                        ctx->partial, ctx->pcount, (int)nb, K, D, Cm, ctx->hneg, ctx->nk, counts, ctx->refine_count);
     HIP_TRY(ctx, hipGetLastError());
@@ -206,6 +241,7 @@ int launch_sqnorm(hclae_ctx *ctx, const float *r, int64_t N, double *part)
 {
     const int64_t n4 = N * (ctx->D / 4);
     const int blocks = stream_blocks(ctx, n4, kStreamThreads * 4);
+    Timed t_(ctx, HCLAE_T_ERROR);
     hipLaunchKernelGGL(k_sqnorm, dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
                        reinterpret_cast<const float4 *>(r), n4, part);
     HIP_TRY(ctx, hipGetLastError());
@@ -359,6 +395,15 @@ int hclae_destroy(hclae_ctx *ctx)
     for (void *p : dev)
         if (p) (void)hipFree(p);
     if (ctx->rec_host) (void)hipHostFree(ctx->rec_host);
+    if (ctx->t_beg) {
+        for (int i = 0; i < kMaxTimed; ++i) {
+            if (ctx->t_beg[i]) (void)hipEventDestroy(ctx->t_beg[i]);
+            if (ctx->t_end && ctx->t_end[i]) (void)hipEventDestroy(ctx->t_end[i]);
+        }
+    }
+    delete[] ctx->t_beg;
+    delete[] ctx->t_end;
+    delete[] ctx->t_cls;
     delete ctx;
     return HCLAE_OK;
 }
@@ -368,8 +413,9 @@ int hclae_heat(hclae_ctx *ctx, int m, int64_t N, int D, const float *C, int M, i
 {
     int rc = check_call(ctx, N, D, M, K);
     if (rc != HCLAE_OK) return rc;
-    if (m < 0 || m >= M || !C || !codes || !residue) return fail(ctx, HCLAE_EINVAL, "hclae_heat: bad argument");
+    if (m < 0 || m >= M) return fail(ctx, HCLAE_EINVAL, "hclae_heat: m out of range");
     if (N == 0) return HCLAE_OK;
+    if (!C || !codes || !residue) return fail(ctx, HCLAE_EINVAL, "hclae_heat: NULL pointer");
     const int b = launch_heat_cool<+1, false>(ctx, m, N, C, codes, residue, nullptr);
     return b < 0 ? b : HCLAE_OK;
 }
@@ -379,8 +425,9 @@ int hclae_cool(hclae_ctx *ctx, int m, int64_t N, int D, const float *C, int M, i
 {
     int rc = check_call(ctx, N, D, M, K);
     if (rc != HCLAE_OK) return rc;
-    if (m < 0 || m >= M || !C || !codes || !xp) return fail(ctx, HCLAE_EINVAL, "hclae_cool: bad argument");
+    if (m < 0 || m >= M) return fail(ctx, HCLAE_EINVAL, "hclae_cool: m out of range");
     if (N == 0) return HCLAE_OK;
+    if (!C || !codes || !xp) return fail(ctx, HCLAE_EINVAL, "hclae_cool: NULL pointer");
     const int b = launch_heat_cool<-1, false>(ctx, m, N, C, codes, xp, nullptr);
     return b < 0 ? b : HCLAE_OK;
 }
@@ -390,8 +437,9 @@ int hclae_assign(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, const
 {
     int rc = check_call(ctx, N, D, M, K);
     if (rc != HCLAE_OK) return rc;
-    if (m < 0 || m >= M || !C || !codes || !xp) return fail(ctx, HCLAE_EINVAL, "hclae_assign: bad argument");
+    if (m < 0 || m >= M) return fail(ctx, HCLAE_EINVAL, "hclae_assign: m out of range");
     if (N == 0) return HCLAE_OK;
+    if (!C || !codes || !xp) return fail(ctx, HCLAE_EINVAL, "hclae_assign: NULL pointer");
     const float *Cm = C + (size_t)m * K * D;
     if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
     if ((rc = launch_assign(ctx, m, N, xp, Cm, codes)) != HCLAE_OK) return rc;
@@ -408,7 +456,8 @@ int hclae_update(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, float
 {
     int rc = check_call(ctx, N, D, M, K);
     if (rc != HCLAE_OK) return rc;
-    if (m < 0 || m >= M || !C || !codes || !xp) return fail(ctx, HCLAE_EINVAL, "hclae_update: bad argument");
+    if (m < 0 || m >= M) return fail(ctx, HCLAE_EINVAL, "hclae_update: m out of range");
+    if (N > 0 && (!C || !codes || !xp)) return fail(ctx, HCLAE_EINVAL, "hclae_update: NULL pointer");
     if (N == 0) {
         if (counts) HIP_TRY(ctx, hipMemsetAsync(counts, 0, sizeof(int32_t) * K, ctx->stream));
         return HCLAE_OK;
@@ -439,8 +488,8 @@ int hclae_encode(hclae_ctx *ctx, const float *X, int64_t N, int D,
 {
     int rc = check_call(ctx, N, D, M, K);
     if (rc != HCLAE_OK) return rc;
-    if (!X || !C || !codes || !residue || X == residue) return fail(ctx, HCLAE_EINVAL, "hclae_encode: bad argument");
     if (N == 0) return HCLAE_OK;
+    if (!X || !C || !codes || !residue || X == residue) return fail(ctx, HCLAE_EINVAL, "hclae_encode: bad argument");
     return enqueue_encode(ctx, X, N, C, codes, residue);
 }
 
@@ -467,7 +516,7 @@ int hclae_anneal_stage(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M,
 {
     int rc = check_call(ctx, N, D, M, K);
     if (rc != HCLAE_OK) return rc;
-    if (m < 0 || m >= M || iters < 0 || !C || !codes || !residue)
+    if (m < 0 || m >= M || iters < 0 || (N > 0 && (!C || !codes || !residue)))
         return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage: bad argument");
     if (init_idx && check_init_idx(init_idx, K, N) != HCLAE_OK)
         return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage: init_idx out of range");
@@ -492,9 +541,9 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
 {
     int rc = check_call(ctx, N, D, M, K);
     if (rc != HCLAE_OK) return rc;
-    if (iters < 0 || !C || !codes || !residue || (reencode_mode != 0 && reencode_mode != 1))
+    if (iters < 0 || (N > 0 && (!C || !codes || !residue)) || (reencode_mode != 0 && reencode_mode != 1))
         return fail(ctx, HCLAE_EINVAL, "hclae_sweep: bad argument");
-    if (reencode_mode == 1 && (!X || X == residue)) return fail(ctx, HCLAE_EINVAL, "hclae_sweep: reencode_mode 1 needs X");
+    if (reencode_mode == 1 && N > 0 && (!X || X == residue)) return fail(ctx, HCLAE_EINVAL, "hclae_sweep: reencode_mode 1 needs X");
     if (init_idx && check_init_idx(init_idx, M * K, N) != HCLAE_OK)
         return fail(ctx, HCLAE_EINVAL, "hclae_sweep: init_idx out of range");
     if (N == 0) {
@@ -521,6 +570,38 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
         if ((rc = fetch_records(ctx, M)) != HCLAE_OK) return rc;
         for (int m = 0; m < M; ++m) err_per_stage[m] = ctx->rec_host[m].sum_after / (double)N;
     }
+    return HCLAE_OK;
+}
+
+int hclae_timing_enable(hclae_ctx *ctx, uint32_t class_mask)
+{
+    if (!ctx) return HCLAE_EINVAL;
+    if (class_mask && !ctx->t_beg) {
+        ctx->t_beg = new (std::nothrow) hipEvent_t[kMaxTimed]();
+        ctx->t_end = new (std::nothrow) hipEvent_t[kMaxTimed]();
+        ctx->t_cls = new (std::nothrow) uint8_t[kMaxTimed]();
+        if (!ctx->t_beg || !ctx->t_end || !ctx->t_cls) return fail(ctx, HCLAE_ENOMEM, "timing pool");
+        for (int i = 0; i < kMaxTimed; ++i) {
+            HIP_TRY(ctx, hipEventCreate(&ctx->t_beg[i]));
+            HIP_TRY(ctx, hipEventCreate(&ctx->t_end[i]));
+        }
+    }
+    ctx->t_mask = class_mask;
+    return HCLAE_OK;
+}
+
+int hclae_timing_read(hclae_ctx *ctx, hclae_kernel_times *out)
+{
+    if (!ctx || !out) return HCLAE_EINVAL;
+    memset(out, 0, sizeof(*out));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    for (int i = 0; i < ctx->t_used; ++i) {
+        float ms = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->t_beg[i], ctx->t_end[i]));
+        out->ms[ctx->t_cls[i]] += (double)ms;
+        out->launches[ctx->t_cls[i]] += 1;
+    }
+    ctx->t_used = 0;
     return HCLAE_OK;
 }
 

@@ -20,7 +20,15 @@ EXPORTS = (
     "hclae_check_shape", "hclae_create", "hclae_destroy", "hclae_last_error",
     "hclae_encode", "hclae_anneal_stage", "hclae_sweep", "hclae_quant_error",
     "hclae_heat", "hclae_cool", "hclae_assign", "hclae_update", "hclae_last_refined",
+    "hclae_timing_enable", "hclae_timing_read",
 )
+
+KERNEL_CLASSES = ("heat", "cool", "assign", "refine", "accumulate", "merge", "norms", "error")
+
+
+class KernelTimes(ctypes.Structure):
+    _fields_ = [("ms", ctypes.c_double * len(KERNEL_CLASSES)),
+                ("launches", ctypes.c_int64 * len(KERNEL_CLASSES))]
 
 
 class StageStats(ctypes.Structure):
@@ -67,6 +75,8 @@ def lib():
     L.hclae_assign.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, vp, vp]
     L.hclae_update.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, vp, vp]
     L.hclae_last_refined.argtypes = [vp, ctypes.POINTER(i64)]
+    L.hclae_timing_enable.argtypes = [vp, ctypes.c_uint32]
+    L.hclae_timing_read.argtypes = [vp, ctypes.POINTER(KernelTimes)]
     for name in EXPORTS:
         if name != "hclae_last_error":
             getattr(L, name).restype = i32
@@ -189,3 +199,16 @@ class Context:
         out = ctypes.c_int64()
         self._chk(lib().hclae_last_refined(self._h, ctypes.byref(out)))
         return out.value
+
+    def timing_enable(self, classes):
+        """classes: iterable of names from KERNEL_CLASSES (empty = off)."""
+        mask = 0
+        for c in classes:
+            mask |= 1 << KERNEL_CLASSES.index(c)
+        self._chk(lib().hclae_timing_enable(self._h, mask))
+
+    def timing_read(self):
+        """{class: (total ms, launches)} since the last read."""
+        kt = KernelTimes()
+        self._chk(lib().hclae_timing_read(self._h, ctypes.byref(kt)))
+        return {c: (kt.ms[i], kt.launches[i]) for i, c in enumerate(KERNEL_CLASSES)}

@@ -1,0 +1,356 @@
+"""GPU-vs-oracle parity of every step of the DA stage (arXiv 1509.05194, Sec. 3.1), through the
+C ABI.  Step-locked: both sides start each step from the same fp32 state.  Bars: codes
+bit-exact outside oracle near-ties (top-2 gap < 1e-5 relative); codebooks, residues and
+quantization error within 1e-4 relative (much tighter bounds are asserted where the
+arithmetic allows)."""
+import numpy as np
+import pytest
+
+from paper_1509_05194_amd import synth
+from parity_util import fresh_state, judge_codes, narrow_state, rel_fro, to_dev
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _ctx(N, D, M, K):
+    from paper_1509_05194_amd import hclae
+    return hclae.Context(N, D, M, K)
+
+
+# shapes: several tiles plus a ragged tail; padded K and D; the D-chunked path (D = 960, 132)
+CASES = {
+    "tiny":    dict(gen="tiny", N=10000, D=16, M=4, K=16, T=2),
+    "sift":    dict(gen="sift", N=20000 + 37, D=128, M=4, K=256, T=2),
+    "odd":     dict(gen="sift", N=1000 + 3, D=36, M=3, K=17, T=2),
+    "k40d132": dict(gen="sift", N=3000 + 1, D=132, M=2, K=40, T=1),
+    "gist":    dict(gen="gist", N=3000 + 5, D=960, M=2, K=256, T=1),
+    "k256d132": dict(gen="sift", N=2000 + 9, D=132, M=2, K=256, T=1),
+}
+_cache = {}
+
+
+def _data(case):
+    c = CASES[case]
+    if c["gen"] == "tiny":
+        return synth.tiny_gmm(N=c["N"], D=c["D"])
+    if c["gen"] == "sift":
+        return synth.sift_like(c["N"], D=c["D"])
+    return synth.gist_like(c["N"], D=c["D"])
+
+
+def _mid_state(case, oracle):
+    """A realistic mid-sweep oracle state: one fresh sweep of T iterations."""
+    if case not in _cache:
+        c = CASES[case]
+        X = _data(case)
+        C, codes, r = fresh_state(X, c["M"], c["K"])
+        idx = synth.init_indices(c["N"], c["M"], c["K"])
+        oracle.sweep(C, codes, r, c["T"], idx)
+        _cache[case] = (X, C, codes, r, idx)
+    X, C, codes, r, idx = _cache[case]
+    return X, C.copy(), codes.copy(), r.copy(), idx
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_heat_and_cool_step(case, oracle):
+    c = CASES[case]
+    X, C, codes, r, _ = _mid_state(case, oracle)
+    ctx = _ctx(c["N"], c["D"], c["M"], c["K"])
+    for m in (0, c["M"] - 1):
+        Cg, codes_g, rg, C64, codes64, r64 = narrow_state(C, codes, r)
+        ctx.heat(m, Cg, codes_g, rg)
+        oracle.heat(r64, codes64, C64, m)
+        # one fp32 add per element: half an ulp of the result
+        got = rg.cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - r64) <= 6.0e-8 * np.abs(r64) + 1e-45)
+        ctx.cool(m, Cg, codes_g, rg)
+        xp64 = got.copy()
+        oracle.cool(xp64, codes64, C64, m)
+        got2 = rg.cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got2 - xp64) <= 6.0e-8 * np.abs(xp64) + 1e-45)
+    ctx.close()
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_assign_step(case, oracle):
+    c = CASES[case]
+    X, C, codes, r, _ = _mid_state(case, oracle)
+    N, M = c["N"], c["M"]
+    ctx = _ctx(N, c["D"], M, c["K"])
+    for m in range(M):
+        Cg, codes_g, rg, C64, codes64, r64 = narrow_state(C, codes, r)
+        oracle.heat(r64, codes64, C64, m)
+        xg = to_dev(r64.astype(np.float32))          # x' as fp32, identical on both sides
+        x64 = r64.astype(np.float32).astype(np.float64)
+        codes_g.fill_(255)
+        codes_g[:, m] = 0
+        dmin = torch.empty(N, dtype=torch.float32, device="cuda:0")
+        ctx.assign(m, xg, Cg, codes_g, dmin)
+        refined = ctx.last_refined()
+        d1, d2, _ = oracle.assign(x64, C64, codes64, m, top2=True)
+        got = codes_g.cpu().numpy()
+        others = [j for j in range(M) if j != m]
+        assert np.all(got[:, others] == 255), "assign wrote outside column m"
+        ndiff, nexempt, bad = judge_codes(oracle, x64, C64, m, got[:, m], codes64[:, m], d1, d2)
+        print("%s m=%d: differ %d, exempt %d, refined %d of %d" % (case, m, ndiff, nexempt, refined, N))
+        assert not bad, "non-exempt code mismatches at %s" % bad[:10]
+        same = got[:, m] == codes64[:, m]
+        dm = dmin.cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(dm[same] - d1[same]) <= 2e-7 * d1[same] + 1e-30)
+    ctx.close()
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_update_step(case, oracle):
+    c = CASES[case]
+    X, C, codes, r, _ = _mid_state(case, oracle)
+    N, M, K = c["N"], c["M"], c["K"]
+    ctx = _ctx(N, c["D"], M, K)
+    m = M - 1
+    Cg, codes_g, rg, C64, codes64, r64 = narrow_state(C, codes, r)
+    oracle.heat(r64, codes64, C64, m)
+    x32 = r64.astype(np.float32)
+    # empty two clusters on purpose: their members move to cluster 0
+    if K > 3:
+        col = codes64[:, m]
+        col[(col == 1) | (col == K - 1)] = 0
+        codes_g = to_dev(codes64)
+    xg = to_dev(x32)
+    C_before = Cg.cpu().numpy().copy()
+    counts = torch.zeros(K, dtype=torch.int32, device="cuda:0")
+    ctx.update(m, xg, Cg, codes_g, counts)
+    x64 = x32.astype(np.float64)
+    cnt_o, empty_o = oracle.update(x64, codes64, C64, m)
+    got = Cg.cpu().numpy()
+    np.testing.assert_array_equal(counts.cpu().numpy().astype(np.int64), cnt_o)
+    for j in range(M):
+        if j != m:
+            np.testing.assert_array_equal(got[j], C_before[j])
+    emp = cnt_o == 0
+    np.testing.assert_array_equal(got[m][emp], C_before[m][emp])       # empty clusters keep their codeword
+    scale = np.linalg.norm(C64[m]) / np.sqrt(K)
+    row_err = np.linalg.norm(got[m].astype(np.float64) - C64[m], axis=1) / scale
+    print("%s update: max row err %.2e (rel. to rms codeword norm), empty %d" % (case, row_err.max(), empty_o))
+    assert row_err.max() <= 1e-5
+    # run-to-run determinism: identical bits
+    Cg2 = to_dev(C_before)
+    ctx.update(m, xg, Cg2, codes_g, None)
+    assert torch.equal(Cg, Cg2)
+    ctx.close()
+
+
+@pytest.mark.parametrize("case", ["tiny", "sift", "gist"])
+def test_quant_error(case, oracle):
+    c = CASES[case]
+    X, C, codes, r, _ = _mid_state(case, oracle)
+    ctx = _ctx(c["N"], c["D"], c["M"], c["K"])
+    r32 = r.astype(np.float32)
+    E = ctx.quant_error(to_dev(r32))
+    Eo = oracle.quant_error(r32.astype(np.float64))
+    assert abs(E - Eo) <= 1e-12 * Eo
+    ctx.close()
+
+
+@pytest.mark.parametrize("case", ["tiny", "sift", "odd", "gist"])
+def test_encode(case, oracle):
+    """Greedy encoding (Eq. 3, L=1).  A vector is followed stage by stage until its first
+    differing code, which must be an exempt near-tie of that stage; later parts of such a
+    vector are not compared (its residue has legitimately changed)."""
+    c = CASES[case]
+    X, C, _, _, _ = _mid_state(case, oracle)
+    N, M, K, D = c["N"], c["M"], c["K"], c["D"]
+    C32 = C.astype(np.float32)
+    C64 = C32.astype(np.float64)
+    ctx = _ctx(N, D, M, K)
+    Xg, Cg = to_dev(X), to_dev(C32)
+    codes_g = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+    rg = torch.empty((N, D), dtype=torch.float32, device="cuda:0")
+    ctx.encode(Xg, Cg, codes_g, rg)
+    got = codes_g.cpu().numpy()
+    r64 = X.astype(np.float64)
+    codes_o = np.zeros((N, M), np.uint8)
+    alive = np.ones(N, bool)
+    n_exempt = 0
+    for m in range(M):
+        d1, d2, _ = oracle.assign(r64, C64, codes_o, m, top2=True)
+        ndiff, nex, bad = judge_codes(oracle, r64, C64, m, np.where(alive, got[:, m], codes_o[:, m]),
+                                      codes_o[:, m], d1, d2)
+        assert not bad, "stage %d: non-exempt mismatches %s" % (m, bad[:10])
+        n_exempt += nex
+        alive &= got[:, m] == codes_o[:, m]
+        oracle.cool(r64, codes_o, C64, m)
+    print("%s encode: exempt %d, compared to the end %d of %d" % (case, n_exempt, alive.sum(), N))
+    res = rg.cpu().numpy().astype(np.float64)
+    scale = np.sqrt((r64 ** 2).sum(1).mean())
+    err = np.linalg.norm(res[alive] - r64[alive], axis=1) / scale
+    assert err.max() <= 1e-5
+    E = ctx.quant_error(rg)
+    assert abs(E - oracle.quant_error(r64)) <= 1e-4 * oracle.quant_error(r64)
+    # x = sum_m C_m[i_m] + r on the GPU's own output
+    recon = oracle.reconstruct(C64, got) + res
+    assert np.abs(recon - X).max() <= 1e-5 * max(np.abs(X).max(), 1.0)
+    ctx.close()
+
+
+def _lockstep_stage(ctx, oracle, m, T, Cg, codes_g, rg, C64, codes64, r64, idx):
+    """Drive one stage step by step on both sides; after each assign the oracle adopts every
+    exempt GPU code so the trajectories stay locked.  Returns the number adopted."""
+    adopted = 0
+    ctx.heat(m, Cg, codes_g, rg)
+    oracle.heat(r64, codes64, C64, m)
+    if idx is not None:
+        Cg[m] = rg[torch.from_numpy(idx).to(rg.device)]        # test-side seeding (buffer copy only)
+        C64[m] = r64[idx]
+    for t in range(T + 1):
+        ctx.assign(m, rg, Cg, codes_g)
+        d1, d2, _ = oracle.assign(r64, C64, codes64, m, top2=True)
+        got = codes_g.cpu().numpy()[:, m]
+        ndiff, nex, bad = judge_codes(oracle, r64, C64, m, got, codes64[:, m], d1, d2)
+        assert not bad, "stage %d assign %d: non-exempt mismatches %s" % (m, t, bad[:10])
+        adopted += nex
+        codes64[:, m] = got
+        if t < T:
+            ctx.update(m, rg, Cg, codes_g)
+            oracle.update(r64, codes64, C64, m)
+            assert rel_fro(Cg[m].cpu().numpy(), C64[m]) <= 1e-5
+    ctx.cool(m, Cg, codes_g, rg)
+    oracle.cool(r64, codes64, C64, m)
+    return adopted
+
+
+@pytest.mark.parametrize("case", ["tiny", "sift"])
+def test_lockstep_sweeps(case, oracle):
+    """Fresh sweep then an annealing sweep, free-running on the GPU state, with tie adoption."""
+    c = CASES[case]
+    N, D, M, K, T = c["N"], c["D"], c["M"], c["K"], 3
+    X = _data(case)
+    idx = synth.init_indices(N, M, K)
+    ctx = _ctx(N, D, M, K)
+    C64, codes64, r64 = fresh_state(X, M, K)
+    Cg = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+    codes_g = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+    rg = to_dev(X)
+    adopted = 0
+    for sweep in range(2):
+        for m in range(M):
+            adopted += _lockstep_stage(ctx, oracle, m, T, Cg, codes_g, rg, C64, codes64, r64,
+                                       idx[m] if sweep == 0 else None)
+            Eg, Eo = ctx.quant_error(rg), oracle.quant_error(r64)
+            assert abs(Eg - Eo) <= 1e-4 * Eo
+            assert rel_fro(rg.cpu().numpy(), r64) <= 1e-4
+    print("%s lockstep: adopted %d near-ties over %d assigns" % (case, adopted, 2 * M * (T + 1)))
+    assert rel_fro(Cg.cpu().numpy(), C64) <= 1e-4
+    ctx.close()
+
+
+def test_free_running_sweeps_tiny(oracle):
+    """Three hclae_sweep calls on config-1 data (10,000 x 16, M=4, K=16) against the oracle's."""
+    c = CASES["tiny"]
+    N, D, M, K, T = c["N"], c["D"], c["M"], c["K"], 10
+    X = _data("tiny")
+    idx = synth.init_indices(N, M, K)
+    ctx = _ctx(N, D, M, K)
+    C64, codes64, r64 = fresh_state(X, M, K)
+    Cg = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+    codes_g = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+    rg = to_dev(X)
+    prev = None
+    for s in range(3):
+        Eo = oracle.sweep(C64, codes64, r64, T, idx if s == 0 else None)
+        Eg = ctx.sweep(Cg, codes_g, rg, T, init_idx=idx if s == 0 else None)
+        mism = float((codes_g.cpu().numpy() != codes64).mean())
+        print("sweep %d: E gpu %s oracle %s, code mismatch %.2e, C err %.2e"
+              % (s, Eg, Eo, mism, rel_fro(Cg.cpu().numpy(), C64)))
+        np.testing.assert_allclose(Eg, Eo, rtol=1e-4)
+        assert np.all(np.diff(Eg) <= 0) and (prev is None or Eg[0] <= prev * (1 + 1e-6))
+        prev = Eg[-1]
+        if mism == 0.0:
+            assert rel_fro(Cg.cpu().numpy(), C64) <= 1e-4
+            assert rel_fro(rg.cpu().numpy(), r64) <= 1e-4
+    ctx.close()
+
+
+def test_stage_stats_and_reencode_mode(oracle):
+    c = CASES["tiny"]
+    N, D, M, K = c["N"], c["D"], c["M"], c["K"]
+    X, C, codes, r, _ = _mid_state("tiny", oracle)
+    ctx = _ctx(N, D, M, K)
+    Cg, codes_g, rg, C64, codes64, r64 = narrow_state(C, codes, r)
+    before = codes_g.clone()
+    E0 = oracle.quant_error(r64)
+    st = ctx.anneal_stage(1, Cg, codes_g, rg, 2)
+    E1 = oracle.anneal_stage(1, C64, codes64, r64, 2)
+    assert abs(st["err_before"] - E0) <= 1e-6 * E0 and abs(st["err_after"] - E1) <= 1e-4 * E1
+    assert st["iters_run"] == 2 and st["empty_clusters"] == 0
+    assert st["codes_changed"] == int((codes_g[:, 1] != before[:, 1]).sum())
+    assert st["err_after"] <= st["err_before"]
+    # reencode_mode 1: state after the sweep is the greedy encoding of X under the final C
+    Xg = to_dev(X)
+    ctx.sweep(Cg, codes_g, rg, 1, X=Xg, reencode_mode=1)
+    codes2 = torch.zeros_like(codes_g)
+    r2 = torch.empty_like(rg)
+    ctx.encode(Xg, Cg, codes2, r2)
+    assert torch.equal(codes2, codes_g) and torch.equal(r2, rg)
+    ctx.close()
+
+
+def test_exact_integer_regime(oracle):
+    """Integer-valued data in [0,255] with codewords that are data rows: every product and
+    partial sum of the first assignment is an integer below 2^24, so fp32 is exact and the
+    codes must equal the oracle's with no exemption, exact ties included."""
+    N, D, K = 50000 + 11, 128, 256
+    X = synth.sift_like(N, D=D)
+    X[1000:1200] = X[:200]                    # exact duplicates of other rows
+    idx = synth.init_indices(N, 1, K)[0]
+    idx[5] = 1003                             # two seeds that are duplicates of each other: an exact tie
+    idx[200] = 3
+    ctx = _ctx(N, D, 1, K)
+    C32 = X[idx][None].copy()
+    Cg, xg = to_dev(C32), to_dev(X)
+    codes_g = torch.zeros((N, 1), dtype=torch.uint8, device="cuda:0")
+    ctx.assign(0, xg, Cg, codes_g)
+    codes_o = np.zeros((N, 1), np.uint8)
+    oracle.assign(X.astype(np.float64), C32.astype(np.float64), codes_o, 0)
+    np.testing.assert_array_equal(codes_g.cpu().numpy(), codes_o)
+    assert codes_o[1003, 0] == 5 and codes_o[3, 0] == 5      # the tie went to the lower index
+    ctx.close()
+
+
+def test_degenerate_shapes(oracle):
+    """K = 1, M = 1, N below one tile, N = 0, all-zero dictionaries (every score ties)."""
+    from paper_1509_05194_amd import hclae
+    # K = 1
+    X = synth.tiny_gmm(N=500, D=16)
+    ctx = _ctx(500, 16, 2, 1)
+    Cg = torch.zeros((2, 1, 16), dtype=torch.float32, device="cuda:0")
+    codes_g = torch.zeros((500, 2), dtype=torch.uint8, device="cuda:0")
+    rg = to_dev(X)
+    E = ctx.sweep(Cg, codes_g, rg, 1, init_idx=np.array([[3], [4]], np.int64))
+    mean = X.astype(np.float64).mean(0)
+    assert np.abs(Cg[0, 0].cpu().numpy() - mean).max() <= 1e-6
+    assert abs(E[0] - ((X - mean) ** 2).sum(1).mean()) <= 1e-5 * E[0]
+    assert int(codes_g.max()) == 0
+    # N = 0 is a no-op
+    empty_r = torch.empty((0, 16), dtype=torch.float32, device="cuda:0")
+    assert ctx.quant_error(empty_r) == 0.0
+    ctx.heat(0, Cg, torch.empty((0, 2), dtype=torch.uint8, device="cuda:0"), empty_r)
+    ctx.close()
+    # tiny N, all-zero dictionaries: every codeword ties, lowest index wins
+    for N in (1, 31, 33):
+        X = synth.sift_like(N, D=128)
+        ctx = _ctx(N, 128, 3, 256)
+        Cg = torch.zeros((3, 256, 128), dtype=torch.float32, device="cuda:0")
+        codes_g = torch.full((N, 3), 9, dtype=torch.uint8, device="cuda:0")
+        rg = torch.empty((N, 128), dtype=torch.float32, device="cuda:0")
+        ctx.encode(to_dev(X), Cg, codes_g, rg)
+        assert int(codes_g.max()) == 0 and torch.equal(rg.cpu(), torch.from_numpy(X))
+        ctx.close()
+    # shape mismatch against the ctx, and N beyond N_max
+    ctx = _ctx(100, 16, 2, 4)
+    L = hclae.lib()
+    assert L.hclae_heat(ctx._h, 0, 10, 32, None, 2, 4, None, None) == hclae.ESTATE
+    assert L.hclae_heat(ctx._h, 0, 101, 16, None, 2, 4, None, None) == hclae.ESTATE
+    assert L.hclae_heat(ctx._h, 2, 10, 16, None, 2, 4, None, None) == hclae.EINVAL
+    ctx.close()
