@@ -22,10 +22,12 @@ constexpr int kAssignWaves = kAssignThreads / kWave;
 constexpr int kTileVec = 32;                        // vectors per wave tile (N side of the MFMA)
 constexpr int kChunkD = 64;                         // dims per register-resident chunk of x'
 
-// One entry of the re-check list.
+// One entry of the re-check list: the vector and the bitmap of its candidate codewords in the
+// layout the wave produces it in.  Bit p of word mask[h][i] stands for codeword
+// 64 i + 8 (p >> 2) + 4 h + (p & 3).
 struct RefineItem {
-    uint32_t n;       // vector index
-    uint32_t span;    // lo | hi << 8 | (exactly two candidates) << 16
+    uint32_t n;
+    uint32_t mask[2][4];
 };
 
 // -||c_k||^2 / 2 in fp32 (computed in fp64) for k < K, -inf for the padding rows up to kpad.
@@ -157,35 +159,31 @@ __device__ __forceinline__ void decide(
             if (acc[b][v] >= thr) mk[b >> 1] |= 1u << ((b & 1) * 16 + v);
 
     // bit p of word i is codeword 64 i + 8 (p >> 2) + 4 h + (p & 3): ascending in (i, p)
-    int cnt = 0, lo = 0x7fffffff, hi = -1;
+    int cnt = 0, lo = 0x7fffffff;
 #pragma unroll
-    for (int i = NW - 1; i >= 0; --i)
+    for (int i = NW - 1; i >= 0; --i) {
+        cnt += __popc(mk[i]);
         if (mk[i]) {
             const int p = __ffs(mk[i]) - 1;
             lo = 64 * i + 8 * (p >> 2) + 4 * h + (p & 3);
         }
-#pragma unroll
-    for (int i = 0; i < NW; ++i) {
-        cnt += __popc(mk[i]);
-        if (mk[i]) {
-            const int p = 31 - __clz(mk[i]);
-            hi = 64 * i + 8 * (p >> 2) + 4 * h + (p & 3);
-        }
     }
     cnt += __shfl_xor(cnt, 32, kWave);
     lo = min(lo, __shfl_xor(lo, 32, kWave));
-    hi = max(hi, __shfl_xor(hi, 32, kWave));
 
+    // provisional code: the lowest candidate (final when it is the only one)
+    unsigned slot = 0;
+    const bool amb = (cnt >= 2) && (n < N);
     if (h == 0 && n < N) {
-        if (cnt == 0) { lo = 0; }                 // only with non-finite input
-        codes[n * M + m] = (uint8_t)lo;
-        if (cnt >= 2) {
-            const unsigned slot = atomicAdd(refine_count, 1u);
-            RefineItem it;
-            it.n = (uint32_t)n;
-            it.span = (uint32_t)lo | ((uint32_t)hi << 8) | ((cnt == 2) ? (1u << 16) : 0u);
-            list[slot] = it;
-        }
+        codes[n * M + m] = (uint8_t)(cnt == 0 ? 0 : lo);     // cnt == 0 only with non-finite input
+        if (amb) slot = atomicAdd(refine_count, 1u);
+    }
+    slot = __shfl(slot, lane & 31, kWave);                    // the h = 1 partner learns the slot
+    if (amb) {
+        RefineItem *it = list + slot;
+        if (h == 0) it->n = (uint32_t)n;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) it->mask[h][i] = (i < NW) ? mk[i] : 0u;
     }
 }
 
@@ -317,34 +315,64 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
 }
 
 // fp64 re-check of the vectors whose fp32 scores were too close to call: direct-form squared
-// distances, candidates in ascending index order, strict '<' (ties keep the lowest index).
-// One wave per list entry; lanes split the D axis.
+// distances summed in ascending dimension order, smallest wins, exact ties go to the lowest
+// index.  A group of 16 lanes takes one list entry and gives each candidate its own lane.
 __global__ __launch_bounds__(256) void k_refine(
     const float *__restrict__ xp, const float *__restrict__ Cm, int D, int M, int m,
     uint8_t *__restrict__ codes, const RefineItem *__restrict__ list,
     const unsigned *__restrict__ refine_count)
 {
-    const int lane = lane_id();
     const unsigned count = *refine_count;
-    const unsigned wpg = gridDim.x * (256 / kWave);
-    for (unsigned i = blockIdx.x * (256 / kWave) + (threadIdx.x >> 6); i < count; i += wpg) {
-        const RefineItem it = list[i];
-        const int lo = it.span & 255, hi = (it.span >> 8) & 255;
-        const int step = (it.span >> 16) & 1 ? (hi - lo) : 1;       // pair: visit lo and hi only
-        const float *x = xp + (size_t)it.n * D;
-        double best = 0.0;
-        int ibest = lo;
-        for (int k = lo; k <= hi; k += step) {
-            const float *c = Cm + (size_t)k * D;
-            double s = 0.0;
-            for (int d = lane; d < D; d += kWave) {
-                const double t = (double)x[d] - (double)c[d];
-                s += t * t;
+    const int l16 = threadIdx.x & 15;
+    const unsigned groups = gridDim.x * (256 / 16);
+    const int d4 = D >> 2;
+    for (unsigned e = blockIdx.x * (256 / 16) + (threadIdx.x >> 4); e < count; e += groups) {
+        const RefineItem it = list[e];
+        int total = 0;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) total += __popc(it.mask[w >> 2][w & 3]);
+        const float4 *x = reinterpret_cast<const float4 *>(xp + (size_t)it.n * D);
+        double best = __builtin_inf();
+        int kbest = 0x7fffffff;
+        for (int base = 0; base < total; base += 16) {
+            int j = base + l16;
+            if (j < total) {
+                // codeword of the j-th set bit
+                int k = 0;
+#pragma unroll
+                for (int w = 0; w < 8; ++w) {
+                    uint32_t bits = it.mask[w >> 2][w & 3];
+                    const int c = __popc(bits);
+                    if (j >= 0 && j < c) {
+                        for (int q = 0; q < j; ++q) bits &= bits - 1;
+                        const int p = __ffs(bits) - 1;
+                        k = 64 * (w & 3) + 8 * (p >> 2) + 4 * (w >> 2) + (p & 3);
+                        j = -1;
+                    } else if (j >= 0) {
+                        j -= c;
+                    }
+                }
+                const float4 *c4 = reinterpret_cast<const float4 *>(Cm + (size_t)k * D);
+                double s = 0.0;
+                for (int d = 0; d < d4; ++d) {
+                    const float4 a = x[d], b = c4[d];
+                    const double t0 = (double)a.x - (double)b.x, t1 = (double)a.y - (double)b.y;
+                    const double t2 = (double)a.z - (double)b.z, t3 = (double)a.w - (double)b.w;
+                    s += t0 * t0;
+                    s += t1 * t1;
+                    s += t2 * t2;
+                    s += t3 * t3;
+                }
+                if (s < best || (s == best && k < kbest)) { best = s; kbest = k; }
             }
-            s = wave_sum(s);
-            if (k == lo || s < best) { best = s; ibest = k; }
         }
-        if (lane == 0) codes[(size_t)it.n * M + m] = (uint8_t)ibest;
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) {
+            const double ob = __shfl_xor(best, o, kWave);
+            const int ok = __shfl_xor(kbest, o, kWave);
+            if (ob < best || (ob == best && ok < kbest)) { best = ob; kbest = ok; }
+        }
+        if (l16 == 0) codes[(size_t)it.n * M + m] = (uint8_t)kbest;
     }
 }
 

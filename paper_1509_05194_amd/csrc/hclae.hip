@@ -217,7 +217,7 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
     if (nb > ctx->upd_blocks) nb = ctx->upd_blocks;
     if (nb < 1) nb = 1;
     int64_t rpb = (N + nb - 1) / nb;
-    const size_t lds = ((size_t)kUpdWaves * K * kUpdSlice + K) * sizeof(float);
+    const size_t lds = ((size_t)K * kUpdWindow + K) * sizeof(float);
     static bool attr_set = false;
     if (!attr_set) {
         HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_accumulate),
