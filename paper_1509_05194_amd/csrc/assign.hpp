@@ -60,16 +60,26 @@ __device__ __forceinline__ void stage_codebook(
     float4 *lds, const float *__restrict__ Cm, int K, int D, int kb, int S)
 {
     const int total = kb * S * kWave;
-    for (int e = threadIdx.x; e < total; e += blockDim.x) {
-        const int l = e & 63;
-        const int bs = e >> 6;
-        const int s = bs % S;
-        const int b = bs / S;
-        const int row = 32 * b + (l & 31);
-        const int col = 8 * s + 4 * (l >> 5);
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (row < K && col < D) v = *reinterpret_cast<const float4 *>(Cm + (size_t)row * D + col);
-        lds[e] = v;
+    constexpr int U = 8;                                   // gathers in flight per thread
+    for (int e0 = threadIdx.x; e0 < total; e0 += U * blockDim.x) {
+        float4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * blockDim.x;
+            const int l = e & 63;
+            const int bs = e >> 6;
+            const int s = bs % S;
+            const int b = bs / S;
+            const int row = 32 * b + (l & 31);
+            const int col = 8 * s + 4 * (l >> 5);
+            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (e < total && row < K && col < D) v[u] = *reinterpret_cast<const float4 *>(Cm + (size_t)row * D + col);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * blockDim.x;
+            if (e < total) lds[e] = v[u];
+        }
     }
 }
 
@@ -214,9 +224,13 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     for (int k = 0; k < K; ++k) hmax = fmaxf(hmax, -lds_h[k]);
     const float cmax = sqrtf(2.f * hmax) * 1.000001f;
 
+    // Static tile schedule balanced per SIMD: waves w and w + 4 of a block share a SIMD (and its
+    // matrix pipe), so tiles are dealt round-robin to the gridDim.x * 4 SIMD slots and the two
+    // waves of a slot take alternate ones; no SIMD gets more than one tile above the average.
     const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
-    const int64_t tstride = (int64_t)gridDim.x * kAssignWaves;
-    const int64_t t0 = (int64_t)blockIdx.x * kAssignWaves + wave;
+    const int64_t nslots = (int64_t)gridDim.x * 4;
+    const int64_t tstride = 2 * nslots;
+    const int64_t t0 = (int64_t)blockIdx.x * 4 + (wave & 3) + nslots * (wave >> 2);
     if (t0 >= ntiles) return;
     const int64_t my_tiles = (ntiles - t0 + tstride - 1) / tstride;
     const int64_t G = my_tiles * NC;                                // (tile, chunk) steps of this wave

@@ -130,7 +130,7 @@ int launch_heat_cool(hclae_ctx *ctx, int m, int64_t N, const float *C, const uin
 {
     const RowGeom g = row_geom(ctx->D);
     const int rows = kStreamThreads >> g.lcw;
-    const int blocks = stream_blocks(ctx, N, rows);
+    const int blocks = stream_blocks(ctx, N, rows * kStreamUnroll);
     const float *Cm = C + (size_t)m * ctx->K * ctx->D;
     Timed t_(ctx, SIGN > 0 ? HCLAE_T_HEAT : HCLAE_T_COOL);
     hipLaunchKernelGGL((k_heat_cool<SIGN, STATS>), dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
@@ -217,7 +217,7 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
     if (nb > ctx->upd_blocks) nb = ctx->upd_blocks;
     if (nb < 1) nb = 1;
     int64_t rpb = (N + nb - 1) / nb;
-    const size_t lds = ((size_t)K * kUpdWindow + K) * sizeof(float);
+    const size_t lds = upd_lds_bytes(K);
     static bool attr_set = false;
     if (!attr_set) {
         HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_accumulate),

@@ -8,6 +8,9 @@
 namespace hclae {
 
 constexpr int kStreamThreads = 256;
+constexpr int kStreamUnroll = 4;
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // Geometry shared by the streaming kernels: a block is (1 << lcw) column threads by
 // (256 >> lcw) rows; column thread tx walks float4 columns tx, tx + cw, ...
@@ -27,30 +30,56 @@ __global__ __launch_bounds__(kStreamThreads) void k_heat_cool(
     uint8_t *__restrict__ old_codes, double *__restrict__ part_err, long long *__restrict__ part_chg)
 {
     __shared__ double red[kStreamThreads / kWave];
+    constexpr int U = kStreamUnroll;                       // independent rows per thread per pass
     const int cw = 1 << g.lcw;
     const int tx = threadIdx.x & (cw - 1);
     const int ty = threadIdx.x >> g.lcw;
     const int rows = kStreamThreads >> g.lcw;
     double err = 0.0;
     long long chg = 0;
-    for (int64_t n = (int64_t)blockIdx.x * rows + ty; n < N; n += (int64_t)gridDim.x * rows) {
-        const int code = codes[n * M + m];
-        float4 *rn = reinterpret_cast<float4 *>(r + n * D);
-        const float4 *c = reinterpret_cast<const float4 *>(Cm + (size_t)code * D);
+    for (int64_t n0 = (int64_t)blockIdx.x * rows * U + ty; n0 < N; n0 += (int64_t)gridDim.x * rows * U) {
+        int code[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t n = n0 + (int64_t)u * rows;
+            ok[u] = n < N;
+            code[u] = ok[u] ? (int)codes[n * M + m] : 0;
+        }
         if (STATS && tx == 0) {
-            if (SIGN > 0) old_codes[n] = (uint8_t)code;
-            else chg += (old_codes[n] != (uint8_t)code);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t n = n0 + (int64_t)u * rows;
+                if (ok[u]) {
+                    if (SIGN > 0) old_codes[n] = (uint8_t)code[u];
+                    else chg += (old_codes[n] != (uint8_t)code[u]);
+                }
+            }
         }
         for (int j = tx; j < g.d4; j += cw) {
-            float4 v = rn[j];
-            const float4 cv = c[j];
-            if (STATS && SIGN > 0)
-                err += (double)v.x * v.x + (double)v.y * v.y + (double)v.z * v.z + (double)v.w * v.w;
-            if (SIGN > 0) { v.x += cv.x; v.y += cv.y; v.z += cv.z; v.w += cv.w; }
-            else          { v.x -= cv.x; v.y -= cv.y; v.z -= cv.z; v.w -= cv.w; }
-            if (STATS && SIGN < 0)
-                err += (double)v.x * v.x + (double)v.y * v.y + (double)v.z * v.z + (double)v.w * v.w;
-            rn[j] = v;
+            floatx4 v[U], cv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t n = n0 + (int64_t)u * rows;
+                if (ok[u]) {
+                    v[u] = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(r + n * D) + j);
+                    cv[u] = *(reinterpret_cast<const floatx4 *>(Cm + (size_t)code[u] * D) + j);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t n = n0 + (int64_t)u * rows;
+                if (ok[u]) {
+                    floatx4 w = v[u];
+                    if (STATS && SIGN > 0)
+                        err += (double)w.x * w.x + (double)w.y * w.y + (double)w.z * w.z + (double)w.w * w.w;
+                    if (SIGN > 0) w = w + cv[u];
+                    else w = w - cv[u];
+                    if (STATS && SIGN < 0)
+                        err += (double)w.x * w.x + (double)w.y * w.y + (double)w.z * w.z + (double)w.w * w.w;
+                    __builtin_nontemporal_store(w, reinterpret_cast<floatx4 *>(r + n * D) + j);
+                }
+            }
         }
     }
     if (STATS) {

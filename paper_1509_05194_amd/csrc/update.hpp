@@ -3,12 +3,13 @@
 //
 // HBM-bound segmented sum without floating-point atomics.  Every block owns a contiguous range
 // of vectors and a window of 128 dims, with one K x 128 accumulator in LDS.  Wave w of the block
-// owns the codewords k with k % 8 == w: it scans the codes of the range, fetches only the rows
-// assigned to its codewords (one whole 512-byte row per load) and adds them to the LDS
-// accumulator with a plain read-add-write.  No two waves ever touch the same accumulator row and
-// a wave adds its rows in ascending vector order, so the sums are independent of timing: two
-// runs give identical bits.  Block partials go to scratch; a second kernel merges them in
-// fp64 in block order, divides, and refreshes the codeword norms.
+// owns the codewords k with k % 8 == w.  The range is taken in segments of 4096 rows: the block
+// first sorts the segment's rows by owner (a stable counting sort on the codes, in LDS), then
+// every wave streams its own rows -- one whole 512-byte row per load, two chunks of 8 loads in
+// flight -- and adds them to its accumulator rows with a plain LDS read-add-write.  No two waves
+// ever touch the same accumulator row and a wave adds its rows in ascending vector order, so the
+// sums do not depend on timing: two runs give identical bits.  Block partials go to scratch; a
+// second kernel merges them in fp64 in block order, divides, and refreshes the codeword norms.
 #pragma once
 #include "common.hpp"
 
@@ -17,7 +18,18 @@ namespace hclae {
 constexpr int kUpdThreads = 512;
 constexpr int kUpdWaves = kUpdThreads / kWave;      // 8 owners of codeword classes k % 8
 constexpr int kUpdWindow = 128;                     // dims per block: two per lane
-constexpr int kUpdDepth = 8;                        // row loads a wave keeps in flight
+constexpr int kUpdDepth = 8;                        // rows per chunk of loads
+constexpr int kUpdSeg = 4096;                       // rows per segment (16-bit row index, 64 batches)
+constexpr uint32_t kUpdNone = 0xffffffffu;
+
+// LDS bytes of k_accumulate for K codewords.
+constexpr size_t upd_lds_bytes(int K)
+{
+    return (size_t)K * kUpdWindow * sizeof(float)             // accumulator
+           + (size_t)kUpdSeg * sizeof(uint32_t)               // row list of a segment
+           + (size_t)(kUpdSeg / kWave) * kUpdWaves * sizeof(int)   // per batch, per owner offsets
+           + 2 * kUpdWaves * sizeof(int);                     // owner bases and totals
+}
 
 // grid: (vector ranges, D windows).  partial: float [gridDim.x][K][D]; pcount: int [gridDim.x][K].
 __global__ __launch_bounds__(kUpdThreads) void k_accumulate(
@@ -27,61 +39,150 @@ __global__ __launch_bounds__(kUpdThreads) void k_accumulate(
 {
     extern __shared__ float4 smem4[];
     float *acc = reinterpret_cast<float *>(smem4);                   // [K][128]
-    int *cnt = reinterpret_cast<int *>(acc + K * kUpdWindow);        // [K]
+    uint32_t *list = reinterpret_cast<uint32_t *>(acc + K * kUpdWindow);          // [kUpdSeg]: row | code << 16
+    int *boff = reinterpret_cast<int *>(list + kUpdSeg);             // [64 batches][8 owners]
+    int *wbase = boff + (kUpdSeg / kWave) * kUpdWaves;               // [8]
+    int *wtotal = wbase + kUpdWaves;                                 // [8]
     const int lane = lane_id();
     const int wave = threadIdx.x >> 6;
     const int d0 = blockIdx.y * kUpdWindow + 2 * lane;               // this lane's two dims
     const bool live = d0 < D;                                        // D % 4 == 0: both or neither
 
-    for (int e = threadIdx.x; e < K * kUpdWindow + K; e += kUpdThreads) acc[e] = 0.f;   // cnt too (bit pattern 0)
-    __syncthreads();
+    for (int e = threadIdx.x; e < K * kUpdWindow / 4; e += kUpdThreads) smem4[e] = make_float4(0.f, 0.f, 0.f, 0.f);
 
     float2 *mine = reinterpret_cast<float2 *>(acc) + lane;
     const int64_t row0 = (int64_t)blockIdx.x * rows_per_block;
     int64_t row1 = row0 + rows_per_block;
     if (row1 > N) row1 = N;
-    for (int64_t base = row0; base < row1; base += kWave) {
-        const int64_t n = base + lane;
-        const int code = (n < row1) ? (int)codes[n * M + m] : -1;
-        unsigned long long todo = __ballot(code >= 0 && (code & (kUpdWaves - 1)) == wave);
-        while (todo) {
-            float2 v[kUpdDepth];
-            int c[kUpdDepth];
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    int own_cnt = 0;                                                 // members of codeword 8 * lane + wave (lane < 32)
+
+    for (int64_t seg0 = row0; seg0 < row1; seg0 += kUpdSeg) {
+        const int segn = (int)((row1 - seg0 < kUpdSeg) ? (row1 - seg0) : kUpdSeg);
+        const int nbatch = (segn + kWave - 1) / kWave;
+        // ---- stable counting sort of the segment's rows by owner wave ----
+        int mycode[kUpdWaves];
 #pragma unroll
-            for (int u = 0; u < kUpdDepth; ++u) {
-                c[u] = -1;
-                if (todo) {
-                    const int bit = __builtin_ctzll(todo);
-                    todo &= todo - 1;
-                    c[u] = __builtin_amdgcn_readlane(code, bit);
-                    v[u] = live ? *reinterpret_cast<const float2 *>(xp + (base + bit) * D + d0) : make_float2(0.f, 0.f);
+        for (int i = 0; i < kUpdWaves; ++i) {
+            const int b = wave + kUpdWaves * i;
+            const int rloc = b * kWave + lane;
+            mycode[i] = (rloc < segn) ? (int)codes[(seg0 + rloc) * M + m] : -1;
+        }
+#pragma unroll
+        for (int i = 0; i < kUpdWaves; ++i) {
+            const int b = wave + kUpdWaves * i;
+            if (b < nbatch) {
+                int mine_cnt = 0;
+#pragma unroll
+                for (int w = 0; w < kUpdWaves; ++w) {
+                    const unsigned long long mk = __ballot(mycode[i] >= 0 && (mycode[i] & (kUpdWaves - 1)) == w);
+                    if (lane == w) mine_cnt = __popcll(mk);
                 }
+                if (lane < kUpdWaves) boff[b * kUpdWaves + lane] = mine_cnt;
             }
+        }
+        __syncthreads();
+        if (threadIdx.x < kUpdWaves) {
+            int run = 0;
+            for (int b = 0; b < nbatch; ++b) {
+                const int t = boff[b * kUpdWaves + threadIdx.x];
+                boff[b * kUpdWaves + threadIdx.x] = run;
+                run += t;
+            }
+            wtotal[threadIdx.x] = run;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int run = 0;
+            for (int w = 0; w < kUpdWaves; ++w) { wbase[w] = run; run += wtotal[w]; }
+        }
+        __syncthreads();
 #pragma unroll
-            for (int u = 0; u < kUpdDepth; ++u) {
-                if (c[u] >= 0) {
-                    float2 *a = mine + c[u] * (kUpdWindow / 2);
-                    float2 t = *a;
-                    t.x += v[u].x;
-                    t.y += v[u].y;
-                    *a = t;
-                    if (lane == 0) cnt[c[u]] += 1;
+        for (int i = 0; i < kUpdWaves; ++i) {
+            const int b = wave + kUpdWaves * i;
+            if (b < nbatch) {
+                const int own = mycode[i] & (kUpdWaves - 1);
+#pragma unroll
+                for (int w = 0; w < kUpdWaves; ++w) {
+                    const unsigned long long mk = __ballot(mycode[i] >= 0 && own == w);
+                    if (mycode[i] >= 0 && own == w)
+                        list[wbase[w] + boff[b * kUpdWaves + w] + __popcll(mk & lt)] =
+                            (uint32_t)(b * kWave + lane) | ((uint32_t)mycode[i] << 16);
                 }
             }
         }
+        __syncthreads();
+
+        // ---- every wave streams its own rows, two chunks of loads in flight ----
+        const uint32_t *L = list + wbase[wave];
+        const int n_own = wtotal[wave];
+        const float *seg_x = xp + seg0 * D + d0;
+        float2 va[kUpdDepth], vb[kUpdDepth];
+        uint32_t ea, eb;
+        auto fetch = [&](int i, float2 (&v)[kUpdDepth], uint32_t &e) {
+            e = (lane < kUpdDepth && i + lane < n_own) ? L[i + lane] : kUpdNone;
+#pragma unroll
+            for (int u = 0; u < kUpdDepth; ++u) {
+                const uint32_t ent = __builtin_amdgcn_readlane(e, u);
+                v[u] = make_float2(0.f, 0.f);
+                if (ent != kUpdNone && live)
+                    v[u] = *reinterpret_cast<const float2 *>(seg_x + (size_t)(ent & 0xffffu) * D);
+            }
+        };
+        auto rmw1 = [&](int c, const float2 &v) {
+            float2 *a = mine + c * (kUpdWindow / 2);
+            float2 t = *a;
+            t.x += v.x;
+            t.y += v.y;
+            *a = t;
+        };
+        auto apply = [&](const float2 (&v)[kUpdDepth], uint32_t e) {
+#pragma unroll
+            for (int u = 0; u < kUpdDepth; u += 2) {
+                const uint32_t e0 = __builtin_amdgcn_readlane(e, u);
+                const uint32_t e1 = __builtin_amdgcn_readlane(e, u + 1);
+                if (e0 == kUpdNone) break;
+                const int c0 = (int)(e0 >> 16);
+                own_cnt += (lane == (c0 >> 3));
+                if (e1 == kUpdNone) { rmw1(c0, v[u]); break; }
+                const int c1 = (int)(e1 >> 16);
+                own_cnt += (lane == (c1 >> 3));
+                if (c0 != c1) {
+                    // distinct accumulator rows: overlap the two LDS round trips
+                    float2 *a0 = mine + c0 * (kUpdWindow / 2);
+                    float2 *a1 = mine + c1 * (kUpdWindow / 2);
+                    float2 t0 = *a0, t1 = *a1;
+                    t0.x += v[u].x; t0.y += v[u].y;
+                    t1.x += v[u + 1].x; t1.y += v[u + 1].y;
+                    *a0 = t0;
+                    *a1 = t1;
+                } else {
+                    rmw1(c0, v[u]);
+                    rmw1(c1, v[u + 1]);
+                }
+            }
+        };
+        fetch(0, va, ea);
+        for (int i = 0; i < n_own; i += 2 * kUpdDepth) {
+            fetch(i + kUpdDepth, vb, eb);
+            apply(va, ea);
+            fetch(i + 2 * kUpdDepth, va, ea);
+            apply(vb, eb);
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     // partial[blockIdx.x][k][window dims]
     float *out = partial + (size_t)blockIdx.x * K * D;
     const int wd = min(kUpdWindow, D - blockIdx.y * kUpdWindow);     // live dims of this window
-    for (int e = threadIdx.x; e < K * kUpdWindow; e += kUpdThreads) {
-        const int k = e / kUpdWindow;
-        const int d = e - k * kUpdWindow;
-        if (d < wd) out[(size_t)k * D + blockIdx.y * kUpdWindow + d] = acc[e];
+    for (int e = threadIdx.x; e < K * (kUpdWindow / 4); e += kUpdThreads) {
+        const int k = e / (kUpdWindow / 4);
+        const int d = 4 * (e - k * (kUpdWindow / 4));
+        if (d < wd)
+            *reinterpret_cast<float4 *>(out + (size_t)k * D + blockIdx.y * kUpdWindow + d) = smem4[e];
     }
-    if (blockIdx.y == 0)
-        for (int k = threadIdx.x; k < K; k += kUpdThreads) pcount[blockIdx.x * K + k] = cnt[k];
+    if (blockIdx.y == 0 && lane < 32 && kUpdWaves * lane + wave < K)
+        pcount[blockIdx.x * K + kUpdWaves * lane + wave] = own_cnt;
 }
 
 // One block per codeword k: n_k = sum_b pcount[b][k];  C_m[k][d] = (sum_b partial[b][k][d]) / n_k,
