@@ -17,7 +17,7 @@ using namespace hclae;
 
 namespace {
 
-constexpr int kMaxParts = 4096;          // upper bound on blocks of a streaming pass
+constexpr int kFlatParts = 4096;         // upper bound on blocks of a flat (copy / reduction) pass
 constexpr int kLdsBudget = 160 * 1024;   // LDS per workgroup on gfx950
 constexpr int kMaxTimed = 4096;          // event pairs kept between two hclae_timing_read calls
 
@@ -43,8 +43,9 @@ struct hclae_ctx {
     int *pcount;             // [upd_blocks][K]
     int *nk;                 // [K]
     int64_t *seed_idx;       // [K]
-    double *part_a, *part_b; // [kMaxParts]
-    long long *part_chg;     // [kMaxParts]
+    double *part_a, *part_b; // [nparts]
+    long long *part_chg;     // [nparts]
+    int nparts;              // max(kFlatParts, heat/cool blocks at N_max)
     StageRecord *rec;        // [M]
     // host
     StageRecord *rec_host;   // pinned [M]
@@ -106,10 +107,24 @@ int stream_blocks(const hclae_ctx *ctx, int64_t work_items, int per_block)
 {
     int64_t need = (work_items + per_block - 1) / per_block;
     int64_t cap = (int64_t)ctx->cus * 8;
-    if (cap > kMaxParts) cap = kMaxParts;
+    if (cap > kFlatParts) cap = kFlatParts;
     if (need > cap) need = cap;
     if (need < 1) need = 1;
     return (int)need;
+}
+
+RowGeom row_geom(int D);
+
+// Blocks of a heat / cool pass over N rows (also the number of partial sums it writes):
+// 32 per CU measured best for the in-place read-modify-write stream, each looping a few times.
+int heat_cool_blocks(int64_t N, int D, int cus)
+{
+    const RowGeom g = row_geom(D);
+    const int64_t per = (int64_t)(kStreamThreads >> g.lcw) * kStreamUnroll;
+    int64_t b = (N + per - 1) / per;
+    if (b > (int64_t)cus * 32) b = (int64_t)cus * 32;
+    if (b < 1) b = 1;
+    return (int)b;
 }
 
 RowGeom row_geom(int D)
@@ -130,7 +145,8 @@ int launch_heat_cool(hclae_ctx *ctx, int m, int64_t N, const float *C, const uin
 {
     const RowGeom g = row_geom(ctx->D);
     const int rows = kStreamThreads >> g.lcw;
-    const int blocks = stream_blocks(ctx, N, rows * kStreamUnroll);
+    const int blocks = heat_cool_blocks(N, ctx->D, ctx->cus);
+    (void)rows;
     const float *Cm = C + (size_t)m * ctx->K * ctx->D;
     Timed t_(ctx, SIGN > 0 ? HCLAE_T_HEAT : HCLAE_T_COOL);
     hipLaunchKernelGGL((k_heat_cool<SIGN, STATS>), dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
@@ -240,9 +256,9 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
 int launch_sqnorm(hclae_ctx *ctx, const float *r, int64_t N, double *part)
 {
     const int64_t n4 = N * (ctx->D / 4);
-    const int blocks = stream_blocks(ctx, n4, kStreamThreads * 4);
+    const int blocks = stream_blocks(ctx, n4, kFlatThreads * 4);
     Timed t_(ctx, HCLAE_T_ERROR);
-    hipLaunchKernelGGL(k_sqnorm, dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
+    hipLaunchKernelGGL(k_sqnorm, dim3(blocks), dim3(kFlatThreads), 0, ctx->stream,
                        reinterpret_cast<const float4 *>(r), n4, part);
     HIP_TRY(ctx, hipGetLastError());
     return blocks;
@@ -271,7 +287,7 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
     if ((rc = launch_assign(ctx, m, N, residue, Cm, codes)) != HCLAE_OK) return rc;
     const int pa = launch_heat_cool<-1, true>(ctx, m, N, C, codes, residue, ctx->part_b);
     if (pa < 0) return pa;
-    hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kStreamThreads), 0, ctx->stream,
+    hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFlatThreads), 0, ctx->stream,
                        ctx->part_a, ctx->part_b, ctx->part_chg, pa, iters > 0 ? ctx->nk : nullptr, K,
                        ctx->refine_count, ctx->rec + slot);
     HIP_TRY(ctx, hipGetLastError());
@@ -283,7 +299,7 @@ int enqueue_encode(hclae_ctx *ctx, const float *X, int64_t N, const float *C, ui
     const int D = ctx->D, K = ctx->K;
     const int64_t n4 = N * (D / 4);
     int rc;
-    hipLaunchKernelGGL(k_copy, dim3(stream_blocks(ctx, n4, kStreamThreads * 4)), dim3(kStreamThreads), 0, ctx->stream,
+    hipLaunchKernelGGL(k_copy, dim3(stream_blocks(ctx, n4, kFlatThreads * 4)), dim3(kFlatThreads), 0, ctx->stream,
                        reinterpret_cast<float4 *>(residue), reinterpret_cast<const float4 *>(X), n4);
     HIP_TRY(ctx, hipGetLastError());
     for (int m = 0; m < ctx->M; ++m) {
@@ -351,6 +367,9 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
     while (ub > 8 && per * ub > ((size_t)256 << 20)) ub /= 2;
     ctx->upd_blocks = ub;
 
+    ctx->nparts = heat_cool_blocks(N_max, D, ctx->cus);
+    if (ctx->nparts < kFlatParts) ctx->nparts = kFlatParts;
+
     struct { void **p; size_t bytes; } allocs[] = {
         {(void **)&ctx->hneg, sizeof(float) * 32 * ctx->kb},
         {(void **)&ctx->refine_count, 256},
@@ -360,9 +379,9 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
         {(void **)&ctx->pcount, sizeof(int) * (size_t)K * ub},
         {(void **)&ctx->nk, sizeof(int) * K},
         {(void **)&ctx->seed_idx, sizeof(int64_t) * K},
-        {(void **)&ctx->part_a, sizeof(double) * kMaxParts},
-        {(void **)&ctx->part_b, sizeof(double) * kMaxParts},
-        {(void **)&ctx->part_chg, sizeof(long long) * kMaxParts},
+        {(void **)&ctx->part_a, sizeof(double) * ctx->nparts},
+        {(void **)&ctx->part_b, sizeof(double) * ctx->nparts},
+        {(void **)&ctx->part_chg, sizeof(long long) * ctx->nparts},
         {(void **)&ctx->rec, sizeof(StageRecord) * M},
     };
     for (auto &a : allocs) {
@@ -444,7 +463,7 @@ int hclae_assign(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, const
     if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
     if ((rc = launch_assign(ctx, m, N, xp, Cm, codes)) != HCLAE_OK) return rc;
     if (dmin) {
-        hipLaunchKernelGGL(k_dist_to_code, dim3(stream_blocks(ctx, N, kStreamThreads / kWave)), dim3(kStreamThreads), 0,
+        hipLaunchKernelGGL(k_dist_to_code, dim3(stream_blocks(ctx, N, kFlatThreads / kWave)), dim3(kFlatThreads), 0,
                            ctx->stream, xp, codes, Cm, N, D, M, m, dmin);
         HIP_TRY(ctx, hipGetLastError());
     }
@@ -474,7 +493,7 @@ int hclae_quant_error(hclae_ctx *ctx, const float *residue, int64_t N, int D, do
     if (N == 0) { *out = 0.0; return HCLAE_OK; }
     const int blocks = launch_sqnorm(ctx, residue, N, ctx->part_b);
     if (blocks < 0) return blocks;
-    hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kStreamThreads), 0, ctx->stream,
+    hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFlatThreads), 0, ctx->stream,
                        (const double *)nullptr, ctx->part_b, (const long long *)nullptr, blocks,
                        (const int *)nullptr, 0, (const unsigned *)nullptr, ctx->rec);
     HIP_TRY(ctx, hipGetLastError());
@@ -559,7 +578,7 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
             if (err_per_stage) {
                 const int blocks = launch_sqnorm(ctx, residue, N, ctx->part_b);
                 if (blocks < 0) return blocks;
-                hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kStreamThreads), 0, ctx->stream,
+                hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFlatThreads), 0, ctx->stream,
                                    (const double *)nullptr, ctx->part_b, (const long long *)nullptr, blocks,
                                    (const int *)nullptr, 0, (const unsigned *)nullptr, ctx->rec + m);
                 HIP_TRY(ctx, hipGetLastError());

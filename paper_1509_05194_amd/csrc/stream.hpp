@@ -7,13 +7,13 @@
 
 namespace hclae {
 
-constexpr int kStreamThreads = 256;
+constexpr int kStreamThreads = 256;    // heat / cool
 constexpr int kStreamUnroll = 4;
+constexpr int kFlatThreads = 256;      // flat float4 passes (copy, reduction, finish)
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-// Geometry shared by the streaming kernels: a block is (1 << lcw) column threads by
-// (256 >> lcw) rows; column thread tx walks float4 columns tx, tx + cw, ...
+// Geometry of heat / cool: a block is (1 << lcw) column threads by (kStreamThreads >> lcw) rows; column thread tx walks float4 columns tx, tx + cw, ...
 struct RowGeom {
     int lcw;        // log2 of column threads per row
     int d4;         // D / 4
@@ -94,22 +94,22 @@ __global__ __launch_bounds__(kStreamThreads) void k_heat_cool(
 }
 
 // r <- X (first step of the greedy encoder), one float4 per thread per pass.
-__global__ __launch_bounds__(kStreamThreads) void k_copy(
+__global__ __launch_bounds__(kFlatThreads) void k_copy(
     float4 *__restrict__ dst, const float4 *__restrict__ src, int64_t n4)
 {
-    for (int64_t i = (int64_t)blockIdx.x * kStreamThreads + threadIdx.x; i < n4;
-         i += (int64_t)gridDim.x * kStreamThreads)
+    for (int64_t i = (int64_t)blockIdx.x * kFlatThreads + threadIdx.x; i < n4;
+         i += (int64_t)gridDim.x * kFlatThreads)
         dst[i] = src[i];
 }
 
 // Partial sums of ||e_x||^2 (Eq. 1, first line), fp64 accumulation.
-__global__ __launch_bounds__(kStreamThreads) void k_sqnorm(
+__global__ __launch_bounds__(kFlatThreads) void k_sqnorm(
     const float4 *__restrict__ r, int64_t n4, double *__restrict__ part_err)
 {
-    __shared__ double red[kStreamThreads / kWave];
+    __shared__ double red[kFlatThreads / kWave];
     double err = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * kStreamThreads + threadIdx.x; i < n4;
-         i += (int64_t)gridDim.x * kStreamThreads) {
+    for (int64_t i = (int64_t)blockIdx.x * kFlatThreads + threadIdx.x; i < n4;
+         i += (int64_t)gridDim.x * kFlatThreads) {
         const float4 v = r[i];
         err += (double)v.x * v.x + (double)v.y * v.y + (double)v.z * v.z + (double)v.w * v.w;
     }
@@ -118,12 +118,12 @@ __global__ __launch_bounds__(kStreamThreads) void k_sqnorm(
 }
 
 // dmin_n = ||xp_n - C_m[codes[n][m]]||^2 in the direct form, one wave-row-group per row.
-__global__ __launch_bounds__(kStreamThreads) void k_dist_to_code(
+__global__ __launch_bounds__(kFlatThreads) void k_dist_to_code(
     const float *__restrict__ xp, const uint8_t *__restrict__ codes, const float *__restrict__ Cm,
     int64_t N, int D, int M, int m, float *__restrict__ dmin)
 {
     const int lane = lane_id();
-    const int wpb = kStreamThreads / kWave;
+    const int wpb = kFlatThreads / kWave;
     for (int64_t n = (int64_t)blockIdx.x * wpb + (threadIdx.x >> 6); n < N; n += (int64_t)gridDim.x * wpb) {
         const float *x = xp + n * D;
         const float *c = Cm + (size_t)codes[n * M + m] * D;
@@ -148,21 +148,21 @@ struct StageRecord {
 };
 
 // Final, fixed-order reduction of the per-block partials into a StageRecord (one block).
-__global__ __launch_bounds__(kStreamThreads) void k_finish_stage(
+__global__ __launch_bounds__(kFlatThreads) void k_finish_stage(
     const double *__restrict__ part_before, const double *__restrict__ part_after,
     const long long *__restrict__ part_chg, int nparts,
     const int *__restrict__ nk, int K, const unsigned *__restrict__ refine_count,
     StageRecord *__restrict__ rec)
 {
-    __shared__ double red[kStreamThreads / kWave];
+    __shared__ double red[kFlatThreads / kWave];
     double a = 0.0, b = 0.0, c = 0.0, e = 0.0;
-    for (int i = threadIdx.x; i < nparts; i += kStreamThreads) {
+    for (int i = threadIdx.x; i < nparts; i += kFlatThreads) {
         if (part_before) a += part_before[i];
         if (part_after) b += part_after[i];
         if (part_chg) c += (double)part_chg[i];
     }
     if (nk)
-        for (int k = threadIdx.x; k < K; k += kStreamThreads) e += (nk[k] == 0);
+        for (int k = threadIdx.x; k < K; k += kFlatThreads) e += (nk[k] == 0);
     a = block_sum(a, red);
     b = block_sum(b, red);
     c = block_sum(c, red);

@@ -41,8 +41,7 @@ __global__ __launch_bounds__(kUpdThreads) void k_accumulate(
     float *acc = reinterpret_cast<float *>(smem4);                   // [K][128]
     uint32_t *list = reinterpret_cast<uint32_t *>(acc + K * kUpdWindow);          // [kUpdSeg]: row | code << 16
     int *boff = reinterpret_cast<int *>(list + kUpdSeg);             // [64 batches][8 owners]
-    int *wbase = boff + (kUpdSeg / kWave) * kUpdWaves;               // [8]
-    int *wtotal = wbase + kUpdWaves;                                 // [8]
+    int *wtotal = boff + (kUpdSeg / kWave) * kUpdWaves;              // [8]
     const int lane = lane_id();
     const int wave = threadIdx.x >> 6;
     const int d0 = blockIdx.y * kUpdWindow + 2 * lane;               // this lane's two dims
@@ -82,21 +81,25 @@ __global__ __launch_bounds__(kUpdThreads) void k_accumulate(
             }
         }
         __syncthreads();
-        if (threadIdx.x < kUpdWaves) {
-            int run = 0;
-            for (int b = 0; b < nbatch; ++b) {
-                const int t = boff[b * kUpdWaves + threadIdx.x];
-                boff[b * kUpdWaves + threadIdx.x] = run;
-                run += t;
+        {
+            // wave w turns the per-batch counts of owner w into exclusive offsets (lane = batch)
+            const int c = (lane < nbatch) ? boff[lane * kUpdWaves + wave] : 0;
+            int incl = c;
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const int t = __shfl_up(incl, o, kWave);
+                if (lane >= o) incl += t;
             }
-            wtotal[threadIdx.x] = run;
+            if (lane < nbatch) boff[lane * kUpdWaves + wave] = incl - c;
+            if (lane == kWave - 1) wtotal[wave] = incl;
         }
         __syncthreads();
-        if (threadIdx.x == 0) {
+        int obase[kUpdWaves];                                        // first list slot of every owner
+        {
             int run = 0;
-            for (int w = 0; w < kUpdWaves; ++w) { wbase[w] = run; run += wtotal[w]; }
+#pragma unroll
+            for (int w = 0; w < kUpdWaves; ++w) { obase[w] = run; run += wtotal[w]; }
         }
-        __syncthreads();
 #pragma unroll
         for (int i = 0; i < kUpdWaves; ++i) {
             const int b = wave + kUpdWaves * i;
@@ -106,7 +109,7 @@ __global__ __launch_bounds__(kUpdThreads) void k_accumulate(
                 for (int w = 0; w < kUpdWaves; ++w) {
                     const unsigned long long mk = __ballot(mycode[i] >= 0 && own == w);
                     if (mycode[i] >= 0 && own == w)
-                        list[wbase[w] + boff[b * kUpdWaves + w] + __popcll(mk & lt)] =
+                        list[obase[w] + boff[b * kUpdWaves + w] + __popcll(mk & lt)] =
                             (uint32_t)(b * kWave + lane) | ((uint32_t)mycode[i] << 16);
                 }
             }
@@ -114,7 +117,10 @@ __global__ __launch_bounds__(kUpdThreads) void k_accumulate(
         __syncthreads();
 
         // ---- every wave streams its own rows, two chunks of loads in flight ----
-        const uint32_t *L = list + wbase[wave];
+        int my_base = 0;
+#pragma unroll
+        for (int w = 0; w < kUpdWaves; ++w) my_base = (w == wave) ? obase[w] : my_base;
+        const uint32_t *L = list + my_base;
         const int n_own = wtotal[wave];
         const float *seg_x = xp + seg0 * D + d0;
         float2 va[kUpdDepth], vb[kUpdDepth];
