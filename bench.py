@@ -116,6 +116,7 @@ def main():
         # one more sweep, outside the timed region, with every kernel class bracketed by events
         ctx.timing_enable(hclae.KERNEL_CLASSES)
         ctx.sweep(C, codes, r, T, want_err=False)
+        ctx.quant_error(r)
         ctx.timing_enable([])
         bt = ctx.timing_read()
         alg_bytes = {"heat": N * (8 * D + 1 + 1), "cool": N * (8 * D + 1 + 1), "accumulate": N * (4 * D + 1),

@@ -259,7 +259,7 @@ int launch_sqnorm(hclae_ctx *ctx, const float *r, int64_t N, double *part)
     const int blocks = stream_blocks(ctx, n4, kFlatThreads * 4);
     Timed t_(ctx, HCLAE_T_ERROR);
     hipLaunchKernelGGL(k_sqnorm, dim3(blocks), dim3(kFlatThreads), 0, ctx->stream,
-                       reinterpret_cast<const float4 *>(r), n4, part);
+                       reinterpret_cast<const floatx4 *>(r), n4, part);
     HIP_TRY(ctx, hipGetLastError());
     return blocks;
 }
@@ -300,7 +300,7 @@ int enqueue_encode(hclae_ctx *ctx, const float *X, int64_t N, const float *C, ui
     const int64_t n4 = N * (D / 4);
     int rc;
     hipLaunchKernelGGL(k_copy, dim3(stream_blocks(ctx, n4, kFlatThreads * 4)), dim3(kFlatThreads), 0, ctx->stream,
-                       reinterpret_cast<float4 *>(residue), reinterpret_cast<const float4 *>(X), n4);
+                       reinterpret_cast<floatx4 *>(residue), reinterpret_cast<const floatx4 *>(X), n4);
     HIP_TRY(ctx, hipGetLastError());
     for (int m = 0; m < ctx->M; ++m) {
         const float *Cm = C + (size_t)m * K * D;

@@ -93,25 +93,41 @@ __global__ __launch_bounds__(kStreamThreads) void k_heat_cool(
     }
 }
 
-// r <- X (first step of the greedy encoder), one float4 per thread per pass.
+// r <- X (first step of the greedy encoder): four float4 per thread in flight.
 __global__ __launch_bounds__(kFlatThreads) void k_copy(
-    float4 *__restrict__ dst, const float4 *__restrict__ src, int64_t n4)
+    floatx4 *__restrict__ dst, const floatx4 *__restrict__ src, int64_t n4)
 {
-    for (int64_t i = (int64_t)blockIdx.x * kFlatThreads + threadIdx.x; i < n4;
-         i += (int64_t)gridDim.x * kFlatThreads)
-        dst[i] = src[i];
+    constexpr int U = 4;
+    const int64_t stride = (int64_t)gridDim.x * kFlatThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kFlatThreads + threadIdx.x; i < n4; i += U * stride) {
+        floatx4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (i + u * stride < n4) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (i + u * stride < n4) __builtin_nontemporal_store(v[u], dst + i + u * stride);
+    }
 }
 
-// Partial sums of ||e_x||^2 (Eq. 1, first line), fp64 accumulation.
+// Partial sums of ||e_x||^2 (Eq. 1, first line), fp64 accumulation, four loads in flight.
 __global__ __launch_bounds__(kFlatThreads) void k_sqnorm(
-    const float4 *__restrict__ r, int64_t n4, double *__restrict__ part_err)
+    const floatx4 *__restrict__ r, int64_t n4, double *__restrict__ part_err)
 {
     __shared__ double red[kFlatThreads / kWave];
+    constexpr int U = 4;
+    const int64_t stride = (int64_t)gridDim.x * kFlatThreads;
     double err = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * kFlatThreads + threadIdx.x; i < n4;
-         i += (int64_t)gridDim.x * kFlatThreads) {
-        const float4 v = r[i];
-        err += (double)v.x * v.x + (double)v.y * v.y + (double)v.z * v.z + (double)v.w * v.w;
+    for (int64_t i = (int64_t)blockIdx.x * kFlatThreads + threadIdx.x; i < n4; i += U * stride) {
+        floatx4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            v[u] = (floatx4){0.f, 0.f, 0.f, 0.f};
+            if (i + u * stride < n4) v[u] = __builtin_nontemporal_load(r + i + u * stride);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            err += (double)v[u].x * v[u].x + (double)v[u].y * v[u].y + (double)v[u].z * v[u].z + (double)v[u].w * v[u].w;
     }
     const double e = block_sum(err, red);
     if (threadIdx.x == 0) part_err[blockIdx.x] = e;

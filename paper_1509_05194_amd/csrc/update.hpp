@@ -18,7 +18,7 @@ namespace hclae {
 constexpr int kUpdThreads = 512;
 constexpr int kUpdWaves = kUpdThreads / kWave;      // 8 owners of codeword classes k % 8
 constexpr int kUpdWindow = 128;                     // dims per block: two per lane
-constexpr int kUpdDepth = 8;                        // rows per chunk of loads
+constexpr int kUpdDepth = 16;                       // rows per chunk of loads
 constexpr int kUpdSeg = 4096;                       // rows per segment (16-bit row index, 64 batches)
 constexpr uint32_t kUpdNone = 0xffffffffu;
 
