@@ -17,9 +17,10 @@ import numpy as np
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0             # MI355X HBM3E peak
 
-# HBM bytes per launch of the assign kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
-# scaled by a copy kernel of known size; None until measured (see profiles/).
-ASSIGN_TRAFFIC_BYTES = None
+# HBM bytes per N=1M launch of the assign kernel from two rocprofv3 --pmc runs (FETCH_SIZE 250,678.5 KiB
+# x 2.000, WRITE_SIZE 9,030.9 KiB x 1.000; factors from a 512 MB device copy in the same runs), recorded
+# in profiles/da_sweep_sift1m_counters.md.  Algorithmic bytes are 513e6.
+ASSIGN_TRAFFIC_BYTES = 5.226e8
 
 
 def main():
@@ -108,7 +109,8 @@ def main():
                    "quant_error_after": E_final},
         "roofline": {"bound": "mfma", "kernel": "k_assign_resident<8> (fp32 MFMA distance contraction + argmin)",
                      "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": ASSIGN_TRAFFIC_BYTES,
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                     "traffic": ASSIGN_TRAFFIC_BYTES if (N, D, K) == (1_000_000, 128, 256) else None,
                      "avg_launch_ms": assign_ms, "launches": a_n, "flops_per_launch": flops},
     }
 
