@@ -1,0 +1,121 @@
+"""Parity at the benchmark's full size and launch configuration (N = 1,000,000, D = 128, K = 256):
+sampled outputs are checked one by one against the oracle, the rest through properties that
+hold at any size (reconstruction, plain-definition means and error, non-increasing E)."""
+import numpy as np
+import pytest
+
+from paper_1509_05194_amd import synth
+from parity_util import judge_codes, to_dev
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+N, D, K = 1_000_000, 128, 256
+
+
+@pytest.fixture(scope="module")
+def data():
+    X = synth.sift_like(N, D=D)
+    return X, to_dev(X)
+
+
+def test_fullsize_steps_sampled(data, oracle):
+    from paper_1509_05194_amd import hclae
+    X, Xg = data
+    M = 2
+    idx = synth.init_indices(N, M, K)
+    ctx = hclae.Context(N, D, M, K)
+    C = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+    C[0] = Xg[torch.from_numpy(idx[0]).cuda()]
+    codes = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+    rng = np.random.default_rng(1)
+    sample = np.sort(rng.choice(N, 4096, replace=False))
+    sample[-1] = N - 1                                     # the ragged tail tile
+    xs64 = X[sample].astype(np.float64)
+
+    # --- assign at full N: sampled codes against the oracle, one by one
+    dmin = torch.empty(N, dtype=torch.float32, device="cuda:0")
+    ctx.assign(0, Xg, C, codes, dmin)
+    C64 = C.cpu().numpy().astype(np.float64)
+    codes_s = np.zeros((len(sample), M), np.uint8)
+    d1, d2, _ = oracle.assign(xs64, C64, codes_s, 0, top2=True)
+    got = codes.cpu().numpy()
+    ndiff, nex, bad = judge_codes(oracle, xs64, C64, 0, got[sample, 0], codes_s[:, 0], d1, d2)
+    print("full-size assign: %d of %d sampled codes differ (%d exempt), refined %d" % (ndiff, len(sample), nex, ctx.last_refined()))
+    assert not bad
+    same = got[sample, 0] == codes_s[:, 0]
+    dm = dmin.cpu().numpy()[sample].astype(np.float64)
+    assert np.all(np.abs(dm[same] - d1[same]) <= 2e-7 * d1[same])
+    assert np.all(got[:, 1] == 0)
+
+    # --- centroid update at full N: every codeword against the plain fp64 mean of its members
+    counts = torch.zeros(K, dtype=torch.int32, device="cuda:0")
+    C_before = C.clone()
+    ctx.update(0, Xg, C, codes, counts)
+    col = codes[:, 0].long()
+    ref_cnt = torch.bincount(col, minlength=K)
+    assert torch.equal(ref_cnt.int(), counts)
+    sums = torch.zeros((K, D), dtype=torch.float64, device="cuda:0").index_add_(0, col, Xg.double())
+    ref = torch.where(ref_cnt[:, None] > 0, sums / ref_cnt.clamp(min=1)[:, None].double(), C_before[0].double())
+    err = (C[0].double() - ref).norm(dim=1) / (ref.norm() / K ** 0.5)
+    print("full-size update: max row error %.2e, empty %d" % (err.max().item(), int((ref_cnt == 0).sum())))
+    assert err.max().item() <= 1e-5
+    Cb = C_before.clone()
+    ctx.update(0, Xg, Cb, codes, None)
+    assert torch.equal(Cb, C)                              # bit-reproducible
+
+    # --- cool at full N, sampled rows against the oracle; E against the plain definition
+    r = Xg.clone()
+    ctx.cool(0, C, codes, r)
+    C64 = C.cpu().numpy().astype(np.float64)
+    rs = xs64.copy()
+    codes_s[:, 0] = got[sample, 0]
+    oracle.cool(rs, codes_s, C64, 0)
+    got_r = r[torch.from_numpy(sample).cuda()].cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got_r - rs) <= 6e-8 * np.abs(rs) + 1e-30)
+    E = ctx.quant_error(r)
+    E_ref = (r.double() ** 2).sum().item() / N
+    assert abs(E - E_ref) <= 1e-10 * E_ref
+    ctx.close()
+
+
+def test_fullsize_sweep_properties(data, oracle):
+    """Free-running fresh sweep + annealing sweep at full size (M = 4, T = 2): E never rises,
+    x = sum_m C_m[i_m] + r holds, stats agree with plain definitions, sampled final codes are the
+    oracle's nearest codewords of the GPU's own x'."""
+    from paper_1509_05194_amd import hclae
+    X, Xg = data
+    M, T = 4, 2
+    idx = synth.init_indices(N, M, K)
+    ctx = hclae.Context(N, D, M, K)
+    C = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+    codes = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+    r = Xg.clone()
+    E1 = ctx.sweep(C, codes, r, T, init_idx=idx)
+    E2 = ctx.sweep(C, codes, r, T)
+    allE = np.concatenate([E1, E2])
+    print("full-size E per stage:", allE)
+    assert np.all(np.diff(allE) <= 1e-7 * allE[:-1])
+    recon = r.clone()
+    for m in range(M):
+        recon += C[m][codes[:, m].long()]
+    assert (recon - Xg).abs().max().item() <= 1e-5 * 255.0
+    E_ref = (r.double() ** 2).sum().item() / N
+    assert abs(allE[-1] - E_ref) <= 1e-10 * E_ref
+
+    # one more stage with stats; then sampled codes of that stage against the oracle
+    st = ctx.anneal_stage(1, C, codes, r, T)
+    assert st["err_before"] == pytest.approx(E_ref, rel=1e-10) and st["err_after"] <= st["err_before"]
+    rng = np.random.default_rng(2)
+    sample = np.sort(rng.choice(N, 2048, replace=False))
+    sg = torch.from_numpy(sample).cuda()
+    xp = (r[sg] + C[1][codes[sg, 1].long()]).cpu().numpy().astype(np.float64)     # heat of the sampled rows (one fp32 add)
+    C64 = C.cpu().numpy().astype(np.float64)
+    codes_s = np.zeros((len(sample), M), np.uint8)
+    d1, d2, _ = oracle.assign(xp, C64, codes_s, 1, top2=True)
+    got = codes[sg, 1].cpu().numpy()
+    ndiff, nex, bad = judge_codes(oracle, xp, C64, 1, got, codes_s[:, 1], d1, d2)
+    print("full-size stage: %d of %d sampled codes differ (%d exempt); stats %s" % (ndiff, len(sample), nex, st))
+    # x' here was rebuilt from the rounded residue, so allow the exemption rule only
+    assert not bad
+    ctx.close()
