@@ -31,14 +31,15 @@ struct RefineItem {
 };
 
 // -||c_k||^2 / 2 in fp32 (computed in fp64) for k < K, -inf for the padding rows up to kpad.
-// One wave per codeword.  Also resets the re-check counter for the assign that follows.
+// One wave per codeword.  Also resets the two counters the assign that follows will fill
+// (refine_count[0]: re-check entries, refine_count[1]: bits of max |x'|).
 __global__ __launch_bounds__(256) void k_codeword_norms(
     const float *__restrict__ Cm, int K, int D, int kpad, float *__restrict__ hneg,
     unsigned *__restrict__ refine_count)
 {
     const int lane = lane_id();
     const int k = blockIdx.x * (256 / kWave) + (threadIdx.x >> 6);
-    if (blockIdx.x == 0 && threadIdx.x == 0) *refine_count = 0u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) { refine_count[0] = 0u; refine_count[1] = 0u; }   // re-check count, max |x'| bits
     if (k >= kpad) return;
     if (k >= K) {
         if (lane == 0) hneg[k] = -__builtin_inff();
@@ -95,10 +96,20 @@ __device__ __forceinline__ void load_x_chunk(
     }
 }
 
+// max |x'| over everything the wave has read, merged into *slot (bit pattern of a non-negative
+// float: integer max is float max, and an integer atomic is order-free).  The centroid-sum kernel
+// that follows derives its fixed-point scale from it.
+__device__ __forceinline__ void publish_absmax(float amax, unsigned *slot)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, kWave));
+    if (lane_id() == 0) atomicMax(slot, __float_as_uint(amax));
+}
+
 template <int KB>
 __device__ __forceinline__ void mfma_chunk(
     floatx16 (&acc)[KB], const float4 (&x)[8], const float4 *__restrict__ lds, int q, int S, int lane,
-    float &xsq)
+    float &xsq, float &amax)
 {
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
@@ -110,6 +121,7 @@ __device__ __forceinline__ void mfma_chunk(
         xsq = fmaf(xv.y, xv.y, xsq);
         xsq = fmaf(xv.z, xv.z, xsq);
         xsq = fmaf(xv.w, xv.w, xsq);
+        amax = fmaxf(fmaxf(amax, fmaxf(fabsf(xv.x), fabsf(xv.y))), fmaxf(fabsf(xv.z), fabsf(xv.w)));
 #pragma unroll
         for (int b = 0; b < KB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[b].x, xv.x, acc[b], 0, 0, 0);
 #pragma unroll
@@ -243,7 +255,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
 
     floatx16 acc[KB];
     float4 xa[8], xb[8];
-    float xsq = 0.f;
+    float xsq = 0.f, amax = 0.f;
     int64_t tile = t0;
     int q = 0;
     load_x_chunk(xa, row_ptr(tile), 0, h, D);
@@ -255,7 +267,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
         if (q1 == NC) { q1 = 0; tile1 = tile + tstride; }
         if (g + 1 < G) load_x_chunk(xb, row_ptr(tile1), q1, h, D);
         if (q == 0) { init_acc<KB>(acc, lds_h, h); xsq = 0.f; }
-        mfma_chunk<KB>(acc, xa, lds_c, q, S, lane, xsq);
+        mfma_chunk<KB>(acc, xa, lds_c, q, S, lane, xsq, amax);
         if (q == NC - 1)
             decide<KB>(acc, xsq, eps, hmax, cmax, lane, tile * kTileVec + r, N, M, m, codes, list, refine_count);
         if (g + 1 >= G) break;
@@ -265,12 +277,13 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
         if (q2 == NC) { q2 = 0; tile2 = tile1 + tstride; }
         if (g + 2 < G) load_x_chunk(xa, row_ptr(tile2), q2, h, D);
         if (q1 == 0) { init_acc<KB>(acc, lds_h, h); xsq = 0.f; }
-        mfma_chunk<KB>(acc, xb, lds_c, q1, S, lane, xsq);
+        mfma_chunk<KB>(acc, xb, lds_c, q1, S, lane, xsq, amax);
         if (q1 == NC - 1)
             decide<KB>(acc, xsq, eps, hmax, cmax, lane, tile1 * kTileVec + r, N, M, m, codes, list, refine_count);
         tile = tile2;
         q = q2;
     }
+    publish_absmax(amax, refine_count + 1);
 }
 
 // Assignment for dimensions whose codebook does not fit LDS: the block walks the D axis in
@@ -298,6 +311,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
     const float cmax = sqrtf(2.f * hmax) * 1.000001f;
 
     const int64_t nbt = (N + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);   // block tiles
+    float amax = 0.f;
     for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
         const int64_t n_raw = (bt * kAssignWaves + wave) * kTileVec + r;
         const int64_t n = n_raw < N ? n_raw : N - 1;
@@ -322,10 +336,11 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
                 lds_c[e] = v;
             }
             __syncthreads();
-            mfma_chunk<KB>(acc, x, lds_c, 0, S, lane, xsq);
+            mfma_chunk<KB>(acc, x, lds_c, 0, S, lane, xsq, amax);
         }
         decide<KB>(acc, xsq, eps, hmax, cmax, lane, n_raw, N, M, m, codes, list, refine_count);
     }
+    publish_absmax(amax, refine_count + 1);
 }
 
 // fp64 re-check of the vectors whose fp32 scores were too close to call: direct-form squared

@@ -39,7 +39,7 @@ struct hclae_ctx {
     unsigned *refine_count;
     RefineItem *refine_list; // [N_max]
     uint8_t *old_codes;      // [N_max]
-    float *partial;          // [upd_blocks][K][D]
+    long long *partial;      // [upd_blocks][K][D] fixed-point centroid sums
     int *pcount;             // [upd_blocks][K]
     int *nk;                 // [K]
     int64_t *seed_idx;       // [K]
@@ -224,12 +224,13 @@ int launch_assign(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float
 }
 
 // Accumulate + merge; leaves hneg = norms of the new Cm and the re-check counter at zero.
+// have_absmax: refine_count[1] already holds max |xp| (the assign kernel just ran on the same xp).
 int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, const uint8_t *codes,
-                  int32_t *counts)
+                  int32_t *counts, bool have_absmax)
 {
     const int D = ctx->D, K = ctx->K;
     const int windows = (D + kUpdWindow - 1) / kUpdWindow;
-    int64_t nb = (N + 255) / 256;                     // at least 256 rows per block
+    int64_t nb = (N + 1023) / 1024;                   // at least 1024 rows per block
     if (nb > ctx->upd_blocks) nb = ctx->upd_blocks;
     if (nb < 1) nb = 1;
     int64_t rpb = (N + nb - 1) / nb;
@@ -240,10 +241,17 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
         attr_set = true;
     }
+    if (!have_absmax) {
+        HIP_TRY(ctx, hipMemsetAsync(ctx->refine_count + 1, 0, sizeof(unsigned), ctx->stream));
+        const int64_t n4 = N * (D / 4);
+        hipLaunchKernelGGL(k_absmax, dim3(stream_blocks(ctx, n4, 256 * 4)), dim3(256), 0, ctx->stream,
+                           reinterpret_cast<const float4 *>(xp), n4, ctx->refine_count + 1);
+        HIP_TRY(ctx, hipGetLastError());
+    }
     {
         Timed t_(ctx, HCLAE_T_ACCUM);
         hipLaunchKernelGGL(k_accumulate, dim3((unsigned)nb, (unsigned)windows), dim3(kUpdThreads), lds, ctx->stream,
-                           xp, codes, N, D, K, ctx->M, m, rpb, ctx->partial, ctx->pcount);
+                           xp, codes, N, D, K, ctx->M, m, rpb, ctx->refine_count + 1, ctx->partial, ctx->pcount);
     }
     HIP_TRY(ctx, hipGetLastError());
     Timed t_(ctx, HCLAE_T_MERGE);
@@ -282,12 +290,12 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
     if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
     for (int t = 0; t < iters; ++t) {
         if ((rc = launch_assign(ctx, m, N, residue, Cm, codes)) != HCLAE_OK) return rc;
-        if ((rc = launch_update(ctx, m, N, residue, Cm, codes, nullptr)) != HCLAE_OK) return rc;
+        if ((rc = launch_update(ctx, m, N, residue, Cm, codes, nullptr, true)) != HCLAE_OK) return rc;
     }
     if ((rc = launch_assign(ctx, m, N, residue, Cm, codes)) != HCLAE_OK) return rc;
     const int pa = launch_heat_cool<-1, true>(ctx, m, N, C, codes, residue, ctx->part_b);
     if (pa < 0) return pa;
-    hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFlatThreads), 0, ctx->stream,
+    hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFinishThreads), 0, ctx->stream,
                        ctx->part_a, ctx->part_b, ctx->part_chg, pa, iters > 0 ? ctx->nk : nullptr, K,
                        ctx->refine_count, ctx->rec + slot);
     HIP_TRY(ctx, hipGetLastError());
@@ -361,10 +369,12 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
     ctx->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     if ((size_t)prop.sharedMemPerBlock < 64 * 1024 && false) { /* LDS limit is raised per kernel below */ }
 
-    // partial sums: at most one vector range per CU, fewer when K*D is large (cap ~256 MB)
-    int ub = ctx->cus;
-    const size_t per = (size_t)K * D * sizeof(float);
-    while (ub > 8 && per * ub > ((size_t)256 << 20)) ub /= 2;
+    // centroid partials: vector ranges x 64-dim windows fill the CUs once; int64 [ranges][K][D]
+    const int windows = (D + kUpdWindow - 1) / kUpdWindow;
+    int ub = ctx->cus / windows;
+    if (ub < 1) ub = 1;
+    const size_t per = (size_t)K * D * sizeof(long long);
+    while (ub > 1 && per * ub > ((size_t)512 << 20)) ub /= 2;
     ctx->upd_blocks = ub;
 
     ctx->nparts = heat_cool_blocks(N_max, D, ctx->cus);
@@ -481,7 +491,7 @@ int hclae_update(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, float
         if (counts) HIP_TRY(ctx, hipMemsetAsync(counts, 0, sizeof(int32_t) * K, ctx->stream));
         return HCLAE_OK;
     }
-    return launch_update(ctx, m, N, xp, C + (size_t)m * K * D, codes, counts);
+    return launch_update(ctx, m, N, xp, C + (size_t)m * K * D, codes, counts, false);
 }
 
 int hclae_quant_error(hclae_ctx *ctx, const float *residue, int64_t N, int D, double *out)
@@ -493,7 +503,7 @@ int hclae_quant_error(hclae_ctx *ctx, const float *residue, int64_t N, int D, do
     if (N == 0) { *out = 0.0; return HCLAE_OK; }
     const int blocks = launch_sqnorm(ctx, residue, N, ctx->part_b);
     if (blocks < 0) return blocks;
-    hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFlatThreads), 0, ctx->stream,
+    hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFinishThreads), 0, ctx->stream,
                        (const double *)nullptr, ctx->part_b, (const long long *)nullptr, blocks,
                        (const int *)nullptr, 0, (const unsigned *)nullptr, ctx->rec);
     HIP_TRY(ctx, hipGetLastError());
@@ -578,7 +588,7 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
             if (err_per_stage) {
                 const int blocks = launch_sqnorm(ctx, residue, N, ctx->part_b);
                 if (blocks < 0) return blocks;
-                hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFlatThreads), 0, ctx->stream,
+                hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFinishThreads), 0, ctx->stream,
                                    (const double *)nullptr, ctx->part_b, (const long long *)nullptr, blocks,
                                    (const int *)nullptr, 0, (const unsigned *)nullptr, ctx->rec + m);
                 HIP_TRY(ctx, hipGetLastError());

@@ -164,21 +164,22 @@ struct StageRecord {
 };
 
 // Final, fixed-order reduction of the per-block partials into a StageRecord (one block).
-__global__ __launch_bounds__(kFlatThreads) void k_finish_stage(
+constexpr int kFinishThreads = 1024;
+__global__ __launch_bounds__(kFinishThreads) void k_finish_stage(
     const double *__restrict__ part_before, const double *__restrict__ part_after,
     const long long *__restrict__ part_chg, int nparts,
     const int *__restrict__ nk, int K, const unsigned *__restrict__ refine_count,
     StageRecord *__restrict__ rec)
 {
-    __shared__ double red[kFlatThreads / kWave];
+    __shared__ double red[kFinishThreads / kWave];
     double a = 0.0, b = 0.0, c = 0.0, e = 0.0;
-    for (int i = threadIdx.x; i < nparts; i += kFlatThreads) {
+    for (int i = threadIdx.x; i < nparts; i += kFinishThreads) {
         if (part_before) a += part_before[i];
         if (part_after) b += part_after[i];
         if (part_chg) c += (double)part_chg[i];
     }
     if (nk)
-        for (int k = threadIdx.x; k < K; k += kFlatThreads) e += (nk[k] == 0);
+        for (int k = threadIdx.x; k < K; k += kFinishThreads) e += (nk[k] == 0);
     a = block_sum(a, red);
     b = block_sum(b, red);
     c = block_sum(c, red);

@@ -1,213 +1,144 @@
 // Centroid half of the k-means that cools a dictionary (Sec. 3.1/3.2): c_m(k) <- mean of the
 // x' assigned to k; an empty cluster keeps its codeword.
 //
-// HBM-bound segmented sum without floating-point atomics.  Every block owns a contiguous range
-// of vectors and a window of 128 dims, with one K x 128 accumulator in LDS.  Wave w of the block
-// owns the codewords k with k % 8 == w.  The range is taken in segments of 4096 rows: the block
-// first sorts the segment's rows by owner (a stable counting sort on the codes, in LDS), then
-// every wave streams its own rows -- one whole 512-byte row per load, two chunks of 8 loads in
-// flight -- and adds them to its accumulator rows with a plain LDS read-add-write.  No two waves
-// ever touch the same accumulator row and a wave adds its rows in ascending vector order, so the
-// sums do not depend on timing: two runs give identical bits.  Block partials go to scratch; a
-// second kernel merges them in fp64 in block order, divides, and refreshes the codeword norms.
+// HBM-bound segmented sum in exact fixed point.  LDS float atomics run at about one lane per
+// clock on this chip while integer LDS atomics keep up with HBM, and integer addition is
+// associative, so the sums are taken on integers: every x' is scaled by a power of two chosen
+// from max |x'| (published by the assign kernel that ran just before) so that |q| <= 2^30,
+// rounded to an int32 q and added as int64 with ds_add_u64 into a K x 64 accumulator (2^30 times
+// 2^31 rows cannot overflow).  The quantisation step is 2^-31..2^-30 of max |x'| -- finer than
+// the fp32 spacing of every element within 2^-6 of the maximum -- and everything after it is
+// exact, so the result does not depend on the order in which waves run: two runs give
+// identical bits and no sort or ownership scheme is needed.  Rows are read once, fully
+// coalesced (a wave-instruction covers one 256-byte half row), 16 rows per wave in flight.
 #pragma once
 #include "common.hpp"
 
 namespace hclae {
 
-constexpr int kUpdThreads = 512;
-constexpr int kUpdWaves = kUpdThreads / kWave;      // 8 owners of codeword classes k % 8
-constexpr int kUpdWindow = 128;                     // dims per block: two per lane
-constexpr int kUpdDepth = 16;                       // rows per chunk of loads
-constexpr int kUpdSeg = 4096;                       // rows per segment (16-bit row index, 64 batches)
-constexpr uint32_t kUpdNone = 0xffffffffu;
+constexpr int kUpdThreads = 1024;
+constexpr int kUpdWaves = kUpdThreads / kWave;      // 16
+constexpr int kUpdWindow = 64;                      // dims per block: one per lane
+constexpr int kUpdDepth = 16;                       // rows a wave keeps in flight
+constexpr int kUpdSeg = 8192;                       // rows per pointer rebase (keeps offsets in 32 bits)
 
-// LDS bytes of k_accumulate for K codewords.
-constexpr size_t upd_lds_bytes(int K)
+// LDS bytes of k_accumulate for K codewords: int64 sums, counts.
+constexpr size_t upd_lds_bytes(int K) { return (size_t)K * kUpdWindow * sizeof(long long) + (size_t)K * sizeof(int); }
+
+// Power-of-two exponent s with max |x'| * 2^s in [2^29, 2^30): q = rint(x' * 2^s) fits int32.
+__device__ __forceinline__ int fixed_point_shift(unsigned xmax_bits)
 {
-    return (size_t)K * kUpdWindow * sizeof(float)             // accumulator
-           + (size_t)kUpdSeg * sizeof(uint32_t)               // row list of a segment
-           + (size_t)(kUpdSeg / kWave) * kUpdWaves * sizeof(int)   // per batch, per owner offsets
-           + 2 * kUpdWaves * sizeof(int);                     // owner bases and totals
+    const float mx = __uint_as_float(xmax_bits);
+    if (!(mx > 0.f) || !(mx < __builtin_inff())) return 0;
+    int e;
+    (void)frexpf(mx, &e);                           // mx = f * 2^e, f in [0.5, 1)
+    return 30 - e;
 }
 
-// grid: (vector ranges, D windows).  partial: float [gridDim.x][K][D]; pcount: int [gridDim.x][K].
+// grid: (vector ranges, 64-dim windows).  partial: int64 [gridDim.x][K][D] (sum of q); pcount: int [gridDim.x][K].
 __global__ __launch_bounds__(kUpdThreads) void k_accumulate(
     const float *__restrict__ xp, const uint8_t *__restrict__ codes,
-    int64_t N, int D, int K, int M, int m, int64_t rows_per_block,
-    float *__restrict__ partial, int *__restrict__ pcount)
+    int64_t N, int D, int K, int M, int m, int64_t rows_per_block, const unsigned *__restrict__ xmax_bits,
+    long long *__restrict__ partial, int *__restrict__ pcount)
 {
     extern __shared__ float4 smem4[];
-    float *acc = reinterpret_cast<float *>(smem4);                   // [K][128]
-    uint32_t *list = reinterpret_cast<uint32_t *>(acc + K * kUpdWindow);          // [kUpdSeg]: row | code << 16
-    int *boff = reinterpret_cast<int *>(list + kUpdSeg);             // [64 batches][8 owners]
-    int *wtotal = boff + (kUpdSeg / kWave) * kUpdWaves;              // [8]
+    unsigned long long *acc = reinterpret_cast<unsigned long long *>(smem4);   // [K][64]
+    unsigned *cnt = reinterpret_cast<unsigned *>(acc + K * kUpdWindow);        // [K]
     const int lane = lane_id();
     const int wave = threadIdx.x >> 6;
-    const int d0 = blockIdx.y * kUpdWindow + 2 * lane;               // this lane's two dims
-    const bool live = d0 < D;                                        // D % 4 == 0: both or neither
+    const int d = blockIdx.y * kUpdWindow + lane;                    // this lane's dim
+    const bool live = d < D;
+    const bool counting = blockIdx.y == 0;
+    const int shift = fixed_point_shift(*xmax_bits);
 
-    for (int e = threadIdx.x; e < K * kUpdWindow / 4; e += kUpdThreads) smem4[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int e = threadIdx.x; e < K * kUpdWindow; e += kUpdThreads) acc[e] = 0ull;
+    for (int e = threadIdx.x; e < K; e += kUpdThreads) cnt[e] = 0u;
+    __syncthreads();
 
-    float2 *mine = reinterpret_cast<float2 *>(acc) + lane;
     const int64_t row0 = (int64_t)blockIdx.x * rows_per_block;
     int64_t row1 = row0 + rows_per_block;
     if (row1 > N) row1 = N;
-    const unsigned long long lt = (1ull << lane) - 1ull;
-    int own_cnt = 0;                                                 // members of codeword 8 * lane + wave (lane < 32)
-
+    unsigned own_cnt[4] = {0u, 0u, 0u, 0u};                          // rows seen with code 64 g + lane
+    const int uwave = __builtin_amdgcn_readfirstlane(wave);          // wave-uniform copy for scalar address math
+    unsigned long long *mine = acc + lane;
     for (int64_t seg0 = row0; seg0 < row1; seg0 += kUpdSeg) {
         const int segn = (int)((row1 - seg0 < kUpdSeg) ? (row1 - seg0) : kUpdSeg);
-        const int nbatch = (segn + kWave - 1) / kWave;
-        // ---- stable counting sort of the segment's rows by owner wave ----
-        int mycode[kUpdWaves];
-#pragma unroll
-        for (int i = 0; i < kUpdWaves; ++i) {
-            const int b = wave + kUpdWaves * i;
-            const int rloc = b * kWave + lane;
-            mycode[i] = (rloc < segn) ? (int)codes[(seg0 + rloc) * M + m] : -1;
-        }
-#pragma unroll
-        for (int i = 0; i < kUpdWaves; ++i) {
-            const int b = wave + kUpdWaves * i;
-            if (b < nbatch) {
-                int mine_cnt = 0;
-#pragma unroll
-                for (int w = 0; w < kUpdWaves; ++w) {
-                    const unsigned long long mk = __ballot(mycode[i] >= 0 && (mycode[i] & (kUpdWaves - 1)) == w);
-                    if (lane == w) mine_cnt = __popcll(mk);
-                }
-                if (lane < kUpdWaves) boff[b * kUpdWaves + lane] = mine_cnt;
-            }
-        }
-        __syncthreads();
-        {
-            // wave w turns the per-batch counts of owner w into exclusive offsets (lane = batch)
-            const int c = (lane < nbatch) ? boff[lane * kUpdWaves + wave] : 0;
-            int incl = c;
-#pragma unroll
-            for (int o = 1; o < kWave; o <<= 1) {
-                const int t = __shfl_up(incl, o, kWave);
-                if (lane >= o) incl += t;
-            }
-            if (lane < nbatch) boff[lane * kUpdWaves + wave] = incl - c;
-            if (lane == kWave - 1) wtotal[wave] = incl;
-        }
-        __syncthreads();
-        int obase[kUpdWaves];                                        // first list slot of every owner
-        {
-            int run = 0;
-#pragma unroll
-            for (int w = 0; w < kUpdWaves; ++w) { obase[w] = run; run += wtotal[w]; }
-        }
-#pragma unroll
-        for (int i = 0; i < kUpdWaves; ++i) {
-            const int b = wave + kUpdWaves * i;
-            if (b < nbatch) {
-                const int own = mycode[i] & (kUpdWaves - 1);
-#pragma unroll
-                for (int w = 0; w < kUpdWaves; ++w) {
-                    const unsigned long long mk = __ballot(mycode[i] >= 0 && own == w);
-                    if (mycode[i] >= 0 && own == w)
-                        list[obase[w] + boff[b * kUpdWaves + w] + __popcll(mk & lt)] =
-                            (uint32_t)(b * kWave + lane) | ((uint32_t)mycode[i] << 16);
-                }
-            }
-        }
-        __syncthreads();
-
-        // ---- every wave streams its own rows, two chunks of loads in flight ----
-        int my_base = 0;
-#pragma unroll
-        for (int w = 0; w < kUpdWaves; ++w) my_base = (w == wave) ? obase[w] : my_base;
-        const uint32_t *L = list + my_base;
-        const int n_own = wtotal[wave];
-        const float *seg_x = xp + seg0 * D + d0;
-        float2 va[kUpdDepth], vb[kUpdDepth];
-        uint32_t ea, eb;
-        auto fetch = [&](int i, float2 (&v)[kUpdDepth], uint32_t &e) {
-            e = (lane < kUpdDepth && i + lane < n_own) ? L[i + lane] : kUpdNone;
+        const float *segx = xp + seg0 * D + (live ? d : 0);          // offsets below stay within 32 bits
+        const uint8_t *segc = codes + seg0 * M + m;
+        for (int r0 = uwave * kUpdDepth; r0 < segn; r0 += kUpdWaves * kUpdDepth) {
+            const int nrow = min(kUpdDepth, segn - r0);              // uniform
+            // lane u < nrow fetches the code of row r0 + u; values reach the scalar unit by readlane
+            const int cvec = (lane < nrow) ? (int)segc[(unsigned)(r0 + lane) * (unsigned)M] : 0;
+            float v[kUpdDepth];
 #pragma unroll
             for (int u = 0; u < kUpdDepth; ++u) {
-                const uint32_t ent = __builtin_amdgcn_readlane(e, u);
-                v[u] = make_float2(0.f, 0.f);
-                if (ent != kUpdNone && live)
-                    v[u] = *reinterpret_cast<const float2 *>(seg_x + (size_t)(ent & 0xffffu) * D);
+                v[u] = 0.f;
+                if (u < nrow) v[u] = __builtin_nontemporal_load(segx + (unsigned)(r0 + u) * (unsigned)D);
             }
-        };
-        auto rmw1 = [&](int c, const float2 &v) {
-            float2 *a = mine + c * (kUpdWindow / 2);
-            float2 t = *a;
-            t.x += v.x;
-            t.y += v.y;
-            *a = t;
-        };
-        auto apply = [&](const float2 (&v)[kUpdDepth], uint32_t e) {
+            unsigned packed = 0u;                                    // four 8-bit counters: codes 64 g + lane
 #pragma unroll
-            for (int u = 0; u < kUpdDepth; u += 2) {
-                const uint32_t e0 = __builtin_amdgcn_readlane(e, u);
-                const uint32_t e1 = __builtin_amdgcn_readlane(e, u + 1);
-                if (e0 == kUpdNone) break;
-                const int c0 = (int)(e0 >> 16);
-                own_cnt += (lane == (c0 >> 3));
-                if (e1 == kUpdNone) { rmw1(c0, v[u]); break; }
-                const int c1 = (int)(e1 >> 16);
-                own_cnt += (lane == (c1 >> 3));
-                if (c0 != c1) {
-                    // distinct accumulator rows: overlap the two LDS round trips
-                    float2 *a0 = mine + c0 * (kUpdWindow / 2);
-                    float2 *a1 = mine + c1 * (kUpdWindow / 2);
-                    float2 t0 = *a0, t1 = *a1;
-                    t0.x += v[u].x; t0.y += v[u].y;
-                    t1.x += v[u + 1].x; t1.y += v[u + 1].y;
-                    *a0 = t0;
-                    *a1 = t1;
-                } else {
-                    rmw1(c0, v[u]);
-                    rmw1(c1, v[u + 1]);
+            for (int u = 0; u < kUpdDepth; ++u) {
+                if (u < nrow) {
+                    const int cc = __builtin_amdgcn_readlane(cvec, u);
+                    const int q = live ? (int)__builtin_rintf(ldexpf(v[u], shift)) : 0;
+                    atomicAdd(mine + cc * kUpdWindow, (unsigned long long)(long long)q);
+                    packed += (lane == (cc & 63)) ? (1u << ((cc >> 6) << 3)) : 0u;
                 }
             }
-        };
-        fetch(0, va, ea);
-        for (int i = 0; i < n_own; i += 2 * kUpdDepth) {
-            fetch(i + kUpdDepth, vb, eb);
-            apply(va, ea);
-            fetch(i + 2 * kUpdDepth, va, ea);
-            apply(vb, eb);
+            if (counting) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) own_cnt[g] += (packed >> (8 * g)) & 255u;
+            }
         }
-        __syncthreads();
     }
+    if (counting) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            if (64 * g + lane < K && own_cnt[g]) atomicAdd(cnt + 64 * g + lane, own_cnt[g]);
+    }
+    __syncthreads();
 
-    // partial[blockIdx.x][k][window dims]
-    float *out = partial + (size_t)blockIdx.x * K * D;
-    const int wd = min(kUpdWindow, D - blockIdx.y * kUpdWindow);     // live dims of this window
-    for (int e = threadIdx.x; e < K * (kUpdWindow / 4); e += kUpdThreads) {
-        const int k = e / (kUpdWindow / 4);
-        const int d = 4 * (e - k * (kUpdWindow / 4));
-        if (d < wd)
-            *reinterpret_cast<float4 *>(out + (size_t)k * D + blockIdx.y * kUpdWindow + d) = smem4[e];
+    long long *out = partial + (size_t)blockIdx.x * K * D;
+    for (int e = threadIdx.x; e < K * kUpdWindow; e += kUpdThreads) {
+        const int k = e / kUpdWindow, j = e - k * kUpdWindow;
+        if (blockIdx.y * kUpdWindow + j < D) out[(size_t)k * D + blockIdx.y * kUpdWindow + j] = (long long)acc[e];
     }
-    if (blockIdx.y == 0 && lane < 32 && kUpdWaves * lane + wave < K)
-        pcount[blockIdx.x * K + kUpdWaves * lane + wave] = own_cnt;
+    if (counting)
+        for (int k = threadIdx.x; k < K; k += kUpdThreads) pcount[blockIdx.x * K + k] = (int)cnt[k];
 }
 
-// One block per codeword k: n_k = sum_b pcount[b][k];  C_m[k][d] = (sum_b partial[b][k][d]) / n_k,
-// summed in fp64 in a fixed order (8 groups of consecutive blocks, each in ascending b, then
-// the groups in ascending order); untouched when n_k == 0.  Then hneg[k] = -||c_k||^2/2 for the
-// next assignment, nk[k] = n_k, and the re-check counter is reset.
-constexpr int kMergeGroups = 8;
+// max |x'| over an array (bits of the float, see publish_absmax); used when the centroid update is
+// called on its own, without the assign kernel that normally provides it.  *slot must start at 0.
+__global__ __launch_bounds__(256) void k_absmax(const float4 *__restrict__ x, int64_t n4, unsigned *__restrict__ slot)
+{
+    float amax = 0.f;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+        const float4 v = x[i];
+        amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, kWave));
+    if (lane_id() == 0) atomicMax(slot, __float_as_uint(amax));
+}
+
+// One block per codeword k: n_k = sum_b pcount[b][k];  C_m[k][d] = 2^-s * (sum_b partial[b][k][d]) / n_k
+// with the integer sum exact (so its order is free: 4 groups of blocks in parallel) and the
+// division in fp64; untouched when n_k == 0.  Then hneg[k] = -||c_k||^2/2 for the next
+// assignment, nk[k] = n_k, and the re-check counter is reset (max |x'| stays: x' has not changed).
+constexpr int kMergeGroups = 4;
+constexpr int kMergePairs = 256 / kMergeGroups;     // dim pairs per pass
 __global__ __launch_bounds__(256) void k_merge(
-    const float *__restrict__ partial, const int *__restrict__ pcount, int nblk,
+    const long long *__restrict__ partial, const int *__restrict__ pcount, int nblk,
     int K, int D, float *__restrict__ Cm, float *__restrict__ hneg, int *__restrict__ nk,
     int *__restrict__ counts_out, unsigned *__restrict__ refine_count)
 {
     __shared__ double red[256 / kWave];
-    __shared__ double comb[kMergeGroups][32][4];
+    __shared__ long long comb[kMergeGroups][kMergePairs][2];
     __shared__ int s_n;
     const int k = blockIdx.x;
-    if (k == 0 && threadIdx.x == 0) *refine_count = 0u;
+    const int shift = fixed_point_shift(refine_count[1]);
+    if (k == 0 && threadIdx.x == 0) refine_count[0] = 0u;
     if (threadIdx.x < kWave) {
-        // integer sum: order-free
         long long c = 0;
         for (int b = threadIdx.x; b < nblk; b += kWave) c += pcount[b * K + k];
         c = wave_sum_ll(c);
@@ -215,39 +146,39 @@ __global__ __launch_bounds__(256) void k_merge(
     }
     __syncthreads();
     const int n = s_n;
-    const int g = threadIdx.x >> 5;                    // block group
-    const int l = threadIdx.x & 31;                    // float4 column within a pass
-    const int d4 = D >> 2;
+    const int g = threadIdx.x / kMergePairs;
+    const int l = threadIdx.x - g * kMergePairs;
     const int per = (nblk + kMergeGroups - 1) / kMergeGroups;
     const int b0 = g * per, b1 = min(nblk, b0 + per);
+    const int npairs = D >> 1;
     double sq = 0.0;
-    for (int j0 = 0; j0 < d4; j0 += 32) {
-        const int j = j0 + l;
-        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-        if (n > 0 && j < d4) {
+    for (int p0 = 0; p0 < npairs; p0 += kMergePairs) {
+        const int pr = p0 + l;
+        long long s0 = 0, s1 = 0;
+        if (n > 0 && pr < npairs) {
             for (int b = b0; b < b1; ++b) {
-                const float4 v = *reinterpret_cast<const float4 *>(partial + ((size_t)b * K + k) * D + 4 * j);
-                s0 += (double)v.x; s1 += (double)v.y; s2 += (double)v.z; s3 += (double)v.w;
+                const longlong2 v = *reinterpret_cast<const longlong2 *>(partial + ((size_t)b * K + k) * D + 2 * pr);
+                s0 += v.x;
+                s1 += v.y;
             }
         }
-        comb[g][l][0] = s0; comb[g][l][1] = s1; comb[g][l][2] = s2; comb[g][l][3] = s3;
+        comb[g][l][0] = s0;
+        comb[g][l][1] = s1;
         __syncthreads();
-        if (g == 0 && j < d4) {
-            float4 c;
-            float4 *dst = reinterpret_cast<float4 *>(Cm + (size_t)k * D + 4 * j);
+        if (g == 0 && pr < npairs) {
+            float2 c;
+            float2 *dst = reinterpret_cast<float2 *>(Cm + (size_t)k * D + 2 * pr);
             if (n > 0) {
-                double t0 = 0.0, t1 = 0.0, t2 = 0.0, t3 = 0.0;
+                long long t0 = 0, t1 = 0;
 #pragma unroll
-                for (int q = 0; q < kMergeGroups; ++q) {
-                    t0 += comb[q][l][0]; t1 += comb[q][l][1]; t2 += comb[q][l][2]; t3 += comb[q][l][3];
-                }
-                const double inv = (double)n;
-                c = make_float4((float)(t0 / inv), (float)(t1 / inv), (float)(t2 / inv), (float)(t3 / inv));
+                for (int q = 0; q < kMergeGroups; ++q) { t0 += comb[q][l][0]; t1 += comb[q][l][1]; }
+                c.x = (float)(ldexp((double)t0, -shift) / (double)n);
+                c.y = (float)(ldexp((double)t1, -shift) / (double)n);
                 *dst = c;
             } else {
                 c = *dst;
             }
-            sq += (double)c.x * c.x + (double)c.y * c.y + (double)c.z * c.z + (double)c.w * c.w;
+            sq += (double)c.x * c.x + (double)c.y * c.y;
         }
         __syncthreads();
     }
