@@ -134,6 +134,36 @@ int hclae_update(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, float
  * bound of the fp32 contraction.  Synchronises the stream.  out: HOST. */
 int hclae_last_refined(hclae_ctx *ctx, int64_t *out);
 
+/* ---- online learning (Sec. 3.4: keep fitting learned dictionaries to newly arriving data) ---- */
+
+/*
+ * The paper states no update rule; the reading taken is running per-codeword sums and counts over
+ * everything seen so far, held by the ctx.  hclae_online_begin sets them from the current
+ * dictionaries: sums = C * n0, counts = n0 (n0: HOST int64[M][K] weights of what C was learned
+ * from, or NULL for all zero, in which case the first chunk replaces every codeword it touches).
+ */
+int hclae_online_begin(hclae_ctx *ctx, const float *C, int M, int K, int D, const int64_t *n0);
+
+/*
+ * One chunk of n new vectors, given as stored descriptors Xu8 (DEVICE uint8 [n][D]).  For each
+ * dictionary m in order, with r the chunk's residue so far (r = x for m = 0):
+ *   assign r to C_m;  add its members to the running sums and counts;  c_m(k) <- sum / count
+ *   where count > 0;  assign again;  r <- r - c_m(i_m).
+ * Updates C in place; writes codes [n][M] and residue [n][D] (both DEVICE, caller-owned, required).
+ * codes_first: DEVICE uint8 [n][M] or NULL; receives the codes of each stage's FIRST assignment,
+ * i.e. the memberships that entered the running sums (codes holds the re-assigned ones).
+ * err: HOST, receives (1/n) sum ||residue||^2 and synchronises the stream; or NULL (no sync).
+ * The caller may overlap the host-to-device copy of the next chunk on another stream.
+ */
+int hclae_online_chunk(hclae_ctx *ctx, const uint8_t *Xu8, int64_t n, int D, float *C, int M, int K,
+                       uint8_t *codes, float *residue, uint8_t *codes_first, double *err);
+
+/* Checkpoint / resume of the online state at a chunk boundary: running sums (HOST double[M][K][D])
+ * and counts (HOST int64[M][K]).  Both synchronise the stream.  Together with C they are the
+ * whole state of the learner. */
+int hclae_online_export(hclae_ctx *ctx, double *run_sum, int64_t *run_cnt);
+int hclae_online_import(hclae_ctx *ctx, const double *run_sum, const int64_t *run_cnt);
+
 /* ---- measurement: per-kernel durations from HIP events on the ctx's stream ------------- */
 
 enum {

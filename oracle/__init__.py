@@ -61,6 +61,8 @@ def _load():
     lib.da_anneal_stage.restype = ctypes.c_double
     lib.da_sweep.argtypes = [_f64p, _u8p, _f64p, _i64, _int, _int, _int, _int, _i64p, _f64p]
     lib.da_reconstruct.argtypes = [_f64p, _u8p, _i64, _int, _int, _int, _f64p]
+    lib.da_online_chunk.argtypes = [_u8p, _i64, _int, _int, _int, _f64p, _f64p, _i64p, _u8p, _f64p]
+    lib.da_online_chunk.restype = ctypes.c_double
     _lib = lib
     return lib
 
@@ -186,3 +188,20 @@ def reconstruct(C, codes):
     xhat = np.empty((N, D), np.float64)
     _load().da_reconstruct(_p(C, _f64p), _p(codes, _u8p), N, D, M, K, _p(xhat, _f64p))
     return xhat
+
+
+def online_chunk(X_u8, C, S, cnt):
+    """One online chunk (uint8 [n][D]) against running sums S float64 [M][K][D] and counts
+    int64 [M][K], all updated in place together with C.  Returns (codes, residue, E)."""
+    _chk(X_u8, np.uint8)
+    _chk(C, np.float64)
+    M, K, D = C.shape
+    n = X_u8.shape[0]
+    assert X_u8.shape == (n, D)
+    _chk(S, np.float64, (M, K, D))
+    _chk(cnt, np.int64, (M, K))
+    codes = np.zeros((n, M), np.uint8)
+    r = np.empty((n, D), np.float64)
+    E = _load().da_online_chunk(_p(X_u8, _u8p), n, D, M, K, _p(C, _f64p), _p(S, _f64p), _p(cnt, _i64p),
+                                _p(codes, _u8p), _p(r, _f64p))
+    return codes, r, E

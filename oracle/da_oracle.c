@@ -251,6 +251,39 @@ void da_sweep(double *C, uint8_t *codes, double *r,
     }
 }
 
+/*
+ * Sec. 3.4, online learning: keep fitting the learned dictionaries to newly arriving data.
+ * The paper gives no update rule; the reading taken is running per-codeword sums S and counts
+ * cnt over everything seen so far.  For one chunk X (uint8 [n][D], as SIFT descriptors are
+ * stored) and each dictionary m in order, with r the chunk's residue so far (r = x for m = 0):
+ *   assign r to C_m;  S_m[k] += sum of its members, cnt_m[k] += their number;
+ *   c_m(k) <- S_m[k] / cnt_m[k] where cnt_m[k] > 0;  assign again;  r <- r - c_m(i_m).
+ * S: double[M][K][D], cnt: int64[M][K] are updated in place.  Returns E of the chunk.
+ */
+double da_online_chunk(const uint8_t *X, int64_t n, int D, int M, int K,
+                       double *C, double *S, int64_t *cnt, uint8_t *codes, double *r)
+{
+    for (size_t i = 0; i < (size_t)n * D; ++i) r[i] = (double)X[i];
+    for (int m = 0; m < M; ++m) {
+        double *Cm = C + (size_t)m * K * D;
+        double *Sm = S + (size_t)m * K * D;
+        int64_t *cm = cnt + (size_t)m * K;
+        da_assign(r, C, n, D, M, K, m, codes, NULL, NULL, NULL);
+        for (int64_t v = 0; v < n; ++v) {
+            const int k = codes[v * M + m];
+            const double *x = r + (size_t)v * D;
+            for (int d = 0; d < D; ++d) Sm[(size_t)k * D + d] = Sm[(size_t)k * D + d] + x[d];
+            cm[k] += 1;
+        }
+        for (int k = 0; k < K; ++k)
+            if (cm[k] > 0)
+                for (int d = 0; d < D; ++d) Cm[(size_t)k * D + d] = Sm[(size_t)k * D + d] / (double)cm[k];
+        da_assign(r, C, n, D, M, K, m, codes, NULL, NULL, NULL);
+        da_cool(r, codes, C, n, D, M, K, m);
+    }
+    return da_quant_error(r, n, D);
+}
+
 /* x_hat_n = sum_m c_m(i_m(n)) (used to check x = x_hat + r). */
 void da_reconstruct(const double *C, const uint8_t *codes, int64_t N, int D, int M, int K,
                     double *xhat)

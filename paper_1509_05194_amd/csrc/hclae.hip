@@ -50,6 +50,10 @@ struct hclae_ctx {
     // host
     StageRecord *rec_host;   // pinned [M]
     int upd_blocks;
+    // online learning state (allocated by hclae_online_begin)
+    double *run_sum;         // [M][K][D]
+    long long *run_cnt;      // [M][K]
+    long long *n0_dev;       // [M][K] staging of the caller's weights
     // optional per-kernel timing (HIP events on ctx->stream)
     uint32_t t_mask;
     int t_used;
@@ -226,7 +230,7 @@ int launch_assign(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float
 // Accumulate + merge; leaves hneg = norms of the new Cm and the re-check counter at zero.
 // have_absmax: refine_count[1] already holds max |xp| (the assign kernel just ran on the same xp).
 int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, const uint8_t *codes,
-                  int32_t *counts, bool have_absmax)
+                  int32_t *counts, bool have_absmax, bool online = false)
 {
     const int D = ctx->D, K = ctx->K;
     const int windows = (D + kUpdWindow - 1) / kUpdWindow;
@@ -256,7 +260,9 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
     HIP_TRY(ctx, hipGetLastError());
     Timed t_(ctx, HCLAE_T_MERGE);
     hipLaunchKernelGGL(k_merge, dim3(K), dim3(256), 0, ctx->stream,
-                       ctx->partial, ctx->pcount, (int)nb, K, D, Cm, ctx->hneg, ctx->nk, counts, ctx->refine_count);
+                       ctx->partial, ctx->pcount, (int)nb, K, D, Cm, ctx->hneg, ctx->nk, counts, ctx->refine_count,
+                       online ? ctx->run_sum + (size_t)m * K * D : (double *)nullptr,
+                       online ? ctx->run_cnt + (size_t)m * K : (long long *)nullptr);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
@@ -420,7 +426,8 @@ int hclae_destroy(hclae_ctx *ctx)
 {
     if (!ctx) return HCLAE_EINVAL;
     void *dev[] = {ctx->hneg, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
-                   ctx->nk, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec};
+                   ctx->nk, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
+                   ctx->run_sum, ctx->run_cnt, ctx->n0_dev};
     for (void *p : dev)
         if (p) (void)hipFree(p);
     if (ctx->rec_host) (void)hipHostFree(ctx->rec_host);
@@ -598,6 +605,96 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
     if (err_per_stage) {
         if ((rc = fetch_records(ctx, M)) != HCLAE_OK) return rc;
         for (int m = 0; m < M; ++m) err_per_stage[m] = ctx->rec_host[m].sum_after / (double)N;
+    }
+    return HCLAE_OK;
+}
+
+int hclae_online_begin(hclae_ctx *ctx, const float *C, int M, int K, int D, const int64_t *n0)
+{
+    int rc = check_call(ctx, 0, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (!C) return fail(ctx, HCLAE_EINVAL, "hclae_online_begin: C is NULL");
+    if (n0)
+        for (int i = 0; i < M * K; ++i)
+            if (n0[i] < 0) return fail(ctx, HCLAE_EINVAL, "hclae_online_begin: negative weight");
+    const size_t rows = (size_t)M * K;
+    if (!ctx->run_sum) {
+        hipError_t e = hipMalloc((void **)&ctx->run_sum, rows * D * sizeof(double));
+        if (e == hipSuccess) e = hipMalloc((void **)&ctx->run_cnt, rows * sizeof(long long));
+        if (e == hipSuccess) e = hipMalloc((void **)&ctx->n0_dev, rows * sizeof(long long));
+        if (e != hipSuccess) return fail(ctx, e == hipErrorOutOfMemory ? HCLAE_ENOMEM : HCLAE_EHIP, "hipMalloc (online state)", e);
+    }
+    if (n0) {
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->n0_dev, n0, rows * sizeof(long long), hipMemcpyHostToDevice, ctx->stream));
+    }
+    const int64_t total = (int64_t)rows * D;
+    hipLaunchKernelGGL(k_online_begin, dim3(stream_blocks(ctx, total, 256)), dim3(256), 0, ctx->stream,
+                       C, n0 ? ctx->n0_dev : (const long long *)nullptr, total, D, ctx->run_sum, ctx->run_cnt);
+    HIP_TRY(ctx, hipGetLastError());
+    if (n0) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));      // n0 was read from caller memory asynchronously
+    return HCLAE_OK;
+}
+
+int hclae_online_export(hclae_ctx *ctx, double *run_sum, int64_t *run_cnt)
+{
+    if (!ctx || !run_sum || !run_cnt) return HCLAE_EINVAL;
+    if (!ctx->run_sum) return fail(ctx, HCLAE_ESTATE, "hclae_online_export before hclae_online_begin");
+    const size_t rows = (size_t)ctx->M * ctx->K;
+    HIP_TRY(ctx, hipMemcpyAsync(run_sum, ctx->run_sum, rows * ctx->D * sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(run_cnt, ctx->run_cnt, rows * sizeof(long long), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HCLAE_OK;
+}
+
+int hclae_online_import(hclae_ctx *ctx, const double *run_sum, const int64_t *run_cnt)
+{
+    if (!ctx || !run_sum || !run_cnt) return HCLAE_EINVAL;
+    if (!ctx->run_sum) return fail(ctx, HCLAE_ESTATE, "hclae_online_import before hclae_online_begin");
+    const size_t rows = (size_t)ctx->M * ctx->K;
+    for (size_t i = 0; i < rows; ++i)
+        if (run_cnt[i] < 0) return fail(ctx, HCLAE_EINVAL, "hclae_online_import: negative count");
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->run_sum, run_sum, rows * ctx->D * sizeof(double), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->run_cnt, run_cnt, rows * sizeof(long long), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HCLAE_OK;
+}
+
+int hclae_online_chunk(hclae_ctx *ctx, const uint8_t *Xu8, int64_t n, int D, float *C, int M, int K,
+                       uint8_t *codes, float *residue, uint8_t *codes_first, double *err)
+{
+    int rc = check_call(ctx, n, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (!ctx->run_sum) return fail(ctx, HCLAE_ESTATE, "hclae_online_chunk before hclae_online_begin");
+    if (D % 16 != 0) return fail(ctx, HCLAE_EINVAL, "hclae_online_chunk: D must be a multiple of 16");
+    if (n == 0) { if (err) *err = 0.0; return HCLAE_OK; }
+    if (!Xu8 || !C || !codes || !residue) return fail(ctx, HCLAE_EINVAL, "hclae_online_chunk: NULL pointer");
+    const int64_t n16 = n * (D / 16);
+    hipLaunchKernelGGL(k_convert_u8, dim3(stream_blocks(ctx, n16, kFlatThreads * 2)), dim3(kFlatThreads), 0, ctx->stream,
+                       residue, Xu8, n16);
+    HIP_TRY(ctx, hipGetLastError());
+    for (int m = 0; m < M; ++m) {
+        float *Cm = C + (size_t)m * K * D;
+        if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
+        if ((rc = launch_assign(ctx, m, n, residue, Cm, codes)) != HCLAE_OK) return rc;
+        if (codes_first) {
+            hipLaunchKernelGGL(k_copy_column, dim3(stream_blocks(ctx, n, kFlatThreads)), dim3(kFlatThreads), 0, ctx->stream,
+                               codes_first, codes, n, M, m);
+            HIP_TRY(ctx, hipGetLastError());
+        }
+        if ((rc = launch_update(ctx, m, n, residue, Cm, codes, nullptr, true, true)) != HCLAE_OK) return rc;
+        if ((rc = launch_assign(ctx, m, n, residue, Cm, codes)) != HCLAE_OK) return rc;
+        const bool last = (m == M - 1) && err;
+        const int b = last ? launch_heat_cool<-1, true>(ctx, m, n, C, codes, residue, ctx->part_b)
+                           : launch_heat_cool<-1, false>(ctx, m, n, C, codes, residue, nullptr);
+        if (b < 0) return b;
+        if (last) {
+            hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFinishThreads), 0, ctx->stream,
+                               (const double *)nullptr, ctx->part_b, (const long long *)nullptr, b,
+                               (const int *)nullptr, 0, (const unsigned *)nullptr, ctx->rec);
+            HIP_TRY(ctx, hipGetLastError());
+            if ((rc = fetch_records(ctx, 1)) != HCLAE_OK) return rc;
+            *err = ctx->rec_host[0].sum_after / (double)n;
+        }
     }
     return HCLAE_OK;
 }

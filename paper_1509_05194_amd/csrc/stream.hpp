@@ -110,6 +110,32 @@ __global__ __launch_bounds__(kFlatThreads) void k_copy(
     }
 }
 
+// r <- float(X) for descriptors stored as bytes (online chunks): 16 bytes in, 64 bytes out per thread.
+__global__ __launch_bounds__(kFlatThreads) void k_convert_u8(
+    float *__restrict__ dst, const uint8_t *__restrict__ src, int64_t n16)
+{
+    typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+    for (int64_t i = (int64_t)blockIdx.x * kFlatThreads + threadIdx.x; i < n16;
+         i += (int64_t)gridDim.x * kFlatThreads) {
+        const uintx4 w = __builtin_nontemporal_load(reinterpret_cast<const uintx4 *>(src) + i);
+        floatx4 *o = reinterpret_cast<floatx4 *>(dst) + 4 * i;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const unsigned u = w[j];
+            floatx4 f = {(float)(u & 255u), (float)((u >> 8) & 255u), (float)((u >> 16) & 255u), (float)(u >> 24)};
+            __builtin_nontemporal_store(f, o + j);
+        }
+    }
+}
+
+// dst[n][m] = src[n][m] for one column m of the code matrix.
+__global__ __launch_bounds__(kFlatThreads) void k_copy_column(
+    uint8_t *__restrict__ dst, const uint8_t *__restrict__ src, int64_t N, int M, int m)
+{
+    for (int64_t n = (int64_t)blockIdx.x * kFlatThreads + threadIdx.x; n < N; n += (int64_t)gridDim.x * kFlatThreads)
+        dst[n * M + m] = src[n * M + m];
+}
+
 // Partial sums of ||e_x||^2 (Eq. 1, first line), fp64 accumulation, four loads in flight.
 __global__ __launch_bounds__(kFlatThreads) void k_sqnorm(
     const floatx4 *__restrict__ r, int64_t n4, double *__restrict__ part_err)

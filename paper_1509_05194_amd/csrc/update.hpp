@@ -130,7 +130,8 @@ constexpr int kMergePairs = 256 / kMergeGroups;     // dim pairs per pass
 __global__ __launch_bounds__(256) void k_merge(
     const long long *__restrict__ partial, const int *__restrict__ pcount, int nblk,
     int K, int D, float *__restrict__ Cm, float *__restrict__ hneg, int *__restrict__ nk,
-    int *__restrict__ counts_out, unsigned *__restrict__ refine_count)
+    int *__restrict__ counts_out, unsigned *__restrict__ refine_count,
+    double *__restrict__ run_sum, long long *__restrict__ run_cnt)
 {
     __shared__ double red[256 / kWave];
     __shared__ long long comb[kMergeGroups][kMergePairs][2];
@@ -145,7 +146,16 @@ __global__ __launch_bounds__(256) void k_merge(
         if (threadIdx.x == 0) s_n = (int)c;
     }
     __syncthreads();
-    const int n = s_n;
+    // online learning: the chunk's sums and counts join the running ones, which then define c_k
+    const bool online = run_sum != nullptr;
+    long long n_all = s_n;
+    if (online) {
+        n_all += run_cnt[k];
+        __syncthreads();
+        if (threadIdx.x == 0) run_cnt[k] = n_all;
+    }
+    const int n = online ? (n_all > 0 ? 1 : 0) : s_n;              // "has members" for the branches below
+    const double denom = online ? (double)n_all : (double)s_n;
     const int g = threadIdx.x / kMergePairs;
     const int l = threadIdx.x - g * kMergePairs;
     const int per = (nblk + kMergeGroups - 1) / kMergeGroups;
@@ -155,7 +165,7 @@ __global__ __launch_bounds__(256) void k_merge(
     for (int p0 = 0; p0 < npairs; p0 += kMergePairs) {
         const int pr = p0 + l;
         long long s0 = 0, s1 = 0;
-        if (n > 0 && pr < npairs) {
+        if (s_n > 0 && pr < npairs) {
             for (int b = b0; b < b1; ++b) {
                 const longlong2 v = *reinterpret_cast<const longlong2 *>(partial + ((size_t)b * K + k) * D + 2 * pr);
                 s0 += v.x;
@@ -172,8 +182,16 @@ __global__ __launch_bounds__(256) void k_merge(
                 long long t0 = 0, t1 = 0;
 #pragma unroll
                 for (int q = 0; q < kMergeGroups; ++q) { t0 += comb[q][l][0]; t1 += comb[q][l][1]; }
-                c.x = (float)(ldexp((double)t0, -shift) / (double)n);
-                c.y = (float)(ldexp((double)t1, -shift) / (double)n);
+                double u0 = ldexp((double)t0, -shift), u1 = ldexp((double)t1, -shift);
+                if (online) {
+                    double *rs = run_sum + (size_t)k * D + 2 * pr;
+                    u0 += rs[0];
+                    u1 += rs[1];
+                    rs[0] = u0;
+                    rs[1] = u1;
+                }
+                c.x = (float)(u0 / denom);
+                c.y = (float)(u1 / denom);
                 *dst = c;
             } else {
                 c = *dst;
@@ -185,8 +203,21 @@ __global__ __launch_bounds__(256) void k_merge(
     sq = block_sum(sq, red);
     if (threadIdx.x == 0) {
         hneg[k] = -(float)(0.5 * sq);
-        nk[k] = n;
-        if (counts_out) counts_out[k] = n;
+        nk[k] = s_n;
+        if (counts_out) counts_out[k] = s_n;
+    }
+}
+
+// Running sums of the online mode from the current dictionaries: sum = c * n0 (n0 may be null: zeros).
+__global__ __launch_bounds__(256) void k_online_begin(
+    const float *__restrict__ C, const long long *__restrict__ n0, int64_t total, int D,
+    double *__restrict__ run_sum, long long *__restrict__ run_cnt)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t row = i / D;
+        const long long w = n0 ? n0[row] : 0;
+        run_sum[i] = (double)C[i] * (double)w;
+        if (i == row * D) run_cnt[row] = w;
     }
 }
 

@@ -20,7 +20,8 @@ EXPORTS = (
     "hclae_check_shape", "hclae_create", "hclae_destroy", "hclae_last_error",
     "hclae_encode", "hclae_anneal_stage", "hclae_sweep", "hclae_quant_error",
     "hclae_heat", "hclae_cool", "hclae_assign", "hclae_update", "hclae_last_refined",
-    "hclae_timing_enable", "hclae_timing_read",
+    "hclae_timing_enable", "hclae_timing_read", "hclae_online_begin", "hclae_online_chunk",
+    "hclae_online_export", "hclae_online_import",
 )
 
 KERNEL_CLASSES = ("heat", "cool", "assign", "refine", "accumulate", "merge", "norms", "error")
@@ -75,6 +76,10 @@ def lib():
     L.hclae_assign.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, vp, vp]
     L.hclae_update.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, vp, vp]
     L.hclae_last_refined.argtypes = [vp, ctypes.POINTER(i64)]
+    L.hclae_online_begin.argtypes = [vp, vp, i32, i32, i32, vp]
+    L.hclae_online_chunk.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
+    L.hclae_online_export.argtypes = [vp, vp, vp]
+    L.hclae_online_import.argtypes = [vp, vp, vp]
     L.hclae_timing_enable.argtypes = [vp, ctypes.c_uint32]
     L.hclae_timing_read.argtypes = [vp, ctypes.POINTER(KernelTimes)]
     for name in EXPORTS:
@@ -199,6 +204,39 @@ class Context:
         out = ctypes.c_int64()
         self._chk(lib().hclae_last_refined(self._h, ctypes.byref(out)))
         return out.value
+
+    # ---- online learning -----------------------------------------------------------------
+    def online_begin(self, C, n0=None):
+        pC, _, _ = self._shapes(0, C)
+        w = None
+        if n0 is not None:
+            w = np.ascontiguousarray(n0, np.int64)
+            assert w.shape == (self.M, self.K)
+        self._chk(lib().hclae_online_begin(self._h, pC, self.M, self.K, self.D,
+                                           w.ctypes.data_as(ctypes.c_void_p) if w is not None else None))
+
+    def online_export(self):
+        S = np.empty((self.M, self.K, self.D), np.float64)
+        cnt = np.empty((self.M, self.K), np.int64)
+        self._chk(lib().hclae_online_export(self._h, S.ctypes.data_as(ctypes.c_void_p), cnt.ctypes.data_as(ctypes.c_void_p)))
+        return S, cnt
+
+    def online_import(self, S, cnt):
+        S = np.ascontiguousarray(S, np.float64)
+        cnt = np.ascontiguousarray(cnt, np.int64)
+        assert S.shape == (self.M, self.K, self.D) and cnt.shape == (self.M, self.K)
+        self._chk(lib().hclae_online_import(self._h, S.ctypes.data_as(ctypes.c_void_p), cnt.ctypes.data_as(ctypes.c_void_p)))
+
+    def online_chunk(self, Xu8, C, codes, residue, want_err=False, codes_first=None):
+        n = Xu8.shape[0]
+        if not (Xu8.is_cuda and Xu8.is_contiguous() and tuple(Xu8.shape) == (n, self.D) and str(Xu8.dtype) == "torch.uint8"):
+            raise TypeError("expected a contiguous CUDA uint8 tensor [n][D]")
+        pC, pcodes, pres = self._shapes(n, C, codes, residue)
+        err = ctypes.c_double()
+        self._chk(lib().hclae_online_chunk(self._h, ctypes.c_void_p(Xu8.data_ptr()), n, self.D, pC, self.M, self.K,
+                                           pcodes, pres, _ptr(codes_first, "u8", (n, self.M)),
+                                           ctypes.byref(err) if want_err else None))
+        return err.value if want_err else None
 
     def timing_enable(self, classes):
         """classes: iterable of names from KERNEL_CLASSES (empty = off)."""

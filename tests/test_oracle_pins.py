@@ -345,3 +345,53 @@ def test_thread_count_does_not_change_results(oracle):
     oracle.set_threads(t0)
     for a, b in zip(outs[0], outs[1]):
         np.testing.assert_array_equal(a, b)
+
+
+# ---------------------------------------------------------------- online chunks (Sec. 3.4)
+def test_online_chunk_is_composition_of_pinned_steps(oracle):
+    """With empty running sums an online chunk is, per dictionary, exactly the pinned steps
+    assign -> update -> assign -> cool (one Lloyd iteration on the chunk's residue)."""
+    X8 = synth.sift_like(1500, D=16, dtype=np.uint8)
+    M, K, D = 3, 8, 16
+    Cs, codes_s, r_s = _fresh_state(X8.astype(np.float32), M, K)
+    oracle.sweep(Cs, codes_s, r_s, 1, synth.init_indices(1500, M, K))      # some learned dictionaries
+    C = Cs.copy()
+    S = np.zeros((M, K, D))
+    cnt = np.zeros((M, K), np.int64)
+    codes, r, E = oracle.online_chunk(X8, C, S, cnt)
+    C2 = Cs.copy()
+    codes2 = np.zeros((1500, M), np.uint8)
+    r2 = X8.astype(np.float64)
+    for m in range(M):
+        oracle.assign(r2, C2, codes2, m)
+        oracle.update(r2, codes2, C2, m)
+        oracle.assign(r2, C2, codes2, m)
+        oracle.cool(r2, codes2, C2, m)
+    np.testing.assert_array_equal(codes, codes2)
+    np.testing.assert_allclose(C, C2, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(r, r2, rtol=0, atol=1e-12)
+    assert E == oracle.quant_error(r)
+    assert np.all(cnt.sum(1) == 1500)
+
+
+def test_online_running_mean_closed_form(oracle):
+    """M = 1, K = 2 on a line: after chunk A then chunk B the codeword is the mean of all members
+    it ever received, (n_A mean_A + n_B mean_B) / (n_A + n_B); prior counts weigh the old codeword."""
+    A = np.array([[0], [2], [100], [104]], np.uint8)
+    B = np.array([[4], [6], [110]], np.uint8)
+    C = np.array([[[1.0], [90.0]]])
+    S = np.zeros((1, 2, 1))
+    cnt = np.zeros((1, 2), np.int64)
+    oracle.online_chunk(A, C, S, cnt)
+    np.testing.assert_array_equal(C.reshape(-1), [1.0, 102.0])
+    codes, r, E = oracle.online_chunk(B, C, S, cnt)
+    np.testing.assert_array_equal(C.reshape(-1), [(0 + 2 + 4 + 6) / 4.0, (100 + 104 + 110) / 3.0])
+    np.testing.assert_array_equal(cnt, [[4, 3]])
+    np.testing.assert_array_equal(codes[:, 0], [0, 0, 1])
+    np.testing.assert_allclose(r.reshape(-1), [4 - 3.0, 6 - 3.0, 110 - 314 / 3.0], rtol=0, atol=1e-13)
+    # prior counts: codeword 0 carries the weight of 10 earlier vectors at 1.0
+    C = np.array([[[1.0], [90.0]]])
+    cnt = np.array([[10, 0]], np.int64)
+    S = C * cnt[:, :, None]
+    oracle.online_chunk(A, C, S, cnt)
+    np.testing.assert_allclose(C.reshape(-1), [(10 * 1.0 + 0 + 2) / 12.0, 102.0], rtol=1e-15)
