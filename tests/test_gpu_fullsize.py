@@ -119,3 +119,25 @@ def test_fullsize_sweep_properties(data, oracle):
     # x' here was rebuilt from the rounded residue, so allow the exemption rule only
     assert not bad
     ctx.close()
+
+
+def test_high_capacity_codes_two_sweeps(data):
+    """128-bit codes (M = 16, K = 256) on the SIFT-shaped data: a fresh sweep and an annealing sweep,
+    E after each of the 32 stages never rises; late stages have small residues next to large
+    codeword norms of early dictionaries, the regime where the expanded distance form cancels most."""
+    from paper_1509_05194_amd import hclae
+    X, Xg = data
+    M, T = 16, 2
+    idx = synth.init_indices(N, M, K)
+    ctx = hclae.Context(N, D, M, K)
+    C = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+    codes = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+    r = Xg.clone()
+    E = np.concatenate([ctx.sweep(C, codes, r, T, init_idx=idx), ctx.sweep(C, codes, r, T)])
+    print("M=16 E series:", np.array2string(E, precision=1))
+    assert E.shape == (32,) and np.all(np.diff(E) <= 1e-7 * E[:-1])
+    recon = r.clone()
+    for m in range(M):
+        recon += C[m][codes[:, m].long()]
+    assert (recon - Xg).abs().max().item() <= 2e-5 * 255.0
+    ctx.close()
