@@ -120,14 +120,17 @@ def main():
     }
 
     if not args.no_breakdown:
-        # one more sweep, outside the timed region, with every kernel class bracketed by events
+        # outside the timed region, every kernel class bracketed by events: one sweep as timed (stage
+        # boundaries fused), then the same stages one by one so that heat and cool run as separate passes
         ctx.timing_enable(hclae.KERNEL_CLASSES)
         ctx.sweep(C, codes, r, T, want_err=False)
+        for m in range(M):
+            ctx.anneal_stage(m, C, codes, r, T, want_stats=False)
         ctx.quant_error(r)
         ctx.timing_enable([])
         bt = ctx.timing_read()
         alg_bytes = {"heat": N * (8 * D + 1 + 1), "cool": N * (8 * D + 1 + 1), "accumulate": N * (4 * D + 1),
-                     "error": N * 4 * D}
+                     "error": N * 4 * D, "transition": N * (8 * D + 2 + 2)}
         kernels = {}
         for cls, (ms, n) in bt.items():
             if n == 0:

@@ -175,6 +175,7 @@ enum {
     HCLAE_T_MERGE,      /* merge of the block partials, division, codeword norms            */
     HCLAE_T_NORMS,      /* codeword norms alone                                             */
     HCLAE_T_ERROR,      /* Eq. 1 reduction alone                                            */
+    HCLAE_T_TRANSITION, /* fused stage boundary of hclae_sweep: new residue of m + heat of m+1 */
     HCLAE_T_COUNT
 };
 

@@ -279,16 +279,21 @@ int launch_sqnorm(hclae_ctx *ctx, const float *r, int64_t N, double *part)
 }
 
 // Enqueues one full stage; by-products land in ctx->rec[slot].  No host synchronisation.
+// heated: residue already holds x' of this stage and ctx->part_a its entry error (the previous
+// stage ended with a fused transition).  next: >= 0 ends the stage with the fused transition into
+// that stage instead of the plain new-residue pass.
 int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, float *residue, int iters,
-                  const int64_t *init_idx, int slot)
+                  const int64_t *init_idx, int slot, bool heated = false, int next = -1)
 {
     const int D = ctx->D, K = ctx->K;
     float *Cm = C + (size_t)m * K * D;
     int rc;
     if (init_idx)   // pageable host memory: the copy is staged before the call returns
         HIP_TRY(ctx, hipMemcpyAsync(ctx->seed_idx, init_idx, sizeof(int64_t) * K, hipMemcpyHostToDevice, ctx->stream));
-    const int pb = launch_heat_cool<+1, true>(ctx, m, N, C, codes, residue, ctx->part_a);
-    if (pb < 0) return pb;
+    if (!heated) {
+        const int pb = launch_heat_cool<+1, true>(ctx, m, N, C, codes, residue, ctx->part_a);
+        if (pb < 0) return pb;
+    }
     if (init_idx) {
         hipLaunchKernelGGL(k_seed, dim3(K), dim3(256), 0, ctx->stream, residue, ctx->seed_idx, K, D, Cm);
         HIP_TRY(ctx, hipGetLastError());
@@ -299,12 +304,28 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
         if ((rc = launch_update(ctx, m, N, residue, Cm, codes, nullptr, true)) != HCLAE_OK) return rc;
     }
     if ((rc = launch_assign(ctx, m, N, residue, Cm, codes)) != HCLAE_OK) return rc;
-    const int pa = launch_heat_cool<-1, true>(ctx, m, N, C, codes, residue, ctx->part_b);
-    if (pa < 0) return pa;
+    int pa;
+    if (next < 0) {
+        pa = launch_heat_cool<-1, true>(ctx, m, N, C, codes, residue, ctx->part_b);
+        if (pa < 0) return pa;
+    } else {
+        const RowGeom g = row_geom(D);
+        pa = heat_cool_blocks(N, D, ctx->cus);
+        Timed t_(ctx, HCLAE_T_TRANSITION);
+        hipLaunchKernelGGL(k_transition, dim3(pa), dim3(kStreamThreads), 0, ctx->stream,
+                           residue, codes, Cm, C + (size_t)next * K * D, N, D, ctx->M, m, next, g,
+                           ctx->old_codes, ctx->part_b, ctx->part_chg);
+        HIP_TRY(ctx, hipGetLastError());
+    }
     hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFinishThreads), 0, ctx->stream,
                        ctx->part_a, ctx->part_b, ctx->part_chg, pa, iters > 0 ? ctx->nk : nullptr, K,
                        ctx->refine_count, ctx->rec + slot);
     HIP_TRY(ctx, hipGetLastError());
+    if (next >= 0) {            // the error after this stage is the entry error of the next one
+        double *t = ctx->part_a;
+        ctx->part_a = ctx->part_b;
+        ctx->part_b = t;
+    }
     return HCLAE_OK;
 }
 
@@ -588,7 +609,10 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
     }
     for (int m = 0; m < M; ++m) {
         const int64_t *idx = init_idx ? init_idx + (size_t)m * K : nullptr;
-        if ((rc = enqueue_stage(ctx, m, N, C, codes, residue, iters, idx, m)) != HCLAE_OK) return rc;
+        // without the full re-encode, stage m ends and stage m+1 begins in one fused pass over the residue
+        const bool fuse = (reencode_mode == 0);
+        if ((rc = enqueue_stage(ctx, m, N, C, codes, residue, iters, idx, m, fuse && m > 0,
+                                (fuse && m + 1 < M) ? m + 1 : -1)) != HCLAE_OK) return rc;
         if (idx) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));   // seed_idx scratch is reused by the next stage
         if (reencode_mode == 1) {
             if ((rc = enqueue_encode(ctx, X, N, C, codes, residue)) != HCLAE_OK) return rc;

@@ -93,6 +93,73 @@ __global__ __launch_bounds__(kStreamThreads) void k_heat_cool(
     }
 }
 
+// Stage boundary inside a sweep, one pass instead of two: e_x = x' - c_m(i_m) (end of stage m) followed
+// at once by x'' = e_x + c_j(i_j) (heat of the next stage j).  The intermediate e_x is rounded to fp32
+// exactly as if it had been stored and reloaded, so the result equals cool(m) then heat(j) bit for bit.
+// By-products: sum ||e_x||^2 (error after stage m = error before stage j), codes of stage m changed
+// since its entry, and the code column of stage j saved for its own change count.
+__global__ __launch_bounds__(kStreamThreads) void k_transition(
+    float *__restrict__ r, const uint8_t *__restrict__ codes, const float *__restrict__ Cm, const float *__restrict__ Cj,
+    int64_t N, int D, int M, int m, int j_stage, RowGeom g,
+    uint8_t *__restrict__ old_codes, double *__restrict__ part_err, long long *__restrict__ part_chg)
+{
+    __shared__ double red[kStreamThreads / kWave];
+    constexpr int U = kStreamUnroll;
+    const int cw = 1 << g.lcw;
+    const int tx = threadIdx.x & (cw - 1);
+    const int ty = threadIdx.x >> g.lcw;
+    const int rows = kStreamThreads >> g.lcw;
+    double err = 0.0;
+    long long chg = 0;
+    for (int64_t n0 = (int64_t)blockIdx.x * rows * U + ty; n0 < N; n0 += (int64_t)gridDim.x * rows * U) {
+        int cm[U], cj[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t n = n0 + (int64_t)u * rows;
+            ok[u] = n < N;
+            cm[u] = ok[u] ? (int)codes[n * M + m] : 0;
+            cj[u] = ok[u] ? (int)codes[n * M + j_stage] : 0;
+        }
+        if (tx == 0) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t n = n0 + (int64_t)u * rows;
+                if (ok[u]) {
+                    chg += (old_codes[n] != (uint8_t)cm[u]);
+                    old_codes[n] = (uint8_t)cj[u];
+                }
+            }
+        }
+        for (int c4 = tx; c4 < g.d4; c4 += cw) {
+            floatx4 v[U], a[U], b[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t n = n0 + (int64_t)u * rows;
+                if (ok[u]) {
+                    v[u] = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(r + n * D) + c4);
+                    a[u] = *(reinterpret_cast<const floatx4 *>(Cm + (size_t)cm[u] * D) + c4);
+                    b[u] = *(reinterpret_cast<const floatx4 *>(Cj + (size_t)cj[u] * D) + c4);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t n = n0 + (int64_t)u * rows;
+                if (ok[u]) {
+                    floatx4 w = v[u] - a[u];
+                    err += (double)w.x * w.x + (double)w.y * w.y + (double)w.z * w.z + (double)w.w * w.w;
+                    w = w + b[u];
+                    __builtin_nontemporal_store(w, reinterpret_cast<floatx4 *>(r + n * D) + c4);
+                }
+            }
+        }
+    }
+    const double e = block_sum(err, red);
+    if (threadIdx.x == 0) part_err[blockIdx.x] = e;
+    const double c = block_sum((double)chg, red);
+    if (threadIdx.x == 0) part_chg[blockIdx.x] = (long long)c;
+}
+
 // r <- X (first step of the greedy encoder): four float4 per thread in flight.
 __global__ __launch_bounds__(kFlatThreads) void k_copy(
     floatx4 *__restrict__ dst, const floatx4 *__restrict__ src, int64_t n4)

@@ -24,7 +24,7 @@ EXPORTS = (
     "hclae_online_export", "hclae_online_import",
 )
 
-KERNEL_CLASSES = ("heat", "cool", "assign", "refine", "accumulate", "merge", "norms", "error")
+KERNEL_CLASSES = ("heat", "cool", "assign", "refine", "accumulate", "merge", "norms", "error", "transition")
 
 
 class KernelTimes(ctypes.Structure):

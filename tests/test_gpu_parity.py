@@ -354,3 +354,33 @@ def test_degenerate_shapes(oracle):
     assert L.hclae_heat(ctx._h, 0, 101, 16, None, 2, 4, None, None) == hclae.ESTATE
     assert L.hclae_heat(ctx._h, 2, 10, 16, None, 2, 4, None, None) == hclae.EINVAL
     ctx.close()
+
+
+@pytest.mark.parametrize("case", ["tiny", "sift", "gist"])
+def test_sweep_equals_stage_by_stage(case, oracle):
+    """hclae_sweep fuses the end of stage m with the heat of stage m+1 into one pass; the result must
+    equal calling hclae_anneal_stage for m = 0..M-1 bit for bit, stats included."""
+    c = CASES[case]
+    N, D, M, K = c["N"], c["D"], c["M"], c["K"]
+    X = _data(case)
+    idx = synth.init_indices(N, M, K)
+    ctx = _ctx(N, D, M, K)
+    outs = []
+    for fused in (True, False):
+        C = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+        codes = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+        r = to_dev(X)
+        errs = []
+        for s in range(2):
+            ii = idx if s == 0 else None
+            if fused:
+                errs.append(ctx.sweep(C, codes, r, 2, init_idx=ii))
+            else:
+                errs.append(np.array([ctx.anneal_stage(m, C, codes, r, 2, ii[m] if ii is not None else None)["err_after"]
+                                      for m in range(M)]))
+        outs.append((C, codes, r, np.concatenate(errs)))
+    assert torch.equal(outs[0][0], outs[1][0])
+    assert torch.equal(outs[0][1], outs[1][1])
+    assert torch.equal(outs[0][2], outs[1][2])
+    np.testing.assert_array_equal(outs[0][3], outs[1][3])
+    ctx.close()
