@@ -384,3 +384,30 @@ def test_sweep_equals_stage_by_stage(case, oracle):
     assert torch.equal(outs[0][2], outs[1][2])
     np.testing.assert_array_equal(outs[0][3], outs[1][3])
     ctx.close()
+
+
+@pytest.mark.parametrize("shape", [dict(N=300 + 7, D=4096, M=1, K=256), dict(N=400 + 1, D=4, M=256, K=3),
+                                   dict(N=257, D=64, M=2, K=256)])
+def test_limits_of_the_shape_check(shape, oracle):
+    """Largest D and M the ABI accepts, the smallest D, K = 256 with D = 64 (one register chunk)."""
+    N, D, M, K = shape["N"], shape["D"], shape["M"], shape["K"]
+    g = np.random.default_rng(N)
+    X = g.standard_normal((N, D)).astype(np.float32)
+    idx = np.stack([g.choice(N, K, replace=False) for _ in range(M)]).astype(np.int64)
+    T = 1
+    stages = min(M, 3)
+    C64, codes64, r64 = fresh_state(X, M, K)
+    ctx = _ctx(N, D, M, K)
+    Cg = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+    codes_g = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+    rg = to_dev(X)
+    adopted = 0
+    for m in list(range(stages - 1)) + [M - 1]:
+        adopted += _lockstep_stage(ctx, oracle, m, T, Cg, codes_g, rg, C64, codes64, r64, idx[m])
+    assert rel_fro(Cg.cpu().numpy(), C64) <= 1e-5
+    # with N close to K most vectors are their own codeword and the residue is (nearly) zero:
+    # measure its error against the scale of the data
+    assert np.linalg.norm(rg.cpu().numpy().astype(np.float64) - r64) <= 1e-6 * np.linalg.norm(X)
+    Eo = oracle.quant_error(r64)
+    assert abs(ctx.quant_error(rg) - Eo) <= 1e-5 * Eo + 1e-10 * float((X.astype(np.float64) ** 2).sum(1).mean())
+    ctx.close()
