@@ -61,6 +61,10 @@ def _load():
     lib.da_anneal_stage.restype = ctypes.c_double
     lib.da_sweep.argtypes = [_f64p, _u8p, _f64p, _i64, _int, _int, _int, _int, _i64p, _f64p]
     lib.da_reconstruct.argtypes = [_f64p, _u8p, _i64, _int, _int, _int, _f64p]
+    lib.da_rotate.argtypes = [_f64p, _i64, _int, _f64p, _int, _f64p]
+    lib.da_anneal_stage_pca.argtypes = [_int, _f64p, _u8p, _f64p, _i64, _int, _int, _int, _f64p,
+                                        ctypes.POINTER(ctypes.c_int), _int, _int, _i64p]
+    lib.da_anneal_stage_pca.restype = ctypes.c_double
     lib.da_online_chunk.argtypes = [_u8p, _i64, _int, _int, _int, _f64p, _f64p, _i64p, _u8p, _f64p]
     lib.da_online_chunk.restype = ctypes.c_double
     _lib = lib
@@ -205,3 +209,54 @@ def online_chunk(X_u8, C, S, cnt):
     E = _load().da_online_chunk(_p(X_u8, _u8p), n, D, M, K, _p(C, _f64p), _p(S, _f64p), _p(cnt, _i64p),
                                 _p(codes, _u8p), _p(r, _f64p))
     return codes, r, E
+
+
+def rotate(x, R, transpose=False):
+    """y_n = R x_n (or R^T x_n); x float64 [N][D], R float64 [D][D] with the axes as rows."""
+    _chk(x, np.float64)
+    N, D = x.shape
+    _chk(R, np.float64, (D, D))
+    y = np.empty_like(x)
+    _load().da_rotate(_p(x, _f64p), N, D, _p(R, _f64p), 1 if transpose else 0, _p(y, _f64p))
+    return y
+
+
+def dimension_schedule(D, I=10):
+    """d_i = ceil(D^(i/I)), i = 1..I, duplicates removed (Sec. 3.2: d_i = d^(i/I), I = 10)."""
+    out = []
+    for i in range(1, I + 1):
+        d = int(np.ceil(D ** (i / I) - 1e-9))
+        d = max(1, min(D, d))
+        if not out or d > out[-1]:
+            out.append(d)
+    out[-1] = D
+    return np.array(out, np.int32)
+
+
+def anneal_stage_pca(m, C, codes, r, R, dims, T, init_idx=None):
+    """One DA iteration on dictionary m with the improved k-means of Sec. 3.2 as cool-down."""
+    N, D, M, K = _dims(C, codes, r)
+    _chk(R, np.float64, (D, D))
+    dims = np.ascontiguousarray(dims, np.int32)
+    assert dims[-1] == D and np.all(np.diff(dims) > 0) and dims[0] >= 1
+    if init_idx is not None:
+        init_idx = np.ascontiguousarray(init_idx, np.int64)
+        assert init_idx.shape == (K,)
+    return _load().da_anneal_stage_pca(m, _p(C, _f64p), _p(codes, _u8p), _p(r, _f64p), N, D, M, K, _p(R, _f64p),
+                                       dims.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), len(dims), T,
+                                       _p(init_idx, _i64p))
+
+
+def pca_axes(xp):
+    """Principal axes of {x'} as rows of R (most variance first): eigenvectors of the centred
+    covariance, LAPACK via NumPy; each axis is signed so that its largest-magnitude entry is positive."""
+    x = np.asarray(xp, np.float64)
+    cov = np.cov(x, rowvar=False, bias=True)
+    w, V = np.linalg.eigh(cov)
+    order = np.argsort(-w, kind="stable")
+    R = V[:, order].T.copy()
+    for i in range(R.shape[0]):
+        j = np.argmax(np.abs(R[i]))
+        if R[i, j] < 0:
+            R[i] = -R[i]
+    return np.ascontiguousarray(R)

@@ -284,6 +284,94 @@ double da_online_chunk(const uint8_t *X, int64_t n, int D, int M, int K,
     return da_quant_error(r, n, D);
 }
 
+/*
+ * Sec. 3.2, step 1 / step 3: y_n = R x_n (transpose == 0) or y_n = R^T x_n (transpose != 0),
+ * R: double[D][D] row-major, its rows are the principal axes.  y may not alias x.
+ */
+void da_rotate(const double *x, int64_t N, int D, const double *R, int transpose, double *y)
+{
+    #pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        const double *xn = x + (size_t)n * D;
+        double *yn = y + (size_t)n * D;
+        for (int i = 0; i < D; ++i) {
+            double s = 0.0;
+            for (int j = 0; j < D; ++j)
+                s = s + (transpose ? R[(size_t)j * D + i] : R[(size_t)i * D + j]) * xn[j];
+            yn[i] = s;
+        }
+    }
+}
+
+/* Nearest codeword using only the first dact coordinates (Sec. 3.2, step 2); Cm: double[K][D]. */
+static void assign_prefix(const double *xr, const double *Cm, int64_t N, int D, int dact, int K,
+                          uint8_t *codes, int M, int m)
+{
+    #pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        const double *x = xr + (size_t)n * D;
+        double best = INFINITY;
+        int ibest = 0;
+        for (int k = 0; k < K; ++k) {
+            const double *c = Cm + (size_t)k * D;
+            double s = 0.0;
+            for (int d = 0; d < dact; ++d) {
+                double t = x[d] - c[d];
+                s = s + t * t;
+            }
+            if (k == 0 || s < best) { best = s; ibest = k; }
+        }
+        codes[n * M + m] = (uint8_t)ibest;
+    }
+}
+
+/*
+ * Sec. 3.2, improved k-means as the cool-down of one DA iteration on dictionary m:
+ *   heat (Sec. 3.1); optional seeding; x^r = R x', C' = R C_m;
+ *   for each d in dims[0] < ... < dims[I-1] = D:  T Lloyd iterations whose assignment uses only the
+ *   first d coordinates of x^r and C' and whose centroid update takes the mean over all D
+ *   coordinates (so the clustering found on few dimensions is what the next, larger prefix starts from);
+ *   C_m = R^T C';  final assign in the original space; new residue.
+ * R is an input (principal axes of {x'} as rows, most variance first).  Returns E after the stage.
+ */
+double da_anneal_stage_pca(int m, double *C, uint8_t *codes, double *r,
+                           int64_t N, int D, int M, int K, const double *R,
+                           const int *dims, int I, int T, const int64_t *init_idx)
+{
+    double *Cm = C + (size_t)m * K * D;
+    da_heat(r, codes, C, N, D, M, K, m);
+    if (init_idx)
+        for (int k = 0; k < K; ++k)
+            memcpy(Cm + (size_t)k * D, r + (size_t)init_idx[k] * D, sizeof(double) * D);
+    double *xr = (double *)malloc(sizeof(double) * (size_t)N * D);
+    double *Cp = (double *)malloc(sizeof(double) * (size_t)K * D);
+    double *S = (double *)malloc(sizeof(double) * (size_t)K * D);
+    int64_t *cnt = (int64_t *)malloc(sizeof(int64_t) * (size_t)K);
+    da_rotate(r, N, D, R, 0, xr);
+    da_rotate(Cm, K, D, R, 0, Cp);
+    for (int i = 0; i < I; ++i) {
+        for (int t = 0; t < T; ++t) {
+            assign_prefix(xr, Cp, N, D, dims[i], K, codes, M, m);
+            memset(S, 0, sizeof(double) * (size_t)K * D);
+            memset(cnt, 0, sizeof(int64_t) * (size_t)K);
+            for (int64_t n = 0; n < N; ++n) {
+                const int k = codes[n * M + m];
+                const double *x = xr + (size_t)n * D;
+                for (int d = 0; d < D; ++d) S[(size_t)k * D + d] = S[(size_t)k * D + d] + x[d];
+                cnt[k] += 1;
+            }
+            for (int k = 0; k < K; ++k)
+                if (cnt[k] > 0)
+                    for (int d = 0; d < D; ++d) Cp[(size_t)k * D + d] = S[(size_t)k * D + d] / (double)cnt[k];
+        }
+    }
+    da_rotate(Cp, K, D, R, 1, Cm);
+    free(xr); free(Cp); free(S); free(cnt);
+    da_assign(r, C, N, D, M, K, m, codes, NULL, NULL, NULL);
+    da_cool(r, codes, C, N, D, M, K, m);
+    return da_quant_error(r, N, D);
+}
+
 /* x_hat_n = sum_m c_m(i_m(n)) (used to check x = x_hat + r). */
 void da_reconstruct(const double *C, const uint8_t *codes, int64_t N, int D, int M, int K,
                     double *xhat)

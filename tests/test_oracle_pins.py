@@ -395,3 +395,85 @@ def test_online_running_mean_closed_form(oracle):
     S = C * cnt[:, :, None]
     oracle.online_chunk(A, C, S, cnt)
     np.testing.assert_allclose(C.reshape(-1), [(10 * 1.0 + 0 + 2) / 12.0, 102.0], rtol=1e-15)
+
+
+# ---------------------------------------------------------------- improved k-means (Sec. 3.2)
+def test_dimension_schedule():
+    """d_i = d^(i/I), I = 10, rounded up and deduplicated; printed values for d = 128 are not in the
+    paper, so the schedule is pinned by its defining properties."""
+    for D in (16, 128, 960):
+        d = oracle_dims(D)
+        assert d[-1] == D and np.all(np.diff(d) > 0) and d[0] == int(np.ceil(D ** 0.1 - 1e-9))
+        full = [D ** (i / 10) for i in range(1, 11)]
+        assert all(any(abs(x - np.ceil(f - 1e-9)) < 1e-9 for f in full) for x in d)
+    assert oracle_dims(128).tolist() == [2, 3, 5, 7, 12, 19, 30, 49, 79, 128]
+
+
+def oracle_dims(D):
+    import oracle
+    return oracle.dimension_schedule(D, 10)
+
+
+def test_rotate_against_matmul(oracle):
+    g = np.random.default_rng(5)
+    x = g.standard_normal((37, 6))
+    R = np.linalg.qr(g.standard_normal((6, 6)))[0]
+    np.testing.assert_allclose(oracle.rotate(x, R), x @ R.T, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(oracle.rotate(x, R, transpose=True), x @ R, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(oracle.rotate(oracle.rotate(x, R), R, transpose=True), x, rtol=0, atol=1e-14)
+    # not symmetric: a transposed R gives something else
+    assert np.abs(x @ R.T - x @ R).max() > 1e-3
+
+
+def test_pca_stage_full_dimension_is_rotation_invariant(oracle):
+    """With the single prefix d_1 = D the improved k-means is plain Lloyd seen through an orthogonal
+    map: same codes, same dictionary, same E as the plain stage, for any orthogonal R."""
+    X = synth.tiny_gmm(N=1500)
+    M, K, T = 2, 8, 3
+    idx = synth.init_indices(1500, M, K)
+    C1, codes1, r1 = _fresh_state(X, M, K)
+    C2, codes2, r2 = _fresh_state(X, M, K)
+    R = np.linalg.qr(np.random.default_rng(9).standard_normal((16, 16)))[0]
+    for m in range(M):
+        E1 = oracle.anneal_stage(m, C1, codes1, r1, T, idx[m])
+        E2 = oracle.anneal_stage_pca(m, C2, codes2, r2, R, np.array([16], np.int32), T, idx[m])
+        np.testing.assert_array_equal(codes1, codes2)
+        np.testing.assert_allclose(C2, C1, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(E2, E1, rtol=1e-12)
+
+
+def test_pca_stage_prefix_clusters_on_selected_coordinates(oracle):
+    """R = a coordinate permutation: the first prefix then clusters on exactly those original
+    coordinates.  One phase on d_1 coordinates followed by the full-dimension phase is checked
+    against scikit-learn Lloyd on the selected columns, then on all columns started from the
+    full-dimension means of the first clustering."""
+    from sklearn.cluster import KMeans
+    X = synth.tiny_gmm(N=2000).astype(np.float64)
+    K, T, d1 = 8, 4, 6                        # chosen so that no cluster empties (the empty-cluster rules differ)
+    perm = np.random.default_rng(5).permutation(16)
+    R = np.eye(16)[perm]                      # (R x)_i = x_perm[i]
+    idx = synth.init_indices(2000, 1, K)[0]
+    C, codes, r = _fresh_state(X.astype(np.float32), 1, K)
+    E = oracle.anneal_stage_pca(0, C, codes, r, R, np.array([d1, 16], np.int32), T, idx)
+    sel = perm[:d1]
+    km1 = KMeans(n_clusters=K, init=X[idx][:, sel], n_init=1, algorithm="lloyd", max_iter=T, tol=0.0).fit(X[:, sel])
+    # sklearn's final labels are re-assigned after the last update; the method's memberships are those
+    # of the T-th assignment, i.e. the labels a run with T-1 updates ends with
+    km1b = KMeans(n_clusters=K, init=X[idx][:, sel], n_init=1, algorithm="lloyd", max_iter=T - 1, tol=0.0).fit(X[:, sel])
+    lab = km1b.labels_
+    np.testing.assert_allclose(np.stack([X[lab == k][:, sel].mean(0) for k in range(K)]), km1.cluster_centers_, atol=1e-12)
+    start = np.stack([X[lab == k].mean(0) for k in range(K)])            # means over ALL coordinates
+    km2 = KMeans(n_clusters=K, init=start, n_init=1, algorithm="lloyd", max_iter=T, tol=0.0).fit(X)
+    assert len(np.unique(km2.labels_)) == K
+    np.testing.assert_allclose(C[0], km2.cluster_centers_, rtol=0, atol=1e-11)
+    np.testing.assert_array_equal(codes[:, 0], km2.labels_)
+    np.testing.assert_allclose(E * 2000, km2.inertia_, rtol=1e-12)
+
+
+def test_pca_axes_properties(oracle):
+    X = synth.sift_like(3000, D=32).astype(np.float64)
+    R = oracle.pca_axes(X)
+    np.testing.assert_allclose(R @ R.T, np.eye(32), atol=1e-12)
+    var = oracle.rotate(X - X.mean(0), R).var(0)
+    assert np.all(np.diff(var) <= 1e-9 * var[0])                          # variance descending
+    np.testing.assert_allclose(var.sum(), X.var(0).sum(), rtol=1e-12)     # trace preserved
