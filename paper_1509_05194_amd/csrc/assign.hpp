@@ -30,22 +30,26 @@ struct RefineItem {
     uint32_t mask[2][4];
 };
 
-// -||c_k||^2 / 2 in fp32 (computed in fp64) for k < K, -inf for the padding rows up to kpad.
+// -||c_k||^2 / 2 in fp32 (computed in fp64) over the first D coordinates of rows of stride ld, for
+// k < K; -inf for the padding rows up to kpad.
 // One wave per codeword.  Also resets the two counters the assign that follows will fill
 // (refine_count[0]: re-check entries, refine_count[1]: bits of max |x'|).
 __global__ __launch_bounds__(256) void k_codeword_norms(
-    const float *__restrict__ Cm, int K, int D, int kpad, float *__restrict__ hneg,
-    unsigned *__restrict__ refine_count)
+    const float *__restrict__ Cm, int K, int D, int ld, int kpad, float *__restrict__ hneg,
+    unsigned *__restrict__ refine_count, int keep_absmax)
 {
     const int lane = lane_id();
     const int k = blockIdx.x * (256 / kWave) + (threadIdx.x >> 6);
-    if (blockIdx.x == 0 && threadIdx.x == 0) { refine_count[0] = 0u; refine_count[1] = 0u; }   // re-check count, max |x'| bits
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        refine_count[0] = 0u;                      // re-check entries
+        if (!keep_absmax) refine_count[1] = 0u;    // bits of max |x'|
+    }
     if (k >= kpad) return;
     if (k >= K) {
         if (lane == 0) hneg[k] = -__builtin_inff();
         return;
     }
-    const float *c = Cm + (size_t)k * D;
+    const float *c = Cm + (size_t)k * ld;
     double s = 0.0;
     for (int d = lane; d < D; d += kWave) s += (double)c[d] * (double)c[d];
     s = wave_sum(s);
@@ -57,8 +61,24 @@ __global__ __launch_bounds__(256) void k_codeword_norms(
 // C[32b + r][8s + 4h .. 8s + 4h + 3]; a wave's ds_read_b128 of one (b, s) is one contiguous
 // kilobyte (no bank conflicts), and component j of it is the A operand of the MFMA that
 // contracts dims {8s + j, 8s + 4 + j}.
+// Only the first D coordinates of each row (stride ld) enter; the rest of the image is zero, so
+// whatever x' holds beyond D contributes nothing to the scores.
+__device__ __forceinline__ float4 load_row_piece(const float *__restrict__ base, int row, int col, int K, int D, int ld)
+{
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (row < K && col < D) {
+        v = *reinterpret_cast<const float4 *>(base + (size_t)row * ld + col);
+        if (col + 3 >= D) {                        // D need not be a multiple of 4
+            if (col + 1 >= D) v.y = 0.f;
+            if (col + 2 >= D) v.z = 0.f;
+            v.w = 0.f;
+        }
+    }
+    return v;
+}
+
 __device__ __forceinline__ void stage_codebook(
-    float4 *lds, const float *__restrict__ Cm, int K, int D, int kb, int S)
+    float4 *lds, const float *__restrict__ Cm, int K, int D, int ld, int kb, int S)
 {
     const int total = kb * S * kWave;
     constexpr int U = 8;                                   // gathers in flight per thread
@@ -74,7 +94,7 @@ __device__ __forceinline__ void stage_codebook(
             const int row = 32 * b + (l & 31);
             const int col = 8 * s + 4 * (l >> 5);
             v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (e < total && row < K && col < D) v[u] = *reinterpret_cast<const float4 *>(Cm + (size_t)row * D + col);
+            if (e < total) v[u] = load_row_piece(Cm, row, col, K, D, ld);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -216,7 +236,7 @@ __device__ __forceinline__ void decide(
 template <int KB>
 __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     const float *__restrict__ xp, const float *__restrict__ Cm, const float *__restrict__ hneg,
-    int64_t N, int D, int K, int M, int m, int NC, float eps,
+    int64_t N, int D, int ld, int K, int M, int m, int NC, float eps,
     uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count)
 {
     extern __shared__ float4 smem4[];
@@ -228,7 +248,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     const int h = lane >> 5;
     const int r = lane & 31;
 
-    stage_codebook(lds_c, Cm, K, D, KB, S);
+    stage_codebook(lds_c, Cm, K, D, ld, KB, S);
     for (int k = threadIdx.x; k < 32 * KB; k += blockDim.x) lds_h[k] = hneg[k];
     __syncthreads();
     // largest ||c||^2/2 over the real codewords (every thread computes the same value)
@@ -250,7 +270,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     auto row_ptr = [&](int64_t tile) {
         int64_t n = tile * kTileVec + r;
         if (n >= N) n = N - 1;                                      // tail rows re-read the last vector
-        return xp + n * D;
+        return xp + n * ld;
     };
 
     floatx16 acc[KB];
@@ -292,7 +312,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
 template <int KB>
 __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
     const float *__restrict__ xp, const float *__restrict__ Cm, const float *__restrict__ hneg,
-    int64_t N, int D, int K, int M, int m, int NC, float eps,
+    int64_t N, int D, int ld, int K, int M, int m, int NC, float eps,
     uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count)
 {
     extern __shared__ float4 smem4[];
@@ -315,7 +335,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
     for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
         const int64_t n_raw = (bt * kAssignWaves + wave) * kTileVec + r;
         const int64_t n = n_raw < N ? n_raw : N - 1;
-        const float *xrow = xp + n * D;
+        const float *xrow = xp + n * ld;
         floatx16 acc[KB];
         float4 x[8];
         float xsq = 0.f;
@@ -331,9 +351,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
                 const int b = bs >> 3;
                 const int row = 32 * b + (l & 31);
                 const int col = kChunkD * q + 8 * s + 4 * (l >> 5);
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (row < K && col < D) v = *reinterpret_cast<const float4 *>(Cm + (size_t)row * D + col);
-                lds_c[e] = v;
+                lds_c[e] = load_row_piece(Cm, row, col, K, D, ld);
             }
             __syncthreads();
             mfma_chunk<KB>(acc, x, lds_c, 0, S, lane, xsq, amax);
@@ -347,7 +365,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
 // distances summed in ascending dimension order, smallest wins, exact ties go to the lowest
 // index.  A group of 16 lanes takes one list entry and gives each candidate its own lane.
 __global__ __launch_bounds__(256) void k_refine(
-    const float *__restrict__ xp, const float *__restrict__ Cm, int D, int M, int m,
+    const float *__restrict__ xp, const float *__restrict__ Cm, int D, int ld, int M, int m,
     uint8_t *__restrict__ codes, const RefineItem *__restrict__ list,
     const unsigned *__restrict__ refine_count)
 {
@@ -360,7 +378,7 @@ __global__ __launch_bounds__(256) void k_refine(
         int total = 0;
 #pragma unroll
         for (int w = 0; w < 8; ++w) total += __popc(it.mask[w >> 2][w & 3]);
-        const float4 *x = reinterpret_cast<const float4 *>(xp + (size_t)it.n * D);
+        const float4 *x = reinterpret_cast<const float4 *>(xp + (size_t)it.n * ld);
         double best = __builtin_inf();
         int kbest = 0x7fffffff;
         for (int base = 0; base < total; base += 16) {
@@ -381,7 +399,7 @@ __global__ __launch_bounds__(256) void k_refine(
                         j -= c;
                     }
                 }
-                const float4 *c4 = reinterpret_cast<const float4 *>(Cm + (size_t)k * D);
+                const float4 *c4 = reinterpret_cast<const float4 *>(Cm + (size_t)k * ld);
                 double s = 0.0;
                 for (int d = 0; d < d4; ++d) {
                     const float4 a = x[d], b = c4[d];
@@ -391,6 +409,10 @@ __global__ __launch_bounds__(256) void k_refine(
                     s += t1 * t1;
                     s += t2 * t2;
                     s += t3 * t3;
+                }
+                for (int d = 4 * d4; d < D; ++d) {                  // D need not be a multiple of 4
+                    const double t = (double)reinterpret_cast<const float *>(x)[d] - (double)reinterpret_cast<const float *>(c4)[d];
+                    s += t * t;
                 }
                 if (s < best || (s == best && k < kbest)) { best = s; kbest = k; }
             }

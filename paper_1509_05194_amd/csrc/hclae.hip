@@ -159,28 +159,32 @@ int launch_heat_cool(hclae_ctx *ctx, int m, int64_t N, const float *C, const uin
     return blocks;
 }
 
-int launch_norms(hclae_ctx *ctx, const float *Cm)
+// dact: leading coordinates that count (<= ld); ld: row stride of Cm.
+int launch_norms(hclae_ctx *ctx, const float *Cm, int dact = 0, int ld = 0, bool keep_absmax = false)
 {
+    if (dact <= 0) dact = ctx->D;
+    if (ld <= 0) ld = ctx->D;
     const int kpad = 32 * ctx->kb;
     Timed t_(ctx, HCLAE_T_NORMS);
     hipLaunchKernelGGL(k_codeword_norms, dim3((kpad + 3) / 4), dim3(256), 0, ctx->stream,
-                       Cm, ctx->K, ctx->D, kpad, ctx->hneg, ctx->refine_count);
+                       Cm, ctx->K, dact, ld, kpad, ctx->hneg, ctx->refine_count, keep_absmax ? 1 : 0);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
 
 template <int KB>
-int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float *Cm, uint8_t *codes)
+int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float *Cm, uint8_t *codes, int dact, int ld)
 {
-    const int D = ctx->D;
-    const int dpad = kChunkD * ctx->NC;
+    const int NC = (dact + kChunkD - 1) / kChunkD;
+    const int dpad = kChunkD * NC;
+    const bool resident = (size_t)32 * KB * dpad * sizeof(float) + 4096 <= (size_t)kLdsBudget;
     // twice the worst-case rounding error of a score: (dpad + 1) roundings of relative size 2^-23
     // on partial sums bounded by h + ||x'|| ||c||, plus the rounding of h itself
     const float eps = 2.02f * (float)(dpad + 2) * 1.1920929e-7f;
     {
     Timed t_(ctx, HCLAE_T_ASSIGN);
-    if (ctx->resident) {
-        const size_t lds = (size_t)KB * 8 * ctx->NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
+    if (resident) {
+        const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
         int64_t blocks = (ntiles + kAssignWaves - 1) / kAssignWaves;
         if (blocks > ctx->cus) blocks = ctx->cus;
@@ -191,7 +195,7 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
             attr_set = true;
         }
         hipLaunchKernelGGL((k_assign_resident<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
-                           xp, Cm, ctx->hneg, N, D, ctx->K, ctx->M, m, ctx->NC, eps,
+                           xp, Cm, ctx->hneg, N, dact, ld, ctx->K, ctx->M, m, NC, eps,
                            codes, ctx->refine_list, ctx->refine_count);
     } else {
         const size_t lds = (size_t)KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
@@ -204,33 +208,37 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
             attr_set = true;
         }
         hipLaunchKernelGGL((k_assign_chunked<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
-                           xp, Cm, ctx->hneg, N, D, ctx->K, ctx->M, m, ctx->NC, eps,
+                           xp, Cm, ctx->hneg, N, dact, ld, ctx->K, ctx->M, m, NC, eps,
                            codes, ctx->refine_list, ctx->refine_count);
     }
     }
     HIP_TRY(ctx, hipGetLastError());
     Timed t_(ctx, HCLAE_T_REFINE);
     hipLaunchKernelGGL(k_refine, dim3(ctx->cus * 4), dim3(256), 0, ctx->stream,
-                       xp, Cm, D, ctx->M, m, codes, ctx->refine_list, ctx->refine_count);
+                       xp, Cm, dact, ld, ctx->M, m, codes, ctx->refine_list, ctx->refine_count);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
 
-// Assumes hneg holds the norms of Cm and the re-check counter is zero.
-int launch_assign(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float *Cm, uint8_t *codes)
+// Assumes hneg holds the norms of Cm (over the same dact coordinates) and the re-check counter is zero.
+int launch_assign(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float *Cm, uint8_t *codes,
+                  int dact = 0, int ld = 0)
 {
+    if (dact <= 0) dact = ctx->D;
+    if (ld <= 0) ld = ctx->D;
     switch (ctx->kb) {
-    case 1: return launch_assign_kb<1>(ctx, m, N, xp, Cm, codes);
-    case 2: return launch_assign_kb<2>(ctx, m, N, xp, Cm, codes);
-    case 4: return launch_assign_kb<4>(ctx, m, N, xp, Cm, codes);
-    default: return launch_assign_kb<8>(ctx, m, N, xp, Cm, codes);
+    case 1: return launch_assign_kb<1>(ctx, m, N, xp, Cm, codes, dact, ld);
+    case 2: return launch_assign_kb<2>(ctx, m, N, xp, Cm, codes, dact, ld);
+    case 4: return launch_assign_kb<4>(ctx, m, N, xp, Cm, codes, dact, ld);
+    default: return launch_assign_kb<8>(ctx, m, N, xp, Cm, codes, dact, ld);
     }
 }
 
 // Accumulate + merge; leaves hneg = norms of the new Cm and the re-check counter at zero.
 // have_absmax: refine_count[1] already holds max |xp| (the assign kernel just ran on the same xp).
+// dnorm: leading coordinates whose squares enter the refreshed codeword norms (0 = all).
 int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, const uint8_t *codes,
-                  int32_t *counts, bool have_absmax, bool online = false)
+                  int32_t *counts, bool have_absmax, bool online = false, int dnorm = 0)
 {
     const int D = ctx->D, K = ctx->K;
     const int windows = (D + kUpdWindow - 1) / kUpdWindow;
@@ -260,7 +268,8 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
     HIP_TRY(ctx, hipGetLastError());
     Timed t_(ctx, HCLAE_T_MERGE);
     hipLaunchKernelGGL(k_merge, dim3(K), dim3(256), 0, ctx->stream,
-                       ctx->partial, ctx->pcount, (int)nb, K, D, Cm, ctx->hneg, ctx->nk, counts, ctx->refine_count,
+                       ctx->partial, ctx->pcount, (int)nb, K, D, dnorm > 0 ? dnorm : D, Cm, ctx->hneg, ctx->nk, counts,
+                       ctx->refine_count,
                        online ? ctx->run_sum + (size_t)m * K * D : (double *)nullptr,
                        online ? ctx->run_cnt + (size_t)m * K : (long long *)nullptr);
     HIP_TRY(ctx, hipGetLastError());

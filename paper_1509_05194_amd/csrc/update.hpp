@@ -129,7 +129,7 @@ constexpr int kMergeGroups = 4;
 constexpr int kMergePairs = 256 / kMergeGroups;     // dim pairs per pass
 __global__ __launch_bounds__(256) void k_merge(
     const long long *__restrict__ partial, const int *__restrict__ pcount, int nblk,
-    int K, int D, float *__restrict__ Cm, float *__restrict__ hneg, int *__restrict__ nk,
+    int K, int D, int dnorm, float *__restrict__ Cm, float *__restrict__ hneg, int *__restrict__ nk,
     int *__restrict__ counts_out, unsigned *__restrict__ refine_count,
     double *__restrict__ run_sum, long long *__restrict__ run_cnt)
 {
@@ -196,7 +196,9 @@ __global__ __launch_bounds__(256) void k_merge(
             } else {
                 c = *dst;
             }
-            sq += (double)c.x * c.x + (double)c.y * c.y;
+            // the next assignment may use only the first dnorm coordinates (improved k-means, Sec. 3.2)
+            if (2 * pr < dnorm) sq += (double)c.x * c.x;
+            if (2 * pr + 1 < dnorm) sq += (double)c.y * c.y;
         }
         __syncthreads();
     }
