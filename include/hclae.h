@@ -164,6 +164,35 @@ int hclae_online_chunk(hclae_ctx *ctx, const uint8_t *Xu8, int64_t n, int D, flo
 int hclae_online_export(hclae_ctx *ctx, double *run_sum, int64_t *run_cnt);
 int hclae_online_import(hclae_ctx *ctx, const double *run_sum, const int64_t *run_cnt);
 
+/* ---- improved k-means for high-dimensional residue (Sec. 3.2) --------------------------------- */
+
+/* Second moments of {x'} for its PCA: mean (DEVICE double[D]) and centred covariance (DEVICE
+ * double[D][D], divided by N).  The eigen-decomposition itself is left to the caller: the rows of R
+ * below are the principal axes, most variance first. */
+int hclae_covariance(hclae_ctx *ctx, const float *xp, int64_t N, int D, double *mean, double *cov);
+
+/* Step 1 / step 3 of Sec. 3.2: out_n = R x_n (transpose == 0) or R^T x_n (transpose != 0) for the N rows
+ * of x.  R: DEVICE float[D][D] row-major.  out: DEVICE float[N][D], must not alias x. */
+int hclae_rotate(hclae_ctx *ctx, const float *x, int64_t N, int D, const float *R, int transpose, float *out);
+
+/* Assignment on a prefix (step 2 of Sec. 3.2): codes[n][m] = argmin_k of the squared distance over the
+ * first dact coordinates of xp_n and C[m][k]; rows keep their stride D. */
+int hclae_assign_prefix(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, const float *C,
+                        int M, int K, int dact, uint8_t *codes);
+
+/*
+ * hclae_anneal_stage with the improved k-means as cool-down:
+ *   heat; [seed]; x^r = R x', C' = R C_m;
+ *   for d in dims[0] < ... < dims[n_dims-1] = D: iters_per_dim Lloyd iterations whose assignment uses the
+ *   first d coordinates and whose centroid update is the mean over all D coordinates;
+ *   C_m = R^T C'; re-encode (assign in the original space); new residue.
+ * R: DEVICE float[D][D].  dims: HOST int[n_dims].  xr: DEVICE float[N][D] scratch (caller-owned, holds
+ * x^r on return).  Other arguments as hclae_anneal_stage.
+ */
+int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M, int K,
+                           uint8_t *codes, float *residue, const float *R, const int *dims, int n_dims,
+                           int iters_per_dim, float *xr, const int64_t *init_idx, hclae_stage_stats *stats);
+
 /* ---- measurement: per-kernel durations from HIP events on the ctx's stream ------------- */
 
 enum {
@@ -176,6 +205,8 @@ enum {
     HCLAE_T_NORMS,      /* codeword norms alone                                             */
     HCLAE_T_ERROR,      /* Eq. 1 reduction alone                                            */
     HCLAE_T_TRANSITION, /* fused stage boundary of hclae_sweep: new residue of m + heat of m+1 */
+    HCLAE_T_ROTATE,     /* projection y = R x (Sec. 3.2)                                    */
+    HCLAE_T_MOMENTS,    /* mean and covariance of x' (Sec. 3.2)                             */
     HCLAE_T_COUNT
 };
 

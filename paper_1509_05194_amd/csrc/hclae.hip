@@ -12,6 +12,7 @@
 #include "assign.hpp"
 #include "stream.hpp"
 #include "update.hpp"
+#include "pca.hpp"
 
 using namespace hclae;
 
@@ -54,6 +55,14 @@ struct hclae_ctx {
     double *run_sum;         // [M][K][D]
     long long *run_cnt;      // [M][K]
     long long *n0_dev;       // [M][K] staging of the caller's weights
+    // improved k-means scratch (allocated on first use)
+    float *pca_rt;           // [D][D] transposed rotation
+    float *pca_crot;         // [K][D] rotated dictionary
+    double *pca_colpart;     // [pca_ncol][D]
+    double *pca_grampart;    // [pca_ngram][D][D]
+    double *pca_mean;        // [D]
+    float *pca_mean32;       // [D]
+    int pca_ncol, pca_ngram;
     // optional per-kernel timing (HIP events on ctx->stream)
     uint32_t t_mask;
     int t_used;
@@ -457,7 +466,8 @@ int hclae_destroy(hclae_ctx *ctx)
     if (!ctx) return HCLAE_EINVAL;
     void *dev[] = {ctx->hneg, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
                    ctx->nk, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
-                   ctx->run_sum, ctx->run_cnt, ctx->n0_dev};
+                   ctx->run_sum, ctx->run_cnt, ctx->n0_dev, ctx->pca_rt, ctx->pca_crot, ctx->pca_colpart,
+                   ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32};
     for (void *p : dev)
         if (p) (void)hipFree(p);
     if (ctx->rec_host) (void)hipHostFree(ctx->rec_host);
@@ -728,6 +738,184 @@ int hclae_online_chunk(hclae_ctx *ctx, const uint8_t *Xu8, int64_t n, int D, flo
             if ((rc = fetch_records(ctx, 1)) != HCLAE_OK) return rc;
             *err = ctx->rec_host[0].sum_after / (double)n;
         }
+    }
+    return HCLAE_OK;
+}
+
+// ---- improved k-means (Sec. 3.2) ---------------------------------------------------------------
+
+static int pca_scratch(hclae_ctx *ctx)
+{
+    if (ctx->pca_rt) return HCLAE_OK;
+    const int D = ctx->D, K = ctx->K;
+    ctx->pca_ncol = 256;
+    // Gram partials: ranges of >= 4096 rows, at most 256 MB of them
+    int ng = (int)(((size_t)256 << 20) / ((size_t)D * D * sizeof(double)));
+    if (ng > 256) ng = 256;
+    if (ng < 1) ng = 1;
+    ctx->pca_ngram = ng;
+    hipError_t e = hipMalloc((void **)&ctx->pca_rt, (size_t)D * D * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->pca_crot, (size_t)K * D * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->pca_colpart, (size_t)ctx->pca_ncol * D * sizeof(double));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->pca_grampart, (size_t)ng * D * D * sizeof(double));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->pca_mean, (size_t)D * sizeof(double));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->pca_mean32, (size_t)D * sizeof(float));
+    if (e != hipSuccess) return fail(ctx, e == hipErrorOutOfMemory ? HCLAE_ENOMEM : HCLAE_EHIP, "hipMalloc (PCA scratch)", e);
+    return HCLAE_OK;
+}
+
+// out = x R^T (rows), R given as is; the caller passes the transposed matrix for R^T.
+static int launch_project(hclae_ctx *ctx, const float *x, int64_t N, const float *R, float *out)
+{
+    const int D = ctx->D;
+    const size_t lds = (size_t)8 * 8 * kWave * sizeof(float4);
+    static bool attr_set = false;
+    if (!attr_set) {
+        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_project),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+        attr_set = true;
+    }
+    const int64_t nbt = (N + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);
+    const int groups = (D + 255) / 256;
+    int64_t blocks = nbt < 2 * ctx->cus ? nbt : 2 * ctx->cus;
+    Timed t_(ctx, HCLAE_T_ROTATE);
+    hipLaunchKernelGGL(k_project, dim3((unsigned)blocks, (unsigned)groups), dim3(kAssignThreads), lds, ctx->stream,
+                       x, R, N, D, out);
+    HIP_TRY(ctx, hipGetLastError());
+    return HCLAE_OK;
+}
+
+static int launch_rotate(hclae_ctx *ctx, const float *x, int64_t N, const float *R, int transpose, float *out)
+{
+    if (!transpose) return launch_project(ctx, x, N, R, out);
+    const int D = ctx->D;
+    hipLaunchKernelGGL(k_transpose, dim3((D * D + 255) / 256), dim3(256), 0, ctx->stream, R, D, ctx->pca_rt);
+    HIP_TRY(ctx, hipGetLastError());
+    return launch_project(ctx, x, N, ctx->pca_rt, out);
+}
+
+int hclae_rotate(hclae_ctx *ctx, const float *x, int64_t N, int D, const float *R, int transpose, float *out)
+{
+    if (!ctx) return HCLAE_EINVAL;
+    int rc = hclae_check_shape(N, D, ctx->M, ctx->K);
+    if (rc != HCLAE_OK) return fail(ctx, rc, "shape out of range");
+    if (D != ctx->D) return fail(ctx, HCLAE_ESTATE, "D differs from hclae_create");
+    if (N == 0) return HCLAE_OK;
+    if (!x || !R || !out || x == out) return fail(ctx, HCLAE_EINVAL, "hclae_rotate: bad argument");
+    if ((rc = pca_scratch(ctx)) != HCLAE_OK) return rc;
+    return launch_rotate(ctx, x, N, R, transpose, out);
+}
+
+int hclae_covariance(hclae_ctx *ctx, const float *xp, int64_t N, int D, double *mean, double *cov)
+{
+    if (!ctx) return HCLAE_EINVAL;
+    int rc = hclae_check_shape(N, D, ctx->M, ctx->K);
+    if (rc != HCLAE_OK) return fail(ctx, rc, "shape out of range");
+    if (D != ctx->D) return fail(ctx, HCLAE_ESTATE, "D differs from hclae_create");
+    if (N < 1 || !xp || !mean || !cov) return fail(ctx, HCLAE_EINVAL, "hclae_covariance: bad argument");
+    if ((rc = pca_scratch(ctx)) != HCLAE_OK) return rc;
+    Timed t_(ctx, HCLAE_T_MOMENTS);
+    int ncol = (int)((N + 1023) / 1024);
+    if (ncol > ctx->pca_ncol) ncol = ctx->pca_ncol;
+    const int64_t rpc = (N + ncol - 1) / ncol;
+    ncol = (int)((N + rpc - 1) / rpc);
+    hipLaunchKernelGGL(k_colsum, dim3(ncol), dim3(256), 0, ctx->stream, xp, N, D, rpc, ctx->pca_colpart);
+    HIP_TRY(ctx, hipGetLastError());
+    hipLaunchKernelGGL(k_mean_finish, dim3((D + 255) / 256), dim3(256), 0, ctx->stream,
+                       ctx->pca_colpart, ncol, N, D, mean, ctx->pca_mean32);
+    HIP_TRY(ctx, hipGetLastError());
+    int ng = (int)((N + 4095) / 4096);
+    if (ng > ctx->pca_ngram) ng = ctx->pca_ngram;
+    const int64_t rpg = (N + ng - 1) / ng;
+    ng = (int)((N + rpg - 1) / rpg);
+    const int tiles = (D + 127) / 128;
+    hipLaunchKernelGGL(k_gram_tile, dim3(ng, tiles, tiles), dim3(512), 0, ctx->stream,
+                       xp, ctx->pca_mean32, N, D, rpg, ctx->pca_grampart);
+    HIP_TRY(ctx, hipGetLastError());
+    hipLaunchKernelGGL(k_cov_finish, dim3(stream_blocks(ctx, (int64_t)D * D, 256)), dim3(256), 0, ctx->stream,
+                       ctx->pca_grampart, ng, N, D, mean, ctx->pca_mean32, cov);
+    HIP_TRY(ctx, hipGetLastError());
+    return HCLAE_OK;
+}
+
+int hclae_assign_prefix(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, const float *C,
+                        int M, int K, int dact, uint8_t *codes)
+{
+    int rc = check_call(ctx, N, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (m < 0 || m >= M || dact < 1 || dact > D) return fail(ctx, HCLAE_EINVAL, "hclae_assign_prefix: m or dact out of range");
+    if (N == 0) return HCLAE_OK;
+    if (!C || !codes || !xp) return fail(ctx, HCLAE_EINVAL, "hclae_assign_prefix: NULL pointer");
+    const float *Cm = C + (size_t)m * K * D;
+    if ((rc = launch_norms(ctx, Cm, dact, D)) != HCLAE_OK) return rc;
+    return launch_assign(ctx, m, N, xp, Cm, codes, dact, D);
+}
+
+int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M, int K,
+                           uint8_t *codes, float *residue, const float *R, const int *dims, int n_dims,
+                           int iters_per_dim, float *xr, const int64_t *init_idx, hclae_stage_stats *stats)
+{
+    int rc = check_call(ctx, N, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (m < 0 || m >= M || iters_per_dim < 0 || n_dims < 1 || !dims)
+        return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: bad argument");
+    for (int i = 0; i < n_dims; ++i)
+        if (dims[i] < 1 || dims[i] > D || (i > 0 && dims[i] <= dims[i - 1]))
+            return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: dims must increase within [1, D]");
+    if (dims[n_dims - 1] != D) return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: the last prefix must be D");
+    if (init_idx)
+        for (int i = 0; i < K; ++i)
+            if (init_idx[i] < 0 || init_idx[i] >= N) return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: init_idx out of range");
+    if (N == 0) { if (stats) memset(stats, 0, sizeof(*stats)); return HCLAE_OK; }
+    if (!C || !codes || !residue || !R || !xr || xr == residue)
+        return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: NULL or aliased pointer");
+    if ((rc = pca_scratch(ctx)) != HCLAE_OK) return rc;
+    float *Cm = C + (size_t)m * K * D;
+    const size_t cbytes = (size_t)K * D * sizeof(float);
+    if (init_idx)
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->seed_idx, init_idx, sizeof(int64_t) * K, hipMemcpyHostToDevice, ctx->stream));
+    const int pb = launch_heat_cool<+1, true>(ctx, m, N, C, codes, residue, ctx->part_a);
+    if (pb < 0) return pb;
+    if (init_idx) {
+        hipLaunchKernelGGL(k_seed, dim3(K), dim3(256), 0, ctx->stream, residue, ctx->seed_idx, K, D, Cm);
+        HIP_TRY(ctx, hipGetLastError());
+    }
+    // into the PCA space: x^r = R x', C' = R C_m (C[m] holds C' until it is rotated back)
+    if ((rc = launch_rotate(ctx, residue, N, R, 0, xr)) != HCLAE_OK) return rc;
+    if ((rc = launch_rotate(ctx, Cm, K, R, 0, ctx->pca_crot)) != HCLAE_OK) return rc;
+    HIP_TRY(ctx, hipMemcpyAsync(Cm, ctx->pca_crot, cbytes, hipMemcpyDeviceToDevice, ctx->stream));
+    // max |x^r| over ALL coordinates for the fixed-point centroid sums: a prefix assignment reads only part of a row
+    if ((rc = launch_norms(ctx, Cm, dims[0], D, false)) != HCLAE_OK) return rc;    // zeroes the slot
+    {
+        const int64_t n4 = N * (D / 4);
+        hipLaunchKernelGGL(k_absmax, dim3(stream_blocks(ctx, n4, 256 * 4)), dim3(256), 0, ctx->stream,
+                           reinterpret_cast<const float4 *>(xr), n4, ctx->refine_count + 1);
+        HIP_TRY(ctx, hipGetLastError());
+    }
+    int iters_run = 0;
+    for (int i = 0; i < n_dims; ++i) {
+        if (iters_per_dim > 0 && (rc = launch_norms(ctx, Cm, dims[i], D, true)) != HCLAE_OK) return rc;
+        for (int t = 0; t < iters_per_dim; ++t, ++iters_run) {
+            if ((rc = launch_assign(ctx, m, N, xr, Cm, codes, dims[i], D)) != HCLAE_OK) return rc;
+            if ((rc = launch_update(ctx, m, N, xr, Cm, codes, nullptr, true, false, dims[i])) != HCLAE_OK) return rc;
+        }
+    }
+    // back: C_m = R^T C'
+    if ((rc = launch_rotate(ctx, Cm, K, R, 1, ctx->pca_crot)) != HCLAE_OK) return rc;
+    HIP_TRY(ctx, hipMemcpyAsync(Cm, ctx->pca_crot, cbytes, hipMemcpyDeviceToDevice, ctx->stream));
+    if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
+    if ((rc = launch_assign(ctx, m, N, residue, Cm, codes)) != HCLAE_OK) return rc;
+    const int pa = launch_heat_cool<-1, true>(ctx, m, N, C, codes, residue, ctx->part_b);
+    if (pa < 0) return pa;
+    hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFinishThreads), 0, ctx->stream,
+                       ctx->part_a, ctx->part_b, ctx->part_chg, pa, iters_run > 0 ? ctx->nk : nullptr, K,
+                       ctx->refine_count, ctx->rec);
+    HIP_TRY(ctx, hipGetLastError());
+    if (stats) {
+        if ((rc = fetch_records(ctx, 1)) != HCLAE_OK) return rc;
+        fill_stats(ctx->rec_host[0], N, iters_run, stats);
+    } else if (init_idx) {
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     }
     return HCLAE_OK;
 }

@@ -22,9 +22,11 @@ EXPORTS = (
     "hclae_heat", "hclae_cool", "hclae_assign", "hclae_update", "hclae_last_refined",
     "hclae_timing_enable", "hclae_timing_read", "hclae_online_begin", "hclae_online_chunk",
     "hclae_online_export", "hclae_online_import",
+    "hclae_covariance", "hclae_rotate", "hclae_assign_prefix", "hclae_anneal_stage_pca",
 )
 
-KERNEL_CLASSES = ("heat", "cool", "assign", "refine", "accumulate", "merge", "norms", "error", "transition")
+KERNEL_CLASSES = ("heat", "cool", "assign", "refine", "accumulate", "merge", "norms", "error", "transition",
+                  "rotate", "moments")
 
 
 class KernelTimes(ctypes.Structure):
@@ -80,6 +82,11 @@ def lib():
     L.hclae_online_chunk.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
     L.hclae_online_export.argtypes = [vp, vp, vp]
     L.hclae_online_import.argtypes = [vp, vp, vp]
+    L.hclae_covariance.argtypes = [vp, vp, i64, i32, vp, vp]
+    L.hclae_rotate.argtypes = [vp, vp, i64, i32, vp, i32, vp]
+    L.hclae_assign_prefix.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, i32, vp]
+    L.hclae_anneal_stage_pca.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, vp,
+                                         ctypes.POINTER(StageStats)]
     L.hclae_timing_enable.argtypes = [vp, ctypes.c_uint32]
     L.hclae_timing_read.argtypes = [vp, ctypes.POINTER(KernelTimes)]
     for name in EXPORTS:
@@ -237,6 +244,43 @@ class Context:
                                            pcodes, pres, _ptr(codes_first, "u8", (n, self.M)),
                                            ctypes.byref(err) if want_err else None))
         return err.value if want_err else None
+
+    # ---- improved k-means (Sec. 3.2) -----------------------------------------------------
+    def covariance(self, xp):
+        """(mean float64 [D], cov float64 [D][D]) of the rows of xp, as CUDA tensors."""
+        import torch
+        N = xp.shape[0]
+        mean = torch.empty(self.D, dtype=torch.float64, device=xp.device)
+        cov = torch.empty((self.D, self.D), dtype=torch.float64, device=xp.device)
+        self._chk(lib().hclae_covariance(self._h, _ptr(xp, "f32", (N, self.D)), N, self.D,
+                                         ctypes.c_void_p(mean.data_ptr()), ctypes.c_void_p(cov.data_ptr())))
+        return mean, cov
+
+    def rotate(self, x, R, out, transpose=False):
+        N = x.shape[0]
+        self._chk(lib().hclae_rotate(self._h, _ptr(x, "f32", (N, self.D)), N, self.D, _ptr(R, "f32", (self.D, self.D)),
+                                     1 if transpose else 0, _ptr(out, "f32", (N, self.D))))
+
+    def assign_prefix(self, m, xp, C, codes, dact):
+        N = xp.shape[0]
+        pC, pcodes, pxp = self._shapes(N, C, codes, xp)
+        self._chk(lib().hclae_assign_prefix(self._h, m, N, self.D, pxp, pC, self.M, self.K, int(dact), pcodes))
+
+    def anneal_stage_pca(self, m, C, codes, residue, R, dims, iters_per_dim, xr, init_idx=None, want_stats=True):
+        N = residue.shape[0]
+        pC, pcodes, pres = self._shapes(N, C, codes, residue)
+        dims = np.ascontiguousarray(dims, np.int32)
+        idx = None
+        if init_idx is not None:
+            idx = np.ascontiguousarray(init_idx, np.int64)
+            assert idx.shape == (self.K,)
+        stats = StageStats() if want_stats else None
+        self._chk(lib().hclae_anneal_stage_pca(
+            self._h, m, N, self.D, pC, self.M, self.K, pcodes, pres, _ptr(R, "f32", (self.D, self.D)),
+            dims.ctypes.data_as(ctypes.c_void_p), len(dims), iters_per_dim, _ptr(xr, "f32", (N, self.D)),
+            idx.ctypes.data_as(ctypes.c_void_p) if idx is not None else None,
+            ctypes.byref(stats) if want_stats else None))
+        return stats.as_dict() if want_stats else None
 
     def timing_enable(self, classes):
         """classes: iterable of names from KERNEL_CLASSES (empty = off)."""

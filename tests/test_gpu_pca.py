@@ -1,0 +1,187 @@
+"""Improved k-means for high-dimensional residue (Sec. 3.2 of arXiv 1509.05194) on the GPU against
+the oracle: second moments, rotation, prefix assignment, and the whole cool-down in lockstep."""
+import numpy as np
+import pytest
+
+from paper_1509_05194_amd import synth
+from parity_util import fresh_state, judge_codes, narrow_state, rel_fro, to_dev
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+SHAPES = {
+    "tiny": dict(gen="tiny", N=5000 + 3, D=16, M=2, K=16),
+    "sift": dict(gen="sift", N=12000 + 5, D=128, M=2, K=256),
+    "d132": dict(gen="sift", N=2000 + 1, D=132, M=1, K=40),
+    "gist": dict(gen="gist", N=2500 + 7, D=960, M=1, K=256),
+}
+
+
+def _data(c):
+    if c["gen"] == "tiny":
+        return synth.tiny_gmm(N=c["N"], D=c["D"])
+    if c["gen"] == "sift":
+        return synth.sift_like(c["N"], D=c["D"])
+    return synth.gist_like(c["N"], D=c["D"])
+
+
+def _ctx(c):
+    from paper_1509_05194_amd import hclae
+    return hclae.Context(c["N"], c["D"], c["M"], c["K"])
+
+
+@pytest.mark.parametrize("case", list(SHAPES))
+def test_covariance(case):
+    c = SHAPES[case]
+    X = _data(c)
+    ctx = _ctx(c)
+    mean, cov = ctx.covariance(to_dev(X))
+    X64 = X.astype(np.float64)
+    ref_mean = X64.mean(0)
+    ref = np.cov(X64, rowvar=False, bias=True)
+    assert np.abs(mean.cpu().numpy() - ref_mean).max() <= 1e-12 * max(np.abs(ref_mean).max(), 1.0)
+    err = np.abs(cov.cpu().numpy() - ref).max() / np.abs(ref).max()
+    print("%s covariance: max error %.2e of the largest entry" % (case, err))
+    assert err <= 1e-5
+    ctx.close()
+
+
+@pytest.mark.parametrize("case", list(SHAPES))
+def test_rotate(case, oracle):
+    c = SHAPES[case]
+    X = _data(c)
+    D = c["D"]
+    R = np.linalg.qr(np.random.default_rng(D).standard_normal((D, D)))[0]
+    R32 = np.ascontiguousarray(R, np.float32)
+    ctx = _ctx(c)
+    xg, Rg = to_dev(X), to_dev(R32)
+    out = torch.empty_like(xg)
+    for tr in (False, True):
+        out.fill_(float("nan"))
+        ctx.rotate(xg, Rg, out, transpose=tr)
+        ref = oracle.rotate(X.astype(np.float64), R32.astype(np.float64), transpose=tr)
+        err = np.abs(out.cpu().numpy() - ref).max() / np.abs(ref).max()
+        print("%s rotate(transpose=%s): max error %.2e of the largest entry" % (case, tr, err))
+        assert err <= 1e-5          # fp32 contraction over D terms
+    ctx.close()
+
+
+@pytest.mark.parametrize("case", list(SHAPES))
+def test_assign_prefix(case, oracle):
+    """Distance over the first dact coordinates = full distance with the other coordinates zeroed on
+    both sides, which is how the oracle's (pinned) assign is used here."""
+    c = SHAPES[case]
+    X = _data(c)
+    N, D, M, K = c["N"], c["D"], c["M"], c["K"]
+    g = np.random.default_rng(1)
+    C32 = np.ascontiguousarray(X[g.choice(N, M * K, replace=False)].reshape(M, K, D))
+    ctx = _ctx(c)
+    xg, Cg = to_dev(X), to_dev(C32)
+    for dact in sorted(set([1, 2, 3, 5, min(D, 63), min(D, 66), D])):
+        codes_g = torch.full((N, M), 255, dtype=torch.uint8, device="cuda:0")
+        ctx.assign_prefix(M - 1, xg, Cg, codes_g, dact)
+        xm = X.astype(np.float64)
+        Cm = C32.astype(np.float64)
+        xm[:, dact:] = 0.0
+        Cm[:, :, dact:] = 0.0
+        codes_o = np.zeros((N, M), np.uint8)
+        d1, d2, _ = oracle.assign(xm, Cm, codes_o, M - 1, top2=True)
+        nd, nex, bad = judge_codes(oracle, xm, Cm, M - 1, codes_g.cpu().numpy()[:, M - 1], codes_o[:, M - 1], d1, d2)
+        assert not bad, "dact=%d: %s" % (dact, bad[:5])
+    ctx.close()
+
+
+def _lockstep_pca_stage(ctx, oracle, m, T, dims, Rg, R64, Cg, codes_g, rg, xr_g, C64, codes64, r64, idx):
+    """Drives the stage through the single-step entry points on the GPU and through the pinned
+    primitives on the oracle, adopting exempt near-ties after every assignment."""
+    adopted = 0
+    N, D = r64.shape
+    ctx.heat(m, Cg, codes_g, rg)
+    oracle.heat(r64, codes64, C64, m)
+    if idx is not None:
+        Cg[m] = rg[torch.from_numpy(idx).to(rg.device)]
+        C64[m] = r64[idx]
+    ctx.rotate(rg, Rg, xr_g, transpose=False)
+    crot = torch.empty_like(Cg[m])
+    ctx.rotate(Cg[m].contiguous(), Rg, crot, transpose=False)
+    Cg[m] = crot
+    xr64 = oracle.rotate(r64, R64)
+    Cp = C64.copy()
+    Cp[m] = oracle.rotate(C64[m], R64)
+    assert rel_fro(xr_g.cpu().numpy(), xr64) <= 1e-5 and rel_fro(Cg[m].cpu().numpy(), Cp[m]) <= 1e-5
+    # step-locked from here: the k-means on prefixes starts from the GPU's rotated data and dictionary
+    # (the rotation is an fp32 contraction, good to 1e-5; checked just above and in test_rotate)
+    xr64 = xr_g.cpu().numpy().astype(np.float64)
+    Cp[m] = Cg[m].cpu().numpy().astype(np.float64)
+    for d in dims:
+        for t in range(T):
+            ctx.assign_prefix(m, xr_g, Cg, codes_g, int(d))
+            xm, Cm = xr64.copy(), Cp.copy()
+            xm[:, d:] = 0.0
+            Cm[m][:, d:] = 0.0
+            d1, d2, _ = oracle.assign(xm, Cm, codes64, m, top2=True)
+            got = codes_g.cpu().numpy()[:, m]
+            nd, nex, bad = judge_codes(oracle, xm, Cm, m, got, codes64[:, m], d1, d2)
+            assert not bad, "prefix %d iteration %d: %s" % (d, t, bad[:5])
+            adopted += nex
+            codes64[:, m] = got
+            ctx.update(m, xr_g, Cg, codes_g)
+            oracle.update(xr64, codes64, Cp, m)
+            assert rel_fro(Cg[m].cpu().numpy(), Cp[m]) <= 2e-5
+    back = torch.empty_like(Cg[m])
+    ctx.rotate(Cg[m].contiguous(), Rg, back, transpose=True)
+    Cg[m] = back
+    C64[m] = oracle.rotate(Cp[m], R64, transpose=True)
+    assert rel_fro(Cg[m].cpu().numpy(), C64[m]) <= 2e-5
+    C64[m] = Cg[m].cpu().numpy().astype(np.float64)                   # step-locked re-encode
+    ctx.assign(m, rg, Cg, codes_g)
+    d1, d2, _ = oracle.assign(r64, C64, codes64, m, top2=True)
+    got = codes_g.cpu().numpy()[:, m]
+    nd, nex, bad = judge_codes(oracle, r64, C64, m, got, codes64[:, m], d1, d2)
+    assert not bad, "re-encode: %s" % bad[:5]
+    adopted += nex
+    codes64[:, m] = got
+    ctx.cool(m, Cg, codes_g, rg)
+    oracle.cool(r64, codes64, C64, m)
+    return adopted
+
+
+@pytest.mark.parametrize("case", ["tiny", "sift", "gist"])
+def test_pca_stage_lockstep_and_entry_point(case, oracle):
+    from paper_1509_05194_amd import hclae
+    c = SHAPES[case]
+    N, D, M, K = c["N"], c["D"], c["M"], c["K"]
+    T = 2 if case != "gist" else 1
+    X = _data(c)
+    idx = synth.init_indices(N, M, K)
+    dims = oracle.dimension_schedule(D, 10)
+    if case == "gist":
+        dims = dims[[1, 4, 7, 9]]                                     # keep the oracle's share of the test short
+    ctx = _ctx(c)
+    C64, codes64, r64 = fresh_state(X, M, K)
+    Cg = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+    codes_g = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+    rg = to_dev(X)
+    xr_g = torch.empty_like(rg)
+    # a second GPU state driven through the one-call entry point
+    C2, codes2, r2, xr2 = Cg.clone(), codes_g.clone(), rg.clone(), torch.empty_like(rg)
+    adopted = 0
+    for m in range(M):
+        # principal axes of the GPU's own x' (heat of a fresh stage is the identity: x' = residue)
+        mean, cov = ctx.covariance(rg)
+        w, V = np.linalg.eigh(cov.cpu().numpy())
+        R64 = np.ascontiguousarray(V[:, np.argsort(-w, kind="stable")].T)
+        R32 = R64.astype(np.float32)
+        R64 = R32.astype(np.float64)                                  # both sides use the same fp32 matrix
+        Rg = to_dev(R32)
+        adopted += _lockstep_pca_stage(ctx, oracle, m, T, dims, Rg, R64, Cg, codes_g, rg, xr_g,
+                                       C64, codes64, r64, idx[m])
+        Eg, Eo = ctx.quant_error(rg), oracle.quant_error(r64)
+        assert abs(Eg - Eo) <= 1e-4 * Eo
+        assert rel_fro(rg.cpu().numpy(), r64) <= 1e-4
+        st = ctx.anneal_stage_pca(m, C2, codes2, r2, Rg, dims, T, xr2, init_idx=idx[m])
+        assert torch.equal(C2, Cg) and torch.equal(codes2, codes_g) and torch.equal(r2, rg)
+        assert st["iters_run"] == T * len(dims) and abs(st["err_after"] - Eg) <= 1e-12 * Eg
+    print("%s improved k-means: adopted %d near-ties; E after the stages %.6g" % (case, adopted, Eg))
+    assert rel_fro(Cg.cpu().numpy(), C64) <= 1e-4
+    ctx.close()
