@@ -749,9 +749,9 @@ static int pca_scratch(hclae_ctx *ctx)
     if (ctx->pca_rt) return HCLAE_OK;
     const int D = ctx->D, K = ctx->K;
     ctx->pca_ncol = 256;
-    // Gram partials: ranges of >= 4096 rows, at most 256 MB of them
+    // Gram partials: ranges of >= 1024 rows, at most 256 MB of them
     int ng = (int)(((size_t)256 << 20) / ((size_t)D * D * sizeof(double)));
-    if (ng > 256) ng = 256;
+    if (ng > 2048) ng = 2048;
     if (ng < 1) ng = 1;
     ctx->pca_ngram = ng;
     hipError_t e = hipMalloc((void **)&ctx->pca_rt, (size_t)D * D * sizeof(float));
@@ -819,12 +819,12 @@ int hclae_covariance(hclae_ctx *ctx, const float *xp, int64_t N, int D, double *
     if (ncol > ctx->pca_ncol) ncol = ctx->pca_ncol;
     const int64_t rpc = (N + ncol - 1) / ncol;
     ncol = (int)((N + rpc - 1) / rpc);
-    hipLaunchKernelGGL(k_colsum, dim3(ncol), dim3(256), 0, ctx->stream, xp, N, D, rpc, ctx->pca_colpart);
+    hipLaunchKernelGGL(k_colsum, dim3(ncol), dim3(256), 0, ctx->stream, xp, N, D, rpc, row_geom(D).lcw, ctx->pca_colpart);
     HIP_TRY(ctx, hipGetLastError());
     hipLaunchKernelGGL(k_mean_finish, dim3((D + 255) / 256), dim3(256), 0, ctx->stream,
                        ctx->pca_colpart, ncol, N, D, mean, ctx->pca_mean32);
     HIP_TRY(ctx, hipGetLastError());
-    int ng = (int)((N + 4095) / 4096);
+    int ng = (int)((N + 1023) / 1024);
     if (ng > ctx->pca_ngram) ng = ctx->pca_ngram;
     const int64_t rpg = (N + ng - 1) / ng;
     ng = (int)((N + rpg - 1) / rpg);

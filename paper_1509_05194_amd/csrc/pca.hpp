@@ -76,23 +76,45 @@ __global__ __launch_bounds__(256) void k_transpose(const float *__restrict__ src
 }
 
 // ---------------------------------------------------------------------------------------------
-// Column sums of x in fp64: part[blockIdx.x][d] over a contiguous range of rows.
+// Column sums of x in fp64: part[blockIdx.x][d] over a contiguous range of rows.  A block is
+// (1 << lcw) float4-column threads by (256 >> lcw) row groups; four rows per thread in flight; the row
+// groups are combined through LDS in ascending order.
 __global__ __launch_bounds__(256) void k_colsum(
-    const float *__restrict__ x, int64_t N, int D, int64_t rows_per_block, double *__restrict__ part)
+    const float *__restrict__ x, int64_t N, int D, int64_t rows_per_block, int lcw, double *__restrict__ part)
 {
+    __shared__ double comb[256][4];
+    const int cw = 1 << lcw, groups = 256 >> lcw;
+    const int tx = threadIdx.x & (cw - 1), ty = threadIdx.x >> lcw;
+    const int d4 = D >> 2;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
     const int64_t r1 = (r0 + rows_per_block < N) ? r0 + rows_per_block : N;
-    for (int d = threadIdx.x; d < D; d += 256) {
+    for (int c0 = 0; c0 < d4; c0 += cw) {
+        const int c4 = c0 + tx;
         double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-        int64_t n = r0;
-        for (; n + 3 < r1; n += 4) {
-            s0 += (double)x[n * D + d];
-            s1 += (double)x[(n + 1) * D + d];
-            s2 += (double)x[(n + 2) * D + d];
-            s3 += (double)x[(n + 3) * D + d];
+        if (c4 < d4) {
+            for (int64_t n = r0 + ty; n < r1; n += 4 * groups) {
+                float4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t row = n + (int64_t)u * groups;
+                    v[u] = (row < r1) ? *(reinterpret_cast<const float4 *>(x + row * D) + c4) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { s0 += (double)v[u].x; s1 += (double)v[u].y; s2 += (double)v[u].z; s3 += (double)v[u].w; }
+            }
         }
-        for (; n < r1; ++n) s0 += (double)x[n * D + d];
-        part[(size_t)blockIdx.x * D + d] = (s0 + s1) + (s2 + s3);
+        comb[threadIdx.x][0] = s0; comb[threadIdx.x][1] = s1; comb[threadIdx.x][2] = s2; comb[threadIdx.x][3] = s3;
+        __syncthreads();
+        if (ty == 0 && c4 < d4) {
+            double t0 = 0.0, t1 = 0.0, t2 = 0.0, t3 = 0.0;
+            for (int g = 0; g < groups; ++g) {
+                const double *q = comb[g * cw + tx];
+                t0 += q[0]; t1 += q[1]; t2 += q[2]; t3 += q[3];
+            }
+            double *o = part + (size_t)blockIdx.x * D + 4 * c4;
+            o[0] = t0; o[1] = t1; o[2] = t2; o[3] = t3;
+        }
+        __syncthreads();
     }
 }
 
@@ -119,32 +141,52 @@ __global__ __launch_bounds__(512) void k_gram_tile(
     double sum0[16], sum1[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) { acc0[v] = 0.f; acc1[v] = 0.f; sum0[v] = 0.0; sum1[v] = 0.0; }
-    constexpr int U = 8;                                            // row pairs in flight
-    constexpr int kFlush = 256;                                     // rows summed in fp32 before moving to fp64
-    for (int64_t n = r0; n < r1; n += 2 * U) {
-        if (n > r0 && ((n - r0) % kFlush) == 0) {
-            // the matrix cores' fp32 accumulation error grows with the number of terms: keep runs short
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                sum0[v] += (double)acc0[v]; sum1[v] += (double)acc1[v];
-                acc0[v] = 0.f; acc1[v] = 0.f;
-            }
-        }
-        float a[U], b0[U], b1[U];
+    constexpr int U = 8;                                            // row pairs per batch
+    constexpr int kFlush = 256 / (2 * U);                           // batches summed in fp32 before moving to fp64
+    // Loads are unconditional (row and column clamped into range) and masked afterwards: guarded loads
+    // would be serialised by the branches around them.
+    const int ca = ai ? i0 + c : 0, cb0 = bj0 ? j0 + c : 0, cb1 = bj1 ? j0 + 32 + c : 0;
+    const float *xa = x + ca, *xb0 = x + cb0, *xb1 = x + cb1;
+    const float fa = ai ? 1.f : 0.f, fb0 = bj0 ? 1.f : 0.f, fb1 = bj1 ? 1.f : 0.f;
+    auto fetch = [&](int64_t n, float (&a)[U], float (&b0)[U], float (&b1)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t row = n + 2 * u + h;
             const bool ok = row < r1;
-            const float *p = x + row * D;
-            a[u] = (ok && ai) ? p[i0 + c] - ma : 0.f;
-            b0[u] = (ok && bj0) ? p[j0 + c] - mb0 : 0.f;
-            b1[u] = (ok && bj1) ? p[j0 + 32 + c] - mb1 : 0.f;
+            const int64_t off = (ok ? row : r1 - 1) * D;
+            const float va = xa[off], vb0 = xb0[off], vb1 = xb1[off];
+            const float live = ok ? 1.f : 0.f;                      // a product keeps the loads unconditional
+            a[u] = (va - ma) * (live * fa);
+            b0[u] = (vb0 - mb0) * (live * fb0);
+            b1[u] = (vb1 - mb1) * (live * fb1);
         }
+    };
+    auto contract = [&](const float (&a)[U], const float (&b0)[U], const float (&b1)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b0[u], acc0, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b1[u], acc1, 0, 0, 0);
         }
+    };
+    auto flush = [&]() {
+        // the matrix cores' fp32 accumulation error grows with the number of terms: keep runs short
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            sum0[v] += (double)acc0[v]; sum1[v] += (double)acc1[v];
+            acc0[v] = 0.f; acc1[v] = 0.f;
+        }
+    };
+    // two register sets: the next batch of rows is in flight while the current one is contracted
+    float a0[U], p0[U], q0[U], a1[U], p1[U], q1[U];
+    fetch(r0, a0, p0, q0);
+    int batch = 0;
+    for (int64_t n = r0; n < r1; n += 4 * U) {
+        fetch(n + 2 * U, a1, p1, q1);
+        contract(a0, p0, q0);
+        if (++batch % kFlush == 0) flush();
+        fetch(n + 4 * U, a0, p0, q0);
+        contract(a1, p1, q1);
+        if (++batch % kFlush == 0) flush();
     }
     double *out = part + (size_t)blockIdx.x * D * D;
 #pragma unroll
@@ -178,8 +220,16 @@ __global__ __launch_bounds__(256) void k_cov_finish(
 {
     for (int e = blockIdx.x * 256 + threadIdx.x; e < D * D; e += gridDim.x * 256) {
         const int i = e / D, j = e - i * D;
-        double g = 0.0;
-        for (int b = 0; b < ngram; ++b) g += grampart[(size_t)b * D * D + e];
+        double g0 = 0.0, g1 = 0.0, g2 = 0.0, g3 = 0.0;
+        int b = 0;
+        for (; b + 3 < ngram; b += 4) {
+            g0 += grampart[(size_t)b * D * D + e];
+            g1 += grampart[(size_t)(b + 1) * D * D + e];
+            g2 += grampart[(size_t)(b + 2) * D * D + e];
+            g3 += grampart[(size_t)(b + 3) * D * D + e];
+        }
+        for (; b < ngram; ++b) g0 += grampart[(size_t)b * D * D + e];
+        const double g = (g0 + g1) + (g2 + g3);
         cov[e] = g / (double)N - (mean[i] - (double)mean32[i]) * (mean[j] - (double)mean32[j]);
     }
 }
