@@ -17,10 +17,10 @@ import numpy as np
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0             # MI355X HBM3E peak
 
-# HBM bytes per N=1M launch of the assign kernel from two rocprofv3 --pmc runs (FETCH_SIZE 250,678.5 KiB
-# x 2.000, WRITE_SIZE 9,030.9 KiB x 1.000; factors from a 512 MB device copy in the same runs), recorded
+# HBM bytes per N=1M launch of the assign kernel from two rocprofv3 --pmc runs (FETCH_SIZE 250,693.0 KiB
+# x 2.000, WRITE_SIZE 8,961.3 KiB x 1.000; factors from a 512 MB device copy in the same runs), recorded
 # in profiles/da_sweep_sift1m_counters.md.  Algorithmic bytes are 513e6.
-ASSIGN_TRAFFIC_BYTES = 5.226e8
+ASSIGN_TRAFFIC_BYTES = 5.226e8   # (250693.0 * 2.000 + 8961.3) KiB
 
 
 def main():
