@@ -193,6 +193,23 @@ int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, in
                            uint8_t *codes, float *residue, const float *R, const int *dims, int n_dims,
                            int iters_per_dim, float *xr, const int64_t *init_idx, hclae_stage_stats *stats);
 
+/* ---- dictionary order and code statistics (Sec. 3.3, Sec. 2.2) --------------------------------- */
+
+/* Sec. 3.3: "rearrange the dictionaries in the descending order of dictionary's elements variance".
+ * The variance of dictionary m is read as (1/K) sum_k ||c_m(k) - mean_k c_m||^2.  Writes var (HOST
+ * double[M], variances in the OLD order) and order (HOST int[M]: new position j holds old dictionary
+ * order[j]; ties keep the lower old index), then permutes C and the columns of codes accordingly, in place.
+ * The residue is unchanged (the sum of the selected codewords does not depend on their order).
+ * var and order may be NULL.  Synchronises the stream. */
+int hclae_reorder_by_variance(hclae_ctx *ctx, int64_t N, int D, float *C, int M, int K, uint8_t *codes,
+                              double *var, int *order);
+
+/* Sec. 2.2: counts behind the self-information H(I_m) and the mutual information of two code parts.
+ * hist: HOST int64[M][K], hist[m][k] = #{n : codes[n][m] == k}.  joint: HOST int64[K][K] for the pair of
+ * columns (a, b), joint[i][j] = #{n : codes[n][a] == i and codes[n][b] == j}; may be NULL.  Synchronises. */
+int hclae_code_stats(hclae_ctx *ctx, const uint8_t *codes, int64_t N, int M, int K,
+                     int64_t *hist, int a, int b, int64_t *joint);
+
 /* ---- measurement: per-kernel durations from HIP events on the ctx's stream ------------- */
 
 enum {

@@ -260,3 +260,39 @@ def pca_axes(xp):
         if R[i, j] < 0:
             R[i] = -R[i]
     return np.ascontiguousarray(R)
+
+
+# ---- dictionary order and code statistics (Sec. 3.3, Sec. 2.2): plain NumPy definitions ----------
+def dictionary_variances(C):
+    """var_m = (1/K) sum_k ||c_m(k) - mean_k c_m||^2 (the reading taken of "variance of a dictionary's elements")."""
+    C = np.asarray(C, np.float64)
+    return ((C - C.mean(axis=1, keepdims=True)) ** 2).sum(axis=2).mean(axis=1)
+
+
+def variance_order(C):
+    """Dictionaries in descending variance; ties keep the lower index.  order[j] = old index at new position j."""
+    v = dictionary_variances(C)
+    return np.array(sorted(range(len(v)), key=lambda j: (-v[j], j)), np.int32)
+
+
+def code_histogram(codes, K):
+    return np.stack([np.bincount(codes[:, m], minlength=K) for m in range(codes.shape[1])]).astype(np.int64)
+
+
+def joint_histogram(codes, a, b, K):
+    J = np.zeros((K, K), np.int64)
+    np.add.at(J, (codes[:, a].astype(np.int64), codes[:, b].astype(np.int64)), 1)
+    return J
+
+
+def entropy_bits(counts):
+    """Plug-in entropy of a count table, in bits (Sec. 2.2: self-information of a code part)."""
+    c = np.asarray(counts, np.float64).reshape(-1)
+    p = c[c > 0] / c.sum()
+    return float(-(p * np.log2(p)).sum())
+
+
+def mutual_information_bits(joint):
+    """I(A;B) = H(A) + H(B) - H(A,B) from the joint count table."""
+    J = np.asarray(joint, np.float64)
+    return entropy_bits(J.sum(1)) + entropy_bits(J.sum(0)) - entropy_bits(J)

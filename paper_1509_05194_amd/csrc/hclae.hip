@@ -13,6 +13,9 @@
 #include "stream.hpp"
 #include "update.hpp"
 #include "pca.hpp"
+#include "stats.hpp"
+#include <algorithm>
+#include <vector>
 
 using namespace hclae;
 
@@ -917,6 +920,78 @@ int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, in
     } else if (init_idx) {
         HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     }
+    return HCLAE_OK;
+}
+
+// ---- dictionary order and code statistics ------------------------------------------------------
+
+int hclae_reorder_by_variance(hclae_ctx *ctx, int64_t N, int D, float *C, int M, int K, uint8_t *codes,
+                              double *var, int *order)
+{
+    int rc = check_call(ctx, N, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (!C || (N > 0 && !codes)) return fail(ctx, HCLAE_EINVAL, "hclae_reorder_by_variance: NULL pointer");
+    const size_t per = (size_t)K * D;
+    double *dvar = nullptr;
+    int *dorder = nullptr;
+    float *tmp = nullptr;
+    hipError_t e = hipMalloc((void **)&dvar, sizeof(double) * M);
+    if (e == hipSuccess) e = hipMalloc((void **)&dorder, sizeof(int) * M);
+    if (e == hipSuccess) e = hipMalloc((void **)&tmp, sizeof(float) * M * per);
+    auto cleanup = [&]() { if (dvar) (void)hipFree(dvar); if (dorder) (void)hipFree(dorder); if (tmp) (void)hipFree(tmp); };
+    if (e != hipSuccess) { cleanup(); return fail(ctx, HCLAE_ENOMEM, "hipMalloc (reorder scratch)", e); }
+    std::vector<double> hv(M);
+    std::vector<int> ho(M);
+    hipLaunchKernelGGL(k_dictionary_variance, dim3(M), dim3(256), 0, ctx->stream, C, K, D, dvar);
+    e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(hv.data(), dvar, sizeof(double) * M, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) { cleanup(); return fail(ctx, HCLAE_EHIP, "dictionary variance", e); }
+    for (int j = 0; j < M; ++j) ho[j] = j;
+    std::stable_sort(ho.begin(), ho.end(), [&](int x, int y) { return hv[x] > hv[y]; });
+    e = hipMemcpyAsync(dorder, ho.data(), sizeof(int) * M, hipMemcpyHostToDevice, ctx->stream);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(k_permute_dictionaries, dim3(stream_blocks(ctx, (int64_t)(M * per), 256)), dim3(256), 0, ctx->stream,
+                           C, dorder, M, per, tmp);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(C, tmp, sizeof(float) * M * per, hipMemcpyDeviceToDevice, ctx->stream);
+    if (e == hipSuccess && N > 0) {
+        hipLaunchKernelGGL(k_permute_code_columns, dim3(stream_blocks(ctx, N, 256)), dim3(256), 0, ctx->stream,
+                           codes, dorder, N, M);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    cleanup();
+    if (e != hipSuccess) return fail(ctx, HCLAE_EHIP, "reorder", e);
+    if (var) for (int j = 0; j < M; ++j) var[j] = hv[j];
+    if (order) for (int j = 0; j < M; ++j) order[j] = ho[j];
+    return HCLAE_OK;
+}
+
+int hclae_code_stats(hclae_ctx *ctx, const uint8_t *codes, int64_t N, int M, int K,
+                     int64_t *hist, int a, int b, int64_t *joint)
+{
+    int rc = check_call(ctx, N, ctx ? ctx->D : 4, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (!hist || (N > 0 && !codes)) return fail(ctx, HCLAE_EINVAL, "hclae_code_stats: NULL pointer");
+    if (joint && (a < 0 || a >= M || b < 0 || b >= M)) return fail(ctx, HCLAE_EINVAL, "hclae_code_stats: column out of range");
+    const size_t nh = (size_t)M * K, nj = joint ? (size_t)K * K : 0;
+    unsigned long long *dev = nullptr;
+    hipError_t e = hipMalloc((void **)&dev, sizeof(unsigned long long) * (nh + nj));
+    if (e != hipSuccess) return fail(ctx, HCLAE_ENOMEM, "hipMalloc (code statistics)", e);
+    hipLaunchKernelGGL(k_zero_u64, dim3(stream_blocks(ctx, (int64_t)(nh + nj), 256)), dim3(256), 0, ctx->stream, dev, nh + nj);
+    e = hipGetLastError();
+    if (e == hipSuccess && N > 0) {
+        hipLaunchKernelGGL(k_code_histograms, dim3(stream_blocks(ctx, N, 256)), dim3(256), 0, ctx->stream,
+                           codes, N, M, K, a, b, dev, joint ? dev + nh : (unsigned long long *)nullptr);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(hist, dev, sizeof(int64_t) * nh, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess && joint) e = hipMemcpyAsync(joint, dev + nh, sizeof(int64_t) * nj, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    (void)hipFree(dev);
+    if (e != hipSuccess) return fail(ctx, HCLAE_EHIP, "code statistics", e);
     return HCLAE_OK;
 }
 

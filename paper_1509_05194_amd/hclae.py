@@ -23,6 +23,7 @@ EXPORTS = (
     "hclae_timing_enable", "hclae_timing_read", "hclae_online_begin", "hclae_online_chunk",
     "hclae_online_export", "hclae_online_import",
     "hclae_covariance", "hclae_rotate", "hclae_assign_prefix", "hclae_anneal_stage_pca",
+    "hclae_reorder_by_variance", "hclae_code_stats",
 )
 
 KERNEL_CLASSES = ("heat", "cool", "assign", "refine", "accumulate", "merge", "norms", "error", "transition",
@@ -87,6 +88,8 @@ def lib():
     L.hclae_assign_prefix.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, i32, vp]
     L.hclae_anneal_stage_pca.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, vp,
                                          ctypes.POINTER(StageStats)]
+    L.hclae_reorder_by_variance.argtypes = [vp, i64, i32, vp, i32, i32, vp, vp, vp]
+    L.hclae_code_stats.argtypes = [vp, vp, i64, i32, i32, vp, i32, i32, vp]
     L.hclae_timing_enable.argtypes = [vp, ctypes.c_uint32]
     L.hclae_timing_read.argtypes = [vp, ctypes.POINTER(KernelTimes)]
     for name in EXPORTS:
@@ -281,6 +284,28 @@ class Context:
             idx.ctypes.data_as(ctypes.c_void_p) if idx is not None else None,
             ctypes.byref(stats) if want_stats else None))
         return stats.as_dict() if want_stats else None
+
+    # ---- dictionary order and code statistics ---------------------------------------------
+    def reorder_by_variance(self, C, codes):
+        """Permutes C and the code columns in place; returns (variances in the old order, order)."""
+        N = codes.shape[0]
+        pC, pcodes, _ = self._shapes(N, C, codes)
+        var = np.zeros(self.M, np.float64)
+        order = np.zeros(self.M, np.int32)
+        self._chk(lib().hclae_reorder_by_variance(self._h, N, self.D, pC, self.M, self.K, pcodes,
+                                                  var.ctypes.data_as(ctypes.c_void_p), order.ctypes.data_as(ctypes.c_void_p)))
+        return var, order
+
+    def code_stats(self, codes, pair=None):
+        """hist int64 [M][K] and, for pair=(a, b), the joint counts int64 [K][K] (else None)."""
+        N = codes.shape[0]
+        _, pcodes, _ = self._shapes(N, None, codes)
+        hist = np.zeros((self.M, self.K), np.int64)
+        joint = np.zeros((self.K, self.K), np.int64) if pair is not None else None
+        a, b = pair if pair is not None else (0, 0)
+        self._chk(lib().hclae_code_stats(self._h, pcodes, N, self.M, self.K, hist.ctypes.data_as(ctypes.c_void_p), a, b,
+                                         joint.ctypes.data_as(ctypes.c_void_p) if joint is not None else None))
+        return hist, joint
 
     def timing_enable(self, classes):
         """classes: iterable of names from KERNEL_CLASSES (empty = off)."""

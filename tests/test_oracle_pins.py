@@ -477,3 +477,41 @@ def test_pca_axes_properties(oracle):
     var = oracle.rotate(X - X.mean(0), R).var(0)
     assert np.all(np.diff(var) <= 1e-9 * var[0])                          # variance descending
     np.testing.assert_allclose(var.sum(), X.var(0).sum(), rtol=1e-12)     # trace preserved
+
+
+# ---------------------------------------------------------------- dictionary order, code statistics
+def test_code_statistics_closed_forms(oracle):
+    """Sec. 2.2: H(I_m) of a uniform code part is log2 K; a part that copies another has mutual
+    information H; independent parts have (nearly) none; H(A,B) = H(A) + H(B) - I(A;B)."""
+    g = np.random.default_rng(8)
+    K, N = 16, 200000
+    codes = np.zeros((N, 3), np.uint8)
+    codes[:, 0] = np.arange(N) % K                      # exactly uniform
+    codes[:, 1] = codes[:, 0]                           # a copy
+    codes[:, 2] = g.integers(0, K, N)                   # independent
+    hist = oracle.code_histogram(codes, K)
+    assert hist.sum(1).tolist() == [N, N, N] and np.all(hist[0] == N // K)
+    assert abs(oracle.entropy_bits(hist[0]) - np.log2(K)) < 1e-12
+    J01 = oracle.joint_histogram(codes, 0, 1, K)
+    assert abs(oracle.mutual_information_bits(J01) - np.log2(K)) < 1e-12
+    J02 = oracle.joint_histogram(codes, 0, 2, K)
+    mi = oracle.mutual_information_bits(J02)
+    assert 0 <= mi < 3 * (K - 1) ** 2 / (2 * N * np.log(2))          # plug-in bias ~ (K-1)^2 / (2 N ln 2)
+    assert abs(oracle.entropy_bits(J02) - (oracle.entropy_bits(J02.sum(1)) + oracle.entropy_bits(J02.sum(0)) - mi)) < 1e-12
+    np.testing.assert_array_equal(J02.sum(1), hist[0])
+    np.testing.assert_array_equal(J02.sum(0), hist[2])
+
+
+def test_variance_order(oracle):
+    """Sec. 3.3: a hierarchy learned from scratch has descending variance; shuffling it and
+    re-ordering by variance restores the hierarchy.  Variance against NumPy's definition."""
+    X, C, codes = synth.planted_lattice(K=4, M=4, D=3, ratio=4.0)
+    v = oracle.dictionary_variances(C)
+    np.testing.assert_allclose(v, [np.var(C[m], axis=0).sum() for m in range(4)], rtol=1e-14)
+    assert np.all(np.diff(v) < 0) and oracle.variance_order(C).tolist() == [0, 1, 2, 3]
+    shuffle = [2, 0, 3, 1]
+    # new position j must hold the shuffled slot that contains old dictionary j: the inverse permutation
+    assert oracle.variance_order(C[shuffle]).tolist() == np.argsort(shuffle).tolist() == [1, 3, 0, 2]
+    Ct = C.copy()
+    Ct[3] = Ct[2]                                                          # a tie keeps the lower index first
+    assert oracle.variance_order(Ct).tolist() == [0, 1, 2, 3]
