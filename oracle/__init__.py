@@ -50,6 +50,9 @@ def _load():
     lib.da_heat.argtypes = [_f64p, _u8p, _f64p, _i64, _int, _int, _int, _int]
     lib.da_cool.argtypes = [_f64p, _u8p, _f64p, _i64, _int, _int, _int, _int]
     lib.da_assign.argtypes = [_f64p, _f64p, _i64, _int, _int, _int, _int, _u8p, _f64p, _f64p, _i32p]
+    lib.da_beam_step.argtypes = [_f32p, _f64p, _i64, _int, _int, _int, _int, _f64p, _u8p, _u8p, _f64p,
+                                 _f64p, _f64p]
+    lib.da_encode_beam.argtypes = [_f32p, _f64p, _i64, _int, _int, _int, _int, _u8p, _f64p, _f64p, _f64p]
     lib.da_dist_to.argtypes = [_f64p, _f64p, _i64, _int, _int, _int, _int]
     lib.da_dist_to.restype = ctypes.c_double
     lib.da_update.argtypes = [_f64p, _u8p, _f64p, _i64, _int, _int, _int, _int, _i64p]
@@ -157,6 +160,45 @@ def encode(X, C):
     r = np.empty((N, D), np.float64)
     _load().da_encode(_p(X, _f32p), _p(C, _f64p), N, D, M, K, _p(codes, _u8p), _p(r, _f64p))
     return codes, r
+
+
+def beam_step(X, Cm, A, L):
+    """One dictionary of the multi-path encoding (Sec. 3.3): A float64 [N][Lc][D] are the kept
+    sums so far.  Returns (parent uint8 [N][Ln], code uint8 [N][Ln], err float64 [N][Ln],
+    A_next float64 [N][Ln][D], gap float64 [N]) with Ln = min(L, K * Lc)."""
+    _chk(X, np.float32)
+    _chk(Cm, np.float64)
+    _chk(A, np.float64)
+    N, D = X.shape
+    K = Cm.shape[0]
+    Lc = A.shape[1]
+    assert Cm.shape == (K, D) and A.shape == (N, Lc, D) and L >= 1
+    Ln = min(L, K * Lc)
+    parent = np.zeros((N, Ln), np.uint8)
+    code = np.zeros((N, Ln), np.uint8)
+    err = np.zeros((N, Ln), np.float64)
+    A_next = np.zeros((N, Ln, D), np.float64)
+    gap = np.zeros(N, np.float64)
+    _load().da_beam_step(_p(X, _f32p), _p(Cm, _f64p), N, D, K, Lc, L, _p(A, _f64p), _p(parent, _u8p),
+                         _p(code, _u8p), _p(err, _f64p), _p(A_next, _f64p), _p(gap, _f64p))
+    return parent, code, err, A_next, gap
+
+
+def encode_beam(X, C, L):
+    """Multi-path encoding with L paths (Sec. 3.3).  Returns (codes uint8 [N][M], r float64
+    [N][D], err float64 [N], gap float64 [N])."""
+    _chk(X, np.float32)
+    _chk(C, np.float64)
+    N, D = X.shape
+    M, K, D2 = C.shape
+    assert D == D2 and L >= 1
+    codes = np.zeros((N, M), np.uint8)
+    r = np.empty((N, D), np.float64)
+    err = np.zeros(N, np.float64)
+    gap = np.zeros(N, np.float64)
+    _load().da_encode_beam(_p(X, _f32p), _p(C, _f64p), N, D, M, K, L, _p(codes, _u8p), _p(r, _f64p),
+                           _p(err, _f64p), _p(gap, _f64p))
+    return codes, r, err, gap
 
 
 def anneal_stage(m, C, codes, r, T, init_idx=None, trace=False):

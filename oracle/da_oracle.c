@@ -14,7 +14,8 @@
  *     that cools (plain full-dimension Lloyd here; the PCA / dimension-adding variant is
  *     not part of this oracle).
  *   - Sec. 3.3, Eq. 1 first line: E = || x - sum_m c_m(i_m(x)) ||^2 ; Eq. 3 with L = 1 is
- *     greedy residual encoding.
+ *     greedy residual encoding; with L > 1 it is the multi-path (beam) encoding of
+ *     da_beam_step / da_encode_beam.
  *   - Table 1 magnitudes fix E as the mean over vectors of the squared residual norm.
  *
  * Readings where the paper is silent: fixed number T of Lloyd iterations per cool-down;
@@ -192,6 +193,134 @@ void da_encode(const float *X, const double *C, int64_t N, int D, int M, int K,
         da_assign(r, C, N, D, M, K, m, codes, NULL, NULL, NULL);
         da_cool(r, codes, C, N, D, M, K, m);
     }
+}
+
+/*
+ * Multi-path encoding, one dictionary (Sec. 3.3, the left-hand side of Eq. 3).
+ *
+ * The beam holds Lc approximations a_l of every vector on the dictionaries before this one
+ * (A: double[N][Lc][D]; Lc = 1 with a = 0 before the first dictionary).  All K*Lc sums
+ * a_l + c(k) are scored by  e(l,k) = || x - a_l - c(k) ||^2  in its direct form and the
+ * Ln = min(L, K*Lc) smallest are kept, in ascending order of e.
+ * Reading where the paper is silent: equal e are ordered by (l, k) ascending, i.e. a stable
+ * sort of the candidates enumerated l-major.
+ *
+ * Outputs per vector: parent[Ln] = l and code[Ln] = k of every kept sum, err[Ln] = its e,
+ * A_next[Ln][D] = a_l + c(k).  gap (may be NULL) receives the smallest relative difference
+ * (e_{i+1} - e_i) / e_{i+1} between neighbours among the first Ln + 1 sorted candidates (a
+ * pair with e_{i+1} = 0 counts as 0; +inf when there is a single candidate): the tests use it
+ * to tell a genuine near-tie from an error.
+ */
+typedef struct { double e; int l, k; } beam_cand;
+
+static int beam_cmp(const void *pa, const void *pb)
+{
+    const beam_cand *a = (const beam_cand *)pa, *b = (const beam_cand *)pb;
+    if (a->e < b->e) return -1;
+    if (a->e > b->e) return 1;
+    if (a->l != b->l) return a->l < b->l ? -1 : 1;
+    return (a->k > b->k) - (a->k < b->k);
+}
+
+void da_beam_step(const float *X, const double *Cm, int64_t N, int D, int K, int Lc, int L,
+                  const double *A, uint8_t *parent, uint8_t *code, double *err,
+                  double *A_next, double *gap)
+{
+    const int total = K * Lc;
+    const int Ln = L < total ? L : total;
+#pragma omp parallel
+    {
+        beam_cand *cand = (beam_cand *)malloc(sizeof(beam_cand) * (size_t)total);
+#pragma omp for schedule(static)
+        for (int64_t n = 0; n < N; ++n) {
+            const float *x = X + (size_t)n * D;
+            for (int l = 0; l < Lc; ++l) {
+                const double *a = A + ((size_t)n * Lc + l) * D;
+                for (int k = 0; k < K; ++k) {
+                    const double *c = Cm + (size_t)k * D;
+                    double e = 0.0;
+                    for (int d = 0; d < D; ++d) {
+                        const double t = (double)x[d] - a[d] - c[d];
+                        e += t * t;
+                    }
+                    cand[l * K + k].e = e;
+                    cand[l * K + k].l = l;
+                    cand[l * K + k].k = k;
+                }
+            }
+            qsort(cand, (size_t)total, sizeof(beam_cand), beam_cmp);   /* total order: no ties left */
+            for (int i = 0; i < Ln; ++i) {
+                parent[(size_t)n * Ln + i] = (uint8_t)cand[i].l;
+                code[(size_t)n * Ln + i] = (uint8_t)cand[i].k;
+                err[(size_t)n * Ln + i] = cand[i].e;
+                const double *a = A + ((size_t)n * Lc + cand[i].l) * D;
+                const double *c = Cm + (size_t)cand[i].k * D;
+                double *an = A_next + ((size_t)n * Ln + i) * D;
+                for (int d = 0; d < D; ++d) an[d] = a[d] + c[d];
+            }
+            if (gap) {
+                double g = INFINITY;
+                const int last = Ln < total ? Ln : total - 1;        /* index of the last right neighbour */
+                for (int i = 0; i < last; ++i) {
+                    const double hi = cand[i + 1].e, lo = cand[i].e;
+                    const double rel = hi > 0.0 ? (hi - lo) / hi : 0.0;
+                    if (rel < g) g = rel;
+                }
+                gap[n] = g;
+            }
+        }
+        free(cand);
+    }
+}
+
+/*
+ * Multi-path encoding of X on all M dictionaries in order (Sec. 3.3): da_beam_step for
+ * m = 1..M starting from the single empty sum, carrying the code prefix of every kept sum;
+ * the answer is the best sum of the last beam.  codes: uint8[N][M]; r: double[N][D] receives
+ * x - sum_m c_m(i_m); err (may be NULL): double[N] its squared norm as scored; gap (may be
+ * NULL): double[N], the smallest da_beam_step gap over the M steps.
+ */
+void da_encode_beam(const float *X, const double *C, int64_t N, int D, int M, int K, int L,
+                    uint8_t *codes, double *r, double *err, double *gap)
+{
+    int Lc = 1;
+    double *A = (double *)calloc((size_t)N * D, sizeof(double));
+    uint8_t *pre = (uint8_t *)calloc((size_t)N * (M > 0 ? M : 1), 1);      /* [N][Lc][M] */
+    double *g = gap ? (double *)malloc(sizeof(double) * (size_t)N) : NULL;
+    double *e = NULL;
+    if (gap) for (int64_t n = 0; n < N; ++n) gap[n] = INFINITY;
+    for (int m = 0; m < M; ++m) {
+        const long total = (long)K * Lc;
+        const int Ln = L < total ? L : (int)total;
+        uint8_t *parent = (uint8_t *)malloc((size_t)N * Ln);
+        uint8_t *code = (uint8_t *)malloc((size_t)N * Ln);
+        double *en = (double *)malloc(sizeof(double) * (size_t)N * Ln);
+        double *An = (double *)malloc(sizeof(double) * (size_t)N * Ln * D);
+        uint8_t *pn = (uint8_t *)calloc((size_t)N * Ln * M, 1);
+        da_beam_step(X, C + (size_t)m * K * D, N, D, K, Lc, L, A, parent, code, en, An, g);
+        for (int64_t n = 0; n < N; ++n) {
+            for (int i = 0; i < Ln; ++i) {
+                const uint8_t *src = pre + ((size_t)n * Lc + parent[(size_t)n * Ln + i]) * M;
+                uint8_t *dst = pn + ((size_t)n * Ln + i) * M;
+                memcpy(dst, src, (size_t)m);
+                dst[m] = code[(size_t)n * Ln + i];
+            }
+            if (gap && g[n] < gap[n]) gap[n] = g[n];
+        }
+        free(A); free(pre); free(parent); free(code); free(e);
+        A = An; pre = pn; e = en; Lc = Ln;
+    }
+    for (int64_t n = 0; n < N; ++n) {
+        memcpy(codes + (size_t)n * M, pre + (size_t)n * Lc * M, (size_t)M);
+        const double *a = A + (size_t)n * Lc * D;
+        for (int d = 0; d < D; ++d) r[(size_t)n * D + d] = (double)X[(size_t)n * D + d] - a[d];
+        if (err) {
+            double q = 0.0;                                            /* M == 0: nothing subtracted */
+            for (int d = 0; d < D; ++d) q += r[(size_t)n * D + d] * r[(size_t)n * D + d];
+            err[n] = e ? e[(size_t)n * Lc] : q;
+        }
+    }
+    free(A); free(pre); free(e); free(g);
 }
 
 /*

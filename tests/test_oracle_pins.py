@@ -515,3 +515,111 @@ def test_variance_order(oracle):
     Ct = C.copy()
     Ct[3] = Ct[2]                                                          # a tie keeps the lower index first
     assert oracle.variance_order(Ct).tolist() == [0, 1, 2, 3]
+
+
+# ---------------------------------------------------------------- multi-path encoding (Sec. 3.3)
+def test_hand_worked_1d_beam(oracle):
+    g = _read_golden("hand_1d_beam.txt")
+    X = g["x"].astype(np.float32).reshape(1, 1)
+    C = np.stack([g["c1"], g["c2"]]).reshape(2, 2, 1)
+    codes, r, err, gap = oracle.encode_beam(X, C, 1)
+    np.testing.assert_array_equal(codes[0], g["greedy_codes"].astype(np.uint8))
+    assert err[0] == g["greedy_err"][0] and r[0, 0] == g["greedy_residue"][0]
+    A0 = np.zeros((1, 1, 1))
+    par, code, e, A1, _ = oracle.beam_step(X, C[0], A0, 2)
+    np.testing.assert_array_equal(code[0], g["beam2_step1_code"].astype(np.uint8))
+    np.testing.assert_array_equal(e[0], g["beam2_step1_err"])
+    par, code, e, A2, _ = oracle.beam_step(X, C[1], A1, 2)
+    np.testing.assert_array_equal(par[0], g["beam2_step2_parent"].astype(np.uint8))
+    np.testing.assert_array_equal(code[0], g["beam2_step2_code"].astype(np.uint8))
+    np.testing.assert_array_equal(e[0], g["beam2_step2_err"])
+    codes, r, err, gap = oracle.encode_beam(X, C, 2)
+    np.testing.assert_array_equal(codes[0], g["beam2_codes"].astype(np.uint8))
+    assert err[0] == g["beam2_err"][0] and r[0, 0] == g["beam2_residue"][0] and gap[0] == g["beam2_gap"][0]
+
+
+def _beam_inputs(N=300, D=6, M=3, K=4, seed=3):
+    rng = np.random.default_rng(seed)
+    X = rng.normal(size=(N, D)).astype(np.float32)
+    C = rng.normal(size=(M, K, D)) * (0.6 ** np.arange(M))[:, None, None]
+    return X, C
+
+
+def test_beam_single_path_is_greedy(oracle):
+    """Eq. 3 with L = 1 keeps the nearest codeword of the running residue at every dictionary."""
+    X, C = _beam_inputs(M=4, K=8)
+    c1, r1 = oracle.encode(X, C)
+    c2, r2, e2, _ = oracle.encode_beam(X, C, 1)
+    np.testing.assert_array_equal(c1, c2)
+    np.testing.assert_allclose(r1, r2, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(e2, (r2 ** 2).sum(1), rtol=1e-13)
+
+
+def test_beam_wide_enough_is_exhaustive(oracle):
+    """With L >= K^(M-1) no prefix is ever dropped, so the result is the global minimiser of the
+    first line of Eq. 1 over all K^M codes (brute force).  Catches a wrong sign, a wrong parent
+    index and a mis-carried prefix."""
+    import itertools
+    X, C = _beam_inputs()
+    M, K, _ = C.shape
+    best = np.full(len(X), np.inf)
+    bc = np.zeros((len(X), M), np.uint8)
+    for combo in itertools.product(range(K), repeat=M):
+        e = ((X - sum(C[m][combo[m]] for m in range(M))) ** 2).sum(1)
+        u = e < best
+        best[u] = e[u]
+        bc[u] = combo
+    for L in (K ** (M - 1), K ** M, 1000):
+        codes, r, err, _ = oracle.encode_beam(X, C, L)
+        np.testing.assert_array_equal(codes, bc)
+        np.testing.assert_allclose(err, best, rtol=1e-13)
+        np.testing.assert_allclose(r, X - oracle.reconstruct(C, codes), rtol=0, atol=1e-14)
+    # a narrower beam can only be as good or worse than the exhaustive answer
+    for L in (1, 2, 5):
+        _, _, err, _ = oracle.encode_beam(X, C, L)
+        assert (err >= best - 1e-12).all()
+
+
+def test_beam_step_equals_eq3_with_lookup_tables(oracle):
+    """Eq. 3 as printed: ||x - a_l||^2 + ||x - c_m(k)||^2 - ||x||^2 + 2 c_m(k)^T a_l, the last term
+    from inner products of dictionary elements tabulated beforehand.  A separate NumPy beam built
+    on those tables must keep the same sums as the direct-form oracle."""
+    X, C = _beam_inputs(N=200, D=8, M=4, K=6, seed=11)
+    M, K, D = C.shape
+    L = 5
+    X64 = X.astype(np.float64)
+    flat = C.reshape(M * K, D)
+    T = (flat @ flat.T).reshape(M, K, M, K)                  # c_a(i)^T c_b(j)
+    xx = (X64 ** 2).sum(1)
+    codes_o, r_o, err_o, gap = oracle.encode_beam(X, C, L)
+    for n in range(len(X)):
+        pre = [()]
+        e_cur = np.array([xx[n]])                            # ||x - 0||^2
+        for m in range(M):
+            tab = ((X64[n][None, :] - C[m]) ** 2).sum(1)     # second term, one per k
+            sc = np.empty((len(pre), K))
+            for l, p in enumerate(pre):
+                cross = sum(T[j, p[j], m, :] for j in range(m)) if m else np.zeros(K)
+                sc[l] = e_cur[l] + tab - xx[n] + 2.0 * cross
+            order = np.argsort(sc.reshape(-1), kind="stable")[: min(L, sc.size)]
+            e_cur = sc.reshape(-1)[order]
+            pre = [pre[o // K] + (o % K,) for o in order]
+        if gap[n] > 1e-9:                                    # expanded and direct forms differ by rounding
+            assert tuple(codes_o[n]) == pre[0]
+        np.testing.assert_allclose(err_o[n], e_cur[0], rtol=1e-9, atol=1e-12)
+    assert (gap > 1e-9).mean() > 0.9
+
+
+def test_beam_tie_order_and_gap(oracle):
+    """Equal errors are kept in (l, k) order and reported as a zero gap."""
+    X = np.array([[1.0, 0.0]], np.float32)
+    Cm = np.array([[1.0, 1.0], [1.0, -1.0], [0.0, 0.0], [1.0, 1.0]])   # k = 0, 1, 3 tie at e = 1
+    A = np.zeros((1, 1, 2))
+    par, code, err, A1, gap = oracle.beam_step(X, Cm, A, 3)
+    assert code[0].tolist() == [0, 1, 2] and err[0].tolist() == [1.0, 1.0, 1.0] and gap[0] == 0.0
+    # two identical beam entries: children of the lower l come first
+    A = np.zeros((1, 2, 2))
+    par, code, err, A2, gap = oracle.beam_step(X, Cm, A, 4)
+    assert list(zip(par[0].tolist(), code[0].tolist())) == [(0, 0), (0, 1), (0, 2), (0, 3)]
+    par, code, err, A2, gap = oracle.beam_step(X, np.array([[1.0, 1.0], [1.0, 0.0]]), A, 3)
+    assert list(zip(par[0].tolist(), code[0].tolist())) == [(0, 1), (1, 1), (0, 0)]
