@@ -101,6 +101,8 @@ int hclae_anneal_stage(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M,
  * reencode_mode 0: each stage re-encodes only its own column (keeps E non-increasing).
  * reencode_mode 1: after each stage all M parts are re-encoded greedily from X
  *                  (hclae_encode); X must then be non-NULL.
+ * reencode_mode 2: as 1 with the multi-path encoder (hclae_encode_beam) of the width set by
+ *                  hclae_set_beam_width (10 unless set).
  * init_idx: HOST int64[M][K] or NULL.  err_per_stage: HOST double[M] or NULL
  * (mean ||e_x||^2 after each stage).
  */
@@ -164,6 +166,38 @@ int hclae_online_chunk(hclae_ctx *ctx, const uint8_t *Xu8, int64_t n, int D, flo
 int hclae_online_export(hclae_ctx *ctx, double *run_sum, int64_t *run_cnt);
 int hclae_online_import(hclae_ctx *ctx, const double *run_sum, const int64_t *run_cnt);
 
+/* ---- multi-path encoding (Sec. 3.3, Eq. 3) ---------------------------------------------------- */
+
+#define HCLAE_MAX_L 32     /* paths kept per vector */
+
+/*
+ * One dictionary of the multi-path encoding.  The beam of every vector is held as residuals
+ * r_l = x - a_l of its Lc kept sums a_l:  rows DEVICE float[N][Lc][D], err DEVICE double[N][Lc] =
+ * ||r_l||^2 (NULL means all zero and is allowed when Lc == 1, where it only shifts every score).
+ * All K * Lc candidates are scored by ||r_l - c(k)||^2 (the left-hand side of Eq. 3) and the
+ * Ln = min(L, K * Lc) smallest are kept in ascending order, equal errors in (l, k) order:
+ *   rows_next DEVICE float[N][Ln][D] = r_l - c(k) (must not alias rows), err_next DEVICE double[N][Ln],
+ *   parent / code DEVICE uint8[N][Ln] = l / k.  err_next, parent and code may be NULL.
+ * Cm: DEVICE float[K][D].  1 <= Lc <= L <= HCLAE_MAX_L, N * L < 2^31.
+ * Decisions are taken on fp64 direct-form errors of the fp32 rows (candidates pre-selected on the
+ * fp32 matrix cores with a rigorous rounding margin).
+ */
+int hclae_beam_step(hclae_ctx *ctx, const float *rows, const double *err, const float *Cm,
+                    int64_t N, int D, int K, int Lc, int L,
+                    float *rows_next, double *err_next, uint8_t *parent, uint8_t *code);
+
+/*
+ * Multi-path encoding of X on dictionaries 0..M-1 in order with L paths; the answer is the best
+ * sum of the last beam.  Writes codes[N][M], residue[N][D] = x - sum_m c_m(i_m) (must not alias X)
+ * and, when err != NULL, err DEVICE double[N] = its squared norm as scored.  L = 1 is hclae_encode.
+ * Scratch for batches of vectors is allocated by the first call and kept by the ctx.
+ */
+int hclae_encode_beam(hclae_ctx *ctx, const float *X, int64_t N, int D, const float *C, int M, int K, int L,
+                      uint8_t *codes, float *residue, double *err);
+
+/* Width of the multi-path re-encode that hclae_sweep runs with reencode_mode 2. */
+int hclae_set_beam_width(hclae_ctx *ctx, int L);
+
 /* ---- improved k-means for high-dimensional residue (Sec. 3.2) --------------------------------- */
 
 /* Second moments of {x'} for its PCA: mean (DEVICE double[D]) and centred covariance (DEVICE
@@ -224,6 +258,8 @@ enum {
     HCLAE_T_TRANSITION, /* fused stage boundary of hclae_sweep: new residue of m + heat of m+1 */
     HCLAE_T_ROTATE,     /* projection y = R x (Sec. 3.2)                                    */
     HCLAE_T_MOMENTS,    /* mean and covariance of x' (Sec. 3.2)                             */
+    HCLAE_T_BEAM_SCORE, /* multi-path encoding: fp32-MFMA scoring and candidate bitmaps     */
+    HCLAE_T_BEAM_EXPAND,/* multi-path encoding: fp64 evaluation, top-L, next beam           */
     HCLAE_T_COUNT
 };
 

@@ -1,0 +1,361 @@
+// Multi-path encoding (Sec. 3.3, Eq. 3): for every vector keep the L best sums a_l of codewords
+// of the dictionaries seen so far; for the next dictionary score all K * L sums a_l + c(k) by
+// || x - a_l - c(k) ||^2 and keep the L smallest.
+//
+// The beam is stored as residuals r_l = x - a_l (fp32 rows), so a candidate's error is
+// || r_l - c(k) ||^2 = e_l - 2 ( r_l . c(k) - ||c(k)||^2 / 2 ) and scoring a dictionary is the same
+// codewords x vectors contraction as the nearest-codeword assignment, over N * L rows.  Two
+// kernels per dictionary:
+//   k_beam_score_*  fp32 matrix cores; per vector finds a threshold that at least L candidates
+//                   reach and writes, per beam row, the bitmap of codewords that reach it minus
+//                   twice the fp32 rounding bound (so the L best in exact arithmetic are in it);
+//   k_beam_expand   evaluates the listed candidates in fp64 in the direct form, sorts them by
+//                   (error, l, k), keeps the first L and writes their residuals, errors and
+//                   code prefixes.
+// The decision is therefore an fp64 direct-form decision, as in the assignment kernels.
+#pragma once
+#include "assign.hpp"
+
+namespace hclae {
+
+constexpr int kBeamMaxL = 32;        // a vector's beam rows must fit one 32-column MFMA tile
+
+// Candidate codewords of one beam row: bit p of w[h][i] is codeword 64 i + 8 (p >> 2) + 4 h + (p & 3).
+struct BeamMask {
+    uint32_t w[2][4];
+};
+
+// Threshold and bitmaps from a wave's scores.  Lane (h, r) holds the scores g = r_l.c - ||c||^2/2
+// of beam row r of the tile against half of the codewords; a candidate's error is e_l - 2 g, so
+// candidates are ranked by g - e_l / 2 (larger is better).
+//   1. per lane, the maximum of each 16-score accumulator block (8 values, shifted by -e_l/2);
+//   2. Ln rounds of "take the largest block maximum of the vector's group of lanes and strike it
+//      out": the value taken in the last round is reached by at least Ln distinct candidates
+//      (ties struck together only lower it);
+//   3. every score within twice the rounding bound of that value is marked.
+// gamma * (hmax + ||r|| cmax + ||r||^2) bounds the rounding error of a shifted score.
+template <int KB>
+__device__ __forceinline__ void beam_select(
+    const floatx16 (&acc)[KB], float xsq, float e_l, float gamma, float hmax, float cmax,
+    int lane, int gbase, int Lc, int Ln, bool valid, BeamMask *__restrict__ out)
+{
+    const int h = lane >> 5;
+    const float ninf = -__builtin_inff();
+    const float shift = 0.5f * e_l;
+    float bm[KB];
+#pragma unroll
+    for (int b = 0; b < KB; ++b) {
+        float t = acc[b][0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) t = fmaxf(t, acc[b][v]);
+        bm[b] = valid ? t - shift : ninf;
+    }
+    const float x2 = xsq + __shfl_xor(xsq, 32, kWave);
+    const float el = fmaxf(e_l, x2) * 1.00001f;
+    const float bound = valid ? gamma * (hmax + sqrtf(el) * cmax + el) : 0.f;
+
+    float tau = ninf;
+    for (int it = 0; it < Ln; ++it) {
+        float top = bm[0];
+#pragma unroll
+        for (int b = 1; b < KB; ++b) top = fmaxf(top, bm[b]);
+        top = fmaxf(top, __shfl_xor(top, 32, kWave));
+        float g = top;
+        for (int j = 0; j < Lc; ++j) g = fmaxf(g, __shfl(top, gbase + j, kWave));
+        tau = g;
+#pragma unroll
+        for (int b = 0; b < KB; ++b) bm[b] = (bm[b] == g) ? ninf : bm[b];
+    }
+    float gb = bound;
+    for (int j = 0; j < Lc; ++j) gb = fmaxf(gb, __shfl(bound, gbase + j, kWave));
+    const float thr = (tau - 2.f * gb) + shift;          // back to the lane's unshifted scores
+
+    constexpr int NW = (KB + 1) / 2;
+    uint32_t mk[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int b = 0; b < KB; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            if (acc[b][v] >= thr) mk[b >> 1] |= 1u << ((b & 1) * 16 + v);
+    (void)NW;
+    if (valid) *reinterpret_cast<uint4 *>(&out->w[h][0]) = make_uint4(mk[0], mk[1], mk[2], mk[3]);
+}
+
+// Scoring with the whole padded codebook resident in LDS (same staging, operand order and
+// two-register-set streaming as k_assign_resident).  A tile holds V = 32 / Lc whole vectors =
+// V * Lc consecutive beam rows; the remaining columns idle.
+template <int KB>
+__global__ __launch_bounds__(kAssignThreads) void k_beam_score_resident(
+    const float *__restrict__ rows, const double *__restrict__ err, const float *__restrict__ Cm,
+    const float *__restrict__ hneg, int64_t N, int Lc, int Ln, int D, int ld, int K, int NC, float gamma,
+    BeamMask *__restrict__ masks)
+{
+    extern __shared__ float4 smem4[];
+    const int S = 8 * NC;
+    float4 *lds_c = smem4;
+    float *lds_h = reinterpret_cast<float *>(smem4 + KB * S * kWave);
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int h = lane >> 5;
+    const int r = lane & 31;
+
+    stage_codebook(lds_c, Cm, K, D, ld, KB, S);
+    for (int k = threadIdx.x; k < 32 * KB; k += blockDim.x) lds_h[k] = hneg[k];
+    __syncthreads();
+    float hmax = 0.f;
+    for (int k = 0; k < K; ++k) hmax = fmaxf(hmax, -lds_h[k]);
+    const float cmax = sqrtf(2.f * hmax) * 1.000001f;
+
+    const int V = kTileVec / Lc;                       // vectors per tile
+    const int RT = V * Lc;                             // beam rows per tile
+    const int gbase = (r < RT) ? (r / Lc) * Lc : 0;
+    const int64_t nrows = N * Lc;
+    const int64_t ntiles = (N + V - 1) / V;
+    const int64_t nslots = (int64_t)gridDim.x * 4;
+    const int64_t tstride = 2 * nslots;
+    const int64_t t0 = (int64_t)blockIdx.x * 4 + (wave & 3) + nslots * (wave >> 2);
+    if (t0 >= ntiles) return;
+    const int64_t my_tiles = (ntiles - t0 + tstride - 1) / tstride;
+    const int64_t G = my_tiles * NC;
+
+    auto row_of = [&](int64_t tile) { return tile * RT + r; };
+    auto row_ptr = [&](int64_t tile) {
+        int64_t n = row_of(tile);
+        if (r >= RT || n >= nrows) n = nrows - 1;      // idle columns re-read the last row
+        return rows + n * ld;
+    };
+    auto e_of = [&](int64_t tile) {
+        int64_t n = row_of(tile);
+        if (r >= RT || n >= nrows) n = nrows - 1;
+        return err ? (float)err[n] : 0.f;
+    };
+
+    floatx16 acc[KB];
+    float4 xa[8], xb[8];
+    float xsq = 0.f, amax = 0.f, e_l = 0.f;
+    int64_t tile = t0;
+    int q = 0;
+    load_x_chunk(xa, row_ptr(tile), 0, h, D);
+    for (int64_t g = 0; g < G; g += 2) {
+        int64_t tile1 = tile;
+        int q1 = q + 1;
+        if (q1 == NC) { q1 = 0; tile1 = tile + tstride; }
+        if (g + 1 < G) load_x_chunk(xb, row_ptr(tile1), q1, h, D);
+        if (q == 0) { init_acc<KB>(acc, lds_h, h); xsq = 0.f; e_l = e_of(tile); }
+        mfma_chunk<KB>(acc, xa, lds_c, q, S, lane, xsq, amax);
+        if (q == NC - 1) {
+            const int64_t row = row_of(tile);
+            const bool valid = r < RT && row < nrows;
+            beam_select<KB>(acc, xsq, e_l, gamma, hmax, cmax, lane, gbase, Lc, Ln, valid, masks + (valid ? row : 0));
+        }
+        if (g + 1 >= G) break;
+        int64_t tile2 = tile1;
+        int q2 = q1 + 1;
+        if (q2 == NC) { q2 = 0; tile2 = tile1 + tstride; }
+        if (g + 2 < G) load_x_chunk(xa, row_ptr(tile2), q2, h, D);
+        if (q1 == 0) { init_acc<KB>(acc, lds_h, h); xsq = 0.f; e_l = e_of(tile1); }
+        mfma_chunk<KB>(acc, xb, lds_c, q1, S, lane, xsq, amax);
+        if (q1 == NC - 1) {
+            const int64_t row = row_of(tile1);
+            const bool valid = r < RT && row < nrows;
+            beam_select<KB>(acc, xsq, e_l, gamma, hmax, cmax, lane, gbase, Lc, Ln, valid, masks + (valid ? row : 0));
+        }
+        tile = tile2;
+        q = q2;
+    }
+}
+
+// Scoring for dimensions whose codebook does not fit LDS (see k_assign_chunked): the block walks
+// the D axis in 64-dim slices, restaging that slice of the codebook for every block tile.
+template <int KB>
+__global__ __launch_bounds__(kAssignThreads) void k_beam_score_chunked(
+    const float *__restrict__ rows, const double *__restrict__ err, const float *__restrict__ Cm,
+    const float *__restrict__ hneg, int64_t N, int Lc, int Ln, int D, int ld, int K, int NC, float gamma,
+    BeamMask *__restrict__ masks)
+{
+    extern __shared__ float4 smem4[];
+    constexpr int S = 8;
+    float4 *lds_c = smem4;
+    float *lds_h = reinterpret_cast<float *>(smem4 + KB * S * kWave);
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int h = lane >> 5;
+    const int r = lane & 31;
+
+    for (int k = threadIdx.x; k < 32 * KB; k += blockDim.x) lds_h[k] = hneg[k];
+    __syncthreads();
+    float hmax = 0.f;
+    for (int k = 0; k < K; ++k) hmax = fmaxf(hmax, -lds_h[k]);
+    const float cmax = sqrtf(2.f * hmax) * 1.000001f;
+
+    const int V = kTileVec / Lc;
+    const int RT = V * Lc;
+    const int gbase = (r < RT) ? (r / Lc) * Lc : 0;
+    const int64_t nrows = N * Lc;
+    const int64_t ntiles = (N + V - 1) / V;
+    const int64_t nbt = (ntiles + kAssignWaves - 1) / kAssignWaves;
+    float amax = 0.f;
+    for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
+        const int64_t tile = bt * kAssignWaves + wave;                 // may lie beyond ntiles: idle wave
+        const int64_t row = tile * RT + r;
+        const bool valid = r < RT && row < nrows;
+        const int64_t rd = valid ? row : nrows - 1;
+        const float *xrow = rows + rd * ld;
+        const float e_l = err ? (float)err[rd] : 0.f;
+        floatx16 acc[KB];
+        float4 x[8];
+        float xsq = 0.f;
+        init_acc<KB>(acc, lds_h, h);
+        for (int q = 0; q < NC; ++q) {
+            load_x_chunk(x, xrow, q, h, D);
+            __syncthreads();
+            for (int e = threadIdx.x; e < KB * S * kWave; e += blockDim.x) {
+                const int l = e & 63;
+                const int bs = e >> 6;
+                const int s = bs & 7;
+                const int b = bs >> 3;
+                const int crow = 32 * b + (l & 31);
+                const int col = kChunkD * q + 8 * s + 4 * (l >> 5);
+                lds_c[e] = load_row_piece(Cm, crow, col, K, D, ld);
+            }
+            __syncthreads();
+            mfma_chunk<KB>(acc, x, lds_c, 0, S, lane, xsq, amax);
+        }
+        beam_select<KB>(acc, xsq, e_l, gamma, hmax, cmax, lane, gbase, Lc, Ln, valid, masks + (valid ? row : 0));
+    }
+}
+
+constexpr int kExpandCap = 256;      // candidates listed per round
+
+// Exact evaluation and selection for one dictionary; one wave (= one 64-thread block slot) per
+// vector.  The vector's marked candidates are listed in LDS (kExpandCap at a time), eight at a
+// time are evaluated in fp64 in the direct form by groups of eight lanes, and each is inserted
+// into a list kept sorted by (error, l, k) across the lanes (lane i holds the i-th best).  The
+// first Ln entries become the next beam: residual rows r_l - c(k) rounded to fp32, their fp64
+// errors, and the parent's code prefix extended by k.
+//   rows_c [N*Lc] stride ldc -> rows_n [N*Ln] stride ldn;  pre_c [N][Lc][M] -> pre_n [N][Ln][M]
+//   (bytes 0..m-1 copied, byte m = k);  err_n, parent, code: [N*Ln], each may be null.
+__global__ __launch_bounds__(kWave) void k_beam_expand(
+    const float *__restrict__ rows_c, int ldc, const BeamMask *__restrict__ masks,
+    const float *__restrict__ Cm, int K, int D, int64_t N, int Lc, int Ln,
+    const uint8_t *__restrict__ pre_c, uint8_t *__restrict__ pre_n, int M, int m,
+    float *__restrict__ rows_n, int ldn, double *__restrict__ err_n,
+    uint8_t *__restrict__ parent, uint8_t *__restrict__ code)
+{
+    __shared__ uint16_t list[kExpandCap];
+    const int lane = lane_id();
+    const int d4n = D >> 2;
+    // words of a vector: j = 8 l + 4 h + i; a lane takes j = lane + 64 t, so (h, i) is fixed per lane
+    const int wh = (lane >> 2) & 1, wi = lane & 3;
+    uint32_t vm = 0u;                                   // bits of real codewords (k < K)
+    for (int p = 0; p < 32; ++p)
+        if (64 * wi + 8 * (p >> 2) + 4 * wh + (p & 3) < K) vm |= 1u << p;
+    const uint32_t *mw = reinterpret_cast<const uint32_t *>(masks);
+    const int nwords = 8 * Lc;
+    const double inf = __builtin_inf();
+
+    for (int64_t n = blockIdx.x; n < N; n += gridDim.x) {
+        uint32_t W[4];
+        int cnt = 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int j = lane + 64 * t;
+            W[t] = (j < nwords) ? (mw[(size_t)n * nwords + j] & vm) : 0u;
+            cnt += __popc(W[t]);
+        }
+        int incl = cnt;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const int y = __shfl_up(incl, o, kWave);
+            if (lane >= o) incl += y;
+        }
+        const int total = __shfl(incl, kWave - 1, kWave);
+        const int off = incl - cnt;
+
+        double E = inf;                                  // lane i: i-th best so far
+        int ID = 0x7fffffff;                             // (l << 8) | k
+        for (int base = 0; base < total; base += kExpandCap) {
+            int pos = off - base;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                uint32_t bits = W[t];
+                const int l = (lane + 64 * t) >> 3;
+                while (bits) {
+                    const int p = __ffs(bits) - 1;
+                    bits &= bits - 1;
+                    if (pos >= 0 && pos < kExpandCap)
+                        list[pos] = (uint16_t)((l << 8) | (64 * wi + 8 * (p >> 2) + 4 * wh + (p & 3)));
+                    ++pos;
+                }
+            }
+            __syncthreads();
+            const int nround = min(kExpandCap, total - base);
+            for (int c0 = 0; c0 < nround; c0 += 8) {
+                const int c = c0 + (lane >> 3);
+                const int ent = (c < nround) ? (int)list[c] : 0;
+                const float4 *a = reinterpret_cast<const float4 *>(rows_c + ((size_t)n * Lc + (ent >> 8)) * ldc);
+                const float4 *b = reinterpret_cast<const float4 *>(Cm + (size_t)(ent & 255) * D);
+                double s = 0.0;
+                for (int d = lane & 7; d < d4n; d += 8) {
+                    const float4 u = a[d], v = b[d];
+                    const double t0 = (double)u.x - (double)v.x, t1 = (double)u.y - (double)v.y;
+                    const double t2 = (double)u.z - (double)v.z, t3 = (double)u.w - (double)v.w;
+                    s += t0 * t0;
+                    s += t1 * t1;
+                    s += t2 * t2;
+                    s += t3 * t3;
+                }
+                s += __shfl_xor(s, 1, kWave);
+                s += __shfl_xor(s, 2, kWave);
+                s += __shfl_xor(s, 4, kWave);
+                if (!(s == s)) s = inf;                  // non-finite input sorts last
+                const int ng = min(8, nround - c0);
+                for (int g = 0; g < ng; ++g) {
+                    const double e = __shfl(s, 8 * g, kWave);
+                    const int id = __shfl(ent, 8 * g, kWave);
+                    const bool less = (E < e) || (E == e && ID < id);
+                    const int at = __popcll(__ballot(less));
+                    if (at < Ln) {
+                        const double Eu = __shfl_up(E, 1, kWave);
+                        const int IDu = __shfl_up(ID, 1, kWave);
+                        if (lane == at) { E = e; ID = id; }
+                        else if (lane > at) { E = Eu; ID = IDu; }
+                    }
+                }
+            }
+            __syncthreads();
+        }
+
+        // the next beam: two rows per pass, 32 lanes each
+        const int half = lane >> 5, l32 = lane & 31;
+        for (int i0 = 0; i0 < Ln; i0 += 2) {
+            const int i = i0 + half;
+            const bool ok = i < Ln;
+            int id = __shfl(ID, ok ? i : 0, kWave);
+            const double e = __shfl(E, ok ? i : 0, kWave);
+            if (id == 0x7fffffff) id = 0;                // fewer candidates than Ln: non-finite input only
+            const int l = id >> 8, k = id & 255;
+            if (ok) {
+                const float4 *a = reinterpret_cast<const float4 *>(rows_c + ((size_t)n * Lc + l) * ldc);
+                const float4 *b = reinterpret_cast<const float4 *>(Cm + (size_t)k * D);
+                float4 *o = reinterpret_cast<float4 *>(rows_n + ((size_t)n * Ln + i) * ldn);
+                for (int d = l32; d < d4n; d += 32) {
+                    const float4 u = a[d], v = b[d];
+                    o[d] = make_float4(u.x - v.x, u.y - v.y, u.z - v.z, u.w - v.w);
+                }
+                const size_t slot = (size_t)n * Ln + i;
+                if (pre_n) {
+                    for (int j = l32; j < m; j += 32) pre_n[slot * M + j] = pre_c[((size_t)n * Lc + l) * M + j];
+                    if (l32 == 0) pre_n[slot * M + m] = (uint8_t)k;
+                }
+                if (l32 == 0) {
+                    if (err_n) err_n[slot] = e;
+                    if (parent) parent[slot] = (uint8_t)l;
+                    if (code) code[slot] = (uint8_t)k;
+                }
+            }
+        }
+    }
+}
+
+}  // namespace hclae

@@ -14,6 +14,7 @@
 #include "update.hpp"
 #include "pca.hpp"
 #include "stats.hpp"
+#include "beam.hpp"
 #include <algorithm>
 #include <vector>
 
@@ -66,6 +67,14 @@ struct hclae_ctx {
     double *pca_mean;        // [D]
     float *pca_mean32;       // [D]
     int pca_ncol, pca_ngram;
+    // multi-path encoding scratch (allocated on first use, regrown when L or the batch grows)
+    int64_t beam_cap;        // vectors per batch the buffers hold
+    int beam_L;              // beam width they were sized for
+    int sweep_L;             // paths of the re-encode of hclae_sweep, reencode_mode 2
+    float *beam_rows[2];     // [beam_cap][beam_L][D] residuals, ping-pong
+    double *beam_err[2];     // [beam_cap][beam_L]
+    uint8_t *beam_pre[2];    // [beam_cap][beam_L][M] code prefixes
+    BeamMask *beam_mask;     // [beam_cap][beam_L]
     // optional per-kernel timing (HIP events on ctx->stream)
     uint32_t t_mask;
     int t_used;
@@ -402,6 +411,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
     memset(ctx, 0, sizeof(*ctx));
     ctx->N_max = N_max; ctx->D = D; ctx->M = M; ctx->K = K;
     ctx->stream = static_cast<hipStream_t>(hip_stream);
+    ctx->sweep_L = 10;                       // the width the paper settles on (Sec. 3.3)
     ctx->kb = K <= 32 ? 1 : K <= 64 ? 2 : K <= 128 ? 4 : 8;
     ctx->NC = (D + kChunkD - 1) / kChunkD;
     ctx->resident = (size_t)32 * ctx->kb * kChunkD * ctx->NC * sizeof(float) + 4096 <= (size_t)kLdsBudget;
@@ -470,7 +480,9 @@ int hclae_destroy(hclae_ctx *ctx)
     void *dev[] = {ctx->hneg, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
                    ctx->nk, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
                    ctx->run_sum, ctx->run_cnt, ctx->n0_dev, ctx->pca_rt, ctx->pca_crot, ctx->pca_colpart,
-                   ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32};
+                   ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32,
+                   ctx->beam_rows[0], ctx->beam_rows[1], ctx->beam_err[0], ctx->beam_err[1],
+                   ctx->beam_pre[0], ctx->beam_pre[1], ctx->beam_mask};
     for (void *p : dev)
         if (p) (void)hipFree(p);
     if (ctx->rec_host) (void)hipHostFree(ctx->rec_host);
@@ -614,15 +626,27 @@ int hclae_anneal_stage(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M,
     return HCLAE_OK;
 }
 
+static int enqueue_encode_beam(hclae_ctx *ctx, const float *X, int64_t N, const float *C, int L,
+                               uint8_t *codes, float *residue, double *err);
+
+int hclae_set_beam_width(hclae_ctx *ctx, int L)
+{
+    if (!ctx) return HCLAE_EINVAL;
+    if (L < 1 || L > kBeamMaxL) return fail(ctx, HCLAE_EINVAL, "hclae_set_beam_width: need 1 <= L <= 32");
+    ctx->sweep_L = L;
+    return HCLAE_OK;
+}
+
 int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int M, int K,
                 uint8_t *codes, float *residue, int iters, int reencode_mode,
                 const int64_t *init_idx, double *err_per_stage)
 {
     int rc = check_call(ctx, N, D, M, K);
     if (rc != HCLAE_OK) return rc;
-    if (iters < 0 || (N > 0 && (!C || !codes || !residue)) || (reencode_mode != 0 && reencode_mode != 1))
+    if (iters < 0 || (N > 0 && (!C || !codes || !residue)) || reencode_mode < 0 || reencode_mode > 2)
         return fail(ctx, HCLAE_EINVAL, "hclae_sweep: bad argument");
-    if (reencode_mode == 1 && N > 0 && (!X || X == residue)) return fail(ctx, HCLAE_EINVAL, "hclae_sweep: reencode_mode 1 needs X");
+    if (reencode_mode != 0 && N > 0 && (!X || X == residue))
+        return fail(ctx, HCLAE_EINVAL, "hclae_sweep: reencode_mode 1 and 2 need X");
     if (init_idx && check_init_idx(init_idx, M * K, N) != HCLAE_OK)
         return fail(ctx, HCLAE_EINVAL, "hclae_sweep: init_idx out of range");
     if (N == 0) {
@@ -636,8 +660,10 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
         if ((rc = enqueue_stage(ctx, m, N, C, codes, residue, iters, idx, m, fuse && m > 0,
                                 (fuse && m + 1 < M) ? m + 1 : -1)) != HCLAE_OK) return rc;
         if (idx) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));   // seed_idx scratch is reused by the next stage
-        if (reencode_mode == 1) {
-            if ((rc = enqueue_encode(ctx, X, N, C, codes, residue)) != HCLAE_OK) return rc;
+        if (reencode_mode != 0) {
+            rc = reencode_mode == 1 ? enqueue_encode(ctx, X, N, C, codes, residue)
+                                    : enqueue_encode_beam(ctx, X, N, C, ctx->sweep_L, codes, residue, nullptr);
+            if (rc != HCLAE_OK) return rc;
             if (err_per_stage) {
                 const int blocks = launch_sqnorm(ctx, residue, N, ctx->part_b);
                 if (blocks < 0) return blocks;
@@ -743,6 +769,190 @@ int hclae_online_chunk(hclae_ctx *ctx, const uint8_t *Xu8, int64_t n, int D, flo
         }
     }
     return HCLAE_OK;
+}
+
+// ---- multi-path encoding (Sec. 3.3) --------------------------------------------------------------
+
+static void beam_release(hclae_ctx *ctx)
+{
+    void *dev[] = {ctx->beam_rows[0], ctx->beam_rows[1], ctx->beam_err[0], ctx->beam_err[1],
+                   ctx->beam_pre[0], ctx->beam_pre[1], ctx->beam_mask};
+    for (void *p : dev)
+        if (p) (void)hipFree(p);
+    ctx->beam_rows[0] = ctx->beam_rows[1] = nullptr;
+    ctx->beam_err[0] = ctx->beam_err[1] = nullptr;
+    ctx->beam_pre[0] = ctx->beam_pre[1] = nullptr;
+    ctx->beam_mask = nullptr;
+    ctx->beam_cap = 0;
+    ctx->beam_L = 0;
+}
+
+// Buffers for batches of `cap` vectors with L paths each.  with_state: also the residual, error and
+// prefix ping-pong buffers (hclae_encode_beam); the single step only needs the candidate bitmaps.
+static int beam_scratch(hclae_ctx *ctx, int64_t cap, int L, bool with_state)
+{
+    const bool have_state = ctx->beam_rows[0] != nullptr;
+    if (ctx->beam_mask && ctx->beam_cap >= cap && ctx->beam_L >= L && (have_state || !with_state)) return HCLAE_OK;
+    // stream-ordered work may still use the old buffers
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->beam_cap > cap) cap = ctx->beam_cap;
+    if (ctx->beam_L > L) L = ctx->beam_L;
+    with_state = with_state || have_state;
+    beam_release(ctx);
+    const size_t rows = (size_t)cap * L;
+    hipError_t e = hipMalloc((void **)&ctx->beam_mask, rows * sizeof(BeamMask));
+    for (int i = 0; i < 2 && with_state; ++i) {
+        if (e == hipSuccess) e = hipMalloc((void **)&ctx->beam_rows[i], rows * ctx->D * sizeof(float));
+        if (e == hipSuccess) e = hipMalloc((void **)&ctx->beam_err[i], rows * sizeof(double));
+        if (e == hipSuccess) e = hipMalloc((void **)&ctx->beam_pre[i], rows * ctx->M);
+    }
+    if (e != hipSuccess) {
+        beam_release(ctx);
+        return fail(ctx, e == hipErrorOutOfMemory ? HCLAE_ENOMEM : HCLAE_EHIP, "hipMalloc (multi-path scratch)", e);
+    }
+    ctx->beam_cap = cap;
+    ctx->beam_L = L;
+    return HCLAE_OK;
+}
+
+extern "C++" {
+template <int KB>
+static int launch_beam_score_kb(hclae_ctx *ctx, const float *rows, const double *err, const float *Cm,
+                                int64_t N, int Lc, int Ln, BeamMask *masks)
+{
+    const int D = ctx->D;
+    const int NC = ctx->NC;
+    const int dpad = kChunkD * NC;
+    // bound on the rounding error of a shifted score, relative to hmax + ||r|| cmax + ||r||^2:
+    // dpad + 1 accumulation steps of relative size 2^-23, plus the roundings of the norm, the
+    // shift by the beam error, the threshold arithmetic and of the residual rows themselves
+    const float gamma = 1.01f * (float)(dpad + 8) * 1.1920929e-7f;
+    const int V = kTileVec / Lc;
+    const int64_t ntiles = (N + V - 1) / V;
+    Timed t_(ctx, HCLAE_T_BEAM_SCORE);
+    if (ctx->resident) {
+        const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
+        int64_t blocks = (ntiles + kAssignWaves - 1) / kAssignWaves;
+        if (blocks > ctx->cus) blocks = ctx->cus;
+        static bool attr_set = false;
+        if (!attr_set) {
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_beam_score_resident<KB>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            attr_set = true;
+        }
+        hipLaunchKernelGGL((k_beam_score_resident<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
+                           rows, err, Cm, ctx->hneg, N, Lc, Ln, D, D, ctx->K, NC, gamma, masks);
+    } else {
+        const size_t lds = (size_t)KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
+        const int64_t nbt = (ntiles + kAssignWaves - 1) / kAssignWaves;
+        int64_t blocks = nbt < 2 * ctx->cus ? nbt : 2 * ctx->cus;
+        static bool attr_set = false;
+        if (!attr_set) {
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_beam_score_chunked<KB>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            attr_set = true;
+        }
+        hipLaunchKernelGGL((k_beam_score_chunked<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
+                           rows, err, Cm, ctx->hneg, N, Lc, Ln, D, D, ctx->K, NC, gamma, masks);
+    }
+    HIP_TRY(ctx, hipGetLastError());
+    return HCLAE_OK;
+}
+}  // extern "C++"
+
+// One dictionary of the beam for N vectors: norms, scoring, exact expansion.  rows_c has stride D.
+static int enqueue_beam_step(hclae_ctx *ctx, const float *rows_c, const double *err_c, const float *Cm,
+                             int64_t N, int Lc, int Ln, const uint8_t *pre_c, uint8_t *pre_n, int m,
+                             float *rows_n, double *err_n, uint8_t *parent, uint8_t *code)
+{
+    int rc;
+    if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
+    switch (ctx->kb) {
+    case 1: rc = launch_beam_score_kb<1>(ctx, rows_c, err_c, Cm, N, Lc, Ln, ctx->beam_mask); break;
+    case 2: rc = launch_beam_score_kb<2>(ctx, rows_c, err_c, Cm, N, Lc, Ln, ctx->beam_mask); break;
+    case 4: rc = launch_beam_score_kb<4>(ctx, rows_c, err_c, Cm, N, Lc, Ln, ctx->beam_mask); break;
+    default: rc = launch_beam_score_kb<8>(ctx, rows_c, err_c, Cm, N, Lc, Ln, ctx->beam_mask); break;
+    }
+    if (rc != HCLAE_OK) return rc;
+    int64_t blocks = N < (int64_t)ctx->cus * 32 ? N : (int64_t)ctx->cus * 32;
+    Timed t_(ctx, HCLAE_T_BEAM_EXPAND);
+    hipLaunchKernelGGL(k_beam_expand, dim3((unsigned)blocks), dim3(kWave), 0, ctx->stream,
+                       rows_c, ctx->D, ctx->beam_mask, Cm, ctx->K, ctx->D, N, Lc, Ln,
+                       pre_c, pre_n, ctx->M, m, rows_n, ctx->D, err_n, parent, code);
+    HIP_TRY(ctx, hipGetLastError());
+    return HCLAE_OK;
+}
+
+static int beam_next_width(int K, int Lc, int L)
+{
+    const long total = (long)K * Lc;
+    return L < total ? L : (int)total;
+}
+
+// Vectors per batch of the multi-path encoder: residual buffers of at most 2^29 floats each.
+static int64_t beam_batch(const hclae_ctx *ctx, int64_t N, int L)
+{
+    int64_t cap = ((int64_t)1 << 29) / ((int64_t)L * ctx->D);
+    if (cap < 1024) cap = 1024;
+    return N < cap ? N : cap;
+}
+
+static int enqueue_encode_beam(hclae_ctx *ctx, const float *X, int64_t N, const float *C, int L,
+                               uint8_t *codes, float *residue, double *err)
+{
+    const int D = ctx->D, K = ctx->K, M = ctx->M;
+    if (N == 0) return HCLAE_OK;
+    const int64_t cap = beam_batch(ctx, N, L);
+    int rc = beam_scratch(ctx, cap, L, true);
+    if (rc != HCLAE_OK) return rc;
+    for (int64_t n0 = 0; n0 < N; n0 += cap) {
+        const int64_t nb = N - n0 < cap ? N - n0 : cap;
+        const float *rows_c = X + n0 * D;
+        const double *err_c = nullptr;
+        const uint8_t *pre_c = nullptr;
+        int Lc = 1;
+        for (int m = 0; m < M; ++m) {
+            const bool last = (m == M - 1);
+            const int Ln = last ? 1 : beam_next_width(K, Lc, L);    // the answer is the best of the last beam
+            float *rows_n = last ? residue + n0 * D : ctx->beam_rows[m & 1];
+            double *err_n = last ? (err ? err + n0 : nullptr) : ctx->beam_err[m & 1];
+            uint8_t *pre_n = last ? codes + n0 * M : ctx->beam_pre[m & 1];
+            rc = enqueue_beam_step(ctx, rows_c, err_c, C + (size_t)m * K * D, nb, Lc, Ln, pre_c, pre_n, m,
+                                   rows_n, err_n, nullptr, nullptr);
+            if (rc != HCLAE_OK) return rc;
+            rows_c = rows_n; err_c = err_n; pre_c = pre_n; Lc = Ln;
+        }
+    }
+    return HCLAE_OK;
+}
+
+int hclae_beam_step(hclae_ctx *ctx, const float *rows, const double *err, const float *Cm,
+                    int64_t N, int D, int K, int Lc, int L,
+                    float *rows_next, double *err_next, uint8_t *parent, uint8_t *code)
+{
+    int rc = check_call(ctx, N, D, ctx ? ctx->M : 1, K);
+    if (rc != HCLAE_OK) return rc;
+    if (L < 1 || L > kBeamMaxL || Lc < 1 || Lc > L)
+        return fail(ctx, HCLAE_EINVAL, "hclae_beam_step: need 1 <= Lc <= L <= 32");
+    if (N == 0) return HCLAE_OK;
+    if (!rows || !Cm || !rows_next || rows_next == rows)
+        return fail(ctx, HCLAE_EINVAL, "hclae_beam_step: NULL or aliased rows");
+    if (N * (int64_t)L >= ((int64_t)1 << 31)) return fail(ctx, HCLAE_EINVAL, "hclae_beam_step: N * L too large");
+    if ((rc = beam_scratch(ctx, N, L, false)) != HCLAE_OK) return rc;
+    return enqueue_beam_step(ctx, rows, err, Cm, N, Lc, beam_next_width(K, Lc, L), nullptr, nullptr, 0,
+                             rows_next, err_next, parent, code);
+}
+
+int hclae_encode_beam(hclae_ctx *ctx, const float *X, int64_t N, int D, const float *C, int M, int K, int L,
+                      uint8_t *codes, float *residue, double *err)
+{
+    int rc = check_call(ctx, N, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (L < 1 || L > kBeamMaxL) return fail(ctx, HCLAE_EINVAL, "hclae_encode_beam: need 1 <= L <= 32");
+    if (N == 0) return HCLAE_OK;
+    if (!X || !C || !codes || !residue || residue == X)
+        return fail(ctx, HCLAE_EINVAL, "hclae_encode_beam: NULL or aliased pointer");
+    return enqueue_encode_beam(ctx, X, N, C, L, codes, residue, err);
 }
 
 // ---- improved k-means (Sec. 3.2) ---------------------------------------------------------------

@@ -24,10 +24,11 @@ EXPORTS = (
     "hclae_online_export", "hclae_online_import",
     "hclae_covariance", "hclae_rotate", "hclae_assign_prefix", "hclae_anneal_stage_pca",
     "hclae_reorder_by_variance", "hclae_code_stats",
+    "hclae_beam_step", "hclae_encode_beam", "hclae_set_beam_width",
 )
 
 KERNEL_CLASSES = ("heat", "cool", "assign", "refine", "accumulate", "merge", "norms", "error", "transition",
-                  "rotate", "moments")
+                  "rotate", "moments", "beam_score", "beam_expand")
 
 
 class KernelTimes(ctypes.Structure):
@@ -90,6 +91,9 @@ def lib():
                                          ctypes.POINTER(StageStats)]
     L.hclae_reorder_by_variance.argtypes = [vp, i64, i32, vp, i32, i32, vp, vp, vp]
     L.hclae_code_stats.argtypes = [vp, vp, i64, i32, i32, vp, i32, i32, vp]
+    L.hclae_beam_step.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp]
+    L.hclae_encode_beam.argtypes = [vp, vp, i64, i32, vp, i32, i32, i32, vp, vp, vp]
+    L.hclae_set_beam_width.argtypes = [vp, i32]
     L.hclae_timing_enable.argtypes = [vp, ctypes.c_uint32]
     L.hclae_timing_read.argtypes = [vp, ctypes.POINTER(KernelTimes)]
     for name in EXPORTS:
@@ -108,7 +112,7 @@ def _ptr(t, dtype_name, shape=None):
     if t is None:
         return None
     import torch
-    want = {"f32": torch.float32, "u8": torch.uint8, "i32": torch.int32}[dtype_name]
+    want = {"f32": torch.float32, "u8": torch.uint8, "i32": torch.int32, "f64": torch.float64}[dtype_name]
     if not (t.is_cuda and t.dtype == want and t.is_contiguous()):
         raise TypeError("expected a contiguous CUDA %s tensor" % dtype_name)
     if shape is not None and tuple(t.shape) != tuple(shape):
@@ -155,6 +159,24 @@ class Context:
         N = X.shape[0]
         pC, pcodes, pres = self._shapes(N, C, codes, residue)
         self._chk(lib().hclae_encode(self._h, _ptr(X, "f32", (N, self.D)), N, self.D, pC, self.M, self.K, pcodes, pres))
+
+    def beam_step(self, rows, err, Cm, L, rows_next, err_next=None, parent=None, code=None):
+        """One dictionary of the multi-path encoding: rows f32 [N][Lc][D], err f64 [N][Lc] or None."""
+        N, Lc = rows.shape[0], rows.shape[1]
+        Ln = min(L, self.K * Lc)
+        self._chk(lib().hclae_beam_step(
+            self._h, _ptr(rows, "f32", (N, Lc, self.D)), _ptr(err, "f64", (N, Lc)), _ptr(Cm, "f32", (self.K, self.D)),
+            N, self.D, self.K, Lc, L, _ptr(rows_next, "f32", (N, Ln, self.D)), _ptr(err_next, "f64", (N, Ln)),
+            _ptr(parent, "u8", (N, Ln)), _ptr(code, "u8", (N, Ln))))
+
+    def encode_beam(self, X, C, L, codes, residue, err=None):
+        N = X.shape[0]
+        pC, pcodes, pres = self._shapes(N, C, codes, residue)
+        self._chk(lib().hclae_encode_beam(self._h, _ptr(X, "f32", (N, self.D)), N, self.D, pC, self.M, self.K, L,
+                                          pcodes, pres, _ptr(err, "f64", (N,))))
+
+    def set_beam_width(self, L):
+        self._chk(lib().hclae_set_beam_width(self._h, L))
 
     def anneal_stage(self, m, C, codes, residue, iters, init_idx=None, want_stats=True):
         N = residue.shape[0]
