@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--online", type=int, default=0, metavar="CHUNKS",
                     help="instead of the sweep benchmark: stream CHUNKS uint8 chunks of --n vectors from pinned host "
                          "memory through the online learner (ring of 4 distinct chunks) and report end-to-end vectors/s")
+    ap.add_argument("--beam", type=int, default=0, metavar="L",
+                    help="instead of the sweep benchmark: learn the dictionaries with one fresh sweep, then time the "
+                         "multi-path encoder (Sec. 3.3) with L paths over the --n resident vectors")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -49,6 +52,8 @@ def main():
     N, D, M, K, T, Q = args.n, 128, args.m, 256, args.iters, args.queries
     if args.online:
         return online_bench(args, torch, hclae, synth, dev)
+    if args.beam:
+        return beam_bench(args, torch, hclae, synth, dev)
 
     t_gen = time.perf_counter()
     X = synth.sift_like(N, D=D)
@@ -163,6 +168,55 @@ def main():
                                          "%d vectors of the same workload, %.1f s" % (T, Ns, tc)}
     out["host_gen_s"] = t_gen
     print(json.dumps(out))
+    ctx.close()
+
+
+def beam_bench(args, torch, hclae, synth, dev):
+    """Multi-path encoding of the N resident vectors with L paths under dictionaries learned from scratch by one
+    sweep.  Reported beside, not instead of, the sweep benchmark."""
+    N, D, M, K, T, L = args.n, 128, args.m, 256, args.iters, args.beam
+    X = synth.sift_like(N, D=D)
+    Xg = torch.from_numpy(X).to(dev)
+    C = torch.zeros((M, K, D), dtype=torch.float32, device=dev)
+    codes = torch.zeros((N, M), dtype=torch.uint8, device=dev)
+    r = Xg.clone()
+    ctx = hclae.Context(N, D, M, K)
+    ctx.sweep(C, codes, r, T, init_idx=synth.init_indices(N, M, K), want_err=False)
+    ctx.encode(Xg, C, codes, r)
+    e_greedy = ctx.quant_error(r)
+    for _ in range(max(args.warmup, 1)):
+        ctx.encode_beam(Xg, C, L, codes, r)
+    torch.cuda.synchronize()
+    ctx.timing_enable(["beam_score", "beam_expand", "norms"])
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.encode_beam(Xg, C, L, codes, r)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ctx.timing_enable([])
+    times = ctx.timing_read()
+    e_beam = ctx.quant_error(r)
+    per = (t1 - t0) / args.steps
+    rows = N * (1 + (M - 1) * min(L, K))                  # beam rows scored per encode: 1 path, then L
+    flops = 2.0 * rows * K * D
+    s_ms, s_n = times["beam_score"]
+    x_ms, x_n = times["beam_expand"]
+    achieved = flops * args.steps / (s_ms * 1e-3) / 1e12 if s_ms else None
+    print(json.dumps({
+        "metric": "multi-path encoding vectors/sec (D=128, K=256, M=%d, L=%d)" % (M, L),
+        "value": N / per, "unit": "vectors/s", "n_gpus": 1, "steps": args.steps, "warmup": max(args.warmup, 1),
+        "ms_per_step": per * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "SIFT-shaped: N=%d, D=128, M=%d, K=256; dictionaries from one fresh DA sweep (T=%d); "
+                               "one step = multi-path encoding of all N vectors with L=%d" % (N, M, T, L),
+                   "quant_error_greedy": e_greedy, "quant_error_multipath": e_beam},
+        "roofline": {"bound": "mfma", "kernel": "k_beam_score_resident<8> (fp32 MFMA scoring of N*L beam rows)",
+                     "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS if achieved else None, "traffic": None,
+                     "flops_per_step": flops},
+        "kernels": {"beam_score": {"ms_per_step": s_ms / args.steps, "launches": s_n},
+                    "beam_expand": {"ms_per_step": x_ms / args.steps, "launches": x_n}},
+    }))
     ctx.close()
 
 

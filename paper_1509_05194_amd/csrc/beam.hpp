@@ -225,14 +225,22 @@ __global__ __launch_bounds__(kAssignThreads) void k_beam_score_chunked(
     }
 }
 
-constexpr int kExpandCap = 256;      // candidates listed per round
+constexpr int kExpandChunk = 32;     // candidates evaluated and ranked at a time
+constexpr int kExpandList = 512;     // candidates listed in LDS at a time
 
-// Exact evaluation and selection for one dictionary; one wave (= one 64-thread block slot) per
-// vector.  The vector's marked candidates are listed in LDS (kExpandCap at a time), eight at a
-// time are evaluated in fp64 in the direct form by groups of eight lanes, and each is inserted
-// into a list kept sorted by (error, l, k) across the lanes (lane i holds the i-th best).  The
-// first Ln entries become the next beam: residual rows r_l - c(k) rounded to fp32, their fp64
-// errors, and the parent's code prefix extended by k.
+// (error, id) order of the candidates: smaller error first, equal errors by id = (l << 8) | k.
+__device__ __forceinline__ bool beam_before(double ea, int ia, double eb, int ib)
+{
+    return (ea < eb) || (ea == eb && ia < ib);
+}
+
+// Exact evaluation and selection for one dictionary; one wave (a 64-thread block) per vector.
+// The vector's marked candidates are listed in LDS (kExpandList at a time).  kExpandChunk at a time they
+// are evaluated in fp64 in the direct form, four lanes per candidate, and land one per lane in
+// lanes 0..31; lanes 32..63 hold the best Ln found so far.  Every lane counts how many of the
+// others come before it in (error, l, k) order: that rank is its position, and ranks below Ln are
+// the new best list (kept in LDS).  After the last chunk the list is the next beam: residual rows
+// r_l - c(k) rounded to fp32, their fp64 errors, and the parent's code prefix extended by k.
 //   rows_c [N*Lc] stride ldc -> rows_n [N*Ln] stride ldn;  pre_c [N][Lc][M] -> pre_n [N][Ln][M]
 //   (bytes 0..m-1 copied, byte m = k);  err_n, parent, code: [N*Ln], each may be null.
 __global__ __launch_bounds__(kWave) void k_beam_expand(
@@ -242,7 +250,9 @@ __global__ __launch_bounds__(kWave) void k_beam_expand(
     float *__restrict__ rows_n, int ldn, double *__restrict__ err_n,
     uint8_t *__restrict__ parent, uint8_t *__restrict__ code)
 {
-    __shared__ uint16_t list[kExpandCap];
+    __shared__ uint16_t list[kExpandList];
+    __shared__ double win_e[kBeamMaxL];
+    __shared__ int win_id[kBeamMaxL];
     const int lane = lane_id();
     const int d4n = D >> 2;
     // words of a vector: j = 8 l + 4 h + i; a lane takes j = lane + 64 t, so (h, i) is fixed per lane
@@ -253,15 +263,24 @@ __global__ __launch_bounds__(kWave) void k_beam_expand(
     const uint32_t *mw = reinterpret_cast<const uint32_t *>(masks);
     const int nwords = 8 * Lc;
     const double inf = __builtin_inf();
+    const int none = 0x7fffffff;
 
+    uint32_t Wn[4];                                      // bitmap words of the next vector, fetched ahead
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int j = lane + 64 * t;
+        Wn[t] = (j < nwords && (int64_t)blockIdx.x < N) ? mw[(size_t)blockIdx.x * nwords + j] : 0u;
+    }
     for (int64_t n = blockIdx.x; n < N; n += gridDim.x) {
         uint32_t W[4];
         int cnt = 0;
+        const int64_t nn = n + gridDim.x;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int j = lane + 64 * t;
-            W[t] = (j < nwords) ? (mw[(size_t)n * nwords + j] & vm) : 0u;
+            W[t] = Wn[t] & vm;
             cnt += __popc(W[t]);
+            Wn[t] = (j < nwords && nn < N) ? mw[(size_t)nn * nwords + j] : 0u;
         }
         int incl = cnt;
 #pragma unroll
@@ -270,12 +289,14 @@ __global__ __launch_bounds__(kWave) void k_beam_expand(
             if (lane >= o) incl += y;
         }
         const int total = __shfl(incl, kWave - 1, kWave);
-        const int off = incl - cnt;
+        const int off = incl - cnt;                      // list position of the lane's first candidate
+        if (lane < kBeamMaxL) { win_e[lane] = inf; win_id[lane] = none; }
+        __syncthreads();
 
-        double E = inf;                                  // lane i: i-th best so far
-        int ID = 0x7fffffff;                             // (l << 8) | k
-        for (int base = 0; base < total; base += kExpandCap) {
-            int pos = off - base;
+        int nwin = 0;                                    // entries of the best list so far
+        for (int lbase = 0; lbase < total; lbase += kExpandList) {
+        {   // list the candidates lbase .. lbase + kExpandList - 1 (any order: the ranking key is total)
+            int at = off - lbase;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 uint32_t bits = W[t];
@@ -283,78 +304,117 @@ __global__ __launch_bounds__(kWave) void k_beam_expand(
                 while (bits) {
                     const int p = __ffs(bits) - 1;
                     bits &= bits - 1;
-                    if (pos >= 0 && pos < kExpandCap)
-                        list[pos] = (uint16_t)((l << 8) | (64 * wi + 8 * (p >> 2) + 4 * wh + (p & 3)));
-                    ++pos;
+                    if (at >= 0 && at < kExpandList)
+                        list[at] = (uint16_t)((l << 8) | (64 * wi + 8 * (p >> 2) + 4 * wh + (p & 3)));
+                    ++at;
                 }
             }
-            __syncthreads();
-            const int nround = min(kExpandCap, total - base);
-            for (int c0 = 0; c0 < nround; c0 += 8) {
-                const int c = c0 + (lane >> 3);
-                const int ent = (c < nround) ? (int)list[c] : 0;
+        }
+        __syncthreads();
+        const int nl = min(kExpandList, total - lbase);
+        for (int base = 0; base < nl; base += kExpandChunk) {
+            const int nc = min(kExpandChunk, nl - base);
+            // evaluate: pass p covers candidates base + 16 p + (lane >> 2), four lanes each
+            double e_mine = inf;
+            int id_mine = none;
+#pragma unroll 1
+            for (int p = 0; p < 2; ++p) {
+                if (16 * p >= nc) break;                 // uniform
+                const int c = 16 * p + (lane >> 2);
+                const int ent = (c < nc) ? (int)list[base + c] : 0;
                 const float4 *a = reinterpret_cast<const float4 *>(rows_c + ((size_t)n * Lc + (ent >> 8)) * ldc);
                 const float4 *b = reinterpret_cast<const float4 *>(Cm + (size_t)(ent & 255) * D);
-                double s = 0.0;
-                for (int d = lane & 7; d < d4n; d += 8) {
-                    const float4 u = a[d], v = b[d];
+                double s0 = 0.0, s1 = 0.0;
+                auto term = [&](const float4 &u, const float4 &v) {
                     const double t0 = (double)u.x - (double)v.x, t1 = (double)u.y - (double)v.y;
                     const double t2 = (double)u.z - (double)v.z, t3 = (double)u.w - (double)v.w;
-                    s += t0 * t0;
-                    s += t1 * t1;
-                    s += t2 * t2;
-                    s += t3 * t3;
+                    s0 = fma(t0, t0, s0);
+                    s1 = fma(t1, t1, s1);
+                    s0 = fma(t2, t2, s0);
+                    s1 = fma(t3, t3, s1);
+                };
+                int d = lane & 3;
+                for (; d + 12 < d4n; d += 16) {          // four float4 pairs in flight per lane
+                    const float4 u0 = a[d], u1 = a[d + 4], u2 = a[d + 8], u3 = a[d + 12];
+                    const float4 v0 = b[d], v1 = b[d + 4], v2 = b[d + 8], v3 = b[d + 12];
+                    term(u0, v0);
+                    term(u1, v1);
+                    term(u2, v2);
+                    term(u3, v3);
                 }
+                for (; d < d4n; d += 4) term(a[d], b[d]);
+                double s = s0 + s1;
                 s += __shfl_xor(s, 1, kWave);
                 s += __shfl_xor(s, 2, kWave);
-                s += __shfl_xor(s, 4, kWave);
                 if (!(s == s)) s = inf;                  // non-finite input sorts last
-                const int ng = min(8, nround - c0);
-                for (int g = 0; g < ng; ++g) {
-                    const double e = __shfl(s, 8 * g, kWave);
-                    const int id = __shfl(ent, 8 * g, kWave);
-                    const bool less = (E < e) || (E == e && ID < id);
-                    const int at = __popcll(__ballot(less));
-                    if (at < Ln) {
-                        const double Eu = __shfl_up(E, 1, kWave);
-                        const int IDu = __shfl_up(ID, 1, kWave);
-                        if (lane == at) { E = e; ID = id; }
-                        else if (lane > at) { E = Eu; ID = IDu; }
-                    }
-                }
+                // candidate 16 p + q sits in lanes 4 q .. 4 q + 3; bring it to lane 16 p + q
+                const double sq = __shfl(s, 4 * (lane & 15), kWave);
+                const int iq = __shfl(ent, 4 * (lane & 15), kWave);
+                if ((lane >> 4) == p && lane < nc) { e_mine = sq; id_mine = iq; }
             }
+            if (lane >= 32) {                            // the best so far
+                const int i = lane - 32;
+                if (i < nwin) { e_mine = win_e[i]; id_mine = win_id[i]; }
+            }
+            __syncthreads();                             // win_* read before it is rewritten
+            // rank among the nc new candidates and the nwin kept ones
+            int rank = 0;
+            for (int j = 0; j < nc; ++j) {
+                const double ej = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(e_mine), j),
+                                                   __builtin_amdgcn_readlane(__double2loint(e_mine), j));
+                const int ij = __builtin_amdgcn_readlane(id_mine, j);
+                rank += beam_before(ej, ij, e_mine, id_mine) ? 1 : 0;
+            }
+            for (int j = 32; j < 32 + nwin; ++j) {
+                const double ej = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(e_mine), j),
+                                                   __builtin_amdgcn_readlane(__double2loint(e_mine), j));
+                const int ij = __builtin_amdgcn_readlane(id_mine, j);
+                rank += beam_before(ej, ij, e_mine, id_mine) ? 1 : 0;
+            }
+            const bool live = (lane < nc) || (lane >= 32 && lane - 32 < nwin);
+            if (live && rank < Ln) { win_e[rank] = e_mine; win_id[rank] = id_mine; }
+            nwin = min(Ln, nwin + nc);
             __syncthreads();
         }
+        }
 
-        // the next beam: two rows per pass, 32 lanes each
-        const int half = lane >> 5, l32 = lane & 31;
-        for (int i0 = 0; i0 < Ln; i0 += 2) {
-            const int i = i0 + half;
-            const bool ok = i < Ln;
-            int id = __shfl(ID, ok ? i : 0, kWave);
-            const double e = __shfl(E, ok ? i : 0, kWave);
-            if (id == 0x7fffffff) id = 0;                // fewer candidates than Ln: non-finite input only
-            const int l = id >> 8, k = id & 255;
-            if (ok) {
-                const float4 *a = reinterpret_cast<const float4 *>(rows_c + ((size_t)n * Lc + l) * ldc);
+        // the next beam: eight rows per pass, eight lanes each
+        const int sub = lane & 7;
+        for (int i0 = 0; i0 < Ln; i0 += 8) {
+            const int i = i0 + (lane >> 3);
+            if (i < Ln) {
+                int id = win_id[i];
+                if (id == none) id = 0;                  // fewer candidates than Ln: non-finite input only
+                const int l = id >> 8, k = id & 255;
+                const size_t src = (size_t)n * Lc + l, slot = (size_t)n * Ln + i;
+                const float4 *a = reinterpret_cast<const float4 *>(rows_c + src * ldc);
                 const float4 *b = reinterpret_cast<const float4 *>(Cm + (size_t)k * D);
-                float4 *o = reinterpret_cast<float4 *>(rows_n + ((size_t)n * Ln + i) * ldn);
-                for (int d = l32; d < d4n; d += 32) {
+                float4 *o = reinterpret_cast<float4 *>(rows_n + slot * ldn);
+                int d = sub;
+                for (; d + 24 < d4n; d += 32) {
+                    const float4 u0 = a[d], u1 = a[d + 8], u2 = a[d + 16], u3 = a[d + 24];
+                    const float4 v0 = b[d], v1 = b[d + 8], v2 = b[d + 16], v3 = b[d + 24];
+                    o[d] = make_float4(u0.x - v0.x, u0.y - v0.y, u0.z - v0.z, u0.w - v0.w);
+                    o[d + 8] = make_float4(u1.x - v1.x, u1.y - v1.y, u1.z - v1.z, u1.w - v1.w);
+                    o[d + 16] = make_float4(u2.x - v2.x, u2.y - v2.y, u2.z - v2.z, u2.w - v2.w);
+                    o[d + 24] = make_float4(u3.x - v3.x, u3.y - v3.y, u3.z - v3.z, u3.w - v3.w);
+                }
+                for (; d < d4n; d += 8) {
                     const float4 u = a[d], v = b[d];
                     o[d] = make_float4(u.x - v.x, u.y - v.y, u.z - v.z, u.w - v.w);
                 }
-                const size_t slot = (size_t)n * Ln + i;
                 if (pre_n) {
-                    for (int j = l32; j < m; j += 32) pre_n[slot * M + j] = pre_c[((size_t)n * Lc + l) * M + j];
-                    if (l32 == 0) pre_n[slot * M + m] = (uint8_t)k;
+                    for (int j = sub; j < m; j += 8) pre_n[slot * M + j] = pre_c[src * M + j];
+                    if (sub == 0) pre_n[slot * M + m] = (uint8_t)k;
                 }
-                if (l32 == 0) {
-                    if (err_n) err_n[slot] = e;
+                if (sub == 0) {
+                    if (err_n) err_n[slot] = win_e[i];
                     if (parent) parent[slot] = (uint8_t)l;
                     if (code) code[slot] = (uint8_t)k;
                 }
             }
         }
+        __syncthreads();                                 // list and win_* are reused by the next vector
     }
 }
 

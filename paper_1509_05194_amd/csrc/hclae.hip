@@ -889,10 +889,10 @@ static int beam_next_width(int K, int Lc, int L)
     return L < total ? L : (int)total;
 }
 
-// Vectors per batch of the multi-path encoder: residual buffers of at most 2^29 floats each.
+// Vectors per batch of the multi-path encoder: residual buffers of at most 2^31 floats (8 GiB) each.
 static int64_t beam_batch(const hclae_ctx *ctx, int64_t N, int L)
 {
-    int64_t cap = ((int64_t)1 << 29) / ((int64_t)L * ctx->D);
+    int64_t cap = ((int64_t)1 << 31) / ((int64_t)L * ctx->D);
     if (cap < 1024) cap = 1024;
     return N < cap ? N : cap;
 }

@@ -142,7 +142,7 @@ def test_encode_beam_batches_and_degenerate_shapes():
     Also N = 0, N = 1, K = 1 and a beam wider than K."""
     from paper_1509_05194_amd import hclae
     D, M, K, L = 960, 2, 256, 32
-    N = 40000 + 3                                    # 2^29 / (32 * 960) = 17476 vectors per batch
+    N = 150000 + 3                                   # 2^31 / (32 * 960) = 69905 vectors per batch
     g = torch.Generator(device="cuda:0").manual_seed(5194)
     X = torch.rand((N, D), generator=g, device="cuda:0")
     C = torch.rand((M, K, D), generator=g, device="cuda:0") * torch.tensor([1.0, 0.3], device="cuda:0")[:, None, None]
@@ -150,7 +150,7 @@ def test_encode_beam_batches_and_degenerate_shapes():
     codes = torch.empty((N, M), dtype=torch.uint8, device="cuda:0")
     res = torch.empty((N, D), dtype=torch.float32, device="cuda:0")
     ctx.encode_beam(X, C, L, codes, res)
-    for lo, hi in ((0, 9000), (17476 - 5, 17476 + 5000), (2 * 17476 - 1, N)):
+    for lo, hi in ((0, 9000), (69905 - 5, 69905 + 5000), (2 * 69905 - 1, N)):
         n = hi - lo
         c2 = torch.empty((n, M), dtype=torch.uint8, device="cuda:0")
         r2 = torch.empty((n, D), dtype=torch.float32, device="cuda:0")

@@ -141,3 +141,47 @@ def test_high_capacity_codes_two_sweeps(data):
         recon += C[m][codes[:, m].long()]
     assert (recon - Xg).abs().max().item() <= 2e-5 * 255.0
     ctx.close()
+
+
+def test_fullsize_multipath_encoding(data, oracle):
+    """Multi-path encoding (Sec. 3.3) of all N vectors with L = 10 in the launch configuration of
+    `bench.py --beam 10`: sampled vectors are re-encoded one by one by the oracle; for all vectors the
+    residue must be x minus the selected codewords and the reported error its squared norm."""
+    from paper_1509_05194_amd import hclae
+    from parity_util import REL_GAP
+    X, Xg = data
+    M, L = 8, 10
+    ctx = hclae.Context(N, D, M, K)
+    C = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+    codes = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+    r = Xg.clone()
+    ctx.sweep(C, codes, r, 2, init_idx=synth.init_indices(N, M, K), want_err=False)
+    e_greedy = ctx.quant_error(r)
+    err = torch.empty(N, dtype=torch.float64, device="cuda:0")
+    ctx.encode_beam(Xg, C, L, codes, r, err)
+    torch.cuda.synchronize()
+    e_beam = ctx.quant_error(r)
+    print("full-size multi-path: E greedy %.1f -> L=%d %.1f" % (e_greedy, L, e_beam))
+    assert e_beam < e_greedy
+    # properties over all N (fp32 on the GPU: one rounding per subtracted codeword)
+    recon = torch.zeros_like(Xg)
+    for m in range(M):
+        recon += C[m][codes[:, m].long()]
+    assert float((Xg - recon - r).abs().max()) <= 1e-6 * 255 * M
+    sq = (r.double() ** 2).sum(1)
+    assert float(((err - sq).abs() / sq.clamp(min=1.0)).max()) <= 5e-6
+    # sampled vectors against the oracle
+    rng = np.random.default_rng(3)
+    sample = np.sort(rng.choice(N, 1500, replace=False))
+    sample[-1] = N - 1
+    C64 = C.cpu().numpy().astype(np.float64)
+    codes_o, r_o, err_o, gap = oracle.encode_beam(np.ascontiguousarray(X[sample]), C64, L)
+    got = codes.cpu().numpy()[sample]
+    differ = np.nonzero((got != codes_o).any(1))[0]
+    bad = [int(sample[i]) for i in differ if not gap[i] < REL_GAP]
+    print("full-size multi-path: %d of %d sampled vectors differ (near-ties)" % (len(differ), len(sample)))
+    assert not bad and len(differ) <= 5
+    ok = np.ones(len(sample), bool)
+    ok[differ] = False
+    np.testing.assert_allclose(err.cpu().numpy()[sample][ok], err_o[ok], rtol=5e-6)
+    ctx.close()
