@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--online", type=int, default=0, metavar="CHUNKS",
                     help="instead of the sweep benchmark: stream CHUNKS uint8 chunks of --n vectors from pinned host "
                          "memory through the online learner (ring of 4 distinct chunks) and report end-to-end vectors/s")
+    ap.add_argument("--contraction", choices=["f32", "split"], default="f32",
+                    help="matrix-core arithmetic of the distance contraction: fp32 MFMA, or fp32 operands split into "
+                         "two bf16 terms on the bf16 MFMA (same results; see hclae_set_contraction)")
     ap.add_argument("--beam", type=int, default=0, metavar="L",
                     help="instead of the sweep benchmark: learn the dictionaries with one fresh sweep, then time the "
                          "multi-path encoder (Sec. 3.3) with L paths over the --n resident vectors")
@@ -69,6 +72,7 @@ def main():
     qcodes = torch.zeros((Q, M), dtype=torch.uint8, device=dev)
     qres = torch.empty((Q, D), dtype=torch.float32, device=dev)
     ctx = hclae.Context(N, D, M, K)
+    ctx.set_contraction(1 if args.contraction == "split" else 0)
 
     def step(first):
         ctx.timing_enable(["assign"])

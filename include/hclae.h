@@ -166,6 +166,20 @@ int hclae_online_chunk(hclae_ctx *ctx, const uint8_t *Xu8, int64_t n, int D, flo
 int hclae_online_export(hclae_ctx *ctx, double *run_sum, int64_t *run_cnt);
 int hclae_online_import(hclae_ctx *ctx, const double *run_sum, const int64_t *run_cnt);
 
+/* ---- choice of the matrix-core arithmetic of the distance contraction ------------------------- */
+
+#define HCLAE_CONTRACT_F32        0   /* fp32 MFMA (default)                                         */
+#define HCLAE_CONTRACT_SPLIT_BF16 1   /* fp32 operands split into two bf16 terms, three bf16 MFMAs   */
+
+/*
+ * Selects how the nearest-codeword kernels (Sec. 3.1 / 3.2 assignment; every entry point that assigns)
+ * form the scores x'.c - ||c||^2/2.  Either way the scores only pre-select candidates within a rigorous
+ * error margin and the decision is the fp64 direct-form re-check, so codes, dictionaries and residues do
+ * not depend on the mode; only the number of vectors that take the re-check does.  Mode 1 applies where
+ * the whole padded dictionary fits LDS (e.g. K = 256, D <= 128); other shapes keep the fp32 kernel.
+ */
+int hclae_set_contraction(hclae_ctx *ctx, int mode);
+
 /* ---- multi-path encoding (Sec. 3.3, Eq. 3) ---------------------------------------------------- */
 
 #define HCLAE_MAX_L 32     /* paths kept per vector */

@@ -1,0 +1,237 @@
+// Nearest-codeword assignment with the distance contraction on the bf16 matrix cores
+// (v_mfma_f32_32x32x16_bf16, 16x the rate of the fp32 MFMA on gfx950), fp32 operands split
+// into two bf16 terms each:  x = xh + xl + dx,  c = ch + cl + dc  with |dx| <= 2^-16 |x|.
+// The score x.c - ||c||^2/2 is accumulated in fp32 as  xh.ch + xh.cl + xl.ch  (three MFMAs per
+// 16 dims); what is dropped, xl.cl + dx.c + x.dc, is bounded by norms the kernel has, and that
+// bound joins the rounding bound of the accumulation in the margin of the decision: every codeword
+// whose score is within the margin of the best goes to the same fp64 direct-form re-check
+// (k_refine) as in the fp32 kernel.  The contraction only pre-selects candidates, so the codes
+// are the same fp64 direct-form decisions whichever kernel ran.
+//
+// Accumulation error of one 32x32x16 bf16 MFMA, measured on gfx950 over 4.6e6 random sums with
+// exponent spreads up to 2^+-16: at most 4.9 * 2^-24 * (|C| + sum |a_k b_k|).  The margin assumes
+// 2^-21 (8 * 2^-24) per MFMA.
+#pragma once
+#include "assign.hpp"
+
+namespace hclae {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+constexpr int kSplitStep = 16;                      // dims per bf16 MFMA
+
+// (a, b) -> packed bf16 pairs hi = RNE(a, b), lo = RNE(a - hi_a, b - hi_b); element 0 in the low half.
+__device__ __forceinline__ void split_pair(float a, float b, uint32_t &hi, uint32_t &lo)
+{
+    const floatx2 v = {a, b};
+    hi = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    const float ha = __uint_as_float(hi << 16), hb = __uint_as_float(hi & 0xffff0000u);
+    const floatx2 rem = {a - ha, b - hb};            // exact: hi keeps the leading 8 bits
+    lo = __builtin_bit_cast(uint32_t, __builtin_convertvector(rem, bf16x2));
+}
+
+__device__ __forceinline__ void split8(const float4 &u, const float4 &v, uint4 &hi, uint4 &lo)
+{
+    split_pair(u.x, u.y, hi.x, lo.x);
+    split_pair(u.z, u.w, hi.y, lo.y);
+    split_pair(v.x, v.y, hi.z, lo.z);
+    split_pair(v.z, v.w, hi.w, lo.w);
+}
+
+// Per-codebook constants of the split: for k < K over the first D coordinates (row stride ld)
+//   out[0] = max_k || cl_k ||   (low parts),   out[1] = max_k || c_k - ch_k - cl_k ||   (what two terms miss)
+// as fp32 rounded up.  One block; each wave takes every 16th codeword.
+__global__ __launch_bounds__(1024) void k_split_norms(
+    const float *__restrict__ Cm, int K, int D, int ld, float *__restrict__ out)
+{
+    __shared__ float red[2][1024 / kWave];
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    double ml = 0.0, md = 0.0;
+    for (int k = wave; k < K; k += 1024 / kWave) {
+        const float *c = Cm + (size_t)k * ld;
+        double sl = 0.0, sd = 0.0;
+        for (int d = lane; d < D; d += kWave) {
+            uint32_t hi, lo;
+            split_pair(c[d], 0.f, hi, lo);
+            const float ch = __uint_as_float(hi << 16), cl = __uint_as_float(lo << 16);
+            const double dc = ((double)c[d] - (double)ch) - (double)cl;
+            sl += (double)cl * (double)cl;
+            sd += dc * dc;
+        }
+        sl = wave_sum(sl);
+        sd = wave_sum(sd);
+        ml = fmax(ml, sl);
+        md = fmax(md, sd);
+    }
+    if (lane == 0) {
+        red[0][wave] = (float)(sqrt(ml) * 1.000001);
+        red[1][wave] = (float)(sqrt(md) * 1.000001);
+    }
+    __syncthreads();
+    if (threadIdx.x < 2) {
+        float v = 0.f;
+        for (int w = 0; w < 1024 / kWave; ++w) v = fmaxf(v, red[threadIdx.x][w]);
+        out[threadIdx.x] = v;
+    }
+}
+
+// LDS image of the split codebook in MFMA operand order.  For row block b (32 codewords), step t
+// (16 dims), part p (0 = high, 1 = low) and lane l = 32 g + r, the uint4 at ((b*T + t)*2 + p)*64 + l
+// holds the bf16 values of C[32b + r][16t + 8g .. 16t + 8g + 7]: every operand read is one
+// contiguous kilobyte.  Coordinates beyond D and rows beyond K are zero.
+__device__ __forceinline__ void stage_codebook_split(
+    uint4 *lds, const float *__restrict__ Cm, int K, int D, int ld, int kb, int T)
+{
+    const int total = kb * T * kWave;
+    for (int e = threadIdx.x; e < total; e += blockDim.x) {
+        const int l = e & 63;
+        const int bt = e >> 6;
+        const int t = bt % T;
+        const int b = bt / T;
+        const int row = 32 * b + (l & 31);
+        const int col = kSplitStep * t + 8 * (l >> 5);
+        const float4 u = load_row_piece(Cm, row, col, K, D, ld);
+        const float4 v = load_row_piece(Cm, row, col + 4, K, D, ld);
+        uint4 hi, lo;
+        split8(u, v, hi, lo);
+        lds[(size_t)(bt * 2 + 0) * kWave + l] = hi;
+        lds[(size_t)(bt * 2 + 1) * kWave + l] = lo;
+    }
+}
+
+// The 64-dim chunk q of a row in B-operand order: lane (g, r) gets, for step t = 0..3, the eight
+// floats x'[row r][64q + 16t + 8g .. + 7] as x[2t], x[2t + 1].
+__device__ __forceinline__ void load_x_chunk_split(
+    float4 (&x)[8], const float *__restrict__ xrow, int q, int g, int D)
+{
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int col = kChunkD * q + kSplitStep * t + 8 * g;
+        x[2 * t] = (col < D) ? *reinterpret_cast<const float4 *>(xrow + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+        x[2 * t + 1] = (col + 4 < D) ? *reinterpret_cast<const float4 *>(xrow + col + 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
+template <int KB>
+__device__ __forceinline__ void mfma_chunk_split(
+    floatx16 (&acc)[KB], const float4 (&x)[8], const uint4 *__restrict__ lds, int q, int T, int lane,
+    float &xsq, float &amax)
+{
+    constexpr int GB = KB < 4 ? KB : 4;              // codeword blocks whose operands are in registers at once
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const float4 u = x[2 * t], v = x[2 * t + 1];
+        xsq = fmaf(u.x, u.x, xsq);
+        xsq = fmaf(u.y, u.y, xsq);
+        xsq = fmaf(u.z, u.z, xsq);
+        xsq = fmaf(u.w, u.w, xsq);
+        xsq = fmaf(v.x, v.x, xsq);
+        xsq = fmaf(v.y, v.y, xsq);
+        xsq = fmaf(v.z, v.z, xsq);
+        xsq = fmaf(v.w, v.w, xsq);
+        amax = fmaxf(fmaxf(amax, fmaxf(fabsf(u.x), fabsf(u.y))), fmaxf(fabsf(u.z), fabsf(u.w)));
+        amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+        uint4 xh4, xl4;
+        split8(u, v, xh4, xl4);
+        const bf16x8 xh = __builtin_bit_cast(bf16x8, xh4), xl = __builtin_bit_cast(bf16x8, xl4);
+#pragma unroll
+        for (int b0 = 0; b0 < KB; b0 += GB) {
+            bf16x8 ch[GB], cl[GB];
+#pragma unroll
+            for (int b = 0; b < GB; ++b) {
+                const size_t at = (size_t)(((b0 + b) * T + 4 * q + t) * 2) * kWave + lane;
+                ch[b] = __builtin_bit_cast(bf16x8, lds[at]);
+                cl[b] = __builtin_bit_cast(bf16x8, lds[at + kWave]);
+            }
+#pragma unroll
+            for (int b = 0; b < GB; ++b) acc[b0 + b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cl[b], xh, acc[b0 + b], 0, 0, 0);
+#pragma unroll
+            for (int b = 0; b < GB; ++b) acc[b0 + b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[b], xl, acc[b0 + b], 0, 0, 0);
+#pragma unroll
+            for (int b = 0; b < GB; ++b) acc[b0 + b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[b], xh, acc[b0 + b], 0, 0, 0);
+        }
+    }
+}
+
+// Same tile schedule, register streaming and decision as k_assign_resident; only the contraction
+// differs.  eps and cmax_eff fold the two bounds into the form the decision uses:
+//   margin = eps * (hmax + ||x'|| * cmax_eff),  eps = 2 * (accumulation bound),
+//   cmax_eff = 1.02 cmax + (split bound per unit ||x'||) / (accumulation bound)
+// (1.02: the accumulated magnitudes are those of the split operands, ||xh|| ||ch|| + ||xh|| ||cl|| + ||xl|| ||ch||).
+template <int KB>
+__global__ __launch_bounds__(kAssignThreads) void k_assign_split(
+    const float *__restrict__ xp, const float *__restrict__ Cm, const float *__restrict__ hneg,
+    const float *__restrict__ split_norms,
+    int64_t N, int D, int ld, int K, int M, int m, int NC, float acc_bound,
+    uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count)
+{
+    extern __shared__ float4 smem4[];
+    const int T = 4 * NC;                                                // 16-dim steps
+    uint4 *lds_c = reinterpret_cast<uint4 *>(smem4);                     // KB * T * 2 * 64 uint4
+    float *lds_h = reinterpret_cast<float *>(smem4 + (size_t)KB * T * 2 * kWave);
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int g = lane >> 5;
+    const int r = lane & 31;
+
+    stage_codebook_split(lds_c, Cm, K, D, ld, KB, T);
+    for (int k = threadIdx.x; k < 32 * KB; k += blockDim.x) lds_h[k] = hneg[k];
+    __syncthreads();
+    float hmax = 0.f;
+    for (int k = 0; k < K; ++k) hmax = fmaxf(hmax, -lds_h[k]);
+    const float cmax = sqrtf(2.f * hmax) * 1.000001f;
+    // dropped terms per unit ||x'||:  ||xl|| ||cl|| + ||dx|| ||c|| + ||x - dx|| ||dc||
+    //   <= 2^-8 (1 + 2^-8) clmax + 2^-16 cmax + (1 + 2^-16) dcmax
+    const float clmax = split_norms[0], dcmax = split_norms[1];
+    const float split_bound = (0.00390625f * 1.00391f) * clmax + 1.52587890625e-5f * cmax + 1.00002f * dcmax;
+    const float eps = 2.f * acc_bound;
+    const float cmax_eff = (cmax * 1.02f + split_bound / acc_bound) * 1.0001f;
+
+    const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
+    const int64_t nslots = (int64_t)gridDim.x * 4;
+    const int64_t tstride = 2 * nslots;
+    const int64_t t0 = (int64_t)blockIdx.x * 4 + (wave & 3) + nslots * (wave >> 2);
+    if (t0 >= ntiles) return;
+    const int64_t my_tiles = (ntiles - t0 + tstride - 1) / tstride;
+    const int64_t G = my_tiles * NC;
+
+    auto row_ptr = [&](int64_t tile) {
+        int64_t n = tile * kTileVec + r;
+        if (n >= N) n = N - 1;
+        return xp + n * ld;
+    };
+
+    floatx16 acc[KB];
+    float4 xa[8], xb[8];
+    float xsq = 0.f, amax = 0.f;
+    int64_t tile = t0;
+    int q = 0;
+    load_x_chunk_split(xa, row_ptr(tile), 0, g, D);
+    for (int64_t s = 0; s < G; s += 2) {
+        int64_t tile1 = tile;
+        int q1 = q + 1;
+        if (q1 == NC) { q1 = 0; tile1 = tile + tstride; }
+        if (s + 1 < G) load_x_chunk_split(xb, row_ptr(tile1), q1, g, D);
+        if (q == 0) { init_acc<KB>(acc, lds_h, g); xsq = 0.f; }
+        mfma_chunk_split<KB>(acc, xa, lds_c, q, T, lane, xsq, amax);
+        if (q == NC - 1)
+            decide<KB>(acc, xsq, eps, hmax, cmax_eff, lane, tile * kTileVec + r, N, M, m, codes, list, refine_count);
+        if (s + 1 >= G) break;
+        int64_t tile2 = tile1;
+        int q2 = q1 + 1;
+        if (q2 == NC) { q2 = 0; tile2 = tile1 + tstride; }
+        if (s + 2 < G) load_x_chunk_split(xa, row_ptr(tile2), q2, g, D);
+        if (q1 == 0) { init_acc<KB>(acc, lds_h, g); xsq = 0.f; }
+        mfma_chunk_split<KB>(acc, xb, lds_c, q1, T, lane, xsq, amax);
+        if (q1 == NC - 1)
+            decide<KB>(acc, xsq, eps, hmax, cmax_eff, lane, tile1 * kTileVec + r, N, M, m, codes, list, refine_count);
+        tile = tile2;
+        q = q2;
+    }
+    publish_absmax(amax, refine_count + 1);
+}
+
+}  // namespace hclae

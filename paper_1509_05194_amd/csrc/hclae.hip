@@ -10,6 +10,7 @@
 
 #include "../../include/hclae.h"
 #include "assign.hpp"
+#include "assign_split.hpp"
 #include "stream.hpp"
 #include "update.hpp"
 #include "pca.hpp"
@@ -41,6 +42,8 @@ struct hclae_ctx {
     int device;
     // scratch (device)
     float *hneg;             // [32*kb]
+    float *split_norms;      // [2] split constants of the codebook in use (contraction 1)
+    int contraction;         // 0: fp32 MFMA, 1: split-bf16 MFMA (resident shapes only)
     unsigned *refine_count;
     RefineItem *refine_list; // [N_max]
     uint8_t *old_codes;      // [N_max]
@@ -204,7 +207,24 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
     const float eps = 2.02f * (float)(dpad + 2) * 1.1920929e-7f;
     {
     Timed t_(ctx, HCLAE_T_ASSIGN);
-    if (resident) {
+    if (resident && ctx->contraction == 1) {
+        const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
+        const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
+        int64_t blocks = (ntiles + kAssignWaves - 1) / kAssignWaves;
+        if (blocks > ctx->cus) blocks = ctx->cus;
+        static bool attr_set = false;
+        if (!attr_set) {
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split<KB>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            attr_set = true;
+        }
+        // 3 MFMAs per 16 dims, each within 2^-21 of the magnitudes it adds; one more for the rounding of the norm
+        const float acc_bound = (float)(3 * (dpad / kSplitStep) + 1) * 4.76837158203125e-7f;
+        hipLaunchKernelGGL(k_split_norms, dim3(1), dim3(1024), 0, ctx->stream, Cm, ctx->K, dact, ld, ctx->split_norms);
+        hipLaunchKernelGGL((k_assign_split<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
+                           xp, Cm, ctx->hneg, ctx->split_norms, N, dact, ld, ctx->K, ctx->M, m, NC, acc_bound,
+                           codes, ctx->refine_list, ctx->refine_count);
+    } else if (resident) {
         const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
         int64_t blocks = (ntiles + kAssignWaves - 1) / kAssignWaves;
@@ -440,6 +460,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
 
     struct { void **p; size_t bytes; } allocs[] = {
         {(void **)&ctx->hneg, sizeof(float) * 32 * ctx->kb},
+        {(void **)&ctx->split_norms, 256},
         {(void **)&ctx->refine_count, 256},
         {(void **)&ctx->refine_list, sizeof(RefineItem) * (size_t)N_max},
         {(void **)&ctx->old_codes, (size_t)N_max},
@@ -477,7 +498,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
 int hclae_destroy(hclae_ctx *ctx)
 {
     if (!ctx) return HCLAE_EINVAL;
-    void *dev[] = {ctx->hneg, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
+    void *dev[] = {ctx->hneg, ctx->split_norms, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
                    ctx->nk, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
                    ctx->run_sum, ctx->run_cnt, ctx->n0_dev, ctx->pca_rt, ctx->pca_crot, ctx->pca_colpart,
                    ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32,
@@ -628,6 +649,15 @@ int hclae_anneal_stage(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M,
 
 static int enqueue_encode_beam(hclae_ctx *ctx, const float *X, int64_t N, const float *C, int L,
                                uint8_t *codes, float *residue, double *err);
+
+int hclae_set_contraction(hclae_ctx *ctx, int mode)
+{
+    if (!ctx) return HCLAE_EINVAL;
+    if (mode != HCLAE_CONTRACT_F32 && mode != HCLAE_CONTRACT_SPLIT_BF16)
+        return fail(ctx, HCLAE_EINVAL, "hclae_set_contraction: unknown mode");
+    ctx->contraction = mode;
+    return HCLAE_OK;
+}
 
 int hclae_set_beam_width(hclae_ctx *ctx, int L)
 {

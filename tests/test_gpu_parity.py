@@ -14,9 +14,25 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
+_CONTRACTION = 0
+
+
+@pytest.fixture(autouse=True, params=[0, 1], ids=["f32", "splitbf16"])
+def contraction(request):
+    """Every test of this module runs with both matrix-core arithmetics of the distance contraction
+    (hclae_set_contraction): the bar is the same, since both only pre-select candidates for the fp64
+    re-check."""
+    global _CONTRACTION
+    _CONTRACTION = request.param
+    yield request.param
+    _CONTRACTION = 0
+
+
 def _ctx(N, D, M, K):
     from paper_1509_05194_amd import hclae
-    return hclae.Context(N, D, M, K)
+    ctx = hclae.Context(N, D, M, K)
+    ctx.set_contraction(_CONTRACTION)
+    return ctx
 
 
 # shapes: several tiles plus a ragged tail; padded K and D; the D-chunked path (D = 960, 132)
