@@ -40,41 +40,30 @@ __device__ __forceinline__ void split8(const float4 &u, const float4 &v, uint4 &
     split_pair(v.z, v.w, hi.w, lo.w);
 }
 
-// Per-codebook constants of the split: for k < K over the first D coordinates (row stride ld)
-//   out[0] = max_k || cl_k ||   (low parts),   out[1] = max_k || c_k - ch_k - cl_k ||   (what two terms miss)
-// as fp32 rounded up.  One block; each wave takes every 16th codeword.
-__global__ __launch_bounds__(1024) void k_split_norms(
+// Per-codeword constants of the split over the first D coordinates (row stride ld), as fp32 rounded up:
+//   out[2k] = || cl_k ||  (low part),   out[2k + 1] = || c_k - ch_k - cl_k ||  (what two terms miss).
+// One wave per codeword; the assign kernel takes the maxima over k.
+__global__ __launch_bounds__(256) void k_split_norms(
     const float *__restrict__ Cm, int K, int D, int ld, float *__restrict__ out)
 {
-    __shared__ float red[2][1024 / kWave];
     const int lane = lane_id();
-    const int wave = threadIdx.x >> 6;
-    double ml = 0.0, md = 0.0;
-    for (int k = wave; k < K; k += 1024 / kWave) {
-        const float *c = Cm + (size_t)k * ld;
-        double sl = 0.0, sd = 0.0;
-        for (int d = lane; d < D; d += kWave) {
-            uint32_t hi, lo;
-            split_pair(c[d], 0.f, hi, lo);
-            const float ch = __uint_as_float(hi << 16), cl = __uint_as_float(lo << 16);
-            const double dc = ((double)c[d] - (double)ch) - (double)cl;
-            sl += (double)cl * (double)cl;
-            sd += dc * dc;
-        }
-        sl = wave_sum(sl);
-        sd = wave_sum(sd);
-        ml = fmax(ml, sl);
-        md = fmax(md, sd);
+    const int k = blockIdx.x * (256 / kWave) + (threadIdx.x >> 6);
+    if (k >= K) return;
+    const float *c = Cm + (size_t)k * ld;
+    double sl = 0.0, sd = 0.0;
+    for (int d = lane; d < D; d += kWave) {
+        uint32_t hi, lo;
+        split_pair(c[d], 0.f, hi, lo);
+        const float ch = __uint_as_float(hi << 16), cl = __uint_as_float(lo << 16);
+        const double dc = ((double)c[d] - (double)ch) - (double)cl;
+        sl += (double)cl * (double)cl;
+        sd += dc * dc;
     }
+    sl = wave_sum(sl);
+    sd = wave_sum(sd);
     if (lane == 0) {
-        red[0][wave] = (float)(sqrt(ml) * 1.000001);
-        red[1][wave] = (float)(sqrt(md) * 1.000001);
-    }
-    __syncthreads();
-    if (threadIdx.x < 2) {
-        float v = 0.f;
-        for (int w = 0; w < 1024 / kWave; ++w) v = fmaxf(v, red[threadIdx.x][w]);
-        out[threadIdx.x] = v;
+        out[2 * k] = (float)(sqrt(sl) * 1.000001);
+        out[2 * k + 1] = (float)(sqrt(sd) * 1.000001);
     }
 }
 
@@ -185,7 +174,22 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_split(
     const float cmax = sqrtf(2.f * hmax) * 1.000001f;
     // dropped terms per unit ||x'||:  ||xl|| ||cl|| + ||dx|| ||c|| + ||x - dx|| ||dc||
     //   <= 2^-8 (1 + 2^-8) clmax + 2^-16 cmax + (1 + 2^-16) dcmax
-    const float clmax = split_norms[0], dcmax = split_norms[1];
+    // maxima of the per-codeword split constants: first wave reduces, everyone reads the result from LDS
+    if (wave == 0) {
+        float a = 0.f, b = 0.f;
+        for (int k = lane; k < K; k += kWave) {
+            a = fmaxf(a, split_norms[2 * k]);
+            b = fmaxf(b, split_norms[2 * k + 1]);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            a = fmaxf(a, __shfl_xor(a, o, kWave));
+            b = fmaxf(b, __shfl_xor(b, o, kWave));
+        }
+        if (lane == 0) { lds_h[32 * KB] = a; lds_h[32 * KB + 1] = b; }
+    }
+    __syncthreads();
+    const float clmax = lds_h[32 * KB], dcmax = lds_h[32 * KB + 1];
     const float split_bound = (0.00390625f * 1.00391f) * clmax + 1.52587890625e-5f * cmax + 1.00002f * dcmax;
     const float eps = 2.f * acc_bound;
     const float cmax_eff = (cmax * 1.02f + split_bound / acc_bound) * 1.0001f;

@@ -42,7 +42,7 @@ struct hclae_ctx {
     int device;
     // scratch (device)
     float *hneg;             // [32*kb]
-    float *split_norms;      // [2] split constants of the codebook in use (contraction 1)
+    float *split_norms;      // [K][2] split constants of the codebook in use (contraction 1)
     int contraction;         // 0: fp32 MFMA, 1: split-bf16 MFMA (resident shapes only)
     unsigned *refine_count;
     RefineItem *refine_list; // [N_max]
@@ -220,7 +220,7 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
         }
         // 3 MFMAs per 16 dims, each within 2^-21 of the magnitudes it adds; one more for the rounding of the norm
         const float acc_bound = (float)(3 * (dpad / kSplitStep) + 1) * 4.76837158203125e-7f;
-        hipLaunchKernelGGL(k_split_norms, dim3(1), dim3(1024), 0, ctx->stream, Cm, ctx->K, dact, ld, ctx->split_norms);
+        hipLaunchKernelGGL(k_split_norms, dim3((ctx->K + 3) / 4), dim3(256), 0, ctx->stream, Cm, ctx->K, dact, ld, ctx->split_norms);
         hipLaunchKernelGGL((k_assign_split<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
                            xp, Cm, ctx->hneg, ctx->split_norms, N, dact, ld, ctx->K, ctx->M, m, NC, acc_bound,
                            codes, ctx->refine_list, ctx->refine_count);
@@ -460,7 +460,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
 
     struct { void **p; size_t bytes; } allocs[] = {
         {(void **)&ctx->hneg, sizeof(float) * 32 * ctx->kb},
-        {(void **)&ctx->split_norms, 256},
+        {(void **)&ctx->split_norms, sizeof(float) * 2 * HCLAE_MAX_K},
         {(void **)&ctx->refine_count, 256},
         {(void **)&ctx->refine_list, sizeof(RefineItem) * (size_t)N_max},
         {(void **)&ctx->old_codes, (size_t)N_max},
