@@ -209,6 +209,7 @@ def beam_bench(args, torch, hclae, synth, dev):
     codes = torch.zeros((N, M), dtype=torch.uint8, device=dev)
     r = Xg.clone()
     ctx = hclae.Context(N, D, M, K)
+    ctx.set_contraction(1 if args.contraction == "split" else 0)
     ctx.sweep(C, codes, r, T, init_idx=synth.init_indices(N, M, K), want_err=False)
     ctx.encode(Xg, C, codes, r)
     e_greedy = ctx.quant_error(r)
@@ -238,7 +239,10 @@ def beam_bench(args, torch, hclae, synth, dev):
         "config": {"workload": "SIFT-shaped: N=%d, D=128, M=%d, K=256; dictionaries from one fresh DA sweep (T=%d); "
                                "one step = multi-path encoding of all N vectors with L=%d" % (N, M, T, L),
                    "quant_error_greedy": e_greedy, "quant_error_multipath": e_beam},
-        "roofline": {"bound": "mfma", "kernel": "k_beam_score_resident<8> (fp32 MFMA scoring of N*L beam rows)",
+        "roofline": {"bound": "mfma", "kernel": ("k_beam_score_resident<8> (fp32 MFMA scoring of N*L beam rows)"
+                                                 if args.contraction == "f32" else
+                                                 "k_beam_score_split<8> (split-bf16 MFMA scoring; algorithmic flop "
+                                                 "against the fp32 peak for comparison)"),
                      "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP32_MFMA_TFLOPS if achieved else None, "traffic": None,
                      "flops_per_step": flops},

@@ -15,6 +15,7 @@
 // The decision is therefore an fp64 direct-form decision, as in the assignment kernels.
 #pragma once
 #include "assign.hpp"
+#include "assign_split.hpp"
 
 namespace hclae {
 
@@ -155,6 +156,110 @@ __global__ __launch_bounds__(kAssignThreads) void k_beam_score_resident(
         if (g + 2 < G) load_x_chunk(xa, row_ptr(tile2), q2, h, D);
         if (q1 == 0) { init_acc<KB>(acc, lds_h, h); xsq = 0.f; e_l = e_of(tile1); }
         mfma_chunk<KB>(acc, xb, lds_c, q1, S, lane, xsq, amax);
+        if (q1 == NC - 1) {
+            const int64_t row = row_of(tile1);
+            const bool valid = r < RT && row < nrows;
+            beam_select<KB>(acc, xsq, e_l, gamma, hmax, cmax, lane, gbase, Lc, Ln, valid, masks + (valid ? row : 0));
+        }
+        tile = tile2;
+        q = q2;
+    }
+}
+
+// The same with the split-bf16 contraction of k_assign_split (operands as two bf16 terms, three bf16
+// MFMAs per 16 dims).  gamma is then the accumulation bound and the bound on the dropped terms enters
+// through the effective codeword norm, exactly as in k_assign_split.
+template <int KB>
+__global__ __launch_bounds__(kAssignThreads) void k_beam_score_split(
+    const float *__restrict__ rows, const double *__restrict__ err, const float *__restrict__ Cm,
+    const float *__restrict__ hneg, const float *__restrict__ split_norms,
+    int64_t N, int Lc, int Ln, int D, int ld, int K, int NC, float gamma,
+    BeamMask *__restrict__ masks)
+{
+    extern __shared__ float4 smem4[];
+    const int T = 4 * NC;                                                // 16-dim steps
+    uint4 *lds_c = reinterpret_cast<uint4 *>(smem4);                     // KB * T * 2 * 64 uint4
+    float *lds_h = reinterpret_cast<float *>(smem4 + (size_t)KB * T * 2 * kWave);
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int h = lane >> 5;
+    const int r = lane & 31;
+
+    stage_codebook_split(lds_c, Cm, K, D, ld, KB, T);
+    for (int k = threadIdx.x; k < 32 * KB; k += blockDim.x) lds_h[k] = hneg[k];
+    __syncthreads();
+    float hmax = 0.f;
+    for (int k = 0; k < K; ++k) hmax = fmaxf(hmax, -lds_h[k]);
+    float cmax = sqrtf(2.f * hmax) * 1.000001f;
+    if (wave == 0) {
+        float a = 0.f, b = 0.f;
+        for (int k = lane; k < K; k += kWave) {
+            a = fmaxf(a, split_norms[2 * k]);
+            b = fmaxf(b, split_norms[2 * k + 1]);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            a = fmaxf(a, __shfl_xor(a, o, kWave));
+            b = fmaxf(b, __shfl_xor(b, o, kWave));
+        }
+        if (lane == 0) { lds_h[32 * KB] = a; lds_h[32 * KB + 1] = b; }
+    }
+    __syncthreads();
+    {   // dropped terms per unit ||r||, folded into the norm the margin multiplies (see k_assign_split)
+        const float clmax = lds_h[32 * KB], dcmax = lds_h[32 * KB + 1];
+        const float split_bound = (0.00390625f * 1.00391f) * clmax + 1.52587890625e-5f * cmax + 1.00002f * dcmax;
+        cmax = (cmax * 1.02f + split_bound / gamma) * 1.0001f;
+    }
+
+    const int V = kTileVec / Lc;                       // vectors per tile
+    const int RT = V * Lc;                             // beam rows per tile
+    const int gbase = (r < RT) ? (r / Lc) * Lc : 0;
+    const int64_t nrows = N * Lc;
+    const int64_t ntiles = (N + V - 1) / V;
+    const int64_t nslots = (int64_t)gridDim.x * 4;
+    const int64_t tstride = 2 * nslots;
+    const int64_t t0 = (int64_t)blockIdx.x * 4 + (wave & 3) + nslots * (wave >> 2);
+    if (t0 >= ntiles) return;
+    const int64_t my_tiles = (ntiles - t0 + tstride - 1) / tstride;
+    const int64_t G = my_tiles * NC;
+
+    auto row_of = [&](int64_t tile) { return tile * RT + r; };
+    auto row_ptr = [&](int64_t tile) {
+        int64_t n = row_of(tile);
+        if (r >= RT || n >= nrows) n = nrows - 1;      // idle columns re-read the last row
+        return rows + n * ld;
+    };
+    auto e_of = [&](int64_t tile) {
+        int64_t n = row_of(tile);
+        if (r >= RT || n >= nrows) n = nrows - 1;
+        return err ? (float)err[n] : 0.f;
+    };
+
+    floatx16 acc[KB];
+    float4 xa[8], xb[8];
+    float xsq = 0.f, amax = 0.f, e_l = 0.f;
+    int64_t tile = t0;
+    int q = 0;
+    load_x_chunk_split(xa, row_ptr(tile), 0, h, D);
+    for (int64_t g = 0; g < G; g += 2) {
+        int64_t tile1 = tile;
+        int q1 = q + 1;
+        if (q1 == NC) { q1 = 0; tile1 = tile + tstride; }
+        if (g + 1 < G) load_x_chunk_split(xb, row_ptr(tile1), q1, h, D);
+        if (q == 0) { init_acc<KB>(acc, lds_h, h); xsq = 0.f; e_l = e_of(tile); }
+        mfma_chunk_split<KB>(acc, xa, lds_c, q, T, lane, xsq, amax);
+        if (q == NC - 1) {
+            const int64_t row = row_of(tile);
+            const bool valid = r < RT && row < nrows;
+            beam_select<KB>(acc, xsq, e_l, gamma, hmax, cmax, lane, gbase, Lc, Ln, valid, masks + (valid ? row : 0));
+        }
+        if (g + 1 >= G) break;
+        int64_t tile2 = tile1;
+        int q2 = q1 + 1;
+        if (q2 == NC) { q2 = 0; tile2 = tile1 + tstride; }
+        if (g + 2 < G) load_x_chunk_split(xa, row_ptr(tile2), q2, h, D);
+        if (q1 == 0) { init_acc<KB>(acc, lds_h, h); xsq = 0.f; e_l = e_of(tile1); }
+        mfma_chunk_split<KB>(acc, xb, lds_c, q1, T, lane, xsq, amax);
         if (q1 == NC - 1) {
             const int64_t row = row_of(tile1);
             const bool valid = r < RT && row < nrows;

@@ -860,7 +860,22 @@ static int launch_beam_score_kb(hclae_ctx *ctx, const float *rows, const double 
     const int V = kTileVec / Lc;
     const int64_t ntiles = (N + V - 1) / V;
     Timed t_(ctx, HCLAE_T_BEAM_SCORE);
-    if (ctx->resident) {
+    if (ctx->resident && ctx->contraction == 1) {
+        const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
+        int64_t blocks = (ntiles + kAssignWaves - 1) / kAssignWaves;
+        if (blocks > ctx->cus) blocks = ctx->cus;
+        static bool attr_set = false;
+        if (!attr_set) {
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_beam_score_split<KB>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            attr_set = true;
+        }
+        // accumulation bound of the split contraction (see launch_assign_kb) plus the roundings of the shift
+        const float acc_bound = (float)(3 * (dpad / kSplitStep) + 9) * 4.76837158203125e-7f;
+        hipLaunchKernelGGL(k_split_norms, dim3((ctx->K + 3) / 4), dim3(256), 0, ctx->stream, Cm, ctx->K, D, D, ctx->split_norms);
+        hipLaunchKernelGGL((k_beam_score_split<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
+                           rows, err, Cm, ctx->hneg, ctx->split_norms, N, Lc, Ln, D, D, ctx->K, NC, acc_bound, masks);
+    } else if (ctx->resident) {
         const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         int64_t blocks = (ntiles + kAssignWaves - 1) / kAssignWaves;
         if (blocks > ctx->cus) blocks = ctx->cus;

@@ -35,9 +35,23 @@ def _dictionaries(oracle, X, M, K, T=2):
     return C32, C32.astype(np.float64)
 
 
+_CONTRACTION = 0
+
+
+@pytest.fixture(autouse=True, params=[0, 1], ids=["f32", "splitbf16"])
+def contraction(request):
+    """Both matrix-core arithmetics of the scoring contraction (hclae_set_contraction); same bar."""
+    global _CONTRACTION
+    _CONTRACTION = request.param
+    yield request.param
+    _CONTRACTION = 0
+
+
 def _ctx(c):
     from paper_1509_05194_amd import hclae
-    return hclae.Context(c["N"], c["D"], c["M"], c["K"])
+    ctx = hclae.Context(c["N"], c["D"], c["M"], c["K"])
+    ctx.set_contraction(_CONTRACTION)
+    return ctx
 
 
 def _cand_err(X64, A, Cm, par, code):
@@ -219,6 +233,7 @@ def test_beam_all_candidates_tie(oracle):
     C64 = C32.astype(np.float64)
     X64 = X.astype(np.float64)
     ctx = hclae.Context(N, D, 2, K)
+    ctx.set_contraction(_CONTRACTION)
     A = np.zeros((N, 1, D))
     err_c = None
     for m in range(2):
