@@ -190,15 +190,20 @@ __device__ __forceinline__ void decide(
     const float x2 = xsq + __shfl_xor(xsq, 32, kWave);
     const float thr = mx - eps * (hmax + sqrtf(x2) * cmax);
 
+    // Candidate bitmaps without compare-and-select chains: the sign of acc - thr is shifted into a word
+    // (v_alignbit), one subtraction and one shift-in per score; the 16 bits of a block end up "1 = below".
     constexpr int NW = (KB + 1) / 2;
     uint32_t mk[NW];
 #pragma unroll
     for (int i = 0; i < NW; ++i) mk[i] = 0u;
 #pragma unroll
-    for (int b = 0; b < KB; ++b)
+    for (int b = 0; b < KB; ++b) {
+        uint32_t below = 0u;
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            if (acc[b][v] >= thr) mk[b >> 1] |= 1u << ((b & 1) * 16 + v);
+        for (int v = 15; v >= 0; --v)
+            below = __builtin_amdgcn_alignbit(below, __float_as_uint(acc[b][v] - thr), 31);   // (below << 1) | sign
+        mk[b >> 1] |= (~below & 0xffffu) << ((b & 1) * 16);
+    }
 
     // bit p of word i is codeword 64 i + 8 (p >> 2) + 4 h + (p & 3): ascending in (i, p)
     int cnt = 0, lo = 0x7fffffff;

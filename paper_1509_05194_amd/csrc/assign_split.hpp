@@ -67,27 +67,28 @@ __global__ __launch_bounds__(256) void k_split_norms(
     }
 }
 
-// LDS image of the split codebook in MFMA operand order.  For row block b (32 codewords), step t
-// (16 dims), part p (0 = high, 1 = low) and lane l = 32 g + r, the uint4 at ((b*T + t)*2 + p)*64 + l
+// LDS image of the split codebook in MFMA operand order.  For step t (16 dims), row block b (32
+// codewords), part p (0 = high, 1 = low) and lane l = 32 g + r, the uint4 at ((t*kb + b)*2 + p)*64 + l
 // holds the bf16 values of C[32b + r][16t + 8g .. 16t + 8g + 7]: every operand read is one
-// contiguous kilobyte.  Coordinates beyond D and rows beyond K are zero.
+// contiguous kilobyte, and the reads of one 64-dim chunk are one base address plus constants below 64 KB.
+// Coordinates beyond D and rows beyond K are zero.
 __device__ __forceinline__ void stage_codebook_split(
     uint4 *lds, const float *__restrict__ Cm, int K, int D, int ld, int kb, int T)
 {
     const int total = kb * T * kWave;
     for (int e = threadIdx.x; e < total; e += blockDim.x) {
         const int l = e & 63;
-        const int bt = e >> 6;
-        const int t = bt % T;
-        const int b = bt / T;
+        const int tb = e >> 6;
+        const int b = tb % kb;
+        const int t = tb / kb;
         const int row = 32 * b + (l & 31);
         const int col = kSplitStep * t + 8 * (l >> 5);
         const float4 u = load_row_piece(Cm, row, col, K, D, ld);
         const float4 v = load_row_piece(Cm, row, col + 4, K, D, ld);
         uint4 hi, lo;
         split8(u, v, hi, lo);
-        lds[(size_t)(bt * 2 + 0) * kWave + l] = hi;
-        lds[(size_t)(bt * 2 + 1) * kWave + l] = lo;
+        lds[(size_t)(tb * 2 + 0) * kWave + l] = hi;
+        lds[(size_t)(tb * 2 + 1) * kWave + l] = lo;
     }
 }
 
@@ -110,6 +111,8 @@ __device__ __forceinline__ void mfma_chunk_split(
     float &xsq, float &amax)
 {
     constexpr int GB = KB < 4 ? KB : 4;              // codeword blocks whose operands are in registers at once
+    const uint4 *chunk = lds + (size_t)(4 * q) * KB * 2 * kWave + lane;
+    (void)T;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const float4 u = x[2 * t], v = x[2 * t + 1];
@@ -131,9 +134,9 @@ __device__ __forceinline__ void mfma_chunk_split(
             bf16x8 ch[GB], cl[GB];
 #pragma unroll
             for (int b = 0; b < GB; ++b) {
-                const size_t at = (size_t)(((b0 + b) * T + 4 * q + t) * 2) * kWave + lane;
-                ch[b] = __builtin_bit_cast(bf16x8, lds[at]);
-                cl[b] = __builtin_bit_cast(bf16x8, lds[at + kWave]);
+                const uint4 *at = chunk + ((t * KB + b0 + b) * 2) * kWave;      // compile-time offset
+                ch[b] = __builtin_bit_cast(bf16x8, at[0]);
+                cl[b] = __builtin_bit_cast(bf16x8, at[kWave]);
             }
 #pragma unroll
             for (int b = 0; b < GB; ++b) acc[b0 + b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cl[b], xh, acc[b0 + b], 0, 0, 0);

@@ -74,10 +74,13 @@ __device__ __forceinline__ void beam_select(
     constexpr int NW = (KB + 1) / 2;
     uint32_t mk[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int b = 0; b < KB; ++b)
+    for (int b = 0; b < KB; ++b) {
+        uint32_t below = 0u;                             // sign bits of acc - thr, shifted in (v_alignbit)
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            if (acc[b][v] >= thr) mk[b >> 1] |= 1u << ((b & 1) * 16 + v);
+        for (int v = 15; v >= 0; --v)
+            below = __builtin_amdgcn_alignbit(below, __float_as_uint(acc[b][v] - thr), 31);
+        mk[b >> 1] |= (~below & 0xffffu) << ((b & 1) * 16);
+    }
     (void)NW;
     if (valid) *reinterpret_cast<uint4 *>(&out->w[h][0]) = make_uint4(mk[0], mk[1], mk[2], mk[3]);
 }
