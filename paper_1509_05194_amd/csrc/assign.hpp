@@ -141,7 +141,8 @@ __device__ __forceinline__ void mfma_chunk(
         xsq = fmaf(xv.y, xv.y, xsq);
         xsq = fmaf(xv.z, xv.z, xsq);
         xsq = fmaf(xv.w, xv.w, xsq);
-        amax = fmaxf(fmaxf(amax, fmaxf(fabsf(xv.x), fabsf(xv.y))), fmaxf(fabsf(xv.z), fabsf(xv.w)));
+        amax = fmaxf(fmaxf(amax, fabsf(xv.x)), fabsf(xv.y));      // one v_max3_f32 per two elements
+        amax = fmaxf(fmaxf(amax, fabsf(xv.z)), fabsf(xv.w));
 #pragma unroll
         for (int b = 0; b < KB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[b].x, xv.x, acc[b], 0, 0, 0);
 #pragma unroll

@@ -124,8 +124,10 @@ __device__ __forceinline__ void mfma_chunk_split(
         xsq = fmaf(v.y, v.y, xsq);
         xsq = fmaf(v.z, v.z, xsq);
         xsq = fmaf(v.w, v.w, xsq);
-        amax = fmaxf(fmaxf(amax, fmaxf(fabsf(u.x), fabsf(u.y))), fmaxf(fabsf(u.z), fabsf(u.w)));
-        amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+        amax = fmaxf(fmaxf(amax, fabsf(u.x)), fabsf(u.y));      // one v_max3_f32 per two elements
+        amax = fmaxf(fmaxf(amax, fabsf(u.z)), fabsf(u.w));
+        amax = fmaxf(fmaxf(amax, fabsf(v.x)), fabsf(v.y));
+        amax = fmaxf(fmaxf(amax, fabsf(v.z)), fabsf(v.w));
         uint4 xh4, xl4;
         split8(u, v, xh4, xl4);
         const bf16x8 xh = __builtin_bit_cast(bf16x8, xh4), xl = __builtin_bit_cast(bf16x8, xl4);
