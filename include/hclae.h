@@ -274,6 +274,7 @@ enum {
     HCLAE_T_MOMENTS,    /* mean and covariance of x' (Sec. 3.2)                             */
     HCLAE_T_BEAM_SCORE, /* multi-path encoding: fp32-MFMA scoring and candidate bitmaps     */
     HCLAE_T_BEAM_EXPAND,/* multi-path encoding: fp64 evaluation, top-L, next beam           */
+    HCLAE_T_ACCUM_MOVED,/* centroid sums advanced by the vectors that changed cluster       */
     HCLAE_T_COUNT
 };
 

@@ -50,6 +50,12 @@ struct hclae_ctx {
     long long *partial;      // [upd_blocks][K][D] fixed-point centroid sums
     int *pcount;             // [upd_blocks][K]
     int *nk;                 // [K]
+    // exact incremental centroid update within a stage (see k_merge)
+    long long *tot_sum;      // [K][D] fixed-point sums of the stage
+    int *tot_cnt;            // [K]
+    uint8_t *upd_col;        // [N_max] code column as of the last centroid pass
+    unsigned long long *moved_list;  // [N_max]
+    unsigned *moved_count;
     int64_t *seed_idx;       // [K]
     double *part_a, *part_b; // [nparts]
     long long *part_chg;     // [nparts]
@@ -278,8 +284,10 @@ int launch_assign(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float
 // Accumulate + merge; leaves hneg = norms of the new Cm and the re-check counter at zero.
 // have_absmax: refine_count[1] already holds max |xp| (the assign kernel just ran on the same xp).
 // dnorm: leading coordinates whose squares enter the refreshed codeword norms (0 = all).
+// keep_totals: also store the integer sums, the counts and the code column, so that the following centroid
+// updates of the same stage can run on the moved vectors alone (launch_update_moved).
 int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, const uint8_t *codes,
-                  int32_t *counts, bool have_absmax, bool online = false, int dnorm = 0)
+                  int32_t *counts, bool have_absmax, bool online = false, int dnorm = 0, bool keep_totals = false)
 {
     const int D = ctx->D, K = ctx->K;
     const int windows = (D + kUpdWindow - 1) / kUpdWindow;
@@ -312,7 +320,45 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
                        ctx->partial, ctx->pcount, (int)nb, K, D, dnorm > 0 ? dnorm : D, Cm, ctx->hneg, ctx->nk, counts,
                        ctx->refine_count,
                        online ? ctx->run_sum + (size_t)m * K * D : (double *)nullptr,
-                       online ? ctx->run_cnt + (size_t)m * K : (long long *)nullptr);
+                       online ? ctx->run_cnt + (size_t)m * K : (long long *)nullptr,
+                       keep_totals ? ctx->tot_sum : (long long *)nullptr, keep_totals ? ctx->tot_cnt : (int *)nullptr, 0);
+    HIP_TRY(ctx, hipGetLastError());
+    if (keep_totals) {
+        hipLaunchKernelGGL(k_save_column, dim3(stream_blocks(ctx, N, 256)), dim3(256), 0, ctx->stream,
+                           codes, N, ctx->M, m, ctx->upd_col);
+        HIP_TRY(ctx, hipGetLastError());
+    }
+    return HCLAE_OK;
+}
+
+// Centroid update from the vectors that changed cluster since the last update of this stage (x' unchanged,
+// max |x'| still published): exact, see k_merge.  Leaves hneg and the counters as launch_update does.
+int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, const uint8_t *codes)
+{
+    const int D = ctx->D, K = ctx->K;
+    const int windows = (D + kUpdWindow - 1) / kUpdWindow;
+    int nb = ctx->upd_blocks < 32 ? ctx->upd_blocks : 32;
+    static bool attr_set = false;
+    if (!attr_set) {
+        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_accumulate_moved),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+        attr_set = true;
+    }
+    {
+        Timed t_(ctx, HCLAE_T_ACCUM_MOVED);
+        HIP_TRY(ctx, hipMemsetAsync(ctx->moved_count, 0, sizeof(unsigned), ctx->stream));
+        hipLaunchKernelGGL(k_moved, dim3(stream_blocks(ctx, N, 256)), dim3(256), 0, ctx->stream,
+                           codes, N, ctx->M, m, ctx->upd_col, ctx->moved_list, ctx->moved_count);
+        HIP_TRY(ctx, hipGetLastError());
+        hipLaunchKernelGGL(k_accumulate_moved, dim3((unsigned)nb, (unsigned)windows), dim3(kUpdThreads), upd_lds_bytes(K),
+                           ctx->stream, xp, ctx->moved_list, ctx->moved_count, D, K, ctx->refine_count + 1,
+                           ctx->partial, ctx->pcount);
+        HIP_TRY(ctx, hipGetLastError());
+    }
+    Timed t_(ctx, HCLAE_T_MERGE);
+    hipLaunchKernelGGL(k_merge, dim3(K), dim3(256), 0, ctx->stream,
+                       ctx->partial, ctx->pcount, nb, K, D, D, Cm, ctx->hneg, ctx->nk, (int *)nullptr,
+                       ctx->refine_count, (double *)nullptr, (long long *)nullptr, ctx->tot_sum, ctx->tot_cnt, 1);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
@@ -349,9 +395,13 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
         HIP_TRY(ctx, hipGetLastError());
     }
     if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
+    // x' stays as it is until the stage ends: the first centroid update sums all vectors and keeps the integer
+    // totals, the others add only the vectors that changed cluster (exact, so the dictionaries are the same)
     for (int t = 0; t < iters; ++t) {
         if ((rc = launch_assign(ctx, m, N, residue, Cm, codes)) != HCLAE_OK) return rc;
-        if ((rc = launch_update(ctx, m, N, residue, Cm, codes, nullptr, true)) != HCLAE_OK) return rc;
+        rc = t == 0 ? launch_update(ctx, m, N, residue, Cm, codes, nullptr, true, false, 0, iters > 1)
+                    : launch_update_moved(ctx, m, N, residue, Cm, codes);
+        if (rc != HCLAE_OK) return rc;
     }
     if ((rc = launch_assign(ctx, m, N, residue, Cm, codes)) != HCLAE_OK) return rc;
     int pa;
@@ -467,6 +517,11 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
         {(void **)&ctx->partial, per * ub},
         {(void **)&ctx->pcount, sizeof(int) * (size_t)K * ub},
         {(void **)&ctx->nk, sizeof(int) * K},
+        {(void **)&ctx->tot_sum, sizeof(long long) * (size_t)K * D},
+        {(void **)&ctx->tot_cnt, sizeof(int) * K},
+        {(void **)&ctx->upd_col, (size_t)N_max},
+        {(void **)&ctx->moved_list, sizeof(unsigned long long) * (size_t)N_max},
+        {(void **)&ctx->moved_count, 256},
         {(void **)&ctx->seed_idx, sizeof(int64_t) * K},
         {(void **)&ctx->part_a, sizeof(double) * ctx->nparts},
         {(void **)&ctx->part_b, sizeof(double) * ctx->nparts},
@@ -499,7 +554,7 @@ int hclae_destroy(hclae_ctx *ctx)
 {
     if (!ctx) return HCLAE_EINVAL;
     void *dev[] = {ctx->hneg, ctx->split_norms, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
-                   ctx->nk, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
+                   ctx->nk, ctx->tot_sum, ctx->tot_cnt, ctx->upd_col, ctx->moved_list, ctx->moved_count, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
                    ctx->run_sum, ctx->run_cnt, ctx->n0_dev, ctx->pca_rt, ctx->pca_crot, ctx->pca_colpart,
                    ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32,
                    ctx->beam_rows[0], ctx->beam_rows[1], ctx->beam_err[0], ctx->beam_err[1],

@@ -107,6 +107,103 @@ __global__ __launch_bounds__(kUpdThreads) void k_accumulate(
         for (int k = threadIdx.x; k < K; k += kUpdThreads) pcount[blockIdx.x * K + k] = (int)cnt[k];
 }
 
+// prev[n] = codes[n][m]: the column as the full centroid pass saw it.
+__global__ __launch_bounds__(256) void k_save_column(
+    const uint8_t *__restrict__ codes, int64_t N, int M, int m, uint8_t *__restrict__ prev)
+{
+    for (int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x; n < N; n += (int64_t)gridDim.x * 256)
+        prev[n] = codes[n * M + m];
+}
+
+// One entry per vector whose code in column m differs from prev[n] (the column as of the last centroid
+// pass): n in the low 32 bits, old code in bits 32..39, new code in bits 40..47.  prev is brought up to
+// date.  *count must start at zero; entries land in no particular order (the sums are order-free).
+__global__ __launch_bounds__(256) void k_moved(
+    const uint8_t *__restrict__ codes, int64_t N, int M, int m, uint8_t *__restrict__ prev,
+    unsigned long long *__restrict__ list, unsigned *__restrict__ count)
+{
+    const int lane = lane_id();
+    for (int64_t n0 = (int64_t)blockIdx.x * 256; n0 < N; n0 += (int64_t)gridDim.x * 256) {
+        const int64_t n = n0 + threadIdx.x;
+        unsigned cn = 0, co = 0;
+        bool moved = false;
+        if (n < N) {
+            cn = codes[n * M + m];
+            co = prev[n];
+            moved = cn != co;
+            if (moved) prev[n] = (uint8_t)cn;
+        }
+        const unsigned long long bal = __ballot(moved);
+        unsigned base = 0;
+        if (lane == 0 && bal) base = atomicAdd(count, (unsigned)__popcll(bal));
+        base = __shfl(base, 0, kWave);
+        if (moved)
+            list[base + __popcll(bal & ((1ull << lane) - 1ull))] =
+                (unsigned long long)(uint32_t)n | ((unsigned long long)co << 32) | ((unsigned long long)cn << 40);
+    }
+}
+
+// k_accumulate over the moved vectors only: +q into the new cluster, -q out of the old one, counts likewise.
+// Same grid roles, scale, rounding and partial layout as k_accumulate; blocks stride over the list.
+__global__ __launch_bounds__(kUpdThreads) void k_accumulate_moved(
+    const float *__restrict__ xp, const unsigned long long *__restrict__ list, const unsigned *__restrict__ count,
+    int D, int K, const unsigned *__restrict__ xmax_bits, long long *__restrict__ partial, int *__restrict__ pcount)
+{
+    extern __shared__ float4 smem4[];
+    unsigned long long *acc = reinterpret_cast<unsigned long long *>(smem4);   // [K][64]
+    int *cnt = reinterpret_cast<int *>(acc + K * kUpdWindow);                  // [K]
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int d = blockIdx.y * kUpdWindow + lane;
+    const bool live = d < D;
+    const bool counting = blockIdx.y == 0;
+    const int shift = fixed_point_shift(*xmax_bits);
+    const unsigned total = *count;
+
+    for (int e = threadIdx.x; e < K * kUpdWindow; e += kUpdThreads) acc[e] = 0ull;
+    for (int e = threadIdx.x; e < K; e += kUpdThreads) cnt[e] = 0;
+    __syncthreads();
+
+    unsigned long long *mine = acc + lane;
+    const unsigned stride = gridDim.x * kUpdWaves * kUpdDepth;
+    for (unsigned e0 = (blockIdx.x * kUpdWaves + wave) * kUpdDepth; e0 < total; e0 += stride) {
+        const int nent = (int)min((unsigned)kUpdDepth, total - e0);            // uniform
+        const unsigned long long ent = (lane < nent) ? list[e0 + lane] : 0ull;
+        const unsigned en = (unsigned)ent, eo = (unsigned)(ent >> 32) & 255u, ec = (unsigned)(ent >> 40) & 255u;
+        float v[kUpdDepth];
+#pragma unroll
+        for (int u = 0; u < kUpdDepth; ++u) {
+            v[u] = 0.f;
+            if (u < nent) {
+                const unsigned n = __builtin_amdgcn_readlane(en, u);
+                v[u] = xp[(size_t)n * D + (live ? d : 0)];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUpdDepth; ++u) {
+            if (u < nent) {
+                const int ko = __builtin_amdgcn_readlane(eo, u), kn = __builtin_amdgcn_readlane(ec, u);
+                const long long q = live ? (long long)(int)__builtin_rintf(ldexpf(v[u], shift)) : 0;
+                atomicAdd(mine + kn * kUpdWindow, (unsigned long long)q);
+                atomicAdd(mine + ko * kUpdWindow, (unsigned long long)(-q));
+            }
+        }
+        if (counting && lane < nent) {
+            atomicAdd(cnt + ec, 1);
+            atomicAdd(cnt + eo, -1);
+        }
+    }
+    __syncthreads();
+
+    long long *out = partial + (size_t)blockIdx.x * K * D;
+    for (int e = threadIdx.x; e < K * kUpdWindow; e += kUpdThreads) {
+        const int k = e / kUpdWindow, j = e - k * kUpdWindow;
+        if (blockIdx.y * kUpdWindow + j < D) out[(size_t)k * D + blockIdx.y * kUpdWindow + j] = (long long)acc[e];
+    }
+    if (counting)
+        for (int k = threadIdx.x; k < K; k += kUpdThreads) pcount[blockIdx.x * K + k] = cnt[k];
+}
+
 // max |x'| over an array (bits of the float, see publish_absmax); used when the centroid update is
 // called on its own, without the assign kernel that normally provides it.  *slot must start at 0.
 __global__ __launch_bounds__(256) void k_absmax(const float4 *__restrict__ x, int64_t n4, unsigned *__restrict__ slot)
@@ -121,6 +218,12 @@ __global__ __launch_bounds__(256) void k_absmax(const float4 *__restrict__ x, in
     if (lane_id() == 0) atomicMax(slot, __float_as_uint(amax));
 }
 
+// Exact incremental form (tot_sum int64 [K][D], tot_cnt int [K]; both may be null): a full pass stores the
+// integer sums and counts of the stage; while x' stays as it is, a later pass over only the vectors that
+// changed cluster (k_moved, k_accumulate_moved: +q into the new cluster, -q out of the old one) advances
+// them with delta != 0.  Integer addition being exact, the totals -- and so the centroids -- are the very
+// numbers a full pass would give.
+//
 // One block per codeword k: n_k = sum_b pcount[b][k];  C_m[k][d] = 2^-s * (sum_b partial[b][k][d]) / n_k
 // with the integer sum exact (so its order is free: 4 groups of blocks in parallel) and the
 // division in fp64; untouched when n_k == 0.  Then hneg[k] = -||c_k||^2/2 for the next
@@ -131,7 +234,8 @@ __global__ __launch_bounds__(256) void k_merge(
     const long long *__restrict__ partial, const int *__restrict__ pcount, int nblk,
     int K, int D, int dnorm, float *__restrict__ Cm, float *__restrict__ hneg, int *__restrict__ nk,
     int *__restrict__ counts_out, unsigned *__restrict__ refine_count,
-    double *__restrict__ run_sum, long long *__restrict__ run_cnt)
+    double *__restrict__ run_sum, long long *__restrict__ run_cnt,
+    long long *__restrict__ tot_sum, int *__restrict__ tot_cnt, int delta)
 {
     __shared__ double red[256 / kWave];
     __shared__ long long comb[kMergeGroups][kMergePairs][2];
@@ -143,7 +247,14 @@ __global__ __launch_bounds__(256) void k_merge(
         long long c = 0;
         for (int b = threadIdx.x; b < nblk; b += kWave) c += pcount[b * K + k];
         c = wave_sum_ll(c);
-        if (threadIdx.x == 0) s_n = (int)c;
+        if (threadIdx.x == 0) {
+            // totals of the stage (tot_*): stored by a full pass, advanced by a pass over the moved vectors
+            if (tot_cnt) {
+                if (delta) c += tot_cnt[k];
+                tot_cnt[k] = (int)c;
+            }
+            s_n = (int)c;
+        }
     }
     __syncthreads();
     // online learning: the chunk's sums and counts join the running ones, which then define c_k
@@ -165,7 +276,7 @@ __global__ __launch_bounds__(256) void k_merge(
     for (int p0 = 0; p0 < npairs; p0 += kMergePairs) {
         const int pr = p0 + l;
         long long s0 = 0, s1 = 0;
-        if (s_n > 0 && pr < npairs) {
+        if ((s_n > 0 || delta) && pr < npairs) {
             for (int b = b0; b < b1; ++b) {
                 const longlong2 v = *reinterpret_cast<const longlong2 *>(partial + ((size_t)b * K + k) * D + 2 * pr);
                 s0 += v.x;
@@ -178,10 +289,19 @@ __global__ __launch_bounds__(256) void k_merge(
         if (g == 0 && pr < npairs) {
             float2 c;
             float2 *dst = reinterpret_cast<float2 *>(Cm + (size_t)k * D + 2 * pr);
-            if (n > 0) {
-                long long t0 = 0, t1 = 0;
+            long long t0 = 0, t1 = 0;
 #pragma unroll
-                for (int q = 0; q < kMergeGroups; ++q) { t0 += comb[q][l][0]; t1 += comb[q][l][1]; }
+            for (int q = 0; q < kMergeGroups; ++q) { t0 += comb[q][l][0]; t1 += comb[q][l][1]; }
+            if (tot_sum) {
+                longlong2 *ts = reinterpret_cast<longlong2 *>(tot_sum + (size_t)k * D + 2 * pr);
+                if (delta) {
+                    const longlong2 old = *ts;
+                    t0 += old.x;
+                    t1 += old.y;
+                }
+                *ts = make_longlong2(t0, t1);
+            }
+            if (n > 0) {
                 double u0 = ldexp((double)t0, -shift), u1 = ldexp((double)t1, -shift);
                 if (online) {
                     double *rs = run_sum + (size_t)k * D + 2 * pr;

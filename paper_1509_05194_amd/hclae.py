@@ -28,7 +28,7 @@ EXPORTS = (
 )
 
 KERNEL_CLASSES = ("heat", "cool", "assign", "refine", "accumulate", "merge", "norms", "error", "transition",
-                  "rotate", "moments", "beam_score", "beam_expand")
+                  "rotate", "moments", "beam_score", "beam_expand", "accumulate_moved")
 
 
 class KernelTimes(ctypes.Structure):

@@ -427,3 +427,38 @@ def test_limits_of_the_shape_check(shape, oracle):
     Eo = oracle.quant_error(r64)
     assert abs(ctx.quant_error(rg) - Eo) <= 1e-5 * Eo + 1e-10 * float((X.astype(np.float64) ** 2).sum(1).mean())
     ctx.close()
+
+
+def test_stage_equals_its_single_steps_bitwise():
+    """hclae_anneal_stage updates the centroids from the moved vectors alone after its first Lloyd
+    iteration (exact integer totals); the single-step calls sum all vectors every time.  Both must give
+    the same bits: dictionaries, codes, residues."""
+    N, D, M, K, T = 40000 + 9, 128, 3, 256, 6
+    X = synth.sift_like(N, D=D)
+    idx = synth.init_indices(N, M, K)
+    out = []
+    for one_call in (True, False):
+        ctx = _ctx(N, D, M, K)
+        Xg = to_dev(X)
+        C = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+        codes = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+        r = Xg.clone()
+        for sweep in range(2):
+            for m in range(M):
+                if one_call:
+                    ctx.anneal_stage(m, C, codes, r, T, init_idx=idx[m] if sweep == 0 else None, want_stats=False)
+                else:
+                    ctx.heat(m, C, codes, r)
+                    if sweep == 0:
+                        C[m] = r[torch.from_numpy(idx[m]).cuda()]
+                    for _ in range(T):
+                        ctx.assign(m, r, C, codes)
+                        ctx.update(m, r, C, codes)
+                    ctx.assign(m, r, C, codes)
+                    ctx.cool(m, C, codes, r)
+        torch.cuda.synchronize()
+        out.append((C.clone(), codes.clone(), r.clone()))
+        ctx.close()
+    assert torch.equal(out[0][0], out[1][0]), "dictionaries differ"
+    assert torch.equal(out[0][1], out[1][1]), "codes differ"
+    assert torch.equal(out[0][2], out[1][2]), "residues differ"
