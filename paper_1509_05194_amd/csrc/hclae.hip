@@ -321,7 +321,8 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
                        ctx->refine_count,
                        online ? ctx->run_sum + (size_t)m * K * D : (double *)nullptr,
                        online ? ctx->run_cnt + (size_t)m * K : (long long *)nullptr,
-                       keep_totals ? ctx->tot_sum : (long long *)nullptr, keep_totals ? ctx->tot_cnt : (int *)nullptr, 0);
+                       keep_totals ? ctx->tot_sum : (long long *)nullptr, keep_totals ? ctx->tot_cnt : (int *)nullptr, 0,
+                       keep_totals ? ctx->moved_count : (unsigned *)nullptr);
     HIP_TRY(ctx, hipGetLastError());
     if (keep_totals) {
         hipLaunchKernelGGL(k_save_column, dim3(stream_blocks(ctx, N, 256)), dim3(256), 0, ctx->stream,
@@ -337,7 +338,7 @@ int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float
 {
     const int D = ctx->D, K = ctx->K;
     const int windows = (D + kUpdWindow - 1) / kUpdWindow;
-    int nb = ctx->upd_blocks < 32 ? ctx->upd_blocks : 32;
+    const int nb = ctx->upd_blocks;                  // upper bound; the kernels use as many as the list is worth
     static bool attr_set = false;
     if (!attr_set) {
         HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_accumulate_moved),
@@ -346,8 +347,8 @@ int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float
     }
     {
         Timed t_(ctx, HCLAE_T_ACCUM_MOVED);
-        HIP_TRY(ctx, hipMemsetAsync(ctx->moved_count, 0, sizeof(unsigned), ctx->stream));
-        hipLaunchKernelGGL(k_moved, dim3(stream_blocks(ctx, N, 256)), dim3(256), 0, ctx->stream,
+        // moved_count is zero here: the merge of the previous pass of this stage reset it
+        hipLaunchKernelGGL(k_moved, dim3((unsigned)((N + kMovedSpan - 1) / kMovedSpan)), dim3(256), 0, ctx->stream,
                            codes, N, ctx->M, m, ctx->upd_col, ctx->moved_list, ctx->moved_count);
         HIP_TRY(ctx, hipGetLastError());
         hipLaunchKernelGGL(k_accumulate_moved, dim3((unsigned)nb, (unsigned)windows), dim3(kUpdThreads), upd_lds_bytes(K),
@@ -358,7 +359,8 @@ int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float
     Timed t_(ctx, HCLAE_T_MERGE);
     hipLaunchKernelGGL(k_merge, dim3(K), dim3(256), 0, ctx->stream,
                        ctx->partial, ctx->pcount, nb, K, D, D, Cm, ctx->hneg, ctx->nk, (int *)nullptr,
-                       ctx->refine_count, (double *)nullptr, (long long *)nullptr, ctx->tot_sum, ctx->tot_cnt, 1);
+                       ctx->refine_count, (double *)nullptr, (long long *)nullptr, ctx->tot_sum, ctx->tot_cnt, 1,
+                       ctx->moved_count);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
@@ -540,6 +542,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
     if (e == hipSuccess) e = hipMemset(ctx->rec, 0, sizeof(StageRecord) * M);
     if (e == hipSuccess) e = hipMemset(ctx->refine_count, 0, 256);
     if (e == hipSuccess) e = hipMemset(ctx->nk, 0, sizeof(int) * K);
+    if (e == hipSuccess) e = hipMemset(ctx->moved_count, 0, 256);
     if (e != hipSuccess) {
         int rc = fail(nullptr, HCLAE_EHIP, "scratch initialisation", e);
         hclae_destroy(ctx);

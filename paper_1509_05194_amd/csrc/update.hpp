@@ -117,34 +117,47 @@ __global__ __launch_bounds__(256) void k_save_column(
 
 // One entry per vector whose code in column m differs from prev[n] (the column as of the last centroid
 // pass): n in the low 32 bits, old code in bits 32..39, new code in bits 40..47.  prev is brought up to
-// date.  *count must start at zero; entries land in no particular order (the sums are order-free).
+// date.  A block takes kMovedSpan consecutive vectors, collects its entries in LDS and claims its stretch of
+// the list with one counter add.  *count must start at zero; the order of the entries is free (the sums do
+// not depend on it).
+constexpr int kMovedSpan = 4096;
 __global__ __launch_bounds__(256) void k_moved(
     const uint8_t *__restrict__ codes, int64_t N, int M, int m, uint8_t *__restrict__ prev,
     unsigned long long *__restrict__ list, unsigned *__restrict__ count)
 {
-    const int lane = lane_id();
-    for (int64_t n0 = (int64_t)blockIdx.x * 256; n0 < N; n0 += (int64_t)gridDim.x * 256) {
-        const int64_t n = n0 + threadIdx.x;
-        unsigned cn = 0, co = 0;
-        bool moved = false;
+    __shared__ unsigned long long found[kMovedSpan];
+    __shared__ unsigned nfound, base;
+    if (threadIdx.x == 0) nfound = 0u;
+    __syncthreads();
+    const int64_t n0 = (int64_t)blockIdx.x * kMovedSpan;
+    for (int i = threadIdx.x; i < kMovedSpan; i += 256) {
+        const int64_t n = n0 + i;
         if (n < N) {
-            cn = codes[n * M + m];
-            co = prev[n];
-            moved = cn != co;
-            if (moved) prev[n] = (uint8_t)cn;
+            const unsigned cn = codes[n * M + m], co = prev[n];
+            if (cn != co) {
+                prev[n] = (uint8_t)cn;
+                found[atomicAdd(&nfound, 1u)] =
+                    (unsigned long long)(uint32_t)n | ((unsigned long long)co << 32) | ((unsigned long long)cn << 40);
+            }
         }
-        const unsigned long long bal = __ballot(moved);
-        unsigned base = 0;
-        if (lane == 0 && bal) base = atomicAdd(count, (unsigned)__popcll(bal));
-        base = __shfl(base, 0, kWave);
-        if (moved)
-            list[base + __popcll(bal & ((1ull << lane) - 1ull))] =
-                (unsigned long long)(uint32_t)n | ((unsigned long long)co << 32) | ((unsigned long long)cn << 40);
     }
+    __syncthreads();
+    if (threadIdx.x == 0 && nfound) base = atomicAdd(count, nfound);
+    __syncthreads();
+    for (unsigned i = threadIdx.x; i < nfound; i += 256) list[base + i] = found[i];
+}
+
+// Blocks (of the x dimension) that the pass over `total` moved vectors uses: enough rows per block to pay
+// for flushing its 128 KB of partial sums.  The merge that follows computes the same number.
+__device__ __forceinline__ int moved_blocks(unsigned total, int max_blocks)
+{
+    const unsigned want = (total + 2047u) / 2048u;
+    return (int)(want < 1u ? 1u : (want > (unsigned)max_blocks ? (unsigned)max_blocks : want));
 }
 
 // k_accumulate over the moved vectors only: +q into the new cluster, -q out of the old one, counts likewise.
-// Same grid roles, scale, rounding and partial layout as k_accumulate; blocks stride over the list.
+// Same grid roles, scale, rounding and partial layout as k_accumulate; the first moved_blocks(count)
+// blocks stride over the list, the others leave at once.
 __global__ __launch_bounds__(kUpdThreads) void k_accumulate_moved(
     const float *__restrict__ xp, const unsigned long long *__restrict__ list, const unsigned *__restrict__ count,
     int D, int K, const unsigned *__restrict__ xmax_bits, long long *__restrict__ partial, int *__restrict__ pcount)
@@ -159,13 +172,15 @@ __global__ __launch_bounds__(kUpdThreads) void k_accumulate_moved(
     const bool counting = blockIdx.y == 0;
     const int shift = fixed_point_shift(*xmax_bits);
     const unsigned total = *count;
+    const int used = moved_blocks(total, (int)gridDim.x);
+    if ((int)blockIdx.x >= used) return;
 
     for (int e = threadIdx.x; e < K * kUpdWindow; e += kUpdThreads) acc[e] = 0ull;
     for (int e = threadIdx.x; e < K; e += kUpdThreads) cnt[e] = 0;
     __syncthreads();
 
     unsigned long long *mine = acc + lane;
-    const unsigned stride = gridDim.x * kUpdWaves * kUpdDepth;
+    const unsigned stride = (unsigned)used * kUpdWaves * kUpdDepth;
     for (unsigned e0 = (blockIdx.x * kUpdWaves + wave) * kUpdDepth; e0 < total; e0 += stride) {
         const int nent = (int)min((unsigned)kUpdDepth, total - e0);            // uniform
         const unsigned long long ent = (lane < nent) ? list[e0 + lane] : 0ull;
@@ -235,7 +250,7 @@ __global__ __launch_bounds__(256) void k_merge(
     int K, int D, int dnorm, float *__restrict__ Cm, float *__restrict__ hneg, int *__restrict__ nk,
     int *__restrict__ counts_out, unsigned *__restrict__ refine_count,
     double *__restrict__ run_sum, long long *__restrict__ run_cnt,
-    long long *__restrict__ tot_sum, int *__restrict__ tot_cnt, int delta)
+    long long *__restrict__ tot_sum, int *__restrict__ tot_cnt, int delta, unsigned *__restrict__ moved_count)
 {
     __shared__ double red[256 / kWave];
     __shared__ long long comb[kMergeGroups][kMergePairs][2];
@@ -243,6 +258,16 @@ __global__ __launch_bounds__(256) void k_merge(
     const int k = blockIdx.x;
     const int shift = fixed_point_shift(refine_count[1]);
     if (k == 0 && threadIdx.x == 0) refine_count[0] = 0u;
+    // after a pass over the moved vectors only the blocks that pass used hold partials; the list counter is
+    // handed back empty (every block reads it before the last one to arrive resets it)
+    if (delta) nblk = moved_blocks(*moved_count, nblk);
+    if (moved_count) {
+        __syncthreads();
+        if (threadIdx.x == 0 && atomicAdd(moved_count + 1, 1u) == gridDim.x - 1) {
+            moved_count[0] = 0u;
+            moved_count[1] = 0u;
+        }
+    }
     if (threadIdx.x < kWave) {
         long long c = 0;
         for (int b = threadIdx.x; b < nblk; b += kWave) c += pcount[b * K + k];
