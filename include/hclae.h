@@ -180,6 +180,16 @@ int hclae_online_import(hclae_ctx *ctx, const double *run_sum, const int64_t *ru
  */
 int hclae_set_contraction(hclae_ctx *ctx, int mode);
 
+/*
+ * Exact pruning of the Lloyd iterations of hclae_anneal_stage / hclae_sweep (on by default; on = 0 switches
+ * it off).  x' is fixed during a stage, so per vector an upper bound on the distance to its codeword and a
+ * lower bound on the distance to all others are kept, aged by how far the codewords move in each centroid
+ * update (triangle inequality), and only vectors whose bounds stop separating are assigned again.  The
+ * bounds include the rounding bounds of the kernels, so the results are those of full assignments, bit for
+ * bit; only the work differs.  Applies where the whole padded dictionary fits LDS.
+ */
+int hclae_set_pruning(hclae_ctx *ctx, int on);
+
 /* ---- multi-path encoding (Sec. 3.3, Eq. 3) ---------------------------------------------------- */
 
 #define HCLAE_MAX_L 32     /* paths kept per vector */
@@ -275,6 +285,8 @@ enum {
     HCLAE_T_BEAM_SCORE, /* multi-path encoding: fp32-MFMA scoring and candidate bitmaps     */
     HCLAE_T_BEAM_EXPAND,/* multi-path encoding: fp64 evaluation, top-L, next beam           */
     HCLAE_T_ACCUM_MOVED,/* centroid sums advanced by the vectors that changed cluster       */
+    HCLAE_T_ASSIGN_ACTIVE, /* assignment of the vectors the distance bounds could not settle  */
+    HCLAE_T_BOUNDS,     /* ageing of the distance bounds and listing of those vectors       */
     HCLAE_T_COUNT
 };
 

@@ -30,6 +30,22 @@ struct RefineItem {
     uint32_t mask[2][4];
 };
 
+// Exact pruning of the assignments of one stage (x' fixed, only the dictionary moves).  For every vector
+// the stage keeps an upper bound bu on the distance to its own codeword and a lower bound bl on the
+// distance to every other one, both rigorous (they include the rounding bound of the scores).  When
+// the dictionary moves, bu grows by the drift of the own codeword and bl shrinks by the largest drift
+// of another one (triangle inequality); while bu < bl the own codeword is still the unique nearest
+// and the vector is not recomputed.  The others are listed (k_bounds_step) and go through the same
+// contraction, decision and fp64 re-check as before, which also renews their bounds.  The codes are
+// therefore exactly those of full assignments.
+//   PRUNE 0: plain assignment.  1: all vectors, and store their bounds.  2: only active[0..*active_count),
+//   and store their bounds.
+struct PruneArgs {
+    float *bu, *bl;                    // [N]
+    const uint32_t *active;            // [*active_count] vector indices (PRUNE 2)
+    const unsigned *active_count;
+};
+
 // -||c_k||^2 / 2 in fp32 (computed in fp64) over the first D coordinates of rows of stride ld, for
 // k < K; -inf for the padding rows up to kpad.
 // One wave per codeword.  Also resets the two counters the assign that follows will fill
@@ -175,21 +191,29 @@ __device__ __forceinline__ void init_acc(floatx16 (&acc)[KB], const float *hneg_
 // Per-vector decision from the wave's scores.  `eps` * (hmax + ||x'|| * cmax) bounds twice the
 // rounding error of any score, so the true nearest codeword is among those within that
 // margin of the best score.
-template <int KB>
+template <int KB, int PRUNE = 0>
 __device__ __forceinline__ void decide(
     const floatx16 (&acc)[KB], float xsq, float eps, float hmax, float cmax, int lane,
     int64_t n, int64_t N, int M, int m, uint8_t *__restrict__ codes,
-    RefineItem *__restrict__ list, unsigned *__restrict__ refine_count)
+    RefineItem *__restrict__ list, unsigned *__restrict__ refine_count, PruneArgs pa = PruneArgs())
 {
     const int h = lane >> 5;
-    float mx = -__builtin_inff();
+    float mx = -__builtin_inff(), m2 = -__builtin_inff();            // best and second best score
 #pragma unroll
     for (int b = 0; b < KB; ++b)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[b][v]);
+        for (int v = 0; v < 16; ++v) {
+            if (PRUNE) m2 = __builtin_amdgcn_fmed3f(mx, m2, acc[b][v]);   // m2 <= mx always: the median is the new second
+            mx = fmaxf(mx, acc[b][v]);
+        }
+    if (PRUNE) {
+        const float mxo = __shfl_xor(mx, 32, kWave), m2o = __shfl_xor(m2, 32, kWave);
+        m2 = fmaxf(fminf(mx, mxo), fmaxf(m2, m2o));
+    }
     mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
     const float x2 = xsq + __shfl_xor(xsq, 32, kWave);
-    const float thr = mx - eps * (hmax + sqrtf(x2) * cmax);
+    const float margin = eps * (hmax + sqrtf(x2) * cmax);
+    const float thr = mx - margin;
 
     // Candidate bitmaps without compare-and-select chains: the sign of acc - thr is shifted into a word
     // (v_alignbit), one subtraction and one shift-in per score; the 16 bits of a block end up "1 = below".
@@ -219,6 +243,23 @@ __device__ __forceinline__ void decide(
     cnt += __shfl_xor(cnt, 32, kWave);
     lo = min(lo, __shfl_xor(lo, 32, kWave));
 
+    if (PRUNE) {
+        // d^2 = ||x'||^2 - 2 score.  With E the rounding bound of a score (half the margin): the own codeword
+        // has true score >= mx - E and every other one <= m2 + E.  A vector that goes to the re-check (or has
+        // no candidate) gets bounds that keep it active.  slack covers the fp32 evaluation of these lines.
+        const float E = 0.5001f * margin;
+        const float slack = 2e-5f * (x2 + 2.f * fabsf(mx) + 2.f * fabsf(m2));
+        float u = __builtin_inff(), l = 0.f;
+        if (cnt == 1) {
+            u = sqrtf(fmaxf(0.f, (x2 - 2.f * (mx - E)) + slack)) * 1.00001f;
+            l = sqrtf(fmaxf(0.f, (x2 - 2.f * (m2 + E)) - slack)) * 0.99999f;
+        }
+        if (h == 0 && n < N) {
+            pa.bu[n] = u;
+            pa.bl[n] = l;
+        }
+    }
+
     // provisional code: the lowest candidate (final when it is the only one)
     unsigned slot = 0;
     const bool amb = (cnt >= 2) && (n < N);
@@ -239,11 +280,12 @@ __device__ __forceinline__ void decide(
 // 32*KB * 64*NC floats fit.  Each wave owns tiles of 32 vectors, streams them from HBM straight
 // into B-operand registers in 64-dim chunks (two register sets, the next chunk in flight while
 // the current one is contracted) and keeps all 32*KB scores of a vector in accumulators.
-template <int KB>
+template <int KB, int PRUNE = 0>
 __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     const float *__restrict__ xp, const float *__restrict__ Cm, const float *__restrict__ hneg,
     int64_t N, int D, int ld, int K, int M, int m, int NC, float eps,
-    uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count)
+    uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count,
+    PruneArgs pa)
 {
     extern __shared__ float4 smem4[];
     const int S = 8 * NC;
@@ -265,7 +307,9 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     // Static tile schedule balanced per SIMD: waves w and w + 4 of a block share a SIMD (and its
     // matrix pipe), so tiles are dealt round-robin to the gridDim.x * 4 SIMD slots and the two
     // waves of a slot take alternate ones; no SIMD gets more than one tile above the average.
-    const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
+    // rows of this launch: all N vectors, or the listed ones (PRUNE 2)
+    const int64_t rows = PRUNE == 2 ? (int64_t)*pa.active_count : N;
+    const int64_t ntiles = (rows + kTileVec - 1) / kTileVec;
     const int64_t nslots = (int64_t)gridDim.x * 4;
     const int64_t tstride = 2 * nslots;
     const int64_t t0 = (int64_t)blockIdx.x * 4 + (wave & 3) + nslots * (wave >> 2);
@@ -273,9 +317,15 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     const int64_t my_tiles = (ntiles - t0 + tstride - 1) / tstride;
     const int64_t G = my_tiles * NC;                                // (tile, chunk) steps of this wave
 
+    // vector behind column r of a tile; N (= "none") for the columns of the ragged tail
+    auto vec_of = [&](int64_t tile) -> int64_t {
+        const int64_t i = tile * kTileVec + r;
+        if (i >= rows) return N;
+        return PRUNE == 2 ? (int64_t)pa.active[i] : i;
+    };
     auto row_ptr = [&](int64_t tile) {
-        int64_t n = tile * kTileVec + r;
-        if (n >= N) n = N - 1;                                      // tail rows re-read the last vector
+        int64_t n = vec_of(tile);
+        if (n >= N) n = PRUNE == 2 ? (int64_t)pa.active[rows - 1] : N - 1;   // tail columns re-read the last row
         return xp + n * ld;
     };
 
@@ -295,7 +345,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
         if (q == 0) { init_acc<KB>(acc, lds_h, h); xsq = 0.f; }
         mfma_chunk<KB>(acc, xa, lds_c, q, S, lane, xsq, amax);
         if (q == NC - 1)
-            decide<KB>(acc, xsq, eps, hmax, cmax, lane, tile * kTileVec + r, N, M, m, codes, list, refine_count);
+            decide<KB, PRUNE>(acc, xsq, eps, hmax, cmax, lane, vec_of(tile), N, M, m, codes, list, refine_count, pa);
         if (g + 1 >= G) break;
         // ---- step g+1 on xb; prefetch step g+2 into xa
         int64_t tile2 = tile1;
@@ -305,7 +355,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
         if (q1 == 0) { init_acc<KB>(acc, lds_h, h); xsq = 0.f; }
         mfma_chunk<KB>(acc, xb, lds_c, q1, S, lane, xsq, amax);
         if (q1 == NC - 1)
-            decide<KB>(acc, xsq, eps, hmax, cmax, lane, tile1 * kTileVec + r, N, M, m, codes, list, refine_count);
+            decide<KB, PRUNE>(acc, xsq, eps, hmax, cmax, lane, vec_of(tile1), N, M, m, codes, list, refine_count, pa);
         tile = tile2;
         q = q2;
     }
@@ -365,6 +415,189 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
         decide<KB>(acc, xsq, eps, hmax, cmax, lane, n_raw, N, M, m, codes, list, refine_count);
     }
     publish_absmax(amax, refine_count + 1);
+}
+
+// The kVolatile + 1 largest entries of drift[0..K) (K <= 256), descending, with their indices; computed by
+// the first wave of a 256-thread block into LDS (top[], tk[]; unused slots 0 / -1).  Ends with a barrier.
+constexpr int kVolatile = 4;
+__device__ __forceinline__ void top_drifts(const float *sdrift, int K, float *top, int *tk)
+{
+    if (threadIdx.x < kWave) {
+        const int lane = threadIdx.x;
+        float v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (lane + kWave * j < K) ? sdrift[lane + kWave * j] : -1.f;
+        for (int i = 0; i <= kVolatile; ++i) {
+            float best = v[0];
+            int at = lane;
+#pragma unroll
+            for (int j = 1; j < 4; ++j)
+                if (v[j] > best) { best = v[j]; at = lane + kWave * j; }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const float ob = __shfl_xor(best, o, kWave);
+                const int oa = __shfl_xor(at, o, kWave);
+                if (ob > best || (ob == best && oa < at)) { best = ob; at = oa; }
+            }
+            if (lane == 0) { top[i] = best > 0.f ? best : 0.f; tk[i] = best > 0.f ? at : -1; }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (at == lane + kWave * j) v[j] = -1.f;             // struck out
+        }
+    }
+    __syncthreads();
+}
+
+// Between two assignments of a stage: age the bounds by the drift of the dictionary (drift[k] >= the
+// distance codeword k moved in the centroid update, 0 for a kept one) and list the vectors that have to
+// be recomputed.  A block takes kBoundSpan consecutive vectors, stages its entries in LDS and claims its
+// stretch of the list with one counter add (*count must be zero on entry; order is free).
+constexpr int kBoundSpan = 1024;
+__global__ __launch_bounds__(256) void k_bounds_step(
+    const uint8_t *__restrict__ codes, int64_t N, int M, int m, const float *__restrict__ drift, int K,
+    float *__restrict__ bu, float *__restrict__ bl, uint32_t *__restrict__ list, unsigned *__restrict__ count)
+{
+    __shared__ uint32_t found[kBoundSpan];
+    __shared__ float sdrift[256];
+    __shared__ unsigned nfound, base;
+    __shared__ float s_top[kVolatile + 1];
+    __shared__ int s_tk[kVolatile + 1];
+    sdrift[threadIdx.x] = (int)threadIdx.x < K ? drift[threadIdx.x] : 0.f;
+    if (threadIdx.x == 0) nfound = 0u;
+    __syncthreads();
+    top_drifts(sdrift, K, s_top, s_tk);
+    const float d1 = s_top[0], d2 = s_top[1];
+    const int k1 = s_tk[0];
+    const int64_t n0 = (int64_t)blockIdx.x * kBoundSpan;
+    constexpr int U = kBoundSpan / 256;
+    int c[U];
+    float u[U], l[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {                                   // all loads first
+        const int64_t n = n0 + j * 256 + threadIdx.x;
+        const int64_t nn = n < N ? n : N - 1;
+        c[j] = codes[nn * M + m];
+        u[j] = bu[nn];
+        l[j] = bl[nn];
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+        const int64_t n = n0 + j * 256 + threadIdx.x;
+        if (n < N) {
+            const float un = (u[j] + sdrift[c[j]]) * 1.000001f;      // rounded up
+            const float ln = (l[j] - ((c[j] == k1) ? d2 : d1)) * 0.999999f;   // rounded down while positive
+            if (un < ln) {
+                bu[n] = un;
+                bl[n] = ln;
+            } else {
+                found[atomicAdd(&nfound, 1u)] = (uint32_t)n;          // its bounds stay as they were
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && nfound) base = atomicAdd(count, nfound);
+    __syncthreads();
+    for (unsigned i = threadIdx.x; i < nfound; i += 256) list[base + i] = found[i];
+}
+
+// Second look at the vectors k_bounds_step listed (in[0..*in_count) -> out[0..*out_count), *out_count zero on
+// entry).  One codeword that moves far (a cluster of few members) costs every vector its lower bound.  When
+// the largest drift stands out from the (kVolatile+1)-th and the list is long, the kVolatile codewords that
+// moved most are treated apart: the lower bound ages by the largest drift of the REST, and the distance to
+// each of those few is computed afresh from x' (expanded form in fp32 with its rounding bound) and joins
+// the lower bound.  Vectors that this settles get their aged bounds and leave the list.  Otherwise the list
+// is passed on as it is.  Eight lanes share a vector.
+__global__ __launch_bounds__(256) void k_bounds_apart(
+    const uint8_t *__restrict__ codes, int64_t N, int M, int m, const float *__restrict__ drift, int K,
+    float *__restrict__ bu, float *__restrict__ bl, const uint32_t *__restrict__ in, const unsigned *__restrict__ in_count,
+    uint32_t *__restrict__ out, unsigned *__restrict__ out_count,
+    const float *__restrict__ xp, int D, const float *__restrict__ Cm)
+{
+    extern __shared__ float4 smem4[];                                // kVolatile rows of D floats
+    float *vrow = reinterpret_cast<float *>(smem4);
+    __shared__ uint32_t found[kBoundSpan];
+    __shared__ float sdrift[256];
+    __shared__ unsigned nfound, base;
+    __shared__ float s_top[kVolatile + 1], s_vnorm[kVolatile];
+    __shared__ int s_tk[kVolatile + 1];
+    const unsigned total = *in_count;
+    sdrift[threadIdx.x] = (int)threadIdx.x < K ? drift[threadIdx.x] : 0.f;
+    __syncthreads();
+    top_drifts(sdrift, K, s_top, s_tk);
+    const float d1 = s_top[0], drest = s_top[kVolatile];
+    // uniform over the grid: worth a gather of the listed rows of x'?
+    const bool apart = K > kVolatile + 1 && d1 > 1.5f * drest && (int64_t)total * 16 > N;
+    if (!apart) {
+        for (unsigned i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) out[i] = in[i];
+        if (blockIdx.x == 0 && threadIdx.x == 0) *out_count = total;
+        return;
+    }
+    for (int e = threadIdx.x; e < kVolatile * D; e += 256) {
+        const int j = e / D;
+        vrow[e] = s_tk[j] >= 0 ? Cm[(size_t)s_tk[j] * D + (e - j * D)] : 0.f;
+    }
+    __syncthreads();
+    if (threadIdx.x < kVolatile) {
+        float q = 0.f;
+        for (int d = 0; d < D; ++d) q = fmaf(vrow[threadIdx.x * D + d], vrow[threadIdx.x * D + d], q);
+        s_vnorm[threadIdx.x] = q;
+    }
+    const int sub = threadIdx.x & 7;
+    const int d4n = D >> 2;
+    for (unsigned e0 = blockIdx.x * kBoundSpan; e0 < total; e0 += gridDim.x * kBoundSpan) {
+        if (threadIdx.x == 0) nfound = 0u;
+        __syncthreads();
+        for (int i0 = 0; i0 < kBoundSpan; i0 += 32) {
+            const unsigned e = e0 + i0 + (threadIdx.x >> 3);
+            const bool ok = e < total;
+            const int64_t n = in[ok ? e : total - 1];
+            const float4 *row = reinterpret_cast<const float4 *>(xp + n * D);
+            float x2 = 0.f, dot[kVolatile];
+#pragma unroll
+            for (int j = 0; j < kVolatile; ++j) dot[j] = 0.f;
+#pragma unroll 4
+            for (int q = sub; q < d4n; q += 8) {
+                const float4 x = row[q];
+                x2 = fmaf(x.x, x.x, fmaf(x.y, x.y, fmaf(x.z, x.z, fmaf(x.w, x.w, x2))));
+#pragma unroll
+                for (int j = 0; j < kVolatile; ++j) {
+                    const float4 c = *reinterpret_cast<const float4 *>(vrow + j * D + 4 * q);
+                    dot[j] = fmaf(x.x, c.x, fmaf(x.y, c.y, fmaf(x.z, c.z, fmaf(x.w, c.w, dot[j]))));
+                }
+            }
+#pragma unroll
+            for (int o = 1; o < 8; o <<= 1) {
+                x2 += __shfl_xor(x2, o, kWave);
+#pragma unroll
+                for (int j = 0; j < kVolatile; ++j) dot[j] += __shfl_xor(dot[j], o, kWave);
+            }
+            if (ok && sub == 0) {
+                const int c = codes[n * M + m];
+                const float u = (bu[n] + sdrift[c]) * 1.000001f;
+                float l = (bl[n] - drest) * 0.999999f;               // the rest moved by at most drest
+#pragma unroll
+                for (int j = 0; j < kVolatile; ++j) {
+                    if (s_tk[j] >= 0 && s_tk[j] != c) {
+                        // ||x' - c_j||^2 in the expanded form; 2e-5 of the magnitudes bounds its fp32 rounding
+                        const float mag = x2 + 2.f * fabsf(dot[j]) + s_vnorm[j];
+                        const float dj2 = (x2 - 2.f * dot[j] + s_vnorm[j]) - 2e-5f * mag;
+                        l = fminf(l, sqrtf(fmaxf(dj2, 0.f)) * 0.999999f);
+                    }
+                }
+                if (u < l) {
+                    bu[n] = u;
+                    bl[n] = l;
+                } else {
+                    found[atomicAdd(&nfound, 1u)] = (uint32_t)n;
+                }
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0 && nfound) base = atomicAdd(out_count, nfound);
+        __syncthreads();
+        for (unsigned i = threadIdx.x; i < nfound; i += 256) out[base + i] = found[i];
+        __syncthreads();
+    }
 }
 
 // fp64 re-check of the vectors whose fp32 scores were too close to call: direct-form squared

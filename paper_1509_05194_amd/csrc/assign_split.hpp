@@ -155,12 +155,13 @@ __device__ __forceinline__ void mfma_chunk_split(
 //   margin = eps * (hmax + ||x'|| * cmax_eff),  eps = 2 * (accumulation bound),
 //   cmax_eff = 1.02 cmax + (split bound per unit ||x'||) / (accumulation bound)
 // (1.02: the accumulated magnitudes are those of the split operands, ||xh|| ||ch|| + ||xh|| ||cl|| + ||xl|| ||ch||).
-template <int KB>
+template <int KB, int PRUNE = 0>
 __global__ __launch_bounds__(kAssignThreads) void k_assign_split(
     const float *__restrict__ xp, const float *__restrict__ Cm, const float *__restrict__ hneg,
     const float *__restrict__ split_norms,
     int64_t N, int D, int ld, int K, int M, int m, int NC, float acc_bound,
-    uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count)
+    uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count,
+    PruneArgs pa)
 {
     extern __shared__ float4 smem4[];
     const int T = 4 * NC;                                                // 16-dim steps
@@ -199,7 +200,9 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_split(
     const float eps = 2.f * acc_bound;
     const float cmax_eff = (cmax * 1.02f + split_bound / acc_bound) * 1.0001f;
 
-    const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
+    // rows of this launch: all N vectors, or the listed ones (PRUNE 2; see PruneArgs)
+    const int64_t rows = PRUNE == 2 ? (int64_t)*pa.active_count : N;
+    const int64_t ntiles = (rows + kTileVec - 1) / kTileVec;
     const int64_t nslots = (int64_t)gridDim.x * 4;
     const int64_t tstride = 2 * nslots;
     const int64_t t0 = (int64_t)blockIdx.x * 4 + (wave & 3) + nslots * (wave >> 2);
@@ -207,9 +210,14 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_split(
     const int64_t my_tiles = (ntiles - t0 + tstride - 1) / tstride;
     const int64_t G = my_tiles * NC;
 
+    auto vec_of = [&](int64_t tile) -> int64_t {
+        const int64_t i = tile * kTileVec + r;
+        if (i >= rows) return N;
+        return PRUNE == 2 ? (int64_t)pa.active[i] : i;
+    };
     auto row_ptr = [&](int64_t tile) {
-        int64_t n = tile * kTileVec + r;
-        if (n >= N) n = N - 1;
+        int64_t n = vec_of(tile);
+        if (n >= N) n = PRUNE == 2 ? (int64_t)pa.active[rows - 1] : N - 1;
         return xp + n * ld;
     };
 
@@ -227,7 +235,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_split(
         if (q == 0) { init_acc<KB>(acc, lds_h, g); xsq = 0.f; }
         mfma_chunk_split<KB>(acc, xa, lds_c, q, T, lane, xsq, amax);
         if (q == NC - 1)
-            decide<KB>(acc, xsq, eps, hmax, cmax_eff, lane, tile * kTileVec + r, N, M, m, codes, list, refine_count);
+            decide<KB, PRUNE>(acc, xsq, eps, hmax, cmax_eff, lane, vec_of(tile), N, M, m, codes, list, refine_count, pa);
         if (s + 1 >= G) break;
         int64_t tile2 = tile1;
         int q2 = q1 + 1;
@@ -236,7 +244,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_split(
         if (q1 == 0) { init_acc<KB>(acc, lds_h, g); xsq = 0.f; }
         mfma_chunk_split<KB>(acc, xb, lds_c, q1, T, lane, xsq, amax);
         if (q1 == NC - 1)
-            decide<KB>(acc, xsq, eps, hmax, cmax_eff, lane, tile1 * kTileVec + r, N, M, m, codes, list, refine_count);
+            decide<KB, PRUNE>(acc, xsq, eps, hmax, cmax_eff, lane, vec_of(tile1), N, M, m, codes, list, refine_count, pa);
         tile = tile2;
         q = q2;
     }

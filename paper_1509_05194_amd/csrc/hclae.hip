@@ -56,6 +56,11 @@ struct hclae_ctx {
     uint8_t *upd_col;        // [N_max] code column as of the last centroid pass
     unsigned long long *moved_list;  // [N_max]
     unsigned *moved_count;
+    // exact pruning of the assignments of a stage (see PruneArgs)
+    int pruning;             // 0 off, 1 on (default)
+    float *bnd_u, *bnd_l;    // [N_max]
+    float *drift;            // [K]
+    uint32_t *active;        // [2][N_max]: list of k_bounds_step, list of k_bounds_apart (the one the assign reads)
     int64_t *seed_idx;       // [K]
     double *part_a, *part_b; // [nparts]
     long long *part_chg;     // [nparts]
@@ -202,17 +207,24 @@ int launch_norms(hclae_ctx *ctx, const float *Cm, int dact = 0, int ld = 0, bool
     return HCLAE_OK;
 }
 
+// prune: 0 plain; 1 all vectors and store the stage's bounds; 2 only the vectors k_bounds_step listed
+// (resident shapes over all D coordinates only; the caller checks).
 template <int KB>
-int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float *Cm, uint8_t *codes, int dact, int ld)
+int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float *Cm, uint8_t *codes, int dact, int ld,
+                     int prune)
 {
+    PruneArgs pa;
+    pa.bu = ctx->bnd_u; pa.bl = ctx->bnd_l;
+    pa.active = ctx->active + ctx->N_max; pa.active_count = ctx->moved_count + 3;
     const int NC = (dact + kChunkD - 1) / kChunkD;
     const int dpad = kChunkD * NC;
     const bool resident = (size_t)32 * KB * dpad * sizeof(float) + 4096 <= (size_t)kLdsBudget;
     // twice the worst-case rounding error of a score: (dpad + 1) roundings of relative size 2^-23
     // on partial sums bounded by h + ||x'|| ||c||, plus the rounding of h itself
     const float eps = 2.02f * (float)(dpad + 2) * 1.1920929e-7f;
+    if (!resident) prune = 0;
     {
-    Timed t_(ctx, HCLAE_T_ASSIGN);
+    Timed t_(ctx, prune == 2 ? HCLAE_T_ASSIGN_ACTIVE : HCLAE_T_ASSIGN);
     if (resident && ctx->contraction == 1) {
         const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
@@ -220,16 +232,21 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
         if (blocks > ctx->cus) blocks = ctx->cus;
         static bool attr_set = false;
         if (!attr_set) {
-            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split<KB>),
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split<KB, 0>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split<KB, 1>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split<KB, 2>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             attr_set = true;
         }
         // 3 MFMAs per 16 dims, each within 2^-21 of the magnitudes it adds; one more for the rounding of the norm
         const float acc_bound = (float)(3 * (dpad / kSplitStep) + 1) * 4.76837158203125e-7f;
         hipLaunchKernelGGL(k_split_norms, dim3((ctx->K + 3) / 4), dim3(256), 0, ctx->stream, Cm, ctx->K, dact, ld, ctx->split_norms);
-        hipLaunchKernelGGL((k_assign_split<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
+        auto kern = prune == 1 ? &k_assign_split<KB, 1> : prune == 2 ? &k_assign_split<KB, 2> : &k_assign_split<KB, 0>;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
                            xp, Cm, ctx->hneg, ctx->split_norms, N, dact, ld, ctx->K, ctx->M, m, NC, acc_bound,
-                           codes, ctx->refine_list, ctx->refine_count);
+                           codes, ctx->refine_list, ctx->refine_count, pa);
     } else if (resident) {
         const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
@@ -237,13 +254,18 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
         if (blocks > ctx->cus) blocks = ctx->cus;
         static bool attr_set = false;
         if (!attr_set) {
-            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB>),
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 0>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 1>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 2>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             attr_set = true;
         }
-        hipLaunchKernelGGL((k_assign_resident<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
+        auto kern = prune == 1 ? &k_assign_resident<KB, 1> : prune == 2 ? &k_assign_resident<KB, 2> : &k_assign_resident<KB, 0>;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
                            xp, Cm, ctx->hneg, N, dact, ld, ctx->K, ctx->M, m, NC, eps,
-                           codes, ctx->refine_list, ctx->refine_count);
+                           codes, ctx->refine_list, ctx->refine_count, pa);
     } else {
         const size_t lds = (size_t)KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t nbt = (N + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);
@@ -269,16 +291,32 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
 
 // Assumes hneg holds the norms of Cm (over the same dact coordinates) and the re-check counter is zero.
 int launch_assign(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float *Cm, uint8_t *codes,
-                  int dact = 0, int ld = 0)
+                  int dact = 0, int ld = 0, int prune = 0)
 {
     if (dact <= 0) dact = ctx->D;
     if (ld <= 0) ld = ctx->D;
+    if (dact != ctx->D || ld != ctx->D) prune = 0;
     switch (ctx->kb) {
-    case 1: return launch_assign_kb<1>(ctx, m, N, xp, Cm, codes, dact, ld);
-    case 2: return launch_assign_kb<2>(ctx, m, N, xp, Cm, codes, dact, ld);
-    case 4: return launch_assign_kb<4>(ctx, m, N, xp, Cm, codes, dact, ld);
-    default: return launch_assign_kb<8>(ctx, m, N, xp, Cm, codes, dact, ld);
+    case 1: return launch_assign_kb<1>(ctx, m, N, xp, Cm, codes, dact, ld, prune);
+    case 2: return launch_assign_kb<2>(ctx, m, N, xp, Cm, codes, dact, ld, prune);
+    case 4: return launch_assign_kb<4>(ctx, m, N, xp, Cm, codes, dact, ld, prune);
+    default: return launch_assign_kb<8>(ctx, m, N, xp, Cm, codes, dact, ld, prune);
     }
+}
+
+// Ages the bounds of the stage by the drift of the last centroid update and lists the vectors to recompute.
+// The two list counters (moved_count[2], [3]) are zero here: the merge that reported the drift reset them.
+int launch_bounds_step(hclae_ctx *ctx, int m, int64_t N, const uint8_t *codes, const float *xp, const float *Cm)
+{
+    Timed t_(ctx, HCLAE_T_BOUNDS);
+    hipLaunchKernelGGL(k_bounds_step, dim3((unsigned)((N + kBoundSpan - 1) / kBoundSpan)), dim3(256), 0, ctx->stream,
+                       codes, N, ctx->M, m, ctx->drift, ctx->K, ctx->bnd_u, ctx->bnd_l, ctx->active, ctx->moved_count + 2);
+    HIP_TRY(ctx, hipGetLastError());
+    hipLaunchKernelGGL(k_bounds_apart, dim3(ctx->cus * 4), dim3(256), (size_t)kVolatile * ctx->D * sizeof(float), ctx->stream,
+                       codes, N, ctx->M, m, ctx->drift, ctx->K, ctx->bnd_u, ctx->bnd_l, ctx->active, ctx->moved_count + 2,
+                       ctx->active + ctx->N_max, ctx->moved_count + 3, xp, ctx->D, Cm);
+    HIP_TRY(ctx, hipGetLastError());
+    return HCLAE_OK;
 }
 
 // Accumulate + merge; leaves hneg = norms of the new Cm and the re-check counter at zero.
@@ -322,7 +360,7 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
                        online ? ctx->run_sum + (size_t)m * K * D : (double *)nullptr,
                        online ? ctx->run_cnt + (size_t)m * K : (long long *)nullptr,
                        keep_totals ? ctx->tot_sum : (long long *)nullptr, keep_totals ? ctx->tot_cnt : (int *)nullptr, 0,
-                       keep_totals ? ctx->moved_count : (unsigned *)nullptr);
+                       keep_totals ? ctx->moved_count : (unsigned *)nullptr, keep_totals ? ctx->drift : (float *)nullptr);
     HIP_TRY(ctx, hipGetLastError());
     if (keep_totals) {
         hipLaunchKernelGGL(k_save_column, dim3(stream_blocks(ctx, N, 256)), dim3(256), 0, ctx->stream,
@@ -360,7 +398,7 @@ int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float
     hipLaunchKernelGGL(k_merge, dim3(K), dim3(256), 0, ctx->stream,
                        ctx->partial, ctx->pcount, nb, K, D, D, Cm, ctx->hneg, ctx->nk, (int *)nullptr,
                        ctx->refine_count, (double *)nullptr, (long long *)nullptr, ctx->tot_sum, ctx->tot_cnt, 1,
-                       ctx->moved_count);
+                       ctx->moved_count, ctx->drift);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
@@ -399,13 +437,19 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
     if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
     // x' stays as it is until the stage ends: the first centroid update sums all vectors and keeps the integer
     // totals, the others add only the vectors that changed cluster (exact, so the dictionaries are the same)
+    // With pruning the first assignment stores distance bounds for every vector; after each centroid update
+    // (which also reports how far every codeword moved) only the vectors whose bounds no longer separate
+    // their codeword from the others are assigned again.  The first update must then keep its totals.
+    const bool prune = ctx->pruning && ctx->resident && iters > 0;
     for (int t = 0; t < iters; ++t) {
-        if ((rc = launch_assign(ctx, m, N, residue, Cm, codes)) != HCLAE_OK) return rc;
-        rc = t == 0 ? launch_update(ctx, m, N, residue, Cm, codes, nullptr, true, false, 0, iters > 1)
+        if (prune && t > 0 && (rc = launch_bounds_step(ctx, m, N, codes, residue, Cm)) != HCLAE_OK) return rc;
+        if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? (t == 0 ? 1 : 2) : 0)) != HCLAE_OK) return rc;
+        rc = t == 0 ? launch_update(ctx, m, N, residue, Cm, codes, nullptr, true, false, 0, iters > 1 || prune)
                     : launch_update_moved(ctx, m, N, residue, Cm, codes);
         if (rc != HCLAE_OK) return rc;
     }
-    if ((rc = launch_assign(ctx, m, N, residue, Cm, codes)) != HCLAE_OK) return rc;
+    if (prune && (rc = launch_bounds_step(ctx, m, N, codes, residue, Cm)) != HCLAE_OK) return rc;
+    if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? 2 : 0)) != HCLAE_OK) return rc;
     int pa;
     if (next < 0) {
         pa = launch_heat_cool<-1, true>(ctx, m, N, C, codes, residue, ctx->part_b);
@@ -484,6 +528,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
     ctx->N_max = N_max; ctx->D = D; ctx->M = M; ctx->K = K;
     ctx->stream = static_cast<hipStream_t>(hip_stream);
     ctx->sweep_L = 10;                       // the width the paper settles on (Sec. 3.3)
+    ctx->pruning = 1;
     ctx->kb = K <= 32 ? 1 : K <= 64 ? 2 : K <= 128 ? 4 : 8;
     ctx->NC = (D + kChunkD - 1) / kChunkD;
     ctx->resident = (size_t)32 * ctx->kb * kChunkD * ctx->NC * sizeof(float) + 4096 <= (size_t)kLdsBudget;
@@ -524,6 +569,10 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
         {(void **)&ctx->upd_col, (size_t)N_max},
         {(void **)&ctx->moved_list, sizeof(unsigned long long) * (size_t)N_max},
         {(void **)&ctx->moved_count, 256},
+        {(void **)&ctx->bnd_u, sizeof(float) * (size_t)N_max},
+        {(void **)&ctx->bnd_l, sizeof(float) * (size_t)N_max},
+        {(void **)&ctx->drift, sizeof(float) * HCLAE_MAX_K},
+        {(void **)&ctx->active, sizeof(uint32_t) * 2 * (size_t)N_max},
         {(void **)&ctx->seed_idx, sizeof(int64_t) * K},
         {(void **)&ctx->part_a, sizeof(double) * ctx->nparts},
         {(void **)&ctx->part_b, sizeof(double) * ctx->nparts},
@@ -557,7 +606,7 @@ int hclae_destroy(hclae_ctx *ctx)
 {
     if (!ctx) return HCLAE_EINVAL;
     void *dev[] = {ctx->hneg, ctx->split_norms, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
-                   ctx->nk, ctx->tot_sum, ctx->tot_cnt, ctx->upd_col, ctx->moved_list, ctx->moved_count, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
+                   ctx->nk, ctx->tot_sum, ctx->tot_cnt, ctx->upd_col, ctx->moved_list, ctx->moved_count, ctx->bnd_u, ctx->bnd_l, ctx->drift, ctx->active, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
                    ctx->run_sum, ctx->run_cnt, ctx->n0_dev, ctx->pca_rt, ctx->pca_crot, ctx->pca_colpart,
                    ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32,
                    ctx->beam_rows[0], ctx->beam_rows[1], ctx->beam_err[0], ctx->beam_err[1],
@@ -707,6 +756,13 @@ int hclae_anneal_stage(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M,
 
 static int enqueue_encode_beam(hclae_ctx *ctx, const float *X, int64_t N, const float *C, int L,
                                uint8_t *codes, float *residue, double *err);
+
+int hclae_set_pruning(hclae_ctx *ctx, int on)
+{
+    if (!ctx) return HCLAE_EINVAL;
+    ctx->pruning = on ? 1 : 0;
+    return HCLAE_OK;
+}
 
 int hclae_set_contraction(hclae_ctx *ctx, int mode)
 {

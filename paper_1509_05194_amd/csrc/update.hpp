@@ -250,7 +250,8 @@ __global__ __launch_bounds__(256) void k_merge(
     int K, int D, int dnorm, float *__restrict__ Cm, float *__restrict__ hneg, int *__restrict__ nk,
     int *__restrict__ counts_out, unsigned *__restrict__ refine_count,
     double *__restrict__ run_sum, long long *__restrict__ run_cnt,
-    long long *__restrict__ tot_sum, int *__restrict__ tot_cnt, int delta, unsigned *__restrict__ moved_count)
+    long long *__restrict__ tot_sum, int *__restrict__ tot_cnt, int delta, unsigned *__restrict__ moved_count,
+    float *__restrict__ drift)
 {
     __shared__ double red[256 / kWave];
     __shared__ long long comb[kMergeGroups][kMergePairs][2];
@@ -261,11 +262,14 @@ __global__ __launch_bounds__(256) void k_merge(
     // after a pass over the moved vectors only the blocks that pass used hold partials; the list counter is
     // handed back empty (every block reads it before the last one to arrive resets it)
     if (delta) nblk = moved_blocks(*moved_count, nblk);
+    // moved_count[2], [3]: the two list counters of the pruning step that follows (k_bounds_step, k_bounds_apart)
     if (moved_count) {
         __syncthreads();
         if (threadIdx.x == 0 && atomicAdd(moved_count + 1, 1u) == gridDim.x - 1) {
             moved_count[0] = 0u;
             moved_count[1] = 0u;
+            moved_count[2] = 0u;
+            moved_count[3] = 0u;
         }
     }
     if (threadIdx.x < kWave) {
@@ -297,7 +301,7 @@ __global__ __launch_bounds__(256) void k_merge(
     const int per = (nblk + kMergeGroups - 1) / kMergeGroups;
     const int b0 = g * per, b1 = min(nblk, b0 + per);
     const int npairs = D >> 1;
-    double sq = 0.0;
+    double sq = 0.0, moved2 = 0.0;                                  // ||c||^2 over dnorm dims; ||c_new - c_old||^2
     for (int p0 = 0; p0 < npairs; p0 += kMergePairs) {
         const int pr = p0 + l;
         long long s0 = 0, s1 = 0;
@@ -337,6 +341,11 @@ __global__ __launch_bounds__(256) void k_merge(
                 }
                 c.x = (float)(u0 / denom);
                 c.y = (float)(u1 / denom);
+                if (drift) {
+                    const float2 old = *dst;
+                    const double e0 = (double)c.x - (double)old.x, e1 = (double)c.y - (double)old.y;
+                    moved2 += e0 * e0 + e1 * e1;
+                }
                 *dst = c;
             } else {
                 c = *dst;
@@ -348,6 +357,10 @@ __global__ __launch_bounds__(256) void k_merge(
         __syncthreads();
     }
     sq = block_sum(sq, red);
+    if (drift) {                                                    // how far the codeword moved, rounded up
+        moved2 = block_sum(moved2, red);
+        if (threadIdx.x == 0) drift[k] = (float)(sqrt(moved2) * 1.000001);
+    }
     if (threadIdx.x == 0) {
         hneg[k] = -(float)(0.5 * sq);
         nk[k] = s_n;

@@ -24,11 +24,12 @@ EXPORTS = (
     "hclae_online_export", "hclae_online_import",
     "hclae_covariance", "hclae_rotate", "hclae_assign_prefix", "hclae_anneal_stage_pca",
     "hclae_reorder_by_variance", "hclae_code_stats",
-    "hclae_beam_step", "hclae_encode_beam", "hclae_set_beam_width", "hclae_set_contraction",
+    "hclae_beam_step", "hclae_encode_beam", "hclae_set_beam_width", "hclae_set_contraction", "hclae_set_pruning",
 )
 
 KERNEL_CLASSES = ("heat", "cool", "assign", "refine", "accumulate", "merge", "norms", "error", "transition",
-                  "rotate", "moments", "beam_score", "beam_expand", "accumulate_moved")
+                  "rotate", "moments", "beam_score", "beam_expand", "accumulate_moved",
+                  "assign_active", "bounds")
 
 
 class KernelTimes(ctypes.Structure):
@@ -95,6 +96,7 @@ def lib():
     L.hclae_encode_beam.argtypes = [vp, vp, i64, i32, vp, i32, i32, i32, vp, vp, vp]
     L.hclae_set_beam_width.argtypes = [vp, i32]
     L.hclae_set_contraction.argtypes = [vp, i32]
+    L.hclae_set_pruning.argtypes = [vp, i32]
     L.hclae_timing_enable.argtypes = [vp, ctypes.c_uint32]
     L.hclae_timing_read.argtypes = [vp, ctypes.POINTER(KernelTimes)]
     for name in EXPORTS:
@@ -175,6 +177,10 @@ class Context:
         pC, pcodes, pres = self._shapes(N, C, codes, residue)
         self._chk(lib().hclae_encode_beam(self._h, _ptr(X, "f32", (N, self.D)), N, self.D, pC, self.M, self.K, L,
                                           pcodes, pres, _ptr(err, "f64", (N,))))
+
+    def set_pruning(self, on):
+        """Exact pruning of the Lloyd iterations of a stage (default on; same results either way)."""
+        self._chk(lib().hclae_set_pruning(self._h, 1 if on else 0))
 
     def set_contraction(self, mode):
         """0: fp32 MFMA; 1: split-bf16 MFMA (same results, see hclae_set_contraction)."""
