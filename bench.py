@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--contraction", choices=["f32", "split"], default="f32",
                     help="matrix-core arithmetic of the distance contraction: fp32 MFMA, or fp32 operands split into "
                          "two bf16 terms on the bf16 MFMA (same results; see hclae_set_contraction)")
+    ap.add_argument("--no-pruning", action="store_true",
+                    help="switch off the exact pruning of the Lloyd iterations (hclae_set_pruning 0): every assignment "
+                         "and every centroid sum then runs over all vectors; same results")
     ap.add_argument("--beam", type=int, default=0, metavar="L",
                     help="instead of the sweep benchmark: learn the dictionaries with one fresh sweep, then time the "
                          "multi-path encoder (Sec. 3.3) with L paths over the --n resident vectors")
@@ -73,6 +76,7 @@ def main():
     qres = torch.empty((Q, D), dtype=torch.float32, device=dev)
     ctx = hclae.Context(N, D, M, K)
     ctx.set_contraction(1 if args.contraction == "split" else 0)
+    ctx.set_pruning(not args.no_pruning)
 
     def step(first):
         ctx.timing_enable(["assign"])
@@ -121,7 +125,9 @@ def main():
                                "one DA sweep + greedy encode of %d held-out queries per step" % (N, M, T, Q),
                    "N": N, "D": D, "M": M, "K": K, "iters": T, "queries": Q,
                    "quant_error_after": E_final},
-        "roofline": {"bound": "mfma", "kernel": ("k_assign_resident<8> (fp32 MFMA distance contraction + argmin)"
+        "roofline": {"bound": "mfma", "kernel": ("k_assign_resident<8> (fp32 MFMA distance contraction + argmin; the "
+                                                 "launches over all N vectors: with pruning the first assignment of "
+                                                 "each stage, which also stores the distance bounds)"
                                                  if args.contraction == "f32" else
                                                  "k_assign_split<8> (split-bf16 MFMA distance contraction + argmin; "
                                                  "algorithmic 2NKD flop against the fp32 peak for comparison)"),
@@ -157,10 +163,8 @@ def main():
             kernels[cls] = e
         out["kernels"] = kernels
 
-    if args.contraction == "f32" and not args.no_breakdown:
-        # the same step with the optional split-bf16 contraction (hclae_set_contraction 1), reported beside the
-        # headline: identical results by construction (same fp64 decisions), another matrix-core arithmetic
-        ctx.set_contraction(1)
+    def timed_variant(setup, restore):
+        setup()
         step(False)
         torch.cuda.synchronize()
         ctx.timing_read()
@@ -169,12 +173,30 @@ def main():
             step(False)
         torch.cuda.synchronize()
         ts = (time.perf_counter() - ts) / args.steps
-        s_ms, s_n = ctx.timing_read()["assign"]
-        ctx.set_contraction(0)
+        v_ms, v_n = ctx.timing_read()["assign"]
+        restore()
+        return ts, v_ms / max(v_n, 1)
+
+    if not args.no_pruning and not args.no_breakdown:
+        # the same step without the exact pruning of the Lloyd iterations: every assignment over all N vectors
+        ts, a_ms1 = timed_variant(lambda: ctx.set_pruning(False), lambda: ctx.set_pruning(True))
+        tf = flops / (a_ms1 * 1e-3) / 1e12
+        out["unpruned"] = {
+            "value": N * M / ts, "unit": "vectors/s per stage", "ms_per_step": ts * 1e3,
+            "assign_avg_launch_ms": a_ms1,
+            ("assign_frac_fp32_mfma_peak" if args.contraction == "f32" else "assign_algorithmic_TFLOPs"):
+                (tf / PEAK_FP32_MFMA_TFLOPS if args.contraction == "f32" else tf),
+            "note": "hclae_set_pruning(0): all (T+1) assignments and all T centroid sums of a stage over all N vectors; "
+                    "same dictionaries, codes and residues"}
+
+    if args.contraction == "f32" and not args.no_breakdown:
+        # the same step with the optional split-bf16 contraction (hclae_set_contraction 1), reported beside the
+        # headline: identical results by construction (same fp64 decisions), another matrix-core arithmetic
+        ts, s_avg = timed_variant(lambda: ctx.set_contraction(1), lambda: ctx.set_contraction(0))
         out["split_bf16_contraction"] = {
             "value": N * M / ts, "unit": "vectors/s per stage", "ms_per_step": ts * 1e3,
-            "assign_avg_launch_ms": s_ms / max(s_n, 1),
-            "assign_algorithmic_TFLOPs": flops / (s_ms / max(s_n, 1) * 1e-3) / 1e12,
+            "assign_avg_launch_ms": s_avg,
+            "assign_algorithmic_TFLOPs": flops / (s_avg * 1e-3) / 1e12,
             "note": "fp32 operands split into two bf16 terms, three bf16 MFMAs per product, fp32 accumulation; "
                     "same codes, dictionaries and residues as the fp32 kernel"}
 

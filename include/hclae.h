@@ -181,12 +181,15 @@ int hclae_online_import(hclae_ctx *ctx, const double *run_sum, const int64_t *ru
 int hclae_set_contraction(hclae_ctx *ctx, int mode);
 
 /*
- * Exact pruning of the Lloyd iterations of hclae_anneal_stage / hclae_sweep (on by default; on = 0 switches
- * it off).  x' is fixed during a stage, so per vector an upper bound on the distance to its codeword and a
- * lower bound on the distance to all others are kept, aged by how far the codewords move in each centroid
- * update (triangle inequality), and only vectors whose bounds stop separating are assigned again.  The
- * bounds include the rounding bounds of the kernels, so the results are those of full assignments, bit for
- * bit; only the work differs.  Applies where the whole padded dictionary fits LDS.
+ * Exact shortcuts of the Lloyd iterations of hclae_anneal_stage / hclae_sweep (on by default; on = 0 makes
+ * every assignment and every centroid sum of a stage run over all N vectors).  x' is fixed during a stage, so
+ * (1) per vector an upper bound on the distance to its codeword and a lower bound on the distance to all
+ *     others are kept, aged by how far the codewords move in each centroid update (triangle inequality), and
+ *     only vectors whose bounds stop separating are assigned again (where the whole padded dictionary fits LDS);
+ * (2) the integer totals of the first centroid update are kept and later updates add only the vectors that
+ *     changed cluster.
+ * The bounds include the rounding bounds of the kernels and the sums are exact integers, so the results are
+ * those of the full passes, bit for bit; only the work differs.
  */
 int hclae_set_pruning(hclae_ctx *ctx, int on);
 

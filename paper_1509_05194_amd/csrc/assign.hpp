@@ -199,16 +199,31 @@ __device__ __forceinline__ void decide(
 {
     const int h = lane >> 5;
     float mx = -__builtin_inff(), m2 = -__builtin_inff();            // best and second best score
-#pragma unroll
-    for (int b = 0; b < KB; ++b)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            if (PRUNE) m2 = __builtin_amdgcn_fmed3f(mx, m2, acc[b][v]);   // m2 <= mx always: the median is the new second
-            mx = fmaxf(mx, acc[b][v]);
-        }
     if (PRUNE) {
+        // top two per accumulator block (independent chains), then merged
+        float bm[KB], b2[KB];
+#pragma unroll
+        for (int b = 0; b < KB; ++b) {
+            bm[b] = acc[b][0];
+            b2[b] = -__builtin_inff();
+#pragma unroll
+            for (int v = 1; v < 16; ++v) {
+                b2[b] = __builtin_amdgcn_fmed3f(bm[b], b2[b], acc[b][v]);   // b2 <= bm always: the median is the new second
+                bm[b] = fmaxf(bm[b], acc[b][v]);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < KB; ++b) {
+            m2 = fmaxf(fminf(mx, bm[b]), fmaxf(m2, b2[b]));
+            mx = fmaxf(mx, bm[b]);
+        }
         const float mxo = __shfl_xor(mx, 32, kWave), m2o = __shfl_xor(m2, 32, kWave);
         m2 = fmaxf(fminf(mx, mxo), fmaxf(m2, m2o));
+    } else {
+#pragma unroll
+        for (int b = 0; b < KB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[b][v]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
     const float x2 = xsq + __shfl_xor(xsq, 32, kWave);

@@ -444,8 +444,9 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
     for (int t = 0; t < iters; ++t) {
         if (prune && t > 0 && (rc = launch_bounds_step(ctx, m, N, codes, residue, Cm)) != HCLAE_OK) return rc;
         if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? (t == 0 ? 1 : 2) : 0)) != HCLAE_OK) return rc;
-        rc = t == 0 ? launch_update(ctx, m, N, residue, Cm, codes, nullptr, true, false, 0, iters > 1 || prune)
-                    : launch_update_moved(ctx, m, N, residue, Cm, codes);
+        rc = (t == 0 || !ctx->pruning)
+                 ? launch_update(ctx, m, N, residue, Cm, codes, nullptr, true, false, 0, ctx->pruning && (iters > 1 || prune))
+                 : launch_update_moved(ctx, m, N, residue, Cm, codes);
         if (rc != HCLAE_OK) return rc;
     }
     if (prune && (rc = launch_bounds_step(ctx, m, N, codes, residue, Cm)) != HCLAE_OK) return rc;

@@ -185,3 +185,41 @@ def test_fullsize_multipath_encoding(data, oracle):
     ok[differ] = False
     np.testing.assert_allclose(err.cpu().numpy()[sample][ok], err_o[ok], rtol=5e-6)
     ctx.close()
+
+
+@pytest.mark.parametrize("contraction", [0, 1], ids=["f32", "splitbf16"])
+def test_fullsize_pruned_sweeps_equal_unpruned(data, contraction):
+    """N = 1,000,000: a fresh sweep and an annealing sweep with the exact pruning of the Lloyd iterations
+    (distance bounds, moved-vector centroid updates) against the same sweeps with every assignment and
+    every centroid sum taken over all vectors (hclae_set_pruning 0 + single steps): identical bits."""
+    from paper_1509_05194_amd import hclae
+    X, Xg = data
+    M, T = 3, 5
+    idx = synth.init_indices(N, M, K)
+    out = []
+    for pruned in (True, False):
+        ctx = hclae.Context(N, D, M, K)
+        ctx.set_contraction(contraction)
+        C = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+        codes = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+        r = Xg.clone()
+        for sweep in range(2):
+            if pruned:
+                ctx.sweep(C, codes, r, T, init_idx=idx if sweep == 0 else None, want_err=False)
+            else:
+                ctx.set_pruning(False)
+                for m in range(M):
+                    ctx.heat(m, C, codes, r)
+                    if sweep == 0:
+                        C[m] = r[torch.from_numpy(idx[m]).cuda()]
+                    for _ in range(T):
+                        ctx.assign(m, r, C, codes)
+                        ctx.update(m, r, C, codes)
+                    ctx.assign(m, r, C, codes)
+                    ctx.cool(m, C, codes, r)
+        torch.cuda.synchronize()
+        out.append((C.clone(), codes.clone(), r.clone()))
+        ctx.close()
+    assert torch.equal(out[0][0], out[1][0]), "dictionaries differ"
+    assert torch.equal(out[0][1], out[1][1]), "codes differ"
+    assert torch.equal(out[0][2], out[1][2]), "residues differ"
