@@ -541,7 +541,7 @@ __global__ __launch_bounds__(256) void k_bounds_apart(
     top_drifts(sdrift, K, s_top, s_tk);
     const float d1 = s_top[0], drest = s_top[kVolatile];
     // uniform over the grid: worth a gather of the listed rows of x'?
-    const bool apart = K > kVolatile + 1 && d1 > 1.5f * drest && (int64_t)total * 16 > N;
+    const bool apart = K > kVolatile + 1 && d1 > 3.0f * drest && (int64_t)total * 8 > N;
     if (!apart) {
         for (unsigned i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) out[i] = in[i];
         if (blockIdx.x == 0 && threadIdx.x == 0) *out_count = total;
