@@ -57,7 +57,8 @@ typedef struct {
     double  err_before;      /* (1/N) sum ||e_x||^2 at stage entry                          */
     double  err_after;       /* same at stage exit                                          */
     int64_t codes_changed;   /* vectors whose i_m differs from its value at stage entry     */
-    int64_t refined;         /* vectors of the final assign decided by the fp64 re-check    */
+    int64_t refined;         /* vectors of the final assign decided by the fp64 re-check
+                                (with pruning: among the vectors that assign recomputed)    */
     int32_t empty_clusters;  /* codewords with no member at the last centroid update        */
     int32_t iters_run;       /* Lloyd iterations executed                                   */
 } hclae_stage_stats;
