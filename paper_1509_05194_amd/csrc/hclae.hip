@@ -372,7 +372,8 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
 
 // Centroid update from the vectors that changed cluster since the last update of this stage (x' unchanged,
 // max |x'| still published): exact, see k_merge.  Leaves hneg and the counters as launch_update does.
-int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, const uint8_t *codes)
+// pruned: the assignment that just ran recomputed only the vectors of the second list of the bound step.
+int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, const uint8_t *codes, bool pruned)
 {
     const int D = ctx->D, K = ctx->K;
     const int windows = (D + kUpdWindow - 1) / kUpdWindow;
@@ -387,7 +388,9 @@ int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float
         Timed t_(ctx, HCLAE_T_ACCUM_MOVED);
         // moved_count is zero here: the merge of the previous pass of this stage reset it
         hipLaunchKernelGGL(k_moved, dim3((unsigned)((N + kMovedSpan - 1) / kMovedSpan)), dim3(256), 0, ctx->stream,
-                           codes, N, ctx->M, m, ctx->upd_col, ctx->moved_list, ctx->moved_count);
+                           codes, N, ctx->M, m, ctx->upd_col, ctx->moved_list, ctx->moved_count,
+                           pruned ? ctx->active + ctx->N_max : (const uint32_t *)nullptr,
+                           pruned ? ctx->moved_count + 3 : (const unsigned *)nullptr);
         HIP_TRY(ctx, hipGetLastError());
         hipLaunchKernelGGL(k_accumulate_moved, dim3((unsigned)nb, (unsigned)windows), dim3(kUpdThreads), upd_lds_bytes(K),
                            ctx->stream, xp, ctx->moved_list, ctx->moved_count, D, K, ctx->refine_count + 1,
@@ -446,7 +449,7 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
         if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? (t == 0 ? 1 : 2) : 0)) != HCLAE_OK) return rc;
         rc = (t == 0 || !ctx->pruning)
                  ? launch_update(ctx, m, N, residue, Cm, codes, nullptr, true, false, 0, ctx->pruning && (iters > 1 || prune))
-                 : launch_update_moved(ctx, m, N, residue, Cm, codes);
+                 : launch_update_moved(ctx, m, N, residue, Cm, codes, prune);
         if (rc != HCLAE_OK) return rc;
     }
     if (prune && (rc = launch_bounds_step(ctx, m, N, codes, residue, Cm)) != HCLAE_OK) return rc;

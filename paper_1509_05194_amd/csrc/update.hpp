@@ -121,30 +121,37 @@ __global__ __launch_bounds__(256) void k_save_column(
 // the list with one counter add.  *count must start at zero; the order of the entries is free (the sums do
 // not depend on it).
 constexpr int kMovedSpan = 4096;
+// cand / cand_count: when non-null only these vectors are looked at (the ones the last assignment recomputed:
+// a vector its distance bounds settled cannot have changed code); blocks then stride over that list.
 __global__ __launch_bounds__(256) void k_moved(
     const uint8_t *__restrict__ codes, int64_t N, int M, int m, uint8_t *__restrict__ prev,
-    unsigned long long *__restrict__ list, unsigned *__restrict__ count)
+    unsigned long long *__restrict__ list, unsigned *__restrict__ count,
+    const uint32_t *__restrict__ cand, const unsigned *__restrict__ cand_count)
 {
     __shared__ unsigned long long found[kMovedSpan];
     __shared__ unsigned nfound, base;
-    if (threadIdx.x == 0) nfound = 0u;
-    __syncthreads();
-    const int64_t n0 = (int64_t)blockIdx.x * kMovedSpan;
-    for (int i = threadIdx.x; i < kMovedSpan; i += 256) {
-        const int64_t n = n0 + i;
-        if (n < N) {
-            const unsigned cn = codes[n * M + m], co = prev[n];
-            if (cn != co) {
-                prev[n] = (uint8_t)cn;
-                found[atomicAdd(&nfound, 1u)] =
-                    (unsigned long long)(uint32_t)n | ((unsigned long long)co << 32) | ((unsigned long long)cn << 40);
+    const int64_t total = cand ? (int64_t)*cand_count : N;
+    for (int64_t i0 = (int64_t)blockIdx.x * kMovedSpan; i0 < total; i0 += (int64_t)gridDim.x * kMovedSpan) {
+        if (threadIdx.x == 0) nfound = 0u;
+        __syncthreads();
+        for (int i = threadIdx.x; i < kMovedSpan; i += 256) {
+            const int64_t j = i0 + i;
+            if (j < total) {
+                const int64_t n = cand ? (int64_t)cand[j] : j;
+                const unsigned cn = codes[n * M + m], co = prev[n];
+                if (cn != co) {
+                    prev[n] = (uint8_t)cn;
+                    found[atomicAdd(&nfound, 1u)] =
+                        (unsigned long long)(uint32_t)n | ((unsigned long long)co << 32) | ((unsigned long long)cn << 40);
+                }
             }
         }
+        __syncthreads();
+        if (threadIdx.x == 0 && nfound) base = atomicAdd(count, nfound);
+        __syncthreads();
+        for (unsigned i = threadIdx.x; i < nfound; i += 256) list[base + i] = found[i];
+        __syncthreads();
     }
-    __syncthreads();
-    if (threadIdx.x == 0 && nfound) base = atomicAdd(count, nfound);
-    __syncthreads();
-    for (unsigned i = threadIdx.x; i < nfound; i += 256) list[base + i] = found[i];
 }
 
 // Blocks (of the x dimension) that the pass over `total` moved vectors uses: enough rows per block to pay
