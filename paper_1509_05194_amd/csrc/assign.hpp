@@ -463,6 +463,22 @@ __device__ __forceinline__ void top_drifts(const float *sdrift, int K, float *to
     __syncthreads();
 }
 
+// The same, once per centroid update, into global memory: top5[0..4] the drifts, top5[8..12] their indices
+// (as floats' bit patterns of ints), for the bound kernels to read.
+__global__ __launch_bounds__(256) void k_drift_top(const float *__restrict__ drift, int K, float *__restrict__ top5)
+{
+    __shared__ float sdrift[256];
+    __shared__ float s_top[kVolatile + 1];
+    __shared__ int s_tk[kVolatile + 1];
+    sdrift[threadIdx.x] = (int)threadIdx.x < K ? drift[threadIdx.x] : 0.f;
+    __syncthreads();
+    top_drifts(sdrift, K, s_top, s_tk);
+    if (threadIdx.x <= kVolatile) {
+        top5[threadIdx.x] = s_top[threadIdx.x];
+        top5[8 + threadIdx.x] = __int_as_float(s_tk[threadIdx.x]);
+    }
+}
+
 // Between two assignments of a stage: age the bounds by the drift of the dictionary (drift[k] >= the
 // distance codeword k moved in the centroid update, 0 for a kept one) and list the vectors that have to
 // be recomputed.  A block takes kBoundSpan consecutive vectors, stages its entries in LDS and claims its
@@ -470,19 +486,17 @@ __device__ __forceinline__ void top_drifts(const float *sdrift, int K, float *to
 constexpr int kBoundSpan = 1024;
 __global__ __launch_bounds__(256) void k_bounds_step(
     const uint8_t *__restrict__ codes, int64_t N, int M, int m, const float *__restrict__ drift, int K,
-    float *__restrict__ bu, float *__restrict__ bl, uint32_t *__restrict__ list, unsigned *__restrict__ count)
+    float *__restrict__ bu, float *__restrict__ bl, uint32_t *__restrict__ list, unsigned *__restrict__ count,
+    const float *__restrict__ top5)
 {
     __shared__ uint32_t found[kBoundSpan];
     __shared__ float sdrift[256];
     __shared__ unsigned nfound, base;
-    __shared__ float s_top[kVolatile + 1];
-    __shared__ int s_tk[kVolatile + 1];
     sdrift[threadIdx.x] = (int)threadIdx.x < K ? drift[threadIdx.x] : 0.f;
     if (threadIdx.x == 0) nfound = 0u;
     __syncthreads();
-    top_drifts(sdrift, K, s_top, s_tk);
-    const float d1 = s_top[0], d2 = s_top[1];
-    const int k1 = s_tk[0];
+    const float d1 = top5[0], d2 = top5[1];
+    const int k1 = __float_as_int(top5[8]);
     const int64_t n0 = (int64_t)blockIdx.x * kBoundSpan;
     constexpr int U = kBoundSpan / 256;
     int c[U];
@@ -526,20 +540,20 @@ __global__ __launch_bounds__(256) void k_bounds_apart(
     const uint8_t *__restrict__ codes, int64_t N, int M, int m, const float *__restrict__ drift, int K,
     float *__restrict__ bu, float *__restrict__ bl, const uint32_t *__restrict__ in, const unsigned *__restrict__ in_count,
     uint32_t *__restrict__ out, unsigned *__restrict__ out_count,
-    const float *__restrict__ xp, int D, const float *__restrict__ Cm)
+    const float *__restrict__ xp, int D, const float *__restrict__ Cm, const float *__restrict__ top5)
 {
     extern __shared__ float4 smem4[];                                // kVolatile rows of D floats
     float *vrow = reinterpret_cast<float *>(smem4);
     __shared__ uint32_t found[kBoundSpan];
     __shared__ float sdrift[256];
     __shared__ unsigned nfound, base;
-    __shared__ float s_top[kVolatile + 1], s_vnorm[kVolatile];
+    __shared__ float s_vnorm[kVolatile];
     __shared__ int s_tk[kVolatile + 1];
     const unsigned total = *in_count;
     sdrift[threadIdx.x] = (int)threadIdx.x < K ? drift[threadIdx.x] : 0.f;
+    if (threadIdx.x <= kVolatile) s_tk[threadIdx.x] = __float_as_int(top5[8 + threadIdx.x]);
     __syncthreads();
-    top_drifts(sdrift, K, s_top, s_tk);
-    const float d1 = s_top[0], drest = s_top[kVolatile];
+    const float d1 = top5[0], drest = top5[kVolatile];
     // uniform over the grid: worth a gather of the listed rows of x'?
     const bool apart = K > kVolatile + 1 && d1 > 3.0f * drest && (int64_t)total * 8 > N;
     if (!apart) {

@@ -309,12 +309,15 @@ int launch_assign(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float
 int launch_bounds_step(hclae_ctx *ctx, int m, int64_t N, const uint8_t *codes, const float *xp, const float *Cm)
 {
     Timed t_(ctx, HCLAE_T_BOUNDS);
+    float *top5 = ctx->drift + HCLAE_MAX_K;
+    hipLaunchKernelGGL(k_drift_top, dim3(1), dim3(256), 0, ctx->stream, ctx->drift, ctx->K, top5);
     hipLaunchKernelGGL(k_bounds_step, dim3((unsigned)((N + kBoundSpan - 1) / kBoundSpan)), dim3(256), 0, ctx->stream,
-                       codes, N, ctx->M, m, ctx->drift, ctx->K, ctx->bnd_u, ctx->bnd_l, ctx->active, ctx->moved_count + 2);
+                       codes, N, ctx->M, m, ctx->drift, ctx->K, ctx->bnd_u, ctx->bnd_l, ctx->active, ctx->moved_count + 2,
+                       top5);
     HIP_TRY(ctx, hipGetLastError());
     hipLaunchKernelGGL(k_bounds_apart, dim3(ctx->cus * 4), dim3(256), (size_t)kVolatile * ctx->D * sizeof(float), ctx->stream,
                        codes, N, ctx->M, m, ctx->drift, ctx->K, ctx->bnd_u, ctx->bnd_l, ctx->active, ctx->moved_count + 2,
-                       ctx->active + ctx->N_max, ctx->moved_count + 3, xp, ctx->D, Cm);
+                       ctx->active + ctx->N_max, ctx->moved_count + 3, xp, ctx->D, Cm, top5);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
@@ -575,7 +578,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
         {(void **)&ctx->moved_count, 256},
         {(void **)&ctx->bnd_u, sizeof(float) * (size_t)N_max},
         {(void **)&ctx->bnd_l, sizeof(float) * (size_t)N_max},
-        {(void **)&ctx->drift, sizeof(float) * HCLAE_MAX_K},
+        {(void **)&ctx->drift, sizeof(float) * (HCLAE_MAX_K + 16)},   // [K] drifts, then k_drift_top's 16 words
         {(void **)&ctx->active, sizeof(uint32_t) * 2 * (size_t)N_max},
         {(void **)&ctx->seed_idx, sizeof(int64_t) * K},
         {(void **)&ctx->part_a, sizeof(double) * ctx->nparts},
