@@ -186,7 +186,7 @@ int hclae_set_contraction(hclae_ctx *ctx, int mode);
  * every assignment and every centroid sum of a stage run over all N vectors).  x' is fixed during a stage, so
  * (1) per vector an upper bound on the distance to its codeword and a lower bound on the distance to all
  *     others are kept, aged by how far the codewords move in each centroid update (triangle inequality), and
- *     only vectors whose bounds stop separating are assigned again (where the whole padded dictionary fits LDS);
+ *     only vectors whose bounds stop separating are assigned again;
  * (2) the integer totals of the first centroid update are kept and later updates add only the vectors that
  *     changed cluster.
  * The bounds include the rounding bounds of the kernels and the sums are exact integers, so the results are

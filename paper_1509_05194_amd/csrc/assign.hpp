@@ -380,11 +380,12 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
 // Assignment for dimensions whose codebook does not fit LDS: the block walks the D axis in
 // 64-dim chunks, restaging that slice of the codebook for every tile of 8 x 32 vectors; the
 // accumulators persist across chunks.
-template <int KB>
+template <int KB, int PRUNE = 0>
 __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
     const float *__restrict__ xp, const float *__restrict__ Cm, const float *__restrict__ hneg,
     int64_t N, int D, int ld, int K, int M, int m, int NC, float eps,
-    uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count)
+    uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count,
+    PruneArgs pa)
 {
     extern __shared__ float4 smem4[];
     constexpr int S = 8;                                            // one chunk resident
@@ -401,12 +402,16 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
     for (int k = 0; k < K; ++k) hmax = fmaxf(hmax, -lds_h[k]);
     const float cmax = sqrtf(2.f * hmax) * 1.000001f;
 
-    const int64_t nbt = (N + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);   // block tiles
+    // rows of this launch: all N vectors, or the listed ones (PRUNE 2; see PruneArgs)
+    const int64_t rows = PRUNE == 2 ? (int64_t)*pa.active_count : N;
+    const int64_t nbt = (rows + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);   // block tiles
     float amax = 0.f;
     for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
-        const int64_t n_raw = (bt * kAssignWaves + wave) * kTileVec + r;
-        const int64_t n = n_raw < N ? n_raw : N - 1;
-        const float *xrow = xp + n * ld;
+        const int64_t i = (bt * kAssignWaves + wave) * kTileVec + r;
+        const int64_t ic = i < rows ? i : rows - 1;                 // tail columns re-read the last row
+        const int64_t nrow = PRUNE == 2 ? (int64_t)pa.active[ic] : ic;
+        const int64_t n_raw = i < rows ? nrow : N;                  // N = "none"
+        const float *xrow = xp + nrow * ld;
         floatx16 acc[KB];
         float4 x[8];
         float xsq = 0.f;
@@ -427,7 +432,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
             __syncthreads();
             mfma_chunk<KB>(acc, x, lds_c, 0, S, lane, xsq, amax);
         }
-        decide<KB>(acc, xsq, eps, hmax, cmax, lane, n_raw, N, M, m, codes, list, refine_count);
+        decide<KB, PRUNE>(acc, xsq, eps, hmax, cmax, lane, n_raw, N, M, m, codes, list, refine_count, pa);
     }
     publish_absmax(amax, refine_count + 1);
 }

@@ -208,7 +208,7 @@ int launch_norms(hclae_ctx *ctx, const float *Cm, int dact = 0, int ld = 0, bool
 }
 
 // prune: 0 plain; 1 all vectors and store the stage's bounds; 2 only the vectors k_bounds_step listed
-// (resident shapes over all D coordinates only; the caller checks).
+// (over all D coordinates only; the caller checks).
 template <int KB>
 int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float *Cm, uint8_t *codes, int dact, int ld,
                      int prune)
@@ -222,7 +222,6 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
     // twice the worst-case rounding error of a score: (dpad + 1) roundings of relative size 2^-23
     // on partial sums bounded by h + ||x'|| ||c||, plus the rounding of h itself
     const float eps = 2.02f * (float)(dpad + 2) * 1.1920929e-7f;
-    if (!resident) prune = 0;
     {
     Timed t_(ctx, prune == 2 ? HCLAE_T_ASSIGN_ACTIVE : HCLAE_T_ASSIGN);
     if (resident && ctx->contraction == 1) {
@@ -272,13 +271,18 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
         int64_t blocks = nbt < 2 * ctx->cus ? nbt : 2 * ctx->cus;
         static bool attr_set = false;
         if (!attr_set) {
-            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_chunked<KB>),
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_chunked<KB, 0>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_chunked<KB, 1>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_chunked<KB, 2>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             attr_set = true;
         }
-        hipLaunchKernelGGL((k_assign_chunked<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
+        auto kern = prune == 1 ? &k_assign_chunked<KB, 1> : prune == 2 ? &k_assign_chunked<KB, 2> : &k_assign_chunked<KB, 0>;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
                            xp, Cm, ctx->hneg, N, dact, ld, ctx->K, ctx->M, m, NC, eps,
-                           codes, ctx->refine_list, ctx->refine_count);
+                           codes, ctx->refine_list, ctx->refine_count, pa);
     }
     }
     HIP_TRY(ctx, hipGetLastError());
@@ -315,6 +319,12 @@ int launch_bounds_step(hclae_ctx *ctx, int m, int64_t N, const uint8_t *codes, c
                        codes, N, ctx->M, m, ctx->drift, ctx->K, ctx->bnd_u, ctx->bnd_l, ctx->active, ctx->moved_count + 2,
                        top5);
     HIP_TRY(ctx, hipGetLastError());
+    static bool attr_set = false;
+    if (!attr_set) {
+        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bounds_apart),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget - 16 * 1024));
+        attr_set = true;
+    }
     hipLaunchKernelGGL(k_bounds_apart, dim3(ctx->cus * 4), dim3(256), (size_t)kVolatile * ctx->D * sizeof(float), ctx->stream,
                        codes, N, ctx->M, m, ctx->drift, ctx->K, ctx->bnd_u, ctx->bnd_l, ctx->active, ctx->moved_count + 2,
                        ctx->active + ctx->N_max, ctx->moved_count + 3, xp, ctx->D, Cm, top5);
@@ -446,7 +456,7 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
     // With pruning the first assignment stores distance bounds for every vector; after each centroid update
     // (which also reports how far every codeword moved) only the vectors whose bounds no longer separate
     // their codeword from the others are assigned again.  The first update must then keep its totals.
-    const bool prune = ctx->pruning && ctx->resident && iters > 0;
+    const bool prune = ctx->pruning && iters > 0;
     for (int t = 0; t < iters; ++t) {
         if (prune && t > 0 && (rc = launch_bounds_step(ctx, m, N, codes, residue, Cm)) != HCLAE_OK) return rc;
         if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? (t == 0 ? 1 : 2) : 0)) != HCLAE_OK) return rc;

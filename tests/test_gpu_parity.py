@@ -429,12 +429,15 @@ def test_limits_of_the_shape_check(shape, oracle):
     ctx.close()
 
 
-def test_stage_equals_its_single_steps_bitwise():
-    """hclae_anneal_stage updates the centroids from the moved vectors alone after its first Lloyd
-    iteration (exact integer totals); the single-step calls sum all vectors every time.  Both must give
-    the same bits: dictionaries, codes, residues."""
-    N, D, M, K, T = 40000 + 9, 128, 3, 256, 6
-    X = synth.sift_like(N, D=D)
+@pytest.mark.parametrize("gen,N,D,M,K,T", [("sift", 40000 + 9, 128, 3, 256, 6), ("gist", 6000 + 5, 960, 2, 256, 5),
+                                           ("tiny", 10000 + 3, 16, 4, 16, 6), ("sift", 8000 + 1, 132, 2, 40, 4)])
+def test_stage_equals_its_single_steps_bitwise(gen, N, D, M, K, T):
+    """hclae_anneal_stage prunes its Lloyd iterations (distance bounds; centroid sums advanced by the moved
+    vectors, exact integer totals); the single-step calls run every assignment and every sum over all
+    vectors.  Both must give the same bits: dictionaries, codes, residues.  Shapes: LDS-resident and
+    D-chunked dictionaries, padded K and D."""
+    X = {"sift": lambda: synth.sift_like(N, D=D), "gist": lambda: synth.gist_like(N, D=D),
+         "tiny": lambda: synth.tiny_gmm(N=N, D=D)}[gen]()
     idx = synth.init_indices(N, M, K)
     out = []
     for one_call in (True, False):
