@@ -437,133 +437,72 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
     publish_absmax(amax, refine_count + 1);
 }
 
-// The kVolatile + 1 largest entries of drift[0..K) (K <= 256), descending, with their indices; computed by
-// the first wave of a 256-thread block into LDS (top[], tk[]; unused slots 0 / -1).  Ends with a barrier.
-constexpr int kVolatile = 4;
-__device__ __forceinline__ void top_drifts(const float *sdrift, int K, float *top, int *tk)
-{
-    if (threadIdx.x < kWave) {
-        const int lane = threadIdx.x;
-        float v[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = (lane + kWave * j < K) ? sdrift[lane + kWave * j] : -1.f;
-        for (int i = 0; i <= kVolatile; ++i) {
-            float best = v[0];
-            int at = lane;
-#pragma unroll
-            for (int j = 1; j < 4; ++j)
-                if (v[j] > best) { best = v[j]; at = lane + kWave * j; }
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-                const float ob = __shfl_xor(best, o, kWave);
-                const int oa = __shfl_xor(at, o, kWave);
-                if (ob > best || (ob == best && oa < at)) { best = ob; at = oa; }
-            }
-            if (lane == 0) { top[i] = best > 0.f ? best : 0.f; tk[i] = best > 0.f ? at : -1; }
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (at == lane + kWave * j) v[j] = -1.f;             // struck out
-        }
-    }
-    __syncthreads();
-}
-
-// The same, once per centroid update, into global memory: top5[0..4] the drifts, top5[8..12] their indices
-// (as floats' bit patterns of ints), for the bound kernels to read.
-__global__ __launch_bounds__(256) void k_drift_top(const float *__restrict__ drift, int K, float *__restrict__ top5)
-{
-    __shared__ float sdrift[256];
-    __shared__ float s_top[kVolatile + 1];
-    __shared__ int s_tk[kVolatile + 1];
-    sdrift[threadIdx.x] = (int)threadIdx.x < K ? drift[threadIdx.x] : 0.f;
-    __syncthreads();
-    top_drifts(sdrift, K, s_top, s_tk);
-    if (threadIdx.x <= kVolatile) {
-        top5[threadIdx.x] = s_top[threadIdx.x];
-        top5[8 + threadIdx.x] = __int_as_float(s_tk[threadIdx.x]);
-    }
-}
-
 // Between two assignments of a stage: age the bounds by the drift of the dictionary (drift[k] >= the
-// distance codeword k moved in the centroid update, 0 for a kept one) and list the vectors that have to
-// be recomputed.  A block takes kBoundSpan consecutive vectors, stages its entries in LDS and claims its
-// stretch of the list with one counter add (*count must be zero on entry; order is free).
+// distance codeword k moved in the centroid update, 0 for a kept one) and list the vectors that have to be
+// recomputed.  A block takes kBoundSpan consecutive vectors, stages its entries in LDS and claims its stretch
+// of the list with one counter add (*count must be zero on entry; order is free).
+//
+// One codeword that moves far (a cluster of few members) costs every vector its lower bound.  When the
+// largest drift stands out from the (kVolatile+1)-th and the block has listed many of its vectors, it looks
+// at them again with the kVolatile codewords that moved most treated apart: the lower bound ages by the largest drift of the REST, and the distance to each of those
+// few is computed afresh from x' (expanded form in fp32 with its rounding bound) and joins the lower bound.
+// Vectors that this settles get their aged bounds and leave the list.  Eight lanes share a vector.
+// Dynamic LDS: kVolatile rows of D floats.
 constexpr int kBoundSpan = 1024;
 __global__ __launch_bounds__(256) void k_bounds_step(
     const uint8_t *__restrict__ codes, int64_t N, int M, int m, const float *__restrict__ drift, int K,
     float *__restrict__ bu, float *__restrict__ bl, uint32_t *__restrict__ list, unsigned *__restrict__ count,
-    const float *__restrict__ top5)
+    const float *__restrict__ xp, int D, const float *__restrict__ Cm)
 {
-    __shared__ uint32_t found[kBoundSpan];
+    extern __shared__ float4 smem4[];
+    float *vrow = reinterpret_cast<float *>(smem4);
+    __shared__ uint32_t found[kBoundSpan], kept[kBoundSpan];
     __shared__ float sdrift[256];
-    __shared__ unsigned nfound, base;
+    __shared__ unsigned nfound, nkept, base;
+    __shared__ float s_vnorm[kVolatile], s_top[kVolatile + 1];
+    __shared__ int s_tk[kVolatile + 1];
     sdrift[threadIdx.x] = (int)threadIdx.x < K ? drift[threadIdx.x] : 0.f;
-    if (threadIdx.x == 0) nfound = 0u;
-    __syncthreads();
-    const float d1 = top5[0], d2 = top5[1];
-    const int k1 = __float_as_int(top5[8]);
+    if (threadIdx.x == 0) { nfound = 0u; nkept = 0u; }
     const int64_t n0 = (int64_t)blockIdx.x * kBoundSpan;
     constexpr int U = kBoundSpan / 256;
     int c[U];
     float u[U], l[U];
 #pragma unroll
-    for (int j = 0; j < U; ++j) {                                   // all loads first
+    for (int j = 0; j < U; ++j) {                                   // all loads first: in flight during the ranking
         const int64_t n = n0 + j * 256 + threadIdx.x;
         const int64_t nn = n < N ? n : N - 1;
         c[j] = codes[nn * M + m];
         u[j] = bu[nn];
         l[j] = bl[nn];
     }
+    __syncthreads();
+    top_drifts(sdrift, K, s_top, s_tk);
+    const float d1 = s_top[0], d2 = s_top[1], drest = s_top[kVolatile];
+    const int k1 = s_tk[0];
+    {
 #pragma unroll
-    for (int j = 0; j < U; ++j) {
-        const int64_t n = n0 + j * 256 + threadIdx.x;
-        if (n < N) {
-            const float un = (u[j] + sdrift[c[j]]) * 1.000001f;      // rounded up
-            const float ln = (l[j] - ((c[j] == k1) ? d2 : d1)) * 0.999999f;   // rounded down while positive
-            if (un < ln) {
-                bu[n] = un;
-                bl[n] = ln;
-            } else {
-                found[atomicAdd(&nfound, 1u)] = (uint32_t)n;          // its bounds stay as they were
+        for (int j = 0; j < U; ++j) {
+            const int64_t n = n0 + j * 256 + threadIdx.x;
+            if (n < N) {
+                const float un = (u[j] + sdrift[c[j]]) * 1.000001f;  // rounded up
+                const float ln = (l[j] - ((c[j] == k1) ? d2 : d1)) * 0.999999f;   // rounded down while positive
+                if (un < ln) {
+                    bu[n] = un;
+                    bl[n] = ln;
+                } else {
+                    found[atomicAdd(&nfound, 1u)] = (uint32_t)n;      // its bounds stay as they were
+                }
             }
         }
     }
     __syncthreads();
-    if (threadIdx.x == 0 && nfound) base = atomicAdd(count, nfound);
-    __syncthreads();
-    for (unsigned i = threadIdx.x; i < nfound; i += 256) list[base + i] = found[i];
-}
-
-// Second look at the vectors k_bounds_step listed (in[0..*in_count) -> out[0..*out_count), *out_count zero on
-// entry).  One codeword that moves far (a cluster of few members) costs every vector its lower bound.  When
-// the largest drift stands out from the (kVolatile+1)-th and the list is long, the kVolatile codewords that
-// moved most are treated apart: the lower bound ages by the largest drift of the REST, and the distance to
-// each of those few is computed afresh from x' (expanded form in fp32 with its rounding bound) and joins
-// the lower bound.  Vectors that this settles get their aged bounds and leave the list.  Otherwise the list
-// is passed on as it is.  Eight lanes share a vector.
-__global__ __launch_bounds__(256) void k_bounds_apart(
-    const uint8_t *__restrict__ codes, int64_t N, int M, int m, const float *__restrict__ drift, int K,
-    float *__restrict__ bu, float *__restrict__ bl, const uint32_t *__restrict__ in, const unsigned *__restrict__ in_count,
-    uint32_t *__restrict__ out, unsigned *__restrict__ out_count,
-    const float *__restrict__ xp, int D, const float *__restrict__ Cm, const float *__restrict__ top5)
-{
-    extern __shared__ float4 smem4[];                                // kVolatile rows of D floats
-    float *vrow = reinterpret_cast<float *>(smem4);
-    __shared__ uint32_t found[kBoundSpan];
-    __shared__ float sdrift[256];
-    __shared__ unsigned nfound, base;
-    __shared__ float s_vnorm[kVolatile];
-    __shared__ int s_tk[kVolatile + 1];
-    const unsigned total = *in_count;
-    sdrift[threadIdx.x] = (int)threadIdx.x < K ? drift[threadIdx.x] : 0.f;
-    if (threadIdx.x <= kVolatile) s_tk[threadIdx.x] = __float_as_int(top5[8 + threadIdx.x]);
-    __syncthreads();
-    const float d1 = top5[0], drest = top5[kVolatile];
-    // uniform over the grid: worth a gather of the listed rows of x'?
-    const bool apart = K > kVolatile + 1 && d1 > 3.0f * drest && (int64_t)total * 8 > N;
+    const unsigned nf = nfound;
+    // worth a gather of the listed rows of x'?
+    const bool apart = K > kVolatile + 1 && d1 > 3.0f * drest && nf * 8u > (unsigned)kBoundSpan;
     if (!apart) {
-        for (unsigned i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) out[i] = in[i];
-        if (blockIdx.x == 0 && threadIdx.x == 0) *out_count = total;
+        if (threadIdx.x == 0 && nf) base = atomicAdd(count, nf);
+        __syncthreads();
+        for (unsigned i = threadIdx.x; i < nf; i += 256) list[base + i] = found[i];
         return;
     }
     for (int e = threadIdx.x; e < kVolatile * D; e += 256) {
@@ -571,67 +510,68 @@ __global__ __launch_bounds__(256) void k_bounds_apart(
         vrow[e] = s_tk[j] >= 0 ? Cm[(size_t)s_tk[j] * D + (e - j * D)] : 0.f;
     }
     __syncthreads();
-    if (threadIdx.x < kVolatile) {
-        float q = 0.f;
-        for (int d = 0; d < D; ++d) q = fmaf(vrow[threadIdx.x * D + d], vrow[threadIdx.x * D + d], q);
-        s_vnorm[threadIdx.x] = q;
+    {
+        const int w = threadIdx.x >> 6;                             // 256 threads = kVolatile waves, one row each
+        double q = 0.0;
+        for (int d = lane_id(); d < D; d += kWave) q += (double)vrow[w * D + d] * (double)vrow[w * D + d];
+        q = wave_sum(q);
+        if (lane_id() == 0) s_vnorm[w] = (float)q;
     }
+    __syncthreads();
     const int sub = threadIdx.x & 7;
     const int d4n = D >> 2;
-    for (unsigned e0 = blockIdx.x * kBoundSpan; e0 < total; e0 += gridDim.x * kBoundSpan) {
-        if (threadIdx.x == 0) nfound = 0u;
-        __syncthreads();
-        for (int i0 = 0; i0 < kBoundSpan; i0 += 32) {
-            const unsigned e = e0 + i0 + (threadIdx.x >> 3);
-            const bool ok = e < total;
-            const int64_t n = in[ok ? e : total - 1];
-            const float4 *row = reinterpret_cast<const float4 *>(xp + n * D);
-            float x2 = 0.f, dot[kVolatile];
+    // fp32 rounding of ||x'||^2 - 2 x'.c + ||c||^2 (D/8 chained fmas per lane, three shuffle adds, the final
+    // sums) as a fraction of ||x'||^2 + 2|x'.c| + ||c||^2
+    const float slack = (float)(D / 8 + 8) * 1.2e-7f;
+    for (unsigned i0 = 0; i0 < nf; i0 += 32) {
+        const unsigned e = i0 + (threadIdx.x >> 3);
+        const bool ok = e < nf;
+        const int64_t n = found[ok ? e : nf - 1];
+        const float4 *row = reinterpret_cast<const float4 *>(xp + n * D);
+        float x2 = 0.f, dot[kVolatile];
 #pragma unroll
-            for (int j = 0; j < kVolatile; ++j) dot[j] = 0.f;
+        for (int j = 0; j < kVolatile; ++j) dot[j] = 0.f;
 #pragma unroll 4
-            for (int q = sub; q < d4n; q += 8) {
-                const float4 x = row[q];
-                x2 = fmaf(x.x, x.x, fmaf(x.y, x.y, fmaf(x.z, x.z, fmaf(x.w, x.w, x2))));
+        for (int q = sub; q < d4n; q += 8) {
+            const float4 x = row[q];
+            x2 = fmaf(x.x, x.x, fmaf(x.y, x.y, fmaf(x.z, x.z, fmaf(x.w, x.w, x2))));
 #pragma unroll
-                for (int j = 0; j < kVolatile; ++j) {
-                    const float4 c = *reinterpret_cast<const float4 *>(vrow + j * D + 4 * q);
-                    dot[j] = fmaf(x.x, c.x, fmaf(x.y, c.y, fmaf(x.z, c.z, fmaf(x.w, c.w, dot[j]))));
-                }
-            }
-#pragma unroll
-            for (int o = 1; o < 8; o <<= 1) {
-                x2 += __shfl_xor(x2, o, kWave);
-#pragma unroll
-                for (int j = 0; j < kVolatile; ++j) dot[j] += __shfl_xor(dot[j], o, kWave);
-            }
-            if (ok && sub == 0) {
-                const int c = codes[n * M + m];
-                const float u = (bu[n] + sdrift[c]) * 1.000001f;
-                float l = (bl[n] - drest) * 0.999999f;               // the rest moved by at most drest
-#pragma unroll
-                for (int j = 0; j < kVolatile; ++j) {
-                    if (s_tk[j] >= 0 && s_tk[j] != c) {
-                        // ||x' - c_j||^2 in the expanded form; 2e-5 of the magnitudes bounds its fp32 rounding
-                        const float mag = x2 + 2.f * fabsf(dot[j]) + s_vnorm[j];
-                        const float dj2 = (x2 - 2.f * dot[j] + s_vnorm[j]) - 2e-5f * mag;
-                        l = fminf(l, sqrtf(fmaxf(dj2, 0.f)) * 0.999999f);
-                    }
-                }
-                if (u < l) {
-                    bu[n] = u;
-                    bl[n] = l;
-                } else {
-                    found[atomicAdd(&nfound, 1u)] = (uint32_t)n;
-                }
+            for (int j = 0; j < kVolatile; ++j) {
+                const float4 c = *reinterpret_cast<const float4 *>(vrow + j * D + 4 * q);
+                dot[j] = fmaf(x.x, c.x, fmaf(x.y, c.y, fmaf(x.z, c.z, fmaf(x.w, c.w, dot[j]))));
             }
         }
-        __syncthreads();
-        if (threadIdx.x == 0 && nfound) base = atomicAdd(out_count, nfound);
-        __syncthreads();
-        for (unsigned i = threadIdx.x; i < nfound; i += 256) out[base + i] = found[i];
-        __syncthreads();
+#pragma unroll
+        for (int o = 1; o < 8; o <<= 1) {
+            x2 += __shfl_xor(x2, o, kWave);
+#pragma unroll
+            for (int j = 0; j < kVolatile; ++j) dot[j] += __shfl_xor(dot[j], o, kWave);
+        }
+        if (ok && sub == 0) {
+            const int c = codes[n * M + m];
+            const float u = (bu[n] + sdrift[c]) * 1.000001f;
+            float l = (bl[n] - drest) * 0.999999f;                   // the rest moved by at most drest
+#pragma unroll
+            for (int j = 0; j < kVolatile; ++j) {
+                if (s_tk[j] >= 0 && s_tk[j] != c) {
+                    const float mag = x2 + 2.f * fabsf(dot[j]) + s_vnorm[j];
+                    const float dj2 = (x2 - 2.f * dot[j] + s_vnorm[j]) - slack * mag;
+                    l = fminf(l, sqrtf(fmaxf(dj2, 0.f)) * 0.999999f);
+                }
+            }
+            if (u < l) {
+                bu[n] = u;
+                bl[n] = l;
+            } else {
+                kept[atomicAdd(&nkept, 1u)] = (uint32_t)n;
+            }
+        }
     }
+    __syncthreads();
+    const unsigned nk = nkept;
+    if (threadIdx.x == 0 && nk) base = atomicAdd(count, nk);
+    __syncthreads();
+    for (unsigned i = threadIdx.x; i < nk; i += 256) list[base + i] = kept[i];
 }
 
 // fp64 re-check of the vectors whose fp32 scores were too close to call: direct-form squared

@@ -44,4 +44,35 @@ __device__ __forceinline__ double block_sum(double v, double *scratch)
     return t;
 }
 
+// The kVolatile + 1 largest entries of drift[0..K) (K <= 256), descending, with their indices; computed by
+// the first wave of a 256-thread block into LDS (top[], tk[]; unused slots 0 / -1).  Ends with a barrier.
+constexpr int kVolatile = 4;
+__device__ __forceinline__ void top_drifts(const float *sdrift, int K, float *top, int *tk)
+{
+    if (threadIdx.x < kWave) {
+        const int lane = threadIdx.x;
+        float v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (lane + kWave * j < K) ? sdrift[lane + kWave * j] : -1.f;
+        for (int i = 0; i <= kVolatile; ++i) {
+            float best = v[0];
+            int at = lane;
+#pragma unroll
+            for (int j = 1; j < 4; ++j)
+                if (v[j] > best) { best = v[j]; at = lane + kWave * j; }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const float ob = __shfl_xor(best, o, kWave);
+                const int oa = __shfl_xor(at, o, kWave);
+                if (ob > best || (ob == best && oa < at)) { best = ob; at = oa; }
+            }
+            if (lane == 0) { top[i] = best > 0.f ? best : 0.f; tk[i] = best > 0.f ? at : -1; }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (at == lane + kWave * j) v[j] = -1.f;             // struck out
+        }
+    }
+    __syncthreads();
+}
+
 }  // namespace hclae

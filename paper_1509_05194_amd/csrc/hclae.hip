@@ -60,7 +60,7 @@ struct hclae_ctx {
     int pruning;             // 0 off, 1 on (default)
     float *bnd_u, *bnd_l;    // [N_max]
     float *drift;            // [K]
-    uint32_t *active;        // [2][N_max]: list of k_bounds_step, list of k_bounds_apart (the one the assign reads)
+    uint32_t *active;        // [N_max]: the vectors k_bounds_step lists for the next assignment
     int64_t *seed_idx;       // [K]
     double *part_a, *part_b; // [nparts]
     long long *part_chg;     // [nparts]
@@ -215,7 +215,7 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
 {
     PruneArgs pa;
     pa.bu = ctx->bnd_u; pa.bl = ctx->bnd_l;
-    pa.active = ctx->active + ctx->N_max; pa.active_count = ctx->moved_count + 3;
+    pa.active = ctx->active; pa.active_count = ctx->moved_count + 3;
     const int NC = (dact + kChunkD - 1) / kChunkD;
     const int dpad = kChunkD * NC;
     const bool resident = (size_t)32 * KB * dpad * sizeof(float) + 4096 <= (size_t)kLdsBudget;
@@ -309,25 +309,20 @@ int launch_assign(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float
 }
 
 // Ages the bounds of the stage by the drift of the last centroid update and lists the vectors to recompute.
-// The two list counters (moved_count[2], [3]) are zero here: the merge that reported the drift reset them.
+// The list counter (moved_count[3]) is zero here: the merge that reported the drift reset it.
 int launch_bounds_step(hclae_ctx *ctx, int m, int64_t N, const uint8_t *codes, const float *xp, const float *Cm)
 {
     Timed t_(ctx, HCLAE_T_BOUNDS);
-    float *top5 = ctx->drift + HCLAE_MAX_K;
-    hipLaunchKernelGGL(k_drift_top, dim3(1), dim3(256), 0, ctx->stream, ctx->drift, ctx->K, top5);
-    hipLaunchKernelGGL(k_bounds_step, dim3((unsigned)((N + kBoundSpan - 1) / kBoundSpan)), dim3(256), 0, ctx->stream,
-                       codes, N, ctx->M, m, ctx->drift, ctx->K, ctx->bnd_u, ctx->bnd_l, ctx->active, ctx->moved_count + 2,
-                       top5);
-    HIP_TRY(ctx, hipGetLastError());
     static bool attr_set = false;
     if (!attr_set) {
-        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bounds_apart),
+        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bounds_step),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget - 16 * 1024));
         attr_set = true;
     }
-    hipLaunchKernelGGL(k_bounds_apart, dim3(ctx->cus * 4), dim3(256), (size_t)kVolatile * ctx->D * sizeof(float), ctx->stream,
-                       codes, N, ctx->M, m, ctx->drift, ctx->K, ctx->bnd_u, ctx->bnd_l, ctx->active, ctx->moved_count + 2,
-                       ctx->active + ctx->N_max, ctx->moved_count + 3, xp, ctx->D, Cm, top5);
+    hipLaunchKernelGGL(k_bounds_step, dim3((unsigned)((N + kBoundSpan - 1) / kBoundSpan)), dim3(256),
+                       (size_t)kVolatile * ctx->D * sizeof(float), ctx->stream,
+                       codes, N, ctx->M, m, ctx->drift, ctx->K, ctx->bnd_u, ctx->bnd_l,
+                       ctx->active, ctx->moved_count + 3, xp, ctx->D, Cm);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
@@ -402,7 +397,7 @@ int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float
         // moved_count is zero here: the merge of the previous pass of this stage reset it
         hipLaunchKernelGGL(k_moved, dim3((unsigned)((N + kMovedSpan - 1) / kMovedSpan)), dim3(256), 0, ctx->stream,
                            codes, N, ctx->M, m, ctx->upd_col, ctx->moved_list, ctx->moved_count,
-                           pruned ? ctx->active + ctx->N_max : (const uint32_t *)nullptr,
+                           pruned ? ctx->active : (const uint32_t *)nullptr,
                            pruned ? ctx->moved_count + 3 : (const unsigned *)nullptr);
         HIP_TRY(ctx, hipGetLastError());
         hipLaunchKernelGGL(k_accumulate_moved, dim3((unsigned)nb, (unsigned)windows), dim3(kUpdThreads), upd_lds_bytes(K),
@@ -588,8 +583,8 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
         {(void **)&ctx->moved_count, 256},
         {(void **)&ctx->bnd_u, sizeof(float) * (size_t)N_max},
         {(void **)&ctx->bnd_l, sizeof(float) * (size_t)N_max},
-        {(void **)&ctx->drift, sizeof(float) * (HCLAE_MAX_K + 16)},   // [K] drifts, then k_drift_top's 16 words
-        {(void **)&ctx->active, sizeof(uint32_t) * 2 * (size_t)N_max},
+        {(void **)&ctx->drift, sizeof(float) * HCLAE_MAX_K},
+        {(void **)&ctx->active, sizeof(uint32_t) * (size_t)N_max},
         {(void **)&ctx->seed_idx, sizeof(int64_t) * K},
         {(void **)&ctx->part_a, sizeof(double) * ctx->nparts},
         {(void **)&ctx->part_b, sizeof(double) * ctx->nparts},

@@ -269,7 +269,7 @@ __global__ __launch_bounds__(256) void k_merge(
     // after a pass over the moved vectors only the blocks that pass used hold partials; the list counter is
     // handed back empty (every block reads it before the last one to arrive resets it)
     if (delta) nblk = moved_blocks(*moved_count, nblk);
-    // moved_count[2], [3]: the two list counters of the pruning step that follows (k_bounds_step, k_bounds_apart)
+    // moved_count[3]: the list counter of the pruning step that follows (k_bounds_step)
     if (moved_count) {
         __syncthreads();
         if (threadIdx.x == 0 && atomicAdd(moved_count + 1, 1u) == gridDim.x - 1) {
