@@ -45,6 +45,21 @@ struct PruneArgs {
     const uint32_t *active;            // [*active_count] vector indices (PRUNE 2)
     const unsigned *active_count;
 };
+// Lower bound stored for a vector that goes to the fp64 re-check: no distance is negative, so the value
+// keeps the vector listed and tells it from all others.
+constexpr float kAmbiguousL = -2.f;
+
+// Which vectors changed cluster since the last centroid update of the stage, found by the re-check kernel that
+// follows a PRUNE 2 assignment (prev == nullptr: not wanted).  Only a vector that assignment recomputed can
+// have changed code.  Entry = n | old code << 32 | new code << 40; order is free.
+struct MovedArgs {
+    uint8_t *prev;                     // [N] code column at the last update; brought up to date
+    unsigned long long *list;
+    unsigned *count;                   // zero on entry
+    const uint32_t *cand;              // [*cand_count] the vectors the assignment recomputed
+    const unsigned *cand_count;
+    const float *bl;                   // [N] kAmbiguousL marks the ones on the re-check list
+};
 
 // -||c_k||^2 / 2 in fp32 (computed in fp64) over the first D coordinates of rows of stride ld, for
 // k < K; -inf for the padding rows up to kpad.
@@ -264,7 +279,7 @@ __device__ __forceinline__ void decide(
         // no candidate) gets bounds that keep it active.  slack covers the fp32 evaluation of these lines.
         const float E = 0.5001f * margin;
         const float slack = 2e-5f * (x2 + 2.f * fabsf(mx) + 2.f * fabsf(m2));
-        float u = __builtin_inff(), l = 0.f;
+        float u = __builtin_inff(), l = cnt >= 2 ? kAmbiguousL : 0.f;
         if (cnt == 1) {
             u = sqrtf(fmaxf(0.f, (x2 - 2.f * (mx - E)) + slack)) * 1.00001f;
             l = sqrtf(fmaxf(0.f, (x2 - 2.f * (m2 + E)) - slack)) * 0.99999f;
@@ -574,15 +589,24 @@ __global__ __launch_bounds__(256) void k_bounds_step(
     for (unsigned i = threadIdx.x; i < nk; i += 256) list[base + i] = kept[i];
 }
 
+constexpr int kMovedSpan = 1024;
 // fp64 re-check of the vectors whose fp32 scores were too close to call: direct-form squared
 // distances summed in ascending dimension order, smallest wins, exact ties go to the lowest
 // index.  A group of 16 lanes takes one list entry and gives each candidate its own lane.
 __global__ __launch_bounds__(256) void k_refine(
     const float *__restrict__ xp, const float *__restrict__ Cm, int D, int ld, int M, int m,
     uint8_t *__restrict__ codes, const RefineItem *__restrict__ list,
-    const unsigned *__restrict__ refine_count)
+    const unsigned *__restrict__ refine_count, MovedArgs mv)
 {
+    __shared__ unsigned long long found[kMovedSpan];
+    __shared__ unsigned nfound, base;
     const unsigned count = *refine_count;
+    // re-checked vectors that changed cluster are staged in LDS like the others while a block's share fits
+    const bool staged = count <= gridDim.x * (unsigned)kMovedSpan;
+    if (mv.prev) {
+        if (threadIdx.x == 0) nfound = 0u;
+        __syncthreads();
+    }
     const int l16 = threadIdx.x & 15;
     const unsigned groups = gridDim.x * (256 / 16);
     const int d4 = D >> 2;
@@ -636,7 +660,52 @@ __global__ __launch_bounds__(256) void k_refine(
             const int ok = __shfl_xor(kbest, o, kWave);
             if (ob < best || (ob == best && ok < kbest)) { best = ob; kbest = ok; }
         }
-        if (l16 == 0) codes[(size_t)it.n * M + m] = (uint8_t)kbest;
+        if (l16 == 0) {
+            codes[(size_t)it.n * M + m] = (uint8_t)kbest;
+            if (mv.prev) {
+                const unsigned co = mv.prev[it.n];
+                if (co != (unsigned)kbest) {
+                    mv.prev[it.n] = (uint8_t)kbest;
+                    const unsigned long long ent =
+                        (unsigned long long)it.n | ((unsigned long long)co << 32) | ((unsigned long long)kbest << 40);
+                    if (staged) found[atomicAdd(&nfound, 1u)] = ent;
+                    else mv.list[atomicAdd(mv.count, 1u)] = ent;
+                }
+            }
+        }
+    }
+    if (!mv.prev) return;
+    __syncthreads();
+    if (threadIdx.x == 0 && nfound) base = atomicAdd(mv.count, nfound);
+    __syncthreads();
+    for (unsigned i = threadIdx.x; i < nfound; i += 256) mv.list[base + i] = found[i];
+    __syncthreads();
+    // The other recomputed vectors have their final code already.  A block takes kMovedSpan list entries at a
+    // time, stages what it finds in LDS and claims its stretch of the output with one counter add.
+    const int64_t total = (int64_t)*mv.cand_count;
+    for (int64_t i0 = (int64_t)blockIdx.x * kMovedSpan; i0 < total; i0 += (int64_t)gridDim.x * kMovedSpan) {
+        if (threadIdx.x == 0) nfound = 0u;
+        __syncthreads();
+#pragma unroll
+        for (int i = threadIdx.x; i < kMovedSpan; i += 256) {
+            const int64_t j = i0 + i;
+            if (j < total) {
+                const int64_t n = mv.cand[j];
+                if (mv.bl[n] != kAmbiguousL) {
+                    const unsigned cn = codes[n * M + m], co = mv.prev[n];
+                    if (cn != co) {
+                        mv.prev[n] = (uint8_t)cn;
+                        found[atomicAdd(&nfound, 1u)] =
+                            (unsigned long long)(uint32_t)n | ((unsigned long long)co << 32) | ((unsigned long long)cn << 40);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0 && nfound) base = atomicAdd(mv.count, nfound);
+        __syncthreads();
+        for (unsigned i = threadIdx.x; i < nfound; i += 256) mv.list[base + i] = found[i];
+        __syncthreads();
     }
 }
 

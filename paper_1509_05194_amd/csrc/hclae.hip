@@ -216,6 +216,14 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
     PruneArgs pa;
     pa.bu = ctx->bnd_u; pa.bl = ctx->bnd_l;
     pa.active = ctx->active; pa.active_count = ctx->moved_count + 3;
+    // prune 3 = 2, and the re-check kernel lists the vectors that changed cluster (moved_count[0] is zero: the
+    // merge of the previous centroid update of this stage reset it)
+    MovedArgs mv = {};
+    if (prune == 3) {
+        mv.prev = ctx->upd_col; mv.list = ctx->moved_list; mv.count = ctx->moved_count;
+        mv.cand = ctx->active; mv.cand_count = ctx->moved_count + 3; mv.bl = ctx->bnd_l;
+        prune = 2;
+    }
     const int NC = (dact + kChunkD - 1) / kChunkD;
     const int dpad = kChunkD * NC;
     const bool resident = (size_t)32 * KB * dpad * sizeof(float) + 4096 <= (size_t)kLdsBudget;
@@ -288,7 +296,7 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
     HIP_TRY(ctx, hipGetLastError());
     Timed t_(ctx, HCLAE_T_REFINE);
     hipLaunchKernelGGL(k_refine, dim3(ctx->cus * 4), dim3(256), 0, ctx->stream,
-                       xp, Cm, dact, ld, ctx->M, m, codes, ctx->refine_list, ctx->refine_count);
+                       xp, Cm, dact, ld, ctx->M, m, codes, ctx->refine_list, ctx->refine_count, mv);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
@@ -380,8 +388,8 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
 
 // Centroid update from the vectors that changed cluster since the last update of this stage (x' unchanged,
 // max |x'| still published): exact, see k_merge.  Leaves hneg and the counters as launch_update does.
-// pruned: the assignment that just ran recomputed only the vectors of the second list of the bound step.
-int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, const uint8_t *codes, bool pruned)
+// The re-check kernel of the assignment that just ran (launch_assign with prune 3) has listed those vectors.
+int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm)
 {
     const int D = ctx->D, K = ctx->K;
     const int windows = (D + kUpdWindow - 1) / kUpdWindow;
@@ -394,12 +402,6 @@ int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float
     }
     {
         Timed t_(ctx, HCLAE_T_ACCUM_MOVED);
-        // moved_count is zero here: the merge of the previous pass of this stage reset it
-        hipLaunchKernelGGL(k_moved, dim3((unsigned)((N + kMovedSpan - 1) / kMovedSpan)), dim3(256), 0, ctx->stream,
-                           codes, N, ctx->M, m, ctx->upd_col, ctx->moved_list, ctx->moved_count,
-                           pruned ? ctx->active : (const uint32_t *)nullptr,
-                           pruned ? ctx->moved_count + 3 : (const unsigned *)nullptr);
-        HIP_TRY(ctx, hipGetLastError());
         hipLaunchKernelGGL(k_accumulate_moved, dim3((unsigned)nb, (unsigned)windows), dim3(kUpdThreads), upd_lds_bytes(K),
                            ctx->stream, xp, ctx->moved_list, ctx->moved_count, D, K, ctx->refine_count + 1,
                            ctx->partial, ctx->pcount);
@@ -454,10 +456,10 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
     const bool prune = ctx->pruning && iters > 0;
     for (int t = 0; t < iters; ++t) {
         if (prune && t > 0 && (rc = launch_bounds_step(ctx, m, N, codes, residue, Cm)) != HCLAE_OK) return rc;
-        if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? (t == 0 ? 1 : 2) : 0)) != HCLAE_OK) return rc;
+        if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? (t == 0 ? 1 : 3) : 0)) != HCLAE_OK) return rc;
         rc = (t == 0 || !ctx->pruning)
                  ? launch_update(ctx, m, N, residue, Cm, codes, nullptr, true, false, 0, ctx->pruning && (iters > 1 || prune))
-                 : launch_update_moved(ctx, m, N, residue, Cm, codes, prune);
+                 : launch_update_moved(ctx, m, N, residue, Cm);
         if (rc != HCLAE_OK) return rc;
     }
     if (prune && (rc = launch_bounds_step(ctx, m, N, codes, residue, Cm)) != HCLAE_OK) return rc;

@@ -115,45 +115,6 @@ __global__ __launch_bounds__(256) void k_save_column(
         prev[n] = codes[n * M + m];
 }
 
-// One entry per vector whose code in column m differs from prev[n] (the column as of the last centroid
-// pass): n in the low 32 bits, old code in bits 32..39, new code in bits 40..47.  prev is brought up to
-// date.  A block takes kMovedSpan consecutive vectors, collects its entries in LDS and claims its stretch of
-// the list with one counter add.  *count must start at zero; the order of the entries is free (the sums do
-// not depend on it).
-constexpr int kMovedSpan = 4096;
-// cand / cand_count: when non-null only these vectors are looked at (the ones the last assignment recomputed:
-// a vector its distance bounds settled cannot have changed code); blocks then stride over that list.
-__global__ __launch_bounds__(256) void k_moved(
-    const uint8_t *__restrict__ codes, int64_t N, int M, int m, uint8_t *__restrict__ prev,
-    unsigned long long *__restrict__ list, unsigned *__restrict__ count,
-    const uint32_t *__restrict__ cand, const unsigned *__restrict__ cand_count)
-{
-    __shared__ unsigned long long found[kMovedSpan];
-    __shared__ unsigned nfound, base;
-    const int64_t total = cand ? (int64_t)*cand_count : N;
-    for (int64_t i0 = (int64_t)blockIdx.x * kMovedSpan; i0 < total; i0 += (int64_t)gridDim.x * kMovedSpan) {
-        if (threadIdx.x == 0) nfound = 0u;
-        __syncthreads();
-        for (int i = threadIdx.x; i < kMovedSpan; i += 256) {
-            const int64_t j = i0 + i;
-            if (j < total) {
-                const int64_t n = cand ? (int64_t)cand[j] : j;
-                const unsigned cn = codes[n * M + m], co = prev[n];
-                if (cn != co) {
-                    prev[n] = (uint8_t)cn;
-                    found[atomicAdd(&nfound, 1u)] =
-                        (unsigned long long)(uint32_t)n | ((unsigned long long)co << 32) | ((unsigned long long)cn << 40);
-                }
-            }
-        }
-        __syncthreads();
-        if (threadIdx.x == 0 && nfound) base = atomicAdd(count, nfound);
-        __syncthreads();
-        for (unsigned i = threadIdx.x; i < nfound; i += 256) list[base + i] = found[i];
-        __syncthreads();
-    }
-}
-
 // Blocks (of the x dimension) that the pass over `total` moved vectors uses: enough rows per block to pay
 // for flushing its 128 KB of partial sums.  The merge that follows computes the same number.
 __device__ __forceinline__ int moved_blocks(unsigned total, int max_blocks)
@@ -242,7 +203,7 @@ __global__ __launch_bounds__(256) void k_absmax(const float4 *__restrict__ x, in
 
 // Exact incremental form (tot_sum int64 [K][D], tot_cnt int [K]; both may be null): a full pass stores the
 // integer sums and counts of the stage; while x' stays as it is, a later pass over only the vectors that
-// changed cluster (k_moved, k_accumulate_moved: +q into the new cluster, -q out of the old one) advances
+// changed cluster (listed by k_refine; k_accumulate_moved: +q into the new cluster, -q out of the old one) advances
 // them with delta != 0.  Integer addition being exact, the totals -- and so the centroids -- are the very
 // numbers a full pass would give.
 //
