@@ -392,26 +392,93 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     publish_absmax(amax, refine_count + 1);
 }
 
-// Assignment for dimensions whose codebook does not fit LDS: the block walks the D axis in
-// 64-dim chunks, restaging that slice of the codebook for every tile of 8 x 32 vectors; the
-// accumulators persist across chunks.
+// Codebook in the order the D-chunked kernel stages it: float4 (q * KB * 8 + b * 8 + s) * 64 + l, l = 32 h + r,
+// holds C[32 b + r][64 q + 8 s + 4 h .. + 3] (zero beyond K and D), so that the slice of 64-dim chunk q is one
+// contiguous piece already in MFMA operand order (see stage_codebook).
+__global__ __launch_bounds__(256) void k_codebook_image(
+    const float *__restrict__ Cm, int K, int D, int ld, int kb, int NC, float4 *__restrict__ img)
+{
+    const int total = NC * kb * 8 * kWave;
+    for (int e = blockIdx.x * 256 + threadIdx.x; e < total; e += gridDim.x * 256) {
+        const int l = e & 63;
+        int bs = e >> 6;
+        const int s = bs & 7;
+        bs >>= 3;
+        const int b = bs % kb, q = bs / kb;
+        img[e] = load_row_piece(Cm, 32 * b + (l & 31), kChunkD * q + 8 * s + 4 * (l >> 5), K, D, ld);
+    }
+}
+
+// One 64-dim chunk of the D-chunked kernel: contracts x (the chunk in registers) with the slice in `cur`, and
+// meanwhile brings in what the next chunk needs: k-step s refills x[s] from xnext (the same columns of the
+// next chunk, or of the next tile's first one) as soon as it has used it, and fetches piece s of the next
+// slice (src: this thread's float4 of piece 0; pieces are 8 * 64 float4 apart) at its start and stores it to
+// `nxt` at its end, with the step's MFMAs between the load and its use.
+template <int KB>
+__device__ __forceinline__ void mfma_chunk_refill(
+    floatx16 (&acc)[KB], float4 (&x)[8], const float4 *__restrict__ cur, float4 *__restrict__ nxt,
+    const float4 *__restrict__ src, const float *__restrict__ xnext, int q, int qn, int D, int lane, int wave,
+    float &xsq, float &amax)
+{
+    const int h = lane >> 5;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        float4 piece = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (s < KB) piece = src[s * 8 * kWave];
+        float4 a[KB];
+#pragma unroll
+        for (int b = 0; b < KB; ++b) a[b] = cur[(b * 8 + s) * kWave + lane];
+        // columns past D (last chunk only) are zeroed here, at use: the refill itself is unconditional (its
+        // address clamped into the row), so that no branch hides from the compiler which loads are in flight
+        float4 xv = x[s];
+        if (kChunkD * q + 8 * s + 4 * h >= D) xv = make_float4(0.f, 0.f, 0.f, 0.f);
+        x[s] = *reinterpret_cast<const float4 *>(xnext + min(kChunkD * qn + 8 * s + 4 * h, D - 4));
+        xsq = fmaf(xv.x, xv.x, xsq);
+        xsq = fmaf(xv.y, xv.y, xsq);
+        xsq = fmaf(xv.z, xv.z, xsq);
+        xsq = fmaf(xv.w, xv.w, xsq);
+        amax = fmaxf(fmaxf(amax, fabsf(xv.x)), fabsf(xv.y));
+        amax = fmaxf(fmaxf(amax, fabsf(xv.z)), fabsf(xv.w));
+#pragma unroll
+        for (int b = 0; b < KB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[b].x, xv.x, acc[b], 0, 0, 0);
+#pragma unroll
+        for (int b = 0; b < KB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[b].y, xv.y, acc[b], 0, 0, 0);
+#pragma unroll
+        for (int b = 0; b < KB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[b].z, xv.z, acc[b], 0, 0, 0);
+        // the store (and the wait for its load) stays behind three quarters of the step's MFMAs; arithmetic,
+        // MFMAs and LDS reads of the next step may still move across
+        __builtin_amdgcn_sched_barrier(0x10f);
+        if (s < KB) nxt[(s * 8 + wave) * kWave + lane] = piece;
+#pragma unroll
+        for (int b = 0; b < KB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[b].w, xv.w, acc[b], 0, 0, 0);
+    }
+}
+
+// Assignment for dimensions whose codebook does not fit LDS: the block walks the D axis in 64-dim chunks for
+// every tile of 8 x 32 vectors, the accumulators persisting across chunks.  Two LDS buffers hold the slice in
+// use and the one being brought in from the codebook image (k_codebook_image), one barrier per chunk; the
+// refills run under the MFMAs (mfma_chunk_refill), across tile boundaries too.
 template <int KB, int PRUNE = 0>
 __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
-    const float *__restrict__ xp, const float *__restrict__ Cm, const float *__restrict__ hneg,
+    const float *__restrict__ xp, const float4 *__restrict__ img, const float *__restrict__ hneg,
     int64_t N, int D, int ld, int K, int M, int m, int NC, float eps,
     uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count,
     PruneArgs pa)
 {
     extern __shared__ float4 smem4[];
-    constexpr int S = 8;                                            // one chunk resident
-    float4 *lds_c = smem4;                                          // KB * 8 * 64 float4
-    float *lds_h = reinterpret_cast<float *>(smem4 + KB * S * kWave);
+    constexpr int CH = KB * 8 * kWave;                              // float4 per slice
+    float4 *buf0 = smem4, *buf1 = smem4 + CH;
+    float *lds_h = reinterpret_cast<float *>(smem4 + 2 * CH);
     const int lane = lane_id();
     const int wave = threadIdx.x >> 6;
     const int h = lane >> 5;
     const int r = lane & 31;
 
     for (int k = threadIdx.x; k < 32 * KB; k += blockDim.x) lds_h[k] = hneg[k];
+    // slice 0 (the same for every tile)
+    const float4 *mine = img + wave * kWave + lane;
+#pragma unroll
+    for (int p = 0; p < KB; ++p) buf0[(p * 8 + wave) * kWave + lane] = mine[p * 8 * kWave];
     __syncthreads();
     float hmax = 0.f;
     for (int k = 0; k < K; ++k) hmax = fmaxf(hmax, -lds_h[k]);
@@ -421,33 +488,40 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
     const int64_t rows = PRUNE == 2 ? (int64_t)*pa.active_count : N;
     const int64_t nbt = (rows + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);   // block tiles
     float amax = 0.f;
-    for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
-        const int64_t i = (bt * kAssignWaves + wave) * kTileVec + r;
-        const int64_t ic = i < rows ? i : rows - 1;                 // tail columns re-read the last row
-        const int64_t nrow = PRUNE == 2 ? (int64_t)pa.active[ic] : ic;
-        const int64_t n_raw = i < rows ? nrow : N;                  // N = "none"
-        const float *xrow = xp + nrow * ld;
-        floatx16 acc[KB];
+    if ((int64_t)blockIdx.x < nbt) {
+        // row of x' this lane feeds for block tile bt (tail columns re-read the last row); vec = N for "none"
+        auto tile_row = [&](int64_t bt, int64_t &vec) -> const float * {
+            const int64_t i = (bt * kAssignWaves + wave) * kTileVec + r;
+            const int64_t ic = i < rows ? i : rows - 1;
+            const int64_t nrow = PRUNE == 2 ? (int64_t)pa.active[ic] : ic;
+            vec = i < rows ? nrow : N;
+            return xp + nrow * ld;
+        };
+        int64_t vec;
+        const float *xrow = tile_row(blockIdx.x, vec);
         float4 x[8];
-        float xsq = 0.f;
-        init_acc<KB>(acc, lds_h, h);
-        for (int q = 0; q < NC; ++q) {
-            load_x_chunk(x, xrow, q, h, D);
-            __syncthreads();                                        // previous chunk fully consumed
-            // slice [64q, 64q+64) of the codebook, as chunk 0 of an S = 8 image
-            for (int e = threadIdx.x; e < KB * S * kWave; e += blockDim.x) {
-                const int l = e & 63;
-                const int bs = e >> 6;
-                const int s = bs & 7;
-                const int b = bs >> 3;
-                const int row = 32 * b + (l & 31);
-                const int col = kChunkD * q + 8 * s + 4 * (l >> 5);
-                lds_c[e] = load_row_piece(Cm, row, col, K, D, ld);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) x[s] = *reinterpret_cast<const float4 *>(xrow + min(8 * s + 4 * h, D - 4));
+        int par = 0;
+        for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
+            int64_t vec_next = vec;
+            const float *xrow_next = xrow;                          // the last tile refills with itself: unused
+            if (bt + gridDim.x < nbt) xrow_next = tile_row(bt + gridDim.x, vec_next);
+            floatx16 acc[KB];
+            float xsq = 0.f;
+            init_acc<KB>(acc, lds_h, h);
+            for (int q = 0; q < NC; ++q) {
+                const bool last = q + 1 == NC;
+                const int qn = last ? 0 : q + 1;
+                mfma_chunk_refill<KB>(acc, x, par ? buf1 : buf0, par ? buf0 : buf1, mine + (size_t)qn * CH,
+                                      last ? xrow_next : xrow, q, qn, D, lane, wave, xsq, amax);
+                __syncthreads();                                    // slice q consumed by all, slice qn complete
+                par ^= 1;
             }
-            __syncthreads();
-            mfma_chunk<KB>(acc, x, lds_c, 0, S, lane, xsq, amax);
+            decide<KB, PRUNE>(acc, xsq, eps, hmax, cmax, lane, vec, N, M, m, codes, list, refine_count, pa);
+            xrow = xrow_next;
+            vec = vec_next;
         }
-        decide<KB, PRUNE>(acc, xsq, eps, hmax, cmax, lane, n_raw, N, M, m, codes, list, refine_count, pa);
     }
     publish_absmax(amax, refine_count + 1);
 }

@@ -42,6 +42,7 @@ struct hclae_ctx {
     int device;
     // scratch (device)
     float *hneg;             // [32*kb]
+    float4 *cb_image;        // [NC][kb*8*64] codebook in staging order (k_codebook_image; D-chunked shapes only)
     float *split_norms;      // [K][2] split constants of the codebook in use (contraction 1)
     int contraction;         // 0: fp32 MFMA, 1: split-bf16 MFMA (resident shapes only)
     unsigned *refine_count;
@@ -274,9 +275,10 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
                            xp, Cm, ctx->hneg, N, dact, ld, ctx->K, ctx->M, m, NC, eps,
                            codes, ctx->refine_list, ctx->refine_count, pa);
     } else {
-        const size_t lds = (size_t)KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
+        // two slices of 64 dims in LDS: one block per CU
+        const size_t lds = (size_t)2 * KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t nbt = (N + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);
-        int64_t blocks = nbt < 2 * ctx->cus ? nbt : 2 * ctx->cus;
+        int64_t blocks = nbt < ctx->cus ? nbt : ctx->cus;
         static bool attr_set = false;
         if (!attr_set) {
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_chunked<KB, 0>),
@@ -287,9 +289,14 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             attr_set = true;
         }
+        if (NC > ctx->NC || KB != ctx->kb)
+            return fail(ctx, HCLAE_EINVAL, "assign: codebook image too small for this shape");
+        const int img_total = NC * KB * 8 * kWave;
+        hipLaunchKernelGGL(k_codebook_image, dim3((img_total + 255) / 256), dim3(256), 0, ctx->stream,
+                           Cm, ctx->K, dact, ld, KB, NC, ctx->cb_image);
         auto kern = prune == 1 ? &k_assign_chunked<KB, 1> : prune == 2 ? &k_assign_chunked<KB, 2> : &k_assign_chunked<KB, 0>;
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
-                           xp, Cm, ctx->hneg, N, dact, ld, ctx->K, ctx->M, m, NC, eps,
+                           xp, ctx->cb_image, ctx->hneg, N, dact, ld, ctx->K, ctx->M, m, NC, eps,
                            codes, ctx->refine_list, ctx->refine_count, pa);
     }
     }
@@ -571,6 +578,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
 
     struct { void **p; size_t bytes; } allocs[] = {
         {(void **)&ctx->hneg, sizeof(float) * 32 * ctx->kb},
+        {(void **)&ctx->cb_image, ctx->resident ? 256 : sizeof(float4) * (size_t)ctx->NC * ctx->kb * 8 * kWave},
         {(void **)&ctx->split_norms, sizeof(float) * 2 * HCLAE_MAX_K},
         {(void **)&ctx->refine_count, 256},
         {(void **)&ctx->refine_list, sizeof(RefineItem) * (size_t)N_max},
@@ -619,7 +627,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
 int hclae_destroy(hclae_ctx *ctx)
 {
     if (!ctx) return HCLAE_EINVAL;
-    void *dev[] = {ctx->hneg, ctx->split_norms, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
+    void *dev[] = {ctx->hneg, ctx->cb_image, ctx->split_norms, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
                    ctx->nk, ctx->tot_sum, ctx->tot_cnt, ctx->upd_col, ctx->moved_list, ctx->moved_count, ctx->bnd_u, ctx->bnd_l, ctx->drift, ctx->active, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
                    ctx->run_sum, ctx->run_cnt, ctx->n0_dev, ctx->pca_rt, ctx->pca_crot, ctx->pca_colpart,
                    ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32,
