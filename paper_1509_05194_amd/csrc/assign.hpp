@@ -666,7 +666,9 @@ __global__ __launch_bounds__(256) void k_bounds_step(
 constexpr int kMovedSpan = 1024;
 // fp64 re-check of the vectors whose fp32 scores were too close to call: direct-form squared
 // distances summed in ascending dimension order, smallest wins, exact ties go to the lowest
-// index.  A group of 16 lanes takes one list entry and gives each candidate its own lane.
+// index.  A group of kRefineLanes lanes takes one list entry and gives each candidate its own lane (most
+// entries have two or three candidates; more take further rounds).
+constexpr int kRefineLanes = 4;
 __global__ __launch_bounds__(256) void k_refine(
     const float *__restrict__ xp, const float *__restrict__ Cm, int D, int ld, int M, int m,
     uint8_t *__restrict__ codes, const RefineItem *__restrict__ list,
@@ -681,10 +683,10 @@ __global__ __launch_bounds__(256) void k_refine(
         if (threadIdx.x == 0) nfound = 0u;
         __syncthreads();
     }
-    const int l16 = threadIdx.x & 15;
-    const unsigned groups = gridDim.x * (256 / 16);
+    const int l16 = threadIdx.x & (kRefineLanes - 1);
+    const unsigned groups = gridDim.x * (256 / kRefineLanes);
     const int d4 = D >> 2;
-    for (unsigned e = blockIdx.x * (256 / 16) + (threadIdx.x >> 4); e < count; e += groups) {
+    for (unsigned e = blockIdx.x * (256 / kRefineLanes) + threadIdx.x / kRefineLanes; e < count; e += groups) {
         const RefineItem it = list[e];
         int total = 0;
 #pragma unroll
@@ -692,8 +694,8 @@ __global__ __launch_bounds__(256) void k_refine(
         const float4 *x = reinterpret_cast<const float4 *>(xp + (size_t)it.n * ld);
         double best = __builtin_inf();
         int kbest = 0x7fffffff;
-        for (int base = 0; base < total; base += 16) {
-            int j = base + l16;
+        for (int first = 0; first < total; first += kRefineLanes) {
+            int j = first + l16;
             if (j < total) {
                 // codeword of the j-th set bit
                 int k = 0;
@@ -712,6 +714,8 @@ __global__ __launch_bounds__(256) void k_refine(
                 }
                 const float4 *c4 = reinterpret_cast<const float4 *>(Cm + (size_t)k * ld);
                 double s = 0.0;
+                // unrolled so that eight rounds of loads are in flight; the additions keep their order
+#pragma unroll 8
                 for (int d = 0; d < d4; ++d) {
                     const float4 a = x[d], b = c4[d];
                     const double t0 = (double)a.x - (double)b.x, t1 = (double)a.y - (double)b.y;
@@ -729,7 +733,7 @@ __global__ __launch_bounds__(256) void k_refine(
             }
         }
 #pragma unroll
-        for (int o = 8; o > 0; o >>= 1) {
+        for (int o = kRefineLanes / 2; o > 0; o >>= 1) {
             const double ob = __shfl_xor(best, o, kWave);
             const int ok = __shfl_xor(kbest, o, kWave);
             if (ob < best || (ob == best && ok < kbest)) { best = ob; kbest = ok; }
