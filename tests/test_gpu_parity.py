@@ -43,6 +43,10 @@ CASES = {
     "k40d132": dict(gen="sift", N=3000 + 1, D=132, M=2, K=40, T=1),
     "gist":    dict(gen="gist", N=3000 + 5, D=960, M=2, K=256, T=1),
     "k256d132": dict(gen="sift", N=2000 + 9, D=132, M=2, K=256, T=1),
+    # D-chunked with one, two and four 32-codeword blocks (odd and even slice counts, a ragged last slice)
+    "k16d2052": dict(gen="gist", N=1500 + 3, D=2052, M=2, K=16, T=1),
+    "k40d960": dict(gen="gist", N=2000 + 1, D=960, M=2, K=40, T=1),
+    "k100d512": dict(gen="gist", N=2000 + 7, D=512, M=2, K=100, T=1),
 }
 _cache = {}
 
@@ -430,7 +434,8 @@ def test_limits_of_the_shape_check(shape, oracle):
 
 
 @pytest.mark.parametrize("gen,N,D,M,K,T", [("sift", 40000 + 9, 128, 3, 256, 6), ("gist", 6000 + 5, 960, 2, 256, 5),
-                                           ("tiny", 10000 + 3, 16, 4, 16, 6), ("sift", 8000 + 1, 132, 2, 40, 4)])
+                                           ("tiny", 10000 + 3, 16, 4, 16, 6), ("sift", 8000 + 1, 132, 2, 40, 4),
+                                           ("gist", 5000 + 3, 512, 2, 100, 4), ("gist", 3000 + 7, 1412, 2, 20, 4)])
 def test_stage_equals_its_single_steps_bitwise(gen, N, D, M, K, T):
     """hclae_anneal_stage prunes its Lloyd iterations (distance bounds; centroid sums advanced by the moved
     vectors, exact integer totals); the single-step calls run every assignment and every sum over all
