@@ -32,6 +32,9 @@ def main():
     ap.add_argument("--m", type=int, default=8)
     ap.add_argument("--iters", type=int, default=10, help="Lloyd iterations T per cool-down")
     ap.add_argument("--queries", type=int, default=10_000)
+    ap.add_argument("--shape", choices=["sift", "gist"], default="sift",
+                    help="sift: the headline workload (D=128).  gist: the same step on GIST-shaped data (D=960, "
+                         "the D-chunked assign kernel; default M=4), reported beside it, never instead of it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
     ap.add_argument("--online", type=int, default=0, metavar="CHUNKS",
@@ -55,15 +58,21 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    N, D, M, K, T, Q = args.n, 128, args.m, 256, args.iters, args.queries
+    gist = args.shape == "gist"
+    if gist and args.m == 8:
+        args.m = 4
+    N, D, M, K, T, Q = args.n, (960 if gist else 128), args.m, 256, args.iters, args.queries
+    if gist and (args.online or args.beam or args.contraction != "f32"):
+        sys.exit("bench.py: --shape gist runs the sweep with the fp32 contraction only")
     if args.online:
         return online_bench(args, torch, hclae, synth, dev)
     if args.beam:
         return beam_bench(args, torch, hclae, synth, dev)
 
     t_gen = time.perf_counter()
-    X = synth.sift_like(N, D=D)
-    Xq = synth.sift_like(Q, D=D, seed=synth.SEED_HELDOUT)
+    gen = synth.gist_like if gist else synth.sift_like
+    X = gen(N, D=D)
+    Xq = gen(Q, D=D, seed=synth.SEED_HELDOUT)
     idx = synth.init_indices(N, M, K)
     t_gen = time.perf_counter() - t_gen
 
@@ -109,7 +118,7 @@ def main():
     E_final = ctx.quant_error(r)
 
     out = {
-        "metric": "DA sweep vectors/sec per stage (D=128,K=256)",
+        "metric": "DA sweep vectors/sec per stage (D=%d,K=256)" % D,
         "value": value,
         "unit": "vectors/s per stage",
         "n_gpus": 1,
@@ -121,13 +130,15 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "SIFT-shaped: N=%d, D=128, M=%d, K=256, T=%d Lloyd iterations per stage; "
-                               "one DA sweep + greedy encode of %d held-out queries per step" % (N, M, T, Q),
+        "config": {"workload": "%s-shaped: N=%d, D=%d, M=%d, K=256, T=%d Lloyd iterations per stage; "
+                               "one DA sweep + greedy encode of %d held-out queries per step"
+                               % ("GIST" if gist else "SIFT", N, D, M, T, Q),
                    "N": N, "D": D, "M": M, "K": K, "iters": T, "queries": Q,
                    "quant_error_after": E_final},
-        "roofline": {"bound": "mfma", "kernel": ("k_assign_resident<8> (fp32 MFMA distance contraction + argmin; the "
+        "roofline": {"bound": "mfma", "kernel": ("%s (fp32 MFMA distance contraction + argmin; the "
                                                  "launches over all N vectors: with pruning the first assignment of "
                                                  "each stage, which also stores the distance bounds)"
+                                                 % ("k_assign_chunked<8>" if gist else "k_assign_resident<8>")
                                                  if args.contraction == "f32" else
                                                  "k_assign_split<8> (split-bf16 MFMA distance contraction + argmin; "
                                                  "algorithmic 2NKD flop against the fp32 peak for comparison)"),
@@ -189,7 +200,7 @@ def main():
             "note": "hclae_set_pruning(0): all (T+1) assignments and all T centroid sums of a stage over all N vectors; "
                     "same dictionaries, codes and residues"}
 
-    if args.contraction == "f32" and not args.no_breakdown:
+    if args.contraction == "f32" and not args.no_breakdown and not gist:
         # the same step with the optional split-bf16 contraction (hclae_set_contraction 1), reported beside the
         # headline: identical results by construction (same fp64 decisions), another matrix-core arithmetic
         ts, s_avg = timed_variant(lambda: ctx.set_contraction(1), lambda: ctx.set_contraction(0))
@@ -202,7 +213,7 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle
-        Ns = N                                              # one full-size stage: about 10 s on 16 threads
+        Ns = N if not gist else N // 8                      # about 10-20 s on 16 threads
         Xs = np.ascontiguousarray(X[:Ns])
         Co = np.zeros((M, K, D), np.float64)
         co = np.zeros((Ns, M), np.uint8)
@@ -214,8 +225,9 @@ def main():
         tc = time.perf_counter() - tc
         out["cpu_baseline"] = {"value": 2 * Ns / tc, "unit": "vectors/s per stage", "cores": oracle.threads(),
                                "kind": "oracle",
-                               "sample": "two DA stages (m=0,1 of a fresh sweep, T=%d, K=256) of the fp64 oracle on all "
-                                         "%d vectors of the same workload, %.1f s" % (T, Ns, tc)}
+                               "sample": "two DA stages (m=0,1 of a fresh sweep, T=%d, K=256) of the fp64 oracle on %s "
+                                         "%d vectors of the same workload, %.1f s"
+                                         % (T, "all" if Ns == N else "the first", Ns, tc)}
     out["host_gen_s"] = t_gen
     print(json.dumps(out))
     ctx.close()
