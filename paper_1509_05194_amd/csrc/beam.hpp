@@ -273,24 +273,28 @@ __global__ __launch_bounds__(kAssignThreads) void k_beam_score_split(
     }
 }
 
-// Scoring for dimensions whose codebook does not fit LDS (see k_assign_chunked): the block walks
-// the D axis in 64-dim slices, restaging that slice of the codebook for every block tile.
+// Scoring for dimensions whose codebook does not fit LDS: as k_assign_chunked, the block walks the D axis in
+// 64-dim slices of the codebook image (k_codebook_image), two LDS buffers alternating, the next slice and the
+// next chunk of the residual rows arriving under the MFMAs (mfma_chunk_refill).
 template <int KB>
 __global__ __launch_bounds__(kAssignThreads) void k_beam_score_chunked(
-    const float *__restrict__ rows, const double *__restrict__ err, const float *__restrict__ Cm,
+    const float *__restrict__ rows, const double *__restrict__ err, const float4 *__restrict__ img,
     const float *__restrict__ hneg, int64_t N, int Lc, int Ln, int D, int ld, int K, int NC, float gamma,
     BeamMask *__restrict__ masks)
 {
     extern __shared__ float4 smem4[];
-    constexpr int S = 8;
-    float4 *lds_c = smem4;
-    float *lds_h = reinterpret_cast<float *>(smem4 + KB * S * kWave);
+    constexpr int CH = KB * 8 * kWave;                              // float4 per slice
+    float4 *buf0 = smem4, *buf1 = smem4 + CH;
+    float *lds_h = reinterpret_cast<float *>(smem4 + 2 * CH);
     const int lane = lane_id();
     const int wave = threadIdx.x >> 6;
     const int h = lane >> 5;
     const int r = lane & 31;
 
     for (int k = threadIdx.x; k < 32 * KB; k += blockDim.x) lds_h[k] = hneg[k];
+    const float4 *mine = img + wave * kWave + lane;
+#pragma unroll
+    for (int p = 0; p < KB; ++p) buf0[(p * 8 + wave) * kWave + lane] = mine[p * 8 * kWave];
     __syncthreads();
     float hmax = 0.f;
     for (int k = 0; k < K; ++k) hmax = fmaxf(hmax, -lds_h[k]);
@@ -302,34 +306,42 @@ __global__ __launch_bounds__(kAssignThreads) void k_beam_score_chunked(
     const int64_t nrows = N * Lc;
     const int64_t ntiles = (N + V - 1) / V;
     const int64_t nbt = (ntiles + kAssignWaves - 1) / kAssignWaves;
+    if ((int64_t)blockIdx.x >= nbt) return;
+    // residual row this lane feeds for block tile bt (idle lanes and waves re-read the last row)
+    auto tile_row = [&](int64_t bt, bool &valid) -> int64_t {
+        const int64_t row = (bt * kAssignWaves + wave) * RT + r;
+        valid = r < RT && row < nrows;
+        return valid ? row : nrows - 1;
+    };
     float amax = 0.f;
+    bool valid;
+    int64_t row = tile_row(blockIdx.x, valid);
+    const float *xrow = rows + row * ld;
+    float4 x[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) x[s] = *reinterpret_cast<const float4 *>(xrow + min(8 * s + 4 * h, D - 4));
+    int par = 0;
     for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
-        const int64_t tile = bt * kAssignWaves + wave;                 // may lie beyond ntiles: idle wave
-        const int64_t row = tile * RT + r;
-        const bool valid = r < RT && row < nrows;
-        const int64_t rd = valid ? row : nrows - 1;
-        const float *xrow = rows + rd * ld;
-        const float e_l = err ? (float)err[rd] : 0.f;
+        bool valid_next = valid;
+        int64_t row_next = row;
+        if (bt + gridDim.x < nbt) row_next = tile_row(bt + gridDim.x, valid_next);
+        const float *xrow_next = rows + row_next * ld;
+        const float e_l = err ? (float)err[row] : 0.f;
         floatx16 acc[KB];
-        float4 x[8];
         float xsq = 0.f;
         init_acc<KB>(acc, lds_h, h);
         for (int q = 0; q < NC; ++q) {
-            load_x_chunk(x, xrow, q, h, D);
+            const bool last = q + 1 == NC;
+            const int qn = last ? 0 : q + 1;
+            mfma_chunk_refill<KB>(acc, x, par ? buf1 : buf0, par ? buf0 : buf1, mine + (size_t)qn * CH,
+                                  last ? xrow_next : xrow, q, qn, D, lane, wave, xsq, amax);
             __syncthreads();
-            for (int e = threadIdx.x; e < KB * S * kWave; e += blockDim.x) {
-                const int l = e & 63;
-                const int bs = e >> 6;
-                const int s = bs & 7;
-                const int b = bs >> 3;
-                const int crow = 32 * b + (l & 31);
-                const int col = kChunkD * q + 8 * s + 4 * (l >> 5);
-                lds_c[e] = load_row_piece(Cm, crow, col, K, D, ld);
-            }
-            __syncthreads();
-            mfma_chunk<KB>(acc, x, lds_c, 0, S, lane, xsq, amax);
+            par ^= 1;
         }
         beam_select<KB>(acc, xsq, e_l, gamma, hmax, cmax, lane, gbase, Lc, Ln, valid, masks + (valid ? row : 0));
+        row = row_next;
+        valid = valid_next;
+        xrow = xrow_next;
     }
 }
 

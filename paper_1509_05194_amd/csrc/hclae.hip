@@ -1024,17 +1024,22 @@ static int launch_beam_score_kb(hclae_ctx *ctx, const float *rows, const double 
         hipLaunchKernelGGL((k_beam_score_resident<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
                            rows, err, Cm, ctx->hneg, N, Lc, Ln, D, D, ctx->K, NC, gamma, masks);
     } else {
-        const size_t lds = (size_t)KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
+        const size_t lds = (size_t)2 * KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t nbt = (ntiles + kAssignWaves - 1) / kAssignWaves;
-        int64_t blocks = nbt < 2 * ctx->cus ? nbt : 2 * ctx->cus;
+        int64_t blocks = nbt < ctx->cus ? nbt : ctx->cus;
         static bool attr_set = false;
         if (!attr_set) {
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_beam_score_chunked<KB>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             attr_set = true;
         }
+        if (NC > ctx->NC || KB != ctx->kb)
+            return fail(ctx, HCLAE_EINVAL, "beam: codebook image too small for this shape");
+        const int img_total = NC * KB * 8 * kWave;
+        hipLaunchKernelGGL(k_codebook_image, dim3((img_total + 255) / 256), dim3(256), 0, ctx->stream,
+                           Cm, ctx->K, D, D, KB, NC, ctx->cb_image);
         hipLaunchKernelGGL((k_beam_score_chunked<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
-                           rows, err, Cm, ctx->hneg, N, Lc, Ln, D, D, ctx->K, NC, gamma, masks);
+                           rows, err, ctx->cb_image, ctx->hneg, N, Lc, Ln, D, D, ctx->K, NC, gamma, masks);
     }
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
