@@ -251,4 +251,203 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_split(
     publish_absmax(amax, refine_count + 1);
 }
 
+// ---- the same contraction for dimensions whose codebook does not fit LDS ---------------------------------
+
+// Split codebook in the order the D-chunked split kernel stages it: the slice of 64-dim chunk q is KB * 512
+// uint4 laid out as in stage_codebook_split with chunk-local steps t = 0..3 (element ((t*KB + b)*2 + p)*64 + l),
+// slices one after the other.  Same size as the fp32 image of k_codebook_image.
+__global__ __launch_bounds__(256) void k_codebook_image_split(
+    const float *__restrict__ Cm, int K, int D, int ld, int kb, int NC, uint4 *__restrict__ img)
+{
+    const int total = NC * 4 * kb * kWave;                          // (q, t, b, l)
+    for (int e = blockIdx.x * 256 + threadIdx.x; e < total; e += gridDim.x * 256) {
+        const int l = e & 63;
+        int tb = e >> 6;
+        const int b = tb % kb;
+        tb /= kb;
+        const int t = tb & 3, q = tb >> 2;
+        const int row = 32 * b + (l & 31);
+        const int col = kChunkD * q + kSplitStep * t + 8 * (l >> 5);
+        const float4 u = load_row_piece(Cm, row, col, K, D, ld);
+        const float4 v = load_row_piece(Cm, row, col + 4, K, D, ld);
+        uint4 hi, lo;
+        split8(u, v, hi, lo);
+        uint4 *dst = img + (size_t)q * kb * 8 * kWave + (size_t)((t * kb + b) * 2) * kWave + l;
+        dst[0] = hi;
+        dst[kWave] = lo;
+    }
+}
+
+// One 64-dim chunk of the D-chunked split kernel (see mfma_chunk_refill): contracts x with the slice in `cur`
+// while the next slice and the next chunk of x' arrive.  Each 16-dim step fetches its share of the thread's KB
+// pieces of the next slice (src: its uint4 of piece 0; pieces are 8 * 64 uint4 apart) at its start and stores
+// them to `nxt` late in the step; x[2t], x[2t+1] are refilled from xnext as soon as step t has them.
+template <int KB>
+__device__ __forceinline__ void mfma_chunk_split_refill(
+    floatx16 (&acc)[KB], float4 (&x)[8], const uint4 *__restrict__ cur, uint4 *__restrict__ nxt,
+    const uint4 *__restrict__ src, const float *__restrict__ xnext, int q, int qn, int D, int lane, int wave,
+    float &xsq, float &amax)
+{
+    constexpr int GB = KB < 4 ? KB : 4;
+    constexpr int PP = (KB + 3) / 4;                                // pieces fetched per step
+    const int g = lane >> 5;
+    const uint4 *chunk = cur + lane;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        // Fetched as relaxed atomics (two 64-bit halves) and fenced for the scheduler: an ordinary load would be
+        // moved down next to its use, where its latency is no longer covered.
+        unsigned long long piece[PP][2];
+#pragma unroll
+        for (int i = 0; i < PP; ++i)
+            if (t * PP + i < KB) {
+                const unsigned long long *s64 = reinterpret_cast<const unsigned long long *>(src + (t * PP + i) * 8 * kWave);
+                piece[i][0] = __hip_atomic_load(s64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                piece[i][1] = __hip_atomic_load(s64 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        __builtin_amdgcn_sched_barrier(0x10f);
+        float4 u = x[2 * t], v = x[2 * t + 1];
+        {
+            // columns past D are zeroed at use; the refill is unconditional, its address clamped into the row
+            const int col = kChunkD * q + kSplitStep * t + 8 * g;
+            if (col >= D) u = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (col + 4 >= D) v = make_float4(0.f, 0.f, 0.f, 0.f);
+            const int coln = kChunkD * qn + kSplitStep * t + 8 * g;
+            x[2 * t] = *reinterpret_cast<const float4 *>(xnext + min(coln, D - 4));
+            x[2 * t + 1] = *reinterpret_cast<const float4 *>(xnext + min(coln + 4, D - 4));
+        }
+        xsq = fmaf(u.x, u.x, xsq);
+        xsq = fmaf(u.y, u.y, xsq);
+        xsq = fmaf(u.z, u.z, xsq);
+        xsq = fmaf(u.w, u.w, xsq);
+        xsq = fmaf(v.x, v.x, xsq);
+        xsq = fmaf(v.y, v.y, xsq);
+        xsq = fmaf(v.z, v.z, xsq);
+        xsq = fmaf(v.w, v.w, xsq);
+        amax = fmaxf(fmaxf(amax, fabsf(u.x)), fabsf(u.y));
+        amax = fmaxf(fmaxf(amax, fabsf(u.z)), fabsf(u.w));
+        amax = fmaxf(fmaxf(amax, fabsf(v.x)), fabsf(v.y));
+        amax = fmaxf(fmaxf(amax, fabsf(v.z)), fabsf(v.w));
+        uint4 xh4, xl4;
+        split8(u, v, xh4, xl4);
+        const bf16x8 xh = __builtin_bit_cast(bf16x8, xh4), xl = __builtin_bit_cast(bf16x8, xl4);
+#pragma unroll
+        for (int b0 = 0; b0 < KB; b0 += GB) {
+            bf16x8 ch[GB], cl[GB];
+#pragma unroll
+            for (int b = 0; b < GB; ++b) {
+                const uint4 *at = chunk + ((t * KB + b0 + b) * 2) * kWave;      // compile-time offset
+                ch[b] = __builtin_bit_cast(bf16x8, at[0]);
+                cl[b] = __builtin_bit_cast(bf16x8, at[kWave]);
+            }
+#pragma unroll
+            for (int b = 0; b < GB; ++b) acc[b0 + b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cl[b], xh, acc[b0 + b], 0, 0, 0);
+#pragma unroll
+            for (int b = 0; b < GB; ++b) acc[b0 + b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[b], xl, acc[b0 + b], 0, 0, 0);
+            if (b0 + GB >= KB) {
+                // the stores (and the waits for their loads) stay behind most of the step's MFMAs
+                __builtin_amdgcn_sched_barrier(0x10f);
+#pragma unroll
+                for (int i = 0; i < PP; ++i)
+                    if (t * PP + i < KB) {
+                        uint4 v4;
+                        v4.x = (uint32_t)piece[i][0]; v4.y = (uint32_t)(piece[i][0] >> 32);
+                        v4.z = (uint32_t)piece[i][1]; v4.w = (uint32_t)(piece[i][1] >> 32);
+                        nxt[((t * PP + i) * 8 + wave) * kWave + lane] = v4;
+                    }
+            }
+#pragma unroll
+            for (int b = 0; b < GB; ++b) acc[b0 + b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[b], xh, acc[b0 + b], 0, 0, 0);
+        }
+    }
+}
+
+// k_assign_chunked with the split-bf16 contraction: tiles, slices, refills and decision as there; margin as
+// in k_assign_split.  img = k_codebook_image_split of the codebook in use.
+template <int KB, int PRUNE = 0>
+__global__ __launch_bounds__(kAssignThreads) void k_assign_split_chunked(
+    const float *__restrict__ xp, const uint4 *__restrict__ img, const float *__restrict__ hneg,
+    const float *__restrict__ split_norms,
+    int64_t N, int D, int ld, int K, int M, int m, int NC, float acc_bound,
+    uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count,
+    PruneArgs pa)
+{
+    extern __shared__ float4 smem4[];
+    constexpr int CH = KB * 8 * kWave;                              // uint4 per slice
+    uint4 *buf0 = reinterpret_cast<uint4 *>(smem4), *buf1 = buf0 + CH;
+    float *lds_h = reinterpret_cast<float *>(smem4 + 2 * CH);
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int g = lane >> 5;
+    const int r = lane & 31;
+
+    for (int k = threadIdx.x; k < 32 * KB; k += blockDim.x) lds_h[k] = hneg[k];
+    const uint4 *mine = img + wave * kWave + lane;
+#pragma unroll
+    for (int p = 0; p < KB; ++p) buf0[(p * 8 + wave) * kWave + lane] = mine[p * 8 * kWave];
+    __syncthreads();
+    float hmax = 0.f;
+    for (int k = 0; k < K; ++k) hmax = fmaxf(hmax, -lds_h[k]);
+    const float cmax = sqrtf(2.f * hmax) * 1.000001f;
+    if (wave == 0) {
+        float a = 0.f, b = 0.f;
+        for (int k = lane; k < K; k += kWave) {
+            a = fmaxf(a, split_norms[2 * k]);
+            b = fmaxf(b, split_norms[2 * k + 1]);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            a = fmaxf(a, __shfl_xor(a, o, kWave));
+            b = fmaxf(b, __shfl_xor(b, o, kWave));
+        }
+        if (lane == 0) { lds_h[32 * KB] = a; lds_h[32 * KB + 1] = b; }
+    }
+    __syncthreads();
+    const float clmax = lds_h[32 * KB], dcmax = lds_h[32 * KB + 1];
+    const float split_bound = (0.00390625f * 1.00391f) * clmax + 1.52587890625e-5f * cmax + 1.00002f * dcmax;
+    const float eps = 2.f * acc_bound;
+    const float cmax_eff = (cmax * 1.02f + split_bound / acc_bound) * 1.0001f;
+
+    const int64_t rows = PRUNE == 2 ? (int64_t)*pa.active_count : N;
+    const int64_t nbt = (rows + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);
+    float amax = 0.f;
+    if ((int64_t)blockIdx.x < nbt) {
+        auto tile_row = [&](int64_t bt, int64_t &vec) -> const float * {
+            const int64_t i = (bt * kAssignWaves + wave) * kTileVec + r;
+            const int64_t ic = i < rows ? i : rows - 1;
+            const int64_t nrow = PRUNE == 2 ? (int64_t)pa.active[ic] : ic;
+            vec = i < rows ? nrow : N;
+            return xp + nrow * ld;
+        };
+        int64_t vec;
+        const float *xrow = tile_row(blockIdx.x, vec);
+        float4 x[8];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            x[2 * t] = *reinterpret_cast<const float4 *>(xrow + min(kSplitStep * t + 8 * g, D - 4));
+            x[2 * t + 1] = *reinterpret_cast<const float4 *>(xrow + min(kSplitStep * t + 8 * g + 4, D - 4));
+        }
+        int par = 0;
+        for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
+            int64_t vec_next = vec;
+            const float *xrow_next = xrow;
+            if (bt + gridDim.x < nbt) xrow_next = tile_row(bt + gridDim.x, vec_next);
+            floatx16 acc[KB];
+            float xsq = 0.f;
+            init_acc<KB>(acc, lds_h, g);
+            for (int q = 0; q < NC; ++q) {
+                const bool last = q + 1 == NC;
+                const int qn = last ? 0 : q + 1;
+                mfma_chunk_split_refill<KB>(acc, x, par ? buf1 : buf0, par ? buf0 : buf1, mine + (size_t)qn * CH,
+                                            last ? xrow_next : xrow, q, qn, D, lane, wave, xsq, amax);
+                __syncthreads();
+                par ^= 1;
+            }
+            decide<KB, PRUNE>(acc, xsq, eps, hmax, cmax_eff, lane, vec, N, M, m, codes, list, refine_count, pa);
+            xrow = xrow_next;
+            vec = vec_next;
+        }
+    }
+    publish_absmax(amax, refine_count + 1);
+}
+
 }  // namespace hclae

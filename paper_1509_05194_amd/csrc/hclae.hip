@@ -44,7 +44,7 @@ struct hclae_ctx {
     float *hneg;             // [32*kb]
     float4 *cb_image;        // [NC][kb*8*64] codebook in staging order (k_codebook_image; D-chunked shapes only)
     float *split_norms;      // [K][2] split constants of the codebook in use (contraction 1)
-    int contraction;         // 0: fp32 MFMA, 1: split-bf16 MFMA (resident shapes only)
+    int contraction;         // 0: fp32 MFMA, 1: split-bf16 MFMA
     unsigned *refine_count;
     RefineItem *refine_list; // [N_max]
     uint8_t *old_codes;      // [N_max]
@@ -255,6 +255,33 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
                            xp, Cm, ctx->hneg, ctx->split_norms, N, dact, ld, ctx->K, ctx->M, m, NC, acc_bound,
                            codes, ctx->refine_list, ctx->refine_count, pa);
+    } else if (ctx->contraction == 1) {
+        // D-chunked, split-bf16: two slices of 64 dims in LDS, one block per CU
+        const size_t lds = (size_t)2 * KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
+        const int64_t nbt = (N + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);
+        int64_t blocks = nbt < ctx->cus ? nbt : ctx->cus;
+        static bool attr_set = false;
+        if (!attr_set) {
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split_chunked<KB, 0>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split_chunked<KB, 1>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split_chunked<KB, 2>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            attr_set = true;
+        }
+        if (NC > ctx->NC || KB != ctx->kb)
+            return fail(ctx, HCLAE_EINVAL, "assign: codebook image too small for this shape");
+        const float acc_bound = (float)(3 * (dpad / kSplitStep) + 1) * 4.76837158203125e-7f;
+        const int img_total = NC * 4 * KB * kWave;
+        hipLaunchKernelGGL(k_split_norms, dim3((ctx->K + 3) / 4), dim3(256), 0, ctx->stream, Cm, ctx->K, dact, ld, ctx->split_norms);
+        hipLaunchKernelGGL(k_codebook_image_split, dim3((img_total + 255) / 256), dim3(256), 0, ctx->stream,
+                           Cm, ctx->K, dact, ld, KB, NC, reinterpret_cast<uint4 *>(ctx->cb_image));
+        auto kern = prune == 1 ? &k_assign_split_chunked<KB, 1> : prune == 2 ? &k_assign_split_chunked<KB, 2>
+                                                                              : &k_assign_split_chunked<KB, 0>;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
+                           xp, reinterpret_cast<const uint4 *>(ctx->cb_image), ctx->hneg, ctx->split_norms, N, dact, ld,
+                           ctx->K, ctx->M, m, NC, acc_bound, codes, ctx->refine_list, ctx->refine_count, pa);
     } else if (resident) {
         const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t ntiles = (N + kTileVec - 1) / kTileVec;

@@ -37,7 +37,10 @@ def _run_sweeps(X, M, K, T, mode, sweeps=2):
 
 
 @pytest.mark.parametrize("gen,N,D,M,K", [("tiny", 10000 + 3, 16, 4, 16), ("sift", 30000 + 7, 128, 3, 256),
-                                         ("sift", 5000 + 1, 20, 2, 100), ("gist", 3000 + 5, 64, 2, 256)])
+                                         ("sift", 5000 + 1, 20, 2, 100), ("gist", 3000 + 5, 64, 2, 256),
+                                         # D-chunked shapes: 8, 4, 2 and 1 codeword blocks, a ragged last slice
+                                         ("gist", 6000 + 5, 960, 2, 256), ("gist", 3000 + 1, 516, 2, 100),
+                                         ("gist", 2000 + 3, 1412, 2, 40), ("gist", 1500 + 7, 2052, 2, 16)])
 def test_split_contraction_gives_identical_results(gen, N, D, M, K):
     X = {"tiny": lambda: synth.tiny_gmm(N=N, D=D), "sift": lambda: synth.sift_like(N, D=D),
          "gist": lambda: synth.gist_like(N, D=D)}[gen]()
