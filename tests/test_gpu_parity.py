@@ -47,6 +47,9 @@ CASES = {
     "k16d2052": dict(gen="gist", N=1500 + 3, D=2052, M=2, K=16, T=1),
     "k40d960": dict(gen="gist", N=2000 + 1, D=960, M=2, K=40, T=1),
     "k100d512": dict(gen="gist", N=2000 + 7, D=512, M=2, K=100, T=1),
+    # D-chunked with more block tiles (256 vectors each) than CUs: blocks walk several tiles, and the refills
+    # of the last slice of a tile already belong to the next one
+    "k256d132n": dict(gen="sift", N=3 * 65536 + 300 + 11, D=132, M=1, K=256, T=1),
 }
 _cache = {}
 
@@ -435,7 +438,8 @@ def test_limits_of_the_shape_check(shape, oracle):
 
 @pytest.mark.parametrize("gen,N,D,M,K,T", [("sift", 40000 + 9, 128, 3, 256, 6), ("gist", 6000 + 5, 960, 2, 256, 5),
                                            ("tiny", 10000 + 3, 16, 4, 16, 6), ("sift", 8000 + 1, 132, 2, 40, 4),
-                                           ("gist", 5000 + 3, 512, 2, 100, 4), ("gist", 3000 + 7, 1412, 2, 20, 4)])
+                                           ("gist", 5000 + 3, 512, 2, 100, 4), ("gist", 3000 + 7, 1412, 2, 20, 4),
+                                           ("sift", 2 * 65536 + 5000 + 5, 132, 1, 256, 4)])
 def test_stage_equals_its_single_steps_bitwise(gen, N, D, M, K, T):
     """hclae_anneal_stage prunes its Lloyd iterations (distance bounds; centroid sums advanced by the moved
     vectors, exact integer totals); the single-step calls run every assignment and every sum over all
