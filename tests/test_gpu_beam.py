@@ -15,6 +15,8 @@ SHAPES = {
     "sift": dict(gen="sift", N=3000 + 5, D=128, M=4, K=256),
     "k100": dict(gen="sift", N=1500 + 1, D=20, M=3, K=100),
     "gist": dict(gen="gist", N=600 + 7, D=960, M=2, K=256),
+    # D-chunked scoring with more block tiles than CUs (24 vectors per block tile at L = 10)
+    "d132n": dict(gen="sift", N=7000 + 3, D=132, M=2, K=256),
 }
 
 
@@ -62,7 +64,8 @@ def _cand_err(X64, A, Cm, par, code):
 
 
 @pytest.mark.parametrize("case,L", [("tiny", 1), ("tiny", 3), ("tiny", 10), ("tiny", 32), ("sift", 2), ("sift", 10),
-                                    ("sift", 16), ("sift", 32), ("k100", 10), ("k100", 7), ("gist", 10), ("gist", 4)])
+                                    ("sift", 16), ("sift", 32), ("k100", 10), ("k100", 7), ("gist", 10), ("gist", 4),
+                                    ("d132n", 10)])
 def test_beam_step_locked(case, L, oracle):
     """Every dictionary: the GPU starts from the oracle's beam (residuals narrowed to fp32) and must
     keep the same sums in the same order wherever the oracle's neighbouring errors differ by more than
@@ -113,7 +116,8 @@ def test_beam_step_locked(case, L, oracle):
     ctx.close()
 
 
-@pytest.mark.parametrize("case,L", [("tiny", 1), ("tiny", 5), ("sift", 1), ("sift", 10), ("k100", 32), ("gist", 10)])
+@pytest.mark.parametrize("case,L", [("tiny", 1), ("tiny", 5), ("sift", 1), ("sift", 10), ("k100", 32), ("gist", 10),
+                                    ("d132n", 10)])
 def test_encode_beam_against_oracle(case, L, oracle):
     c = SHAPES[case]
     X = _data(c)
