@@ -100,6 +100,8 @@ def main():
         first = False
     torch.cuda.synchronize()
     ctx.timing_read()
+    # the state the timed steps start from: the variants below are timed over the very same steps
+    snap = None if args.no_breakdown else (C.clone(), codes.clone(), r.clone())
 
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -177,7 +179,7 @@ def main():
 
     def timed_variant(setup, restore):
         setup()
-        step(False)
+        C.copy_(snap[0]); codes.copy_(snap[1]); r.copy_(snap[2])
         torch.cuda.synchronize()
         ctx.timing_read()
         ts = time.perf_counter()
@@ -186,7 +188,9 @@ def main():
         torch.cuda.synchronize()
         ts = (time.perf_counter() - ts) / args.steps
         v_ms, v_n = ctx.timing_read()["assign"]
+        e_v = ctx.quant_error(r)
         restore()
+        assert e_v == E_final, "variant ended at another quantization error: %r vs %r" % (e_v, E_final)
         return ts, v_ms / max(v_n, 1)
 
     if not args.no_pruning and not args.no_breakdown:
@@ -199,7 +203,7 @@ def main():
             ("assign_frac_fp32_mfma_peak" if args.contraction == "f32" else "assign_algorithmic_TFLOPs"):
                 (tf / PEAK_FP32_MFMA_TFLOPS if args.contraction == "f32" else tf),
             "note": "hclae_set_pruning(0): all (T+1) assignments and all T centroid sums of a stage over all N vectors; "
-                    "same dictionaries, codes and residues"}
+                    "the same steps from the same state, same dictionaries, codes and residues"}
 
     if args.contraction == "f32" and not args.no_breakdown:
         # the same step with the optional split-bf16 contraction (hclae_set_contraction 1), reported beside the
@@ -210,7 +214,7 @@ def main():
             "assign_avg_launch_ms": s_avg,
             "assign_algorithmic_TFLOPs": flops / (s_avg * 1e-3) / 1e12,
             "note": "fp32 operands split into two bf16 terms, three bf16 MFMAs per product, fp32 accumulation; "
-                    "same codes, dictionaries and residues as the fp32 kernel"}
+                    "the same steps from the same state, same codes, dictionaries and residues as the fp32 kernel"}
 
     if not args.no_cpu_baseline:
         import oracle
