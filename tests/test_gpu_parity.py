@@ -51,6 +51,24 @@ CASES = {
     # of the last slice of a tile already belong to the next one
     "k256d132n": dict(gen="sift", N=3 * 65536 + 300 + 11, D=132, M=1, K=256, T=1),
 }
+
+
+def _random_shapes(seed, count, n_max):
+    """Seeded random shapes: any D that is a multiple of 4 (LDS-resident and D-chunked dictionaries, ragged
+    last slices), any K (padded codeword blocks), N from a few vectors to several tiles."""
+    g = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        K = int(g.choice([int(g.integers(1, 9)), int(g.integers(9, 257))]))
+        D = 4 * int(g.choice([int(g.integers(1, 40)), int(g.integers(40, 560))]))
+        N = int(g.integers(K + 1, n_max))
+        out.append(dict(gen=str(g.choice(["sift", "gist", "tiny"])), N=N, D=D, M=int(g.integers(1, 4)), K=K,
+                        T=int(g.integers(1, 4))))
+    return out
+
+
+for _i, _c in enumerate(_random_shapes(1509, 6, 4000)):
+    CASES["rnd%d" % _i] = _c
 _cache = {}
 
 
@@ -439,7 +457,8 @@ def test_limits_of_the_shape_check(shape, oracle):
 @pytest.mark.parametrize("gen,N,D,M,K,T", [("sift", 40000 + 9, 128, 3, 256, 6), ("gist", 6000 + 5, 960, 2, 256, 5),
                                            ("tiny", 10000 + 3, 16, 4, 16, 6), ("sift", 8000 + 1, 132, 2, 40, 4),
                                            ("gist", 5000 + 3, 512, 2, 100, 4), ("gist", 3000 + 7, 1412, 2, 20, 4),
-                                           ("sift", 2 * 65536 + 5000 + 5, 132, 1, 256, 4)])
+                                           ("sift", 2 * 65536 + 5000 + 5, 132, 1, 256, 4)]
+                         + [(c["gen"], c["N"], c["D"], c["M"], c["K"], c["T"] + 2) for c in _random_shapes(5194, 10, 9000)])
 def test_stage_equals_its_single_steps_bitwise(gen, N, D, M, K, T):
     """hclae_anneal_stage prunes its Lloyd iterations (distance bounds; centroid sums advanced by the moved
     vectors, exact integer totals); the single-step calls run every assignment and every sum over all
