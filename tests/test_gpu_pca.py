@@ -25,9 +25,23 @@ def _data(c):
     return synth.gist_like(c["N"], D=c["D"])
 
 
+_CONTRACTION = 0
+
+
+@pytest.fixture(autouse=True, params=[0, 1], ids=["f32", "splitbf16"])
+def contraction(request):
+    """Both matrix-core arithmetics of the distance contraction (prefix assignments included): same bar."""
+    global _CONTRACTION
+    _CONTRACTION = request.param
+    yield request.param
+    _CONTRACTION = 0
+
+
 def _ctx(c):
     from paper_1509_05194_amd import hclae
-    return hclae.Context(c["N"], c["D"], c["M"], c["K"])
+    ctx = hclae.Context(c["N"], c["D"], c["M"], c["K"])
+    ctx.set_contraction(_CONTRACTION)
+    return ctx
 
 
 @pytest.mark.parametrize("case", list(SHAPES))
