@@ -137,13 +137,16 @@ __device__ __forceinline__ void stage_codebook(
 
 // Loads the 64-dim chunk q of the wave's 32-vector tile into B-operand order:
 // lane (h, r) gets x'[row r][64q + 8s + 4h .. +3] for s = 0..7.
+// PREFIX: only the first `steps` 8-dim steps of the chunk are wanted (the others are not contracted either).
+template <bool PREFIX = false>
 __device__ __forceinline__ void load_x_chunk(
-    float4 (&x)[8], const float *__restrict__ xrow, int q, int h, int D)
+    float4 (&x)[8], const float *__restrict__ xrow, int q, int h, int D, int steps = 8)
 {
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
         const int col = kChunkD * q + 8 * s + 4 * h;
-        x[s] = (col < D) ? *reinterpret_cast<const float4 *>(xrow + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+        x[s] = (col < D && (!PREFIX || s < steps)) ? *reinterpret_cast<const float4 *>(xrow + col)
+                                                   : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 }
 
@@ -157,13 +160,16 @@ __device__ __forceinline__ void publish_absmax(float amax, unsigned *slot)
     if (lane_id() == 0) atomicMax(slot, __float_as_uint(amax));
 }
 
-template <int KB>
+// PREFIX: the chunk ends after `steps` of its eight 8-dim steps (a short prefix of the coordinates counts;
+// the codebook image is zero beyond it, so the steps left out would add nothing).
+template <int KB, bool PREFIX = false>
 __device__ __forceinline__ void mfma_chunk(
     floatx16 (&acc)[KB], const float4 (&x)[8], const float4 *__restrict__ lds, int q, int S, int lane,
-    float &xsq, float &amax)
+    float &xsq, float &amax, int steps = 8)
 {
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
+        if (PREFIX && s >= steps) break;
         float4 a[KB];
 #pragma unroll
         for (int b = 0; b < KB; ++b) a[b] = lds[(b * S + 8 * q + s) * kWave + lane];
@@ -310,7 +316,9 @@ __device__ __forceinline__ void decide(
 // 32*KB * 64*NC floats fit.  Each wave owns tiles of 32 vectors, streams them from HBM straight
 // into B-operand registers in 64-dim chunks (two register sets, the next chunk in flight while
 // the current one is contracted) and keeps all 32*KB scores of a vector in accumulators.
-template <int KB, int PRUNE = 0>
+// PREFIX (with PRUNE 0): the last 64-dim chunk stops after the 8-dim steps that hold coordinates below D
+// (assignments on a short prefix of the coordinates, Sec. 3.2: D = 2 costs one step, not eight).
+template <int KB, int PRUNE = 0, bool PREFIX = false>
 __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     const float *__restrict__ xp, const float *__restrict__ Cm, const float *__restrict__ hneg,
     int64_t N, int D, int ld, int K, int M, int m, int NC, float eps,
@@ -364,16 +372,18 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     float xsq = 0.f, amax = 0.f;
     int64_t tile = t0;
     int q = 0;
-    load_x_chunk(xa, row_ptr(tile), 0, h, D);
+    const int steps_last = PREFIX ? (D - kChunkD * (NC - 1) + 7) / 8 : 8;
+    auto steps_of = [&](int qq) { return (PREFIX && qq == NC - 1) ? steps_last : 8; };
+    load_x_chunk<PREFIX>(xa, row_ptr(tile), 0, h, D, steps_of(0));
     // Steps come in pairs so that the two register sets alternate with static names.
     for (int64_t g = 0; g < G; g += 2) {
         // ---- step g on xa; prefetch step g+1 into xb
         int64_t tile1 = tile;
         int q1 = q + 1;
         if (q1 == NC) { q1 = 0; tile1 = tile + tstride; }
-        if (g + 1 < G) load_x_chunk(xb, row_ptr(tile1), q1, h, D);
+        if (g + 1 < G) load_x_chunk<PREFIX>(xb, row_ptr(tile1), q1, h, D, steps_of(q1));
         if (q == 0) { init_acc<KB>(acc, lds_h, h); xsq = 0.f; }
-        mfma_chunk<KB>(acc, xa, lds_c, q, S, lane, xsq, amax);
+        mfma_chunk<KB, PREFIX>(acc, xa, lds_c, q, S, lane, xsq, amax, steps_of(q));
         if (q == NC - 1)
             decide<KB, PRUNE>(acc, xsq, eps, hmax, cmax, lane, vec_of(tile), N, M, m, codes, list, refine_count, pa);
         if (g + 1 >= G) break;
@@ -381,9 +391,9 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
         int64_t tile2 = tile1;
         int q2 = q1 + 1;
         if (q2 == NC) { q2 = 0; tile2 = tile1 + tstride; }
-        if (g + 2 < G) load_x_chunk(xa, row_ptr(tile2), q2, h, D);
+        if (g + 2 < G) load_x_chunk<PREFIX>(xa, row_ptr(tile2), q2, h, D, steps_of(q2));
         if (q1 == 0) { init_acc<KB>(acc, lds_h, h); xsq = 0.f; }
-        mfma_chunk<KB>(acc, xb, lds_c, q1, S, lane, xsq, amax);
+        mfma_chunk<KB, PREFIX>(acc, xb, lds_c, q1, S, lane, xsq, amax, steps_of(q1));
         if (q1 == NC - 1)
             decide<KB, PRUNE>(acc, xsq, eps, hmax, cmax, lane, vec_of(tile1), N, M, m, codes, list, refine_count, pa);
         tile = tile2;

@@ -297,7 +297,16 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             attr_set = true;
         }
-        auto kern = prune == 1 ? &k_assign_resident<KB, 1> : prune == 2 ? &k_assign_resident<KB, 2> : &k_assign_resident<KB, 0>;
+        // the last chunk holds fewer than eight 8-dim steps with coordinates that count: stop after them
+        const bool prefix = prune == 0 && (dact % kChunkD) != 0 && (dact % kChunkD) <= kChunkD - 8;
+        static bool attr_set_p = false;
+        if (prefix && !attr_set_p) {
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 0, true>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            attr_set_p = true;
+        }
+        auto kern = prefix ? &k_assign_resident<KB, 0, true>
+                  : prune == 1 ? &k_assign_resident<KB, 1> : prune == 2 ? &k_assign_resident<KB, 2> : &k_assign_resident<KB, 0>;
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
                            xp, Cm, ctx->hneg, N, dact, ld, ctx->K, ctx->M, m, NC, eps,
                            codes, ctx->refine_list, ctx->refine_count, pa);
