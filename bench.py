@@ -17,10 +17,13 @@ import numpy as np
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0             # MI355X HBM3E peak
 
-# HBM bytes per N=1M launch of the assign kernel from two rocprofv3 --pmc runs (FETCH_SIZE 250,693.0 KiB
-# x 2.000, WRITE_SIZE 8,961.3 KiB x 1.000; factors from a 512 MB device copy in the same runs), recorded
-# in profiles/da_sweep_sift1m_counters.md.  Algorithmic bytes are 513e6.
-ASSIGN_TRAFFIC_BYTES = 5.226e8   # (250693.0 * 2.000 + 8961.3) KiB
+# HBM bytes per N=1M launch of the assign kernel from two rocprofv3 --pmc runs (FETCH_SIZE 250,684.0 KiB
+# x 2.000, WRITE_SIZE 20,701.9 KiB x 1.000; factors from a 512 MB device copy in the same runs), recorded
+# in profiles/da_sweep_sift1m_counters.md: the launches that also store the distance bounds.  Algorithmic
+# bytes are 521e6 (x', codes, bounds).
+ASSIGN_TRAFFIC_BYTES = 5.346e8   # (250684.0 * 2.000 + 20701.9) KiB
+# the same for the D-chunked kernel at N=1M, D=960 (profiles/da_sweep_gist1m_counters.md); algorithmic 3.841e9
+ASSIGN_TRAFFIC_BYTES_GIST = 4.037e9   # (1962932.8 * 2.000 + 16579.8) KiB
 
 
 def main():
@@ -147,7 +150,9 @@ def main():
                                                  % ("k_assign_split_chunked<8>" if gist else "k_assign_split<8>")),
                      "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": ASSIGN_TRAFFIC_BYTES if (N, D, K) == (1_000_000, 128, 256) and args.contraction == "f32" else None,
+                     "traffic": (ASSIGN_TRAFFIC_BYTES if (N, D, K) == (1_000_000, 128, 256) else
+                                 ASSIGN_TRAFFIC_BYTES_GIST if (N, D, K) == (1_000_000, 960, 256) else None)
+                                if args.contraction == "f32" and not args.no_pruning else None,
                      "avg_launch_ms": assign_ms, "launches": a_n, "flops_per_launch": flops},
     }
 
