@@ -236,7 +236,7 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
     if (resident && ctx->contraction == 1) {
         const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
-        int64_t blocks = (ntiles + kAssignWaves - 1) / kAssignWaves;
+        int64_t blocks = (ntiles + 3) / 4;                      // few tiles: one per SIMD before any SIMD gets two
         if (blocks > ctx->cus) blocks = ctx->cus;
         static bool attr_set = false;
         if (!attr_set) {
@@ -285,7 +285,7 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
     } else if (resident) {
         const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
-        int64_t blocks = (ntiles + kAssignWaves - 1) / kAssignWaves;
+        int64_t blocks = (ntiles + 3) / 4;                      // few tiles: one per SIMD before any SIMD gets two
         if (blocks > ctx->cus) blocks = ctx->cus;
         static bool attr_set = false;
         if (!attr_set) {
@@ -1034,7 +1034,7 @@ static int launch_beam_score_kb(hclae_ctx *ctx, const float *rows, const double 
     Timed t_(ctx, HCLAE_T_BEAM_SCORE);
     if (ctx->resident && ctx->contraction == 1) {
         const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
-        int64_t blocks = (ntiles + kAssignWaves - 1) / kAssignWaves;
+        int64_t blocks = (ntiles + 3) / 4;                      // few tiles: one per SIMD before any SIMD gets two
         if (blocks > ctx->cus) blocks = ctx->cus;
         static bool attr_set = false;
         if (!attr_set) {
@@ -1049,7 +1049,7 @@ static int launch_beam_score_kb(hclae_ctx *ctx, const float *rows, const double 
                            rows, err, Cm, ctx->hneg, ctx->split_norms, N, Lc, Ln, D, D, ctx->K, NC, acc_bound, masks);
     } else if (ctx->resident) {
         const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
-        int64_t blocks = (ntiles + kAssignWaves - 1) / kAssignWaves;
+        int64_t blocks = (ntiles + 3) / 4;                      // few tiles: one per SIMD before any SIMD gets two
         if (blocks > ctx->cus) blocks = ctx->cus;
         static bool attr_set = false;
         if (!attr_set) {
