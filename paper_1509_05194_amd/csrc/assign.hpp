@@ -547,8 +547,9 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
 // few is computed afresh from x' (expanded form in fp32 with its rounding bound) and joins the lower bound.
 // Vectors that this settles get their aged bounds and leave the list.  Eight lanes share a vector.
 // Dynamic LDS: kVolatile rows of D floats.
-constexpr int kBoundSpan = 1024;
-__global__ __launch_bounds__(256) void k_bounds_step(
+constexpr int kBoundSpan = 4096;
+constexpr int kBoundThreads = 1024;
+__global__ __launch_bounds__(kBoundThreads) void k_bounds_step(
     const uint8_t *__restrict__ codes, int64_t N, int M, int m, const float *__restrict__ drift, int K,
     float *__restrict__ bu, float *__restrict__ bl, uint32_t *__restrict__ list, unsigned *__restrict__ count,
     const float *__restrict__ xp, int D, const float *__restrict__ Cm)
@@ -560,15 +561,15 @@ __global__ __launch_bounds__(256) void k_bounds_step(
     __shared__ unsigned nfound, nkept, base;
     __shared__ float s_vnorm[kVolatile], s_top[kVolatile + 1];
     __shared__ int s_tk[kVolatile + 1];
-    sdrift[threadIdx.x] = (int)threadIdx.x < K ? drift[threadIdx.x] : 0.f;
+    if (threadIdx.x < 256) sdrift[threadIdx.x] = (int)threadIdx.x < K ? drift[threadIdx.x] : 0.f;
     if (threadIdx.x == 0) { nfound = 0u; nkept = 0u; }
     const int64_t n0 = (int64_t)blockIdx.x * kBoundSpan;
-    constexpr int U = kBoundSpan / 256;
+    constexpr int U = kBoundSpan / kBoundThreads;
     int c[U];
     float u[U], l[U];
 #pragma unroll
     for (int j = 0; j < U; ++j) {                                   // all loads first: in flight during the ranking
-        const int64_t n = n0 + j * 256 + threadIdx.x;
+        const int64_t n = n0 + j * kBoundThreads + threadIdx.x;
         const int64_t nn = n < N ? n : N - 1;
         c[j] = codes[nn * M + m];
         u[j] = bu[nn];
@@ -581,7 +582,7 @@ __global__ __launch_bounds__(256) void k_bounds_step(
     {
 #pragma unroll
         for (int j = 0; j < U; ++j) {
-            const int64_t n = n0 + j * 256 + threadIdx.x;
+            const int64_t n = n0 + j * kBoundThreads + threadIdx.x;
             if (n < N) {
                 const float un = (u[j] + sdrift[c[j]]) * 1.000001f;  // rounded up
                 const float ln = (l[j] - ((c[j] == k1) ? d2 : d1)) * 0.999999f;   // rounded down while positive
@@ -601,20 +602,22 @@ __global__ __launch_bounds__(256) void k_bounds_step(
     if (!apart) {
         if (threadIdx.x == 0 && nf) base = atomicAdd(count, nf);
         __syncthreads();
-        for (unsigned i = threadIdx.x; i < nf; i += 256) list[base + i] = found[i];
+        for (unsigned i = threadIdx.x; i < nf; i += kBoundThreads) list[base + i] = found[i];
         return;
     }
-    for (int e = threadIdx.x; e < kVolatile * D; e += 256) {
+    for (int e = threadIdx.x; e < kVolatile * D; e += kBoundThreads) {
         const int j = e / D;
         vrow[e] = s_tk[j] >= 0 ? Cm[(size_t)s_tk[j] * D + (e - j * D)] : 0.f;
     }
     __syncthreads();
     {
-        const int w = threadIdx.x >> 6;                             // 256 threads = kVolatile waves, one row each
-        double q = 0.0;
-        for (int d = lane_id(); d < D; d += kWave) q += (double)vrow[w * D + d] * (double)vrow[w * D + d];
-        q = wave_sum(q);
-        if (lane_id() == 0) s_vnorm[w] = (float)q;
+        const int w = threadIdx.x >> 6;                             // the first kVolatile waves, one row each
+        if (w < kVolatile) {
+            double q = 0.0;
+            for (int d = lane_id(); d < D; d += kWave) q += (double)vrow[w * D + d] * (double)vrow[w * D + d];
+            q = wave_sum(q);
+            if (lane_id() == 0) s_vnorm[w] = (float)q;
+        }
     }
     __syncthreads();
     const int sub = threadIdx.x & 7;
@@ -622,7 +625,7 @@ __global__ __launch_bounds__(256) void k_bounds_step(
     // fp32 rounding of ||x'||^2 - 2 x'.c + ||c||^2 (D/8 chained fmas per lane, three shuffle adds, the final
     // sums) as a fraction of ||x'||^2 + 2|x'.c| + ||c||^2
     const float slack = (float)(D / 8 + 8) * 1.2e-7f;
-    for (unsigned i0 = 0; i0 < nf; i0 += 32) {
+    for (unsigned i0 = 0; i0 < nf; i0 += kBoundThreads / 8) {
         const unsigned e = i0 + (threadIdx.x >> 3);
         const bool ok = e < nf;
         const int64_t n = found[ok ? e : nf - 1];
@@ -670,7 +673,7 @@ __global__ __launch_bounds__(256) void k_bounds_step(
     const unsigned nk = nkept;
     if (threadIdx.x == 0 && nk) base = atomicAdd(count, nk);
     __syncthreads();
-    for (unsigned i = threadIdx.x; i < nk; i += 256) list[base + i] = kept[i];
+    for (unsigned i = threadIdx.x; i < nk; i += kBoundThreads) list[base + i] = kept[i];
 }
 
 constexpr int kMovedSpan = 1024;

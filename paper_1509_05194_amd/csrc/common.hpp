@@ -45,7 +45,7 @@ __device__ __forceinline__ double block_sum(double v, double *scratch)
 }
 
 // The kVolatile + 1 largest entries of drift[0..K) (K <= 256), descending, with their indices; computed by
-// the first wave of a 256-thread block into LDS (top[], tk[]; unused slots 0 / -1).  Ends with a barrier.
+// the first wave of the block into LDS (top[], tk[]; unused slots 0 / -1).  Ends with a barrier.
 constexpr int kVolatile = 4;
 __device__ __forceinline__ void top_drifts(const float *sdrift, int K, float *top, int *tk)
 {

@@ -367,10 +367,10 @@ int launch_bounds_step(hclae_ctx *ctx, int m, int64_t N, const uint8_t *codes, c
     static bool attr_set = false;
     if (!attr_set) {
         HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bounds_step),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget - 16 * 1024));
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget - 40 * 1024));
         attr_set = true;
     }
-    hipLaunchKernelGGL(k_bounds_step, dim3((unsigned)((N + kBoundSpan - 1) / kBoundSpan)), dim3(256),
+    hipLaunchKernelGGL(k_bounds_step, dim3((unsigned)((N + kBoundSpan - 1) / kBoundSpan)), dim3(kBoundThreads),
                        (size_t)kVolatile * ctx->D * sizeof(float), ctx->stream,
                        codes, N, ctx->M, m, ctx->drift, ctx->K, ctx->bnd_u, ctx->bnd_l,
                        ctx->active, ctx->moved_count + 3, xp, ctx->D, Cm);
