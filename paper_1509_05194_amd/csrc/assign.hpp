@@ -690,16 +690,21 @@ __global__ __launch_bounds__(256) void k_refine(
     __shared__ unsigned long long found[kMovedSpan];
     __shared__ unsigned nfound, base;
     const unsigned count = *refine_count;
+    // With the moved-vector list wanted, the two jobs run side by side: the first half of the blocks re-checks,
+    // the second half scans the other recomputed vectors (below).
+    const unsigned nr = mv.prev ? gridDim.x / 2 : gridDim.x;        // blocks that re-check
+    const bool scans = blockIdx.x >= nr;
     // re-checked vectors that changed cluster are staged in LDS like the others while a block's share fits
-    const bool staged = count <= gridDim.x * (unsigned)kMovedSpan;
+    const bool staged = count <= nr * (unsigned)kMovedSpan;
     if (mv.prev) {
         if (threadIdx.x == 0) nfound = 0u;
         __syncthreads();
     }
     const int l16 = threadIdx.x & (kRefineLanes - 1);
-    const unsigned groups = gridDim.x * (256 / kRefineLanes);
+    const unsigned groups = nr * (256 / kRefineLanes);
     const int d4 = D >> 2;
-    for (unsigned e = blockIdx.x * (256 / kRefineLanes) + threadIdx.x / kRefineLanes; e < count; e += groups) {
+    for (unsigned e = scans ? count : blockIdx.x * (256 / kRefineLanes) + threadIdx.x / kRefineLanes; e < count;
+         e += groups) {
         const RefineItem it = list[e];
         int total = 0;
 #pragma unroll
@@ -766,15 +771,18 @@ __global__ __launch_bounds__(256) void k_refine(
         }
     }
     if (!mv.prev) return;
-    __syncthreads();
-    if (threadIdx.x == 0 && nfound) base = atomicAdd(mv.count, nfound);
-    __syncthreads();
-    for (unsigned i = threadIdx.x; i < nfound; i += 256) mv.list[base + i] = found[i];
-    __syncthreads();
+    if (!scans) {
+        __syncthreads();
+        if (threadIdx.x == 0 && nfound) base = atomicAdd(mv.count, nfound);
+        __syncthreads();
+        for (unsigned i = threadIdx.x; i < nfound; i += 256) mv.list[base + i] = found[i];
+        return;
+    }
     // The other recomputed vectors have their final code already.  A block takes kMovedSpan list entries at a
     // time, stages what it finds in LDS and claims its stretch of the output with one counter add.
     const int64_t total = (int64_t)*mv.cand_count;
-    for (int64_t i0 = (int64_t)blockIdx.x * kMovedSpan; i0 < total; i0 += (int64_t)gridDim.x * kMovedSpan) {
+    const int64_t ns = gridDim.x - nr;                              // blocks that scan
+    for (int64_t i0 = (int64_t)(blockIdx.x - nr) * kMovedSpan; i0 < total; i0 += ns * kMovedSpan) {
         if (threadIdx.x == 0) nfound = 0u;
         __syncthreads();
 #pragma unroll
