@@ -3,6 +3,8 @@ header declares, and rejects bad arguments before touching HIP."""
 import ctypes
 import os
 import re
+import subprocess
+import sys
 
 import pytest
 
@@ -75,3 +77,18 @@ def test_product_path_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in src.lower().replace("the cpu oracle's tests", ""), f
+
+
+def test_null_ctx_is_einval_for_the_settings():
+    L = hclae.lib()
+    assert L.hclae_set_pruning(None, 1) == hclae.EINVAL
+    assert L.hclae_set_contraction(None, 0) == hclae.EINVAL
+    assert L.hclae_set_beam_width(None, 10) == hclae.EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build runs on one GPU: bench.py says so and exits before it touches a device."""
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert p.returncode != 0
+    assert "ONE GPU" in p.stderr
