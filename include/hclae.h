@@ -177,8 +177,7 @@ int hclae_online_import(hclae_ctx *ctx, const double *run_sum, const int64_t *ru
  * form the scores x'.c - ||c||^2/2.  Either way the scores only pre-select candidates within a rigorous
  * error margin and the decision is the fp64 direct-form re-check, so codes, dictionaries and residues do
  * not depend on the mode; only the number of vectors that take the re-check does.  Mode 1 applies to the
- * assignments of every shape; the multi-path scoring (hclae_beam_step, hclae_encode_beam) follows it where
- * the whole padded dictionary fits LDS (e.g. K = 256, D <= 128) and keeps the fp32 kernel elsewhere.
+ * assignments and to the multi-path scoring (hclae_beam_step, hclae_encode_beam) of every shape.
  */
 int hclae_set_contraction(hclae_ctx *ctx, int mode);
 

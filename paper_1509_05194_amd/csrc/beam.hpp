@@ -345,6 +345,99 @@ __global__ __launch_bounds__(kAssignThreads) void k_beam_score_chunked(
     }
 }
 
+// k_beam_score_chunked with the split-bf16 contraction (see k_assign_split_chunked and k_beam_score_split):
+// img = k_codebook_image_split of the codebook in use; gamma is the accumulation bound.
+template <int KB>
+__global__ __launch_bounds__(kAssignThreads) void k_beam_score_split_chunked(
+    const float *__restrict__ rows, const double *__restrict__ err, const uint4 *__restrict__ img,
+    const float *__restrict__ hneg, const float *__restrict__ split_norms,
+    int64_t N, int Lc, int Ln, int D, int ld, int K, int NC, float gamma,
+    BeamMask *__restrict__ masks)
+{
+    extern __shared__ float4 smem4[];
+    constexpr int CH = KB * 8 * kWave;                              // uint4 per slice
+    uint4 *buf0 = reinterpret_cast<uint4 *>(smem4), *buf1 = buf0 + CH;
+    float *lds_h = reinterpret_cast<float *>(smem4 + 2 * CH);
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int h = lane >> 5;
+    const int r = lane & 31;
+
+    for (int k = threadIdx.x; k < 32 * KB; k += blockDim.x) lds_h[k] = hneg[k];
+    const uint4 *mine = img + wave * kWave + lane;
+#pragma unroll
+    for (int p = 0; p < KB; ++p) buf0[(p * 8 + wave) * kWave + lane] = mine[p * 8 * kWave];
+    __syncthreads();
+    float hmax = 0.f;
+    for (int k = 0; k < K; ++k) hmax = fmaxf(hmax, -lds_h[k]);
+    float cmax = sqrtf(2.f * hmax) * 1.000001f;
+    if (wave == 0) {
+        float a = 0.f, b = 0.f;
+        for (int k = lane; k < K; k += kWave) {
+            a = fmaxf(a, split_norms[2 * k]);
+            b = fmaxf(b, split_norms[2 * k + 1]);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            a = fmaxf(a, __shfl_xor(a, o, kWave));
+            b = fmaxf(b, __shfl_xor(b, o, kWave));
+        }
+        if (lane == 0) { lds_h[32 * KB] = a; lds_h[32 * KB + 1] = b; }
+    }
+    __syncthreads();
+    {   // dropped terms per unit ||r||, folded into the norm the margin multiplies (see k_assign_split)
+        const float clmax = lds_h[32 * KB], dcmax = lds_h[32 * KB + 1];
+        const float split_bound = (0.00390625f * 1.00391f) * clmax + 1.52587890625e-5f * cmax + 1.00002f * dcmax;
+        cmax = (cmax * 1.02f + split_bound / gamma) * 1.0001f;
+    }
+
+    const int V = kTileVec / Lc;
+    const int RT = V * Lc;
+    const int gbase = (r < RT) ? (r / Lc) * Lc : 0;
+    const int64_t nrows = N * Lc;
+    const int64_t ntiles = (N + V - 1) / V;
+    const int64_t nbt = (ntiles + kAssignWaves - 1) / kAssignWaves;
+    if ((int64_t)blockIdx.x >= nbt) return;
+    auto tile_row = [&](int64_t bt, bool &valid) -> int64_t {
+        const int64_t row = (bt * kAssignWaves + wave) * RT + r;
+        valid = r < RT && row < nrows;
+        return valid ? row : nrows - 1;
+    };
+    float amax = 0.f;
+    bool valid;
+    int64_t row = tile_row(blockIdx.x, valid);
+    const float *xrow = rows + row * ld;
+    float4 x[8];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        x[2 * t] = *reinterpret_cast<const float4 *>(xrow + min(kSplitStep * t + 8 * h, D - 4));
+        x[2 * t + 1] = *reinterpret_cast<const float4 *>(xrow + min(kSplitStep * t + 8 * h + 4, D - 4));
+    }
+    int par = 0;
+    for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
+        bool valid_next = valid;
+        int64_t row_next = row;
+        if (bt + gridDim.x < nbt) row_next = tile_row(bt + gridDim.x, valid_next);
+        const float *xrow_next = rows + row_next * ld;
+        const float e_l = err ? (float)err[row] : 0.f;
+        floatx16 acc[KB];
+        float xsq = 0.f;
+        init_acc<KB>(acc, lds_h, h);
+        for (int q = 0; q < NC; ++q) {
+            const bool last = q + 1 == NC;
+            const int qn = last ? 0 : q + 1;
+            mfma_chunk_split_refill<KB>(acc, x, par ? buf1 : buf0, par ? buf0 : buf1, mine + (size_t)qn * CH,
+                                        last ? xrow_next : xrow, q, qn, D, lane, wave, xsq, amax);
+            __syncthreads();
+            par ^= 1;
+        }
+        beam_select<KB>(acc, xsq, e_l, gamma, hmax, cmax, lane, gbase, Lc, Ln, valid, masks + (valid ? row : 0));
+        row = row_next;
+        valid = valid_next;
+        xrow = xrow_next;
+    }
+}
+
 constexpr int kExpandChunk = 32;     // candidates evaluated and ranked at a time
 constexpr int kExpandList = 512;     // candidates listed in LDS at a time
 

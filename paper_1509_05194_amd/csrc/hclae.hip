@@ -1047,6 +1047,27 @@ static int launch_beam_score_kb(hclae_ctx *ctx, const float *rows, const double 
         hipLaunchKernelGGL(k_split_norms, dim3((ctx->K + 3) / 4), dim3(256), 0, ctx->stream, Cm, ctx->K, D, D, ctx->split_norms);
         hipLaunchKernelGGL((k_beam_score_split<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
                            rows, err, Cm, ctx->hneg, ctx->split_norms, N, Lc, Ln, D, D, ctx->K, NC, acc_bound, masks);
+    } else if (ctx->contraction == 1) {
+        // D-chunked, split-bf16: two slices of 64 dims in LDS, one block per CU
+        const size_t lds = (size_t)2 * KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
+        const int64_t nbt = (ntiles + kAssignWaves - 1) / kAssignWaves;
+        int64_t blocks = nbt < ctx->cus ? nbt : ctx->cus;
+        static bool attr_set = false;
+        if (!attr_set) {
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_beam_score_split_chunked<KB>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            attr_set = true;
+        }
+        if (NC > ctx->NC || KB != ctx->kb)
+            return fail(ctx, HCLAE_EINVAL, "beam: codebook image too small for this shape");
+        const float acc_bound = (float)(3 * (dpad / kSplitStep) + 9) * 4.76837158203125e-7f;
+        const int img_total = NC * 4 * KB * kWave;
+        hipLaunchKernelGGL(k_split_norms, dim3((ctx->K + 3) / 4), dim3(256), 0, ctx->stream, Cm, ctx->K, D, D, ctx->split_norms);
+        hipLaunchKernelGGL(k_codebook_image_split, dim3((img_total + 255) / 256), dim3(256), 0, ctx->stream,
+                           Cm, ctx->K, D, D, KB, NC, reinterpret_cast<uint4 *>(ctx->cb_image));
+        hipLaunchKernelGGL((k_beam_score_split_chunked<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
+                           rows, err, reinterpret_cast<const uint4 *>(ctx->cb_image), ctx->hneg, ctx->split_norms,
+                           N, Lc, Ln, D, D, ctx->K, NC, acc_bound, masks);
     } else if (ctx->resident) {
         const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         int64_t blocks = (ntiles + 3) / 4;                      // few tiles: one per SIMD before any SIMD gets two
