@@ -17,6 +17,11 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "da_oracle.c")
 _LIB = os.path.join(_HERE, "libda_oracle.so")
+# The mutation tests (tests/test_oracle_mutations.py) point this at a copy of da_oracle.c with one planted
+# mistake and check that the pins notice it.
+if os.environ.get("DA_ORACLE_SRC"):
+    _SRC = os.environ["DA_ORACLE_SRC"]
+    _LIB = _SRC + ".so"
 _lib = None
 
 
