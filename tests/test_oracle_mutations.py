@@ -38,6 +38,21 @@ MUTATIONS = [
     ("encode_skips_the_residue_update",
      "        da_assign(r, C, N, D, M, K, m, codes, NULL, NULL, NULL);\n        da_cool(r, codes, C, N, D, M, K, m);\n    }\n}",
      "        da_assign(r, C, N, D, M, K, m, codes, NULL, NULL, NULL);\n    }\n}", 0),
+    # online learning (Sec. 3.4) and the improved k-means (Sec. 3.2)
+    ("online_counts_not_kept", "            cm[k] += 1;", "            cm[k] = 1;", 0),
+    ("online_without_second_assign",
+     "        da_assign(r, C, n, D, M, K, m, codes, NULL, NULL, NULL);\n        da_cool(r, codes, C, n, D, M, K, m);\n    }\n    return da_quant_error(r, n, D);",
+     "        da_cool(r, codes, C, n, D, M, K, m);\n    }\n    return da_quant_error(r, n, D);", 0),
+    ("rotation_transposed", "(transpose ? R[(size_t)j * D + i] : R[(size_t)i * D + j])",
+     "(transpose ? R[(size_t)i * D + j] : R[(size_t)j * D + i])", 0),
+    ("prefix_assignment_uses_all_coordinates", "for (int d = 0; d < dact; ++d) {", "for (int d = 0; d < D; ++d) {", 0),
+    ("prefix_mean_over_the_prefix_only",
+     "for (int d = 0; d < D; ++d) Cp[(size_t)k * D + d] = S[(size_t)k * D + d] / (double)cnt[k];",
+     "for (int d = 0; d < dims[i]; ++d) Cp[(size_t)k * D + d] = S[(size_t)k * D + d] / (double)cnt[k];", 0),
+    ("dictionary_not_rotated_back", "    da_rotate(Cp, K, D, R, 1, Cm);", "    da_rotate(Cp, K, D, R, 0, Cm);", 0),
+    ("reconstruction_skips_the_last_dictionary",
+     "        for (int m = 0; m < M; ++m) {\n            const double *c = C + ((size_t)m * K + codes[n * M + m]) * D;",
+     "        for (int m = 0; m + 1 < M; ++m) {\n            const double *c = C + ((size_t)m * K + codes[n * M + m]) * D;", 0),
 ]
 
 
