@@ -81,5 +81,46 @@ def test_pins_catch_a_planted_mistake(tmp_path, name, old, new, which):
     dst = tmp_path / ("da_oracle_%s.c" % name)
     dst.write_text(mutant)
     p = _run_pins(dict(os.environ, DA_ORACLE_SRC=str(dst)))
-    assert p.returncode != 0, "no pin noticed the planted mistake '%s'" % name
-    assert "failed" in p.stdout or "error" in p.stdout.lower(), p.stdout[-1500:]
+    assert p.returncode == 1, "no pin noticed the planted mistake '%s'\n%s" % (name, p.stdout[-1500:] + p.stderr[-1500:])
+    assert " failed" in p.stdout, p.stdout[-1500:]
+
+
+# ---- the NumPy half of the oracle (schedule, principal axes, dictionary order, code statistics) ------------
+PY_MUTATIONS = [
+    ("schedule_rounds_down", "d = int(np.ceil(D ** (i / I) - 1e-9))", "d = int(np.floor(D ** (i / I) - 1e-9))"),
+    ("axes_least_variance_first", 'order = np.argsort(-w, kind="stable")', 'order = np.argsort(w, kind="stable")'),
+    ("variance_without_the_mean", "((C - C.mean(axis=1, keepdims=True)) ** 2)", "((C) ** 2)"),
+    ("order_ascending", "key=lambda j: (-v[j], j)", "key=lambda j: (v[j], j)"),
+    ("entropy_in_nats", "return float(-(p * np.log2(p)).sum())", "return float(-(p * np.log(p)).sum())"),
+    ("information_adds_the_joint_entropy", "+ entropy_bits(J.sum(0)) - entropy_bits(J)",
+     "+ entropy_bits(J.sum(0)) + entropy_bits(J)"),
+    ("joint_histogram_of_one_column", "(codes[:, a].astype(np.int64), codes[:, b].astype(np.int64))",
+     "(codes[:, a].astype(np.int64), codes[:, a].astype(np.int64))"),
+]
+
+
+def _run_pins_with_package(tmp_path, init_text):
+    pkg = tmp_path / "oracle"
+    pkg.mkdir()
+    (pkg / "__init__.py").write_text(init_text)
+    (pkg / "da_oracle.c").write_text(open(SRC).read())
+    # the copied package is imported first, so every later "import oracle" of the child gets it
+    code = ("import sys; sys.path.insert(0, %r); import oracle; assert oracle.__file__.startswith(%r); "
+            "import pytest; sys.exit(pytest.main([%r, '-x', '-q', '-p', 'no:cacheprovider']))"
+            % (str(tmp_path), str(tmp_path), os.path.join(ROOT, "tests", "test_oracle_pins.py")))
+    env = {k: v for k, v in os.environ.items() if k != "DA_ORACLE_SRC"}
+    return subprocess.run([sys.executable, "-c", code], cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
+
+
+def test_pins_pass_on_a_faithful_copy_of_the_package(tmp_path):
+    p = _run_pins_with_package(tmp_path, open(os.path.join(ROOT, "oracle", "__init__.py")).read())
+    assert p.returncode == 0, p.stdout[-2000:] + p.stderr[-2000:]
+
+
+@pytest.mark.parametrize("name,old,new", PY_MUTATIONS, ids=[m[0] for m in PY_MUTATIONS])
+def test_pins_catch_a_planted_mistake_in_the_numpy_half(tmp_path, name, old, new):
+    text = open(os.path.join(ROOT, "oracle", "__init__.py")).read()
+    assert text.count(old) == 1, "the passage to mutate is gone: update the mutation table"
+    p = _run_pins_with_package(tmp_path, text.replace(old, new))
+    assert p.returncode == 1, "no pin noticed the planted mistake '%s'\n%s" % (name, p.stdout[-1500:] + p.stderr[-1500:])
+    assert " failed" in p.stdout, p.stdout[-1500:]
