@@ -106,6 +106,9 @@ int hclae_anneal_stage(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M,
  *                  hclae_set_beam_width (10 unless set).
  * init_idx: HOST int64[M][K] or NULL.  err_per_stage: HOST double[M] or NULL
  * (mean ||e_x||^2 after each stage).
+ * With reencode_mode 0, init_idx == NULL and err_per_stage == NULL the call only enqueues kernels on the
+ * context's stream (no allocation, copy, memset or synchronisation; all data-dependent sizes are read on the
+ * device), so it may be recorded into a HIP graph on that stream and replayed.
  */
 int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int M, int K,
                 uint8_t *codes, float *residue, int iters, int reencode_mode,
