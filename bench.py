@@ -38,7 +38,7 @@ def main():
     ap.add_argument("--queries", type=int, default=10_000)
     ap.add_argument("--shape", choices=["sift", "gist"], default="sift",
                     help="sift: the headline workload (D=128).  gist: the same step on GIST-shaped data (D=960, "
-                         "the D-chunked assign kernel; default M=4), reported beside it, never instead of it")
+                         "the D-chunked assign kernel), reported beside it, never instead of it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
     ap.add_argument("--online", type=int, default=0, metavar="CHUNKS",
@@ -63,8 +63,6 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     gist = args.shape == "gist"
-    if gist and args.m == 8:
-        args.m = 4
     N, D, M, K, T, Q = args.n, (960 if gist else 128), args.m, 256, args.iters, args.queries
     if gist and (args.online or args.beam):
         sys.exit("bench.py: --shape gist runs the sweep only")
