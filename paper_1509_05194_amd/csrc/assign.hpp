@@ -442,7 +442,7 @@ __device__ __forceinline__ void mfma_chunk_refill(
         // address clamped into the row), so that no branch hides from the compiler which loads are in flight
         float4 xv = x[s];
         if (kChunkD * q + 8 * s + 4 * h >= D) xv = make_float4(0.f, 0.f, 0.f, 0.f);
-        x[s] = *reinterpret_cast<const float4 *>(xnext + min(kChunkD * qn + 8 * s + 4 * h, D - 4));
+        x[s] = *reinterpret_cast<const float4 *>(xnext + min(kChunkD * qn + 8 * s + 4 * h, last_piece(D)));
         xsq = fmaf(xv.x, xv.x, xsq);
         xsq = fmaf(xv.y, xv.y, xsq);
         xsq = fmaf(xv.z, xv.z, xsq);
@@ -511,7 +511,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
         const float *xrow = tile_row(blockIdx.x, vec);
         float4 x[8];
 #pragma unroll
-        for (int s = 0; s < 8; ++s) x[s] = *reinterpret_cast<const float4 *>(xrow + min(8 * s + 4 * h, D - 4));
+        for (int s = 0; s < 8; ++s) x[s] = *reinterpret_cast<const float4 *>(xrow + min(8 * s + 4 * h, last_piece(D)));
         int par = 0;
         for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
             int64_t vec_next = vec;

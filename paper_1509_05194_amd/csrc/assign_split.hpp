@@ -312,8 +312,8 @@ __device__ __forceinline__ void mfma_chunk_split_refill(
             if (col >= D) u = make_float4(0.f, 0.f, 0.f, 0.f);
             if (col + 4 >= D) v = make_float4(0.f, 0.f, 0.f, 0.f);
             const int coln = kChunkD * qn + kSplitStep * t + 8 * g;
-            x[2 * t] = *reinterpret_cast<const float4 *>(xnext + min(coln, D - 4));
-            x[2 * t + 1] = *reinterpret_cast<const float4 *>(xnext + min(coln + 4, D - 4));
+            x[2 * t] = *reinterpret_cast<const float4 *>(xnext + min(coln, last_piece(D)));
+            x[2 * t + 1] = *reinterpret_cast<const float4 *>(xnext + min(coln + 4, last_piece(D)));
         }
         xsq = fmaf(u.x, u.x, xsq);
         xsq = fmaf(u.y, u.y, xsq);
@@ -423,8 +423,8 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_split_chunked(
         float4 x[8];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            x[2 * t] = *reinterpret_cast<const float4 *>(xrow + min(kSplitStep * t + 8 * g, D - 4));
-            x[2 * t + 1] = *reinterpret_cast<const float4 *>(xrow + min(kSplitStep * t + 8 * g + 4, D - 4));
+            x[2 * t] = *reinterpret_cast<const float4 *>(xrow + min(kSplitStep * t + 8 * g, last_piece(D)));
+            x[2 * t + 1] = *reinterpret_cast<const float4 *>(xrow + min(kSplitStep * t + 8 * g + 4, last_piece(D)));
         }
         int par = 0;
         for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {

@@ -319,7 +319,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_beam_score_chunked(
     const float *xrow = rows + row * ld;
     float4 x[8];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) x[s] = *reinterpret_cast<const float4 *>(xrow + min(8 * s + 4 * h, D - 4));
+    for (int s = 0; s < 8; ++s) x[s] = *reinterpret_cast<const float4 *>(xrow + min(8 * s + 4 * h, last_piece(D)));
     int par = 0;
     for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
         bool valid_next = valid;
@@ -410,8 +410,8 @@ __global__ __launch_bounds__(kAssignThreads) void k_beam_score_split_chunked(
     float4 x[8];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        x[2 * t] = *reinterpret_cast<const float4 *>(xrow + min(kSplitStep * t + 8 * h, D - 4));
-        x[2 * t + 1] = *reinterpret_cast<const float4 *>(xrow + min(kSplitStep * t + 8 * h + 4, D - 4));
+        x[2 * t] = *reinterpret_cast<const float4 *>(xrow + min(kSplitStep * t + 8 * h, last_piece(D)));
+        x[2 * t + 1] = *reinterpret_cast<const float4 *>(xrow + min(kSplitStep * t + 8 * h + 4, last_piece(D)));
     }
     int par = 0;
     for (int64_t bt = blockIdx.x; bt < nbt; bt += gridDim.x) {

@@ -44,6 +44,11 @@ __device__ __forceinline__ double block_sum(double v, double *scratch)
     return t;
 }
 
+// First column of the last 4-float piece of a row that starts below D: the clamp for unconditional row loads
+// whose out-of-range columns are zeroed at use.  D itself need not be a multiple of 4 (a prefix of the
+// coordinates); the row it lies in is, so the piece is inside the row.
+__device__ __forceinline__ int last_piece(int D) { return ((D + 3) & ~3) - 4; }
+
 // The kVolatile + 1 largest entries of drift[0..K) (K <= 256), descending, with their indices; computed by
 // the first wave of the block into LDS (top[], tk[]; unused slots 0 / -1).  Ends with a barrier.
 constexpr int kVolatile = 4;
