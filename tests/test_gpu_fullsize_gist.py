@@ -91,3 +91,54 @@ def test_gist_fullsize_sweep_properties(data, oracle):
     print("GIST-shaped full-size stage: %d of %d sampled codes differ (%d exempt); stats %s" % (ndiff, len(sample), nex, st))
     assert not bad
     ctx.close()
+
+
+def test_more_than_2_to_31_elements(data, oracle):
+    """N * D = 2.2e9 floats in one array (N = 2,300,003, D = 960): row offsets no longer fit 32 bits.  The
+    sweep with the exact shortcuts must equal the single steps bit for bit, and an assignment sampled at the
+    head, the middle and the tail of the array must be the oracle's."""
+    from paper_1509_05194_amd import hclae
+    _, Xg = data
+    Xbig = torch.cat([Xg, Xg * 0.97 + 0.001, Xg[:300_003] * 1.04])
+    Nb, M, T = Xbig.shape[0], 2, 2
+    assert Nb * D > 2 ** 31
+    idx = synth.init_indices(Nb, M, K)
+    outs = []
+    for one_call in (True, False):
+        ctx = hclae.Context(Nb, D, M, K)
+        C = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+        codes = torch.zeros((Nb, M), dtype=torch.uint8, device="cuda:0")
+        r = Xbig.clone()
+        for sweep in range(2):
+            if one_call:
+                ctx.sweep(C, codes, r, T, init_idx=idx if sweep == 0 else None, want_err=False)
+            else:
+                for m in range(M):
+                    ctx.heat(m, C, codes, r)
+                    if sweep == 0:
+                        C[m] = r[torch.from_numpy(idx[m]).cuda()]
+                    for _ in range(T):
+                        ctx.assign(m, r, C, codes)
+                        ctx.update(m, r, C, codes)
+                    ctx.assign(m, r, C, codes)
+                    ctx.cool(m, C, codes, r)
+        torch.cuda.synchronize()
+        outs.append((C.clone(), codes.clone(), r.clone()))
+        if one_call:
+            ctx.heat(M - 1, C, codes, r)
+            cg = codes.clone()
+            ctx.assign(M - 1, r, C, cg)
+            sel = np.concatenate([np.arange(0, 1000), np.arange(Nb // 2, Nb // 2 + 1000), np.arange(Nb - 1000, Nb)])
+            sel_g = torch.from_numpy(sel).cuda()
+            xs64 = r[sel_g].cpu().numpy().astype(np.float64)
+            C64 = C.cpu().numpy().astype(np.float64)
+            codes_s = np.zeros((len(sel), M), np.uint8)
+            d1, d2, _ = oracle.assign(xs64, C64, codes_s, M - 1, top2=True)
+            got = cg[sel_g, M - 1].cpu().numpy()
+            ndiff, nex, bad = judge_codes(oracle, xs64, C64, M - 1, got, codes_s[:, M - 1], d1, d2)
+            assert not bad
+        ctx.close()
+        del C, codes, r
+    assert torch.equal(outs[0][0], outs[1][0]), "dictionaries differ"
+    assert torch.equal(outs[0][1], outs[1][1]), "codes differ"
+    assert torch.equal(outs[0][2], outs[1][2]), "residues differ"
