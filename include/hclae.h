@@ -151,7 +151,8 @@ int hclae_last_refined(hclae_ctx *ctx, int64_t *out);
 int hclae_online_begin(hclae_ctx *ctx, const float *C, int M, int K, int D, const int64_t *n0);
 
 /*
- * One chunk of n new vectors, given as stored descriptors Xu8 (DEVICE uint8 [n][D]).  For each
+ * One chunk of n new vectors, given as stored descriptors Xu8 (DEVICE uint8 [n][D], 16-byte aligned,
+ * else HCLAE_EINVAL).  For each
  * dictionary m in order, with r the chunk's residue so far (r = x for m = 0):
  *   assign r to C_m;  add its members to the running sums and counts;  c_m(k) <- sum / count
  *   where count > 0;  assign again;  r <- r - c_m(i_m).

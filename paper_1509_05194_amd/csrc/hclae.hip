@@ -939,12 +939,13 @@ int hclae_online_chunk(hclae_ctx *ctx, const uint8_t *Xu8, int64_t n, int D, flo
     int rc = check_call(ctx, n, D, M, K);
     if (rc != HCLAE_OK) return rc;
     if (!ctx->run_sum) return fail(ctx, HCLAE_ESTATE, "hclae_online_chunk before hclae_online_begin");
-    if (D % 16 != 0) return fail(ctx, HCLAE_EINVAL, "hclae_online_chunk: D must be a multiple of 16");
     if (n == 0) { if (err) *err = 0.0; return HCLAE_OK; }
     if (!Xu8 || !C || !codes || !residue) return fail(ctx, HCLAE_EINVAL, "hclae_online_chunk: NULL pointer");
-    const int64_t n16 = n * (D / 16);
-    hipLaunchKernelGGL(k_convert_u8, dim3(stream_blocks(ctx, n16, kFlatThreads * 2)), dim3(kFlatThreads), 0, ctx->stream,
-                       residue, Xu8, n16);
+    if (reinterpret_cast<uintptr_t>(Xu8) % 16 != 0)
+        return fail(ctx, HCLAE_EINVAL, "hclae_online_chunk: Xu8 must be 16-byte aligned");
+    const int64_t total = n * (int64_t)D;
+    hipLaunchKernelGGL(k_convert_u8, dim3(stream_blocks(ctx, (total >> 4) + 1, kFlatThreads * 2)), dim3(kFlatThreads), 0,
+                       ctx->stream, residue, Xu8, total);
     HIP_TRY(ctx, hipGetLastError());
     for (int m = 0; m < M; ++m) {
         float *Cm = C + (size_t)m * K * D;

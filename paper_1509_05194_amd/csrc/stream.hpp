@@ -177,11 +177,14 @@ __global__ __launch_bounds__(kFlatThreads) void k_copy(
     }
 }
 
-// r <- float(X) for descriptors stored as bytes (online chunks): 16 bytes in, 64 bytes out per thread.
+// r <- float(X) for descriptors stored as bytes (online chunks): 16 bytes in, 64 bytes out per thread, over the
+// flat array of `total` bytes (src 16-byte aligned); the last total % 16 bytes go one per thread.
 __global__ __launch_bounds__(kFlatThreads) void k_convert_u8(
-    float *__restrict__ dst, const uint8_t *__restrict__ src, int64_t n16)
+    float *__restrict__ dst, const uint8_t *__restrict__ src, int64_t total)
 {
     typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+    const int64_t n16 = total >> 4;
+    if (blockIdx.x == 0 && 16 * n16 + threadIdx.x < total) dst[16 * n16 + threadIdx.x] = (float)src[16 * n16 + threadIdx.x];
     for (int64_t i = (int64_t)blockIdx.x * kFlatThreads + threadIdx.x; i < n16;
          i += (int64_t)gridDim.x * kFlatThreads) {
         const uintx4 w = __builtin_nontemporal_load(reinterpret_cast<const uintx4 *>(src) + i);

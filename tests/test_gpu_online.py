@@ -97,6 +97,17 @@ def test_online_chunks_match_oracle(oracle, weighted):
     ctx2.close()
 
 
+def test_online_chunks_any_row_length(oracle, monkeypatch):
+    """The same step-locked comparison on a shape whose rows are no multiple of 16 bytes (D = 36), with a
+    padded codeword block (K = 17) and a chunk byte count that leaves a tail of 12 bytes."""
+    import sys
+    mod = sys.modules[__name__]
+    for name, value in dict(D=36, M=3, K=17, CH=3000 + 7, NCH=3).items():
+        monkeypatch.setattr(mod, name, value)
+    assert (CH * D) % 16 == 12
+    test_online_chunks_match_oracle(oracle, True)
+
+
 def test_pipelined_host_chunks_give_identical_results():
     """uint8 chunks in pinned host memory, copied by hipMemcpyAsync on a side stream into two
     device staging buffers while the previous chunk is processed; same bits as the serial run."""
