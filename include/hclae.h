@@ -11,8 +11,10 @@
  *   residue e_x = x - sum_m c_m(i_m(x));  intermediate vector x' = e_x + c_m(i_m(x)).
  *
  * Layouts (all row-major, all DEVICE memory unless marked HOST):
- *   X, residue : float   [N][D]      (D % 4 == 0, base 16-byte aligned)
+ *   X, residue : float   [N][D]      (D % 4 == 0)
  *   C          : float   [M][K][D]
+ *   Every float array (these, beam rows, R, rotated copies) is read and written four floats at a
+ *   time: its base must be 16-byte aligned, else the call returns HCLAE_EINVAL.
  *   codes      : uint8_t [N][M]      (the paper's M-byte code; K <= 256)
  *
  * Ownership: every data pointer is caller-owned; the library neither allocates nor frees

@@ -143,6 +143,13 @@ int check_call(hclae_ctx *ctx, int64_t N, int D, int M, int K)
     return HCLAE_OK;
 }
 
+// Float arrays are read and written four floats at a time: 16-byte aligned bases (NULL passes: checked apart).
+template <typename... P>
+bool misaligned(P... p)
+{
+    return (((reinterpret_cast<uintptr_t>(p)) | ...) & 15u) != 0;
+}
+
 int stream_blocks(const hclae_ctx *ctx, int64_t work_items, int per_block)
 {
     int64_t need = (work_items + per_block - 1) / per_block;
@@ -693,6 +700,7 @@ int hclae_heat(hclae_ctx *ctx, int m, int64_t N, int D, const float *C, int M, i
     if (m < 0 || m >= M) return fail(ctx, HCLAE_EINVAL, "hclae_heat: m out of range");
     if (N == 0) return HCLAE_OK;
     if (!C || !codes || !residue) return fail(ctx, HCLAE_EINVAL, "hclae_heat: NULL pointer");
+    if (misaligned(C, residue)) return fail(ctx, HCLAE_EINVAL, "hclae_heat: float arrays must be 16-byte aligned");
     const int b = launch_heat_cool<+1, false>(ctx, m, N, C, codes, residue, nullptr);
     return b < 0 ? b : HCLAE_OK;
 }
@@ -705,6 +713,7 @@ int hclae_cool(hclae_ctx *ctx, int m, int64_t N, int D, const float *C, int M, i
     if (m < 0 || m >= M) return fail(ctx, HCLAE_EINVAL, "hclae_cool: m out of range");
     if (N == 0) return HCLAE_OK;
     if (!C || !codes || !xp) return fail(ctx, HCLAE_EINVAL, "hclae_cool: NULL pointer");
+    if (misaligned(C, xp)) return fail(ctx, HCLAE_EINVAL, "hclae_cool: float arrays must be 16-byte aligned");
     const int b = launch_heat_cool<-1, false>(ctx, m, N, C, codes, xp, nullptr);
     return b < 0 ? b : HCLAE_OK;
 }
@@ -717,6 +726,7 @@ int hclae_assign(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, const
     if (m < 0 || m >= M) return fail(ctx, HCLAE_EINVAL, "hclae_assign: m out of range");
     if (N == 0) return HCLAE_OK;
     if (!C || !codes || !xp) return fail(ctx, HCLAE_EINVAL, "hclae_assign: NULL pointer");
+    if (misaligned(C, xp)) return fail(ctx, HCLAE_EINVAL, "hclae_assign: float arrays must be 16-byte aligned");
     const float *Cm = C + (size_t)m * K * D;
     if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
     if ((rc = launch_assign(ctx, m, N, xp, Cm, codes)) != HCLAE_OK) return rc;
@@ -735,6 +745,7 @@ int hclae_update(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, float
     if (rc != HCLAE_OK) return rc;
     if (m < 0 || m >= M) return fail(ctx, HCLAE_EINVAL, "hclae_update: m out of range");
     if (N > 0 && (!C || !codes || !xp)) return fail(ctx, HCLAE_EINVAL, "hclae_update: NULL pointer");
+    if (misaligned(C, xp)) return fail(ctx, HCLAE_EINVAL, "hclae_update: float arrays must be 16-byte aligned");
     if (N == 0) {
         if (counts) HIP_TRY(ctx, hipMemsetAsync(counts, 0, sizeof(int32_t) * K, ctx->stream));
         return HCLAE_OK;
@@ -748,6 +759,7 @@ int hclae_quant_error(hclae_ctx *ctx, const float *residue, int64_t N, int D, do
     int rc = check_call(ctx, N, D, ctx->M, ctx->K);
     if (rc != HCLAE_OK) return rc;
     if (!out || (!residue && N > 0)) return fail(ctx, HCLAE_EINVAL, "hclae_quant_error: bad argument");
+    if (misaligned(residue)) return fail(ctx, HCLAE_EINVAL, "hclae_quant_error: float arrays must be 16-byte aligned");
     if (N == 0) { *out = 0.0; return HCLAE_OK; }
     const int blocks = launch_sqnorm(ctx, residue, N, ctx->part_b);
     if (blocks < 0) return blocks;
@@ -767,6 +779,7 @@ int hclae_encode(hclae_ctx *ctx, const float *X, int64_t N, int D,
     if (rc != HCLAE_OK) return rc;
     if (N == 0) return HCLAE_OK;
     if (!X || !C || !codes || !residue || X == residue) return fail(ctx, HCLAE_EINVAL, "hclae_encode: bad argument");
+    if (misaligned(X, C, residue)) return fail(ctx, HCLAE_EINVAL, "hclae_encode: float arrays must be 16-byte aligned");
     return enqueue_encode(ctx, X, N, C, codes, residue);
 }
 
@@ -795,6 +808,7 @@ int hclae_anneal_stage(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M,
     if (rc != HCLAE_OK) return rc;
     if (m < 0 || m >= M || iters < 0 || (N > 0 && (!C || !codes || !residue)))
         return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage: bad argument");
+    if (misaligned(C, residue)) return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage: float arrays must be 16-byte aligned");
     if (init_idx && check_init_idx(init_idx, K, N) != HCLAE_OK)
         return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage: init_idx out of range");
     if (N == 0) {
@@ -847,6 +861,7 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
     if (rc != HCLAE_OK) return rc;
     if (iters < 0 || (N > 0 && (!C || !codes || !residue)) || reencode_mode < 0 || reencode_mode > 2)
         return fail(ctx, HCLAE_EINVAL, "hclae_sweep: bad argument");
+    if (misaligned(X, C, residue)) return fail(ctx, HCLAE_EINVAL, "hclae_sweep: float arrays must be 16-byte aligned");
     if (reencode_mode != 0 && N > 0 && (!X || X == residue))
         return fail(ctx, HCLAE_EINVAL, "hclae_sweep: reencode_mode 1 and 2 need X");
     if (init_idx && check_init_idx(init_idx, M * K, N) != HCLAE_OK)
@@ -941,6 +956,7 @@ int hclae_online_chunk(hclae_ctx *ctx, const uint8_t *Xu8, int64_t n, int D, flo
     if (!ctx->run_sum) return fail(ctx, HCLAE_ESTATE, "hclae_online_chunk before hclae_online_begin");
     if (n == 0) { if (err) *err = 0.0; return HCLAE_OK; }
     if (!Xu8 || !C || !codes || !residue) return fail(ctx, HCLAE_EINVAL, "hclae_online_chunk: NULL pointer");
+    if (misaligned(C, residue)) return fail(ctx, HCLAE_EINVAL, "hclae_online_chunk: float arrays must be 16-byte aligned");
     if (reinterpret_cast<uintptr_t>(Xu8) % 16 != 0)
         return fail(ctx, HCLAE_EINVAL, "hclae_online_chunk: Xu8 must be 16-byte aligned");
     const int64_t total = n * (int64_t)D;
@@ -1181,6 +1197,7 @@ int hclae_beam_step(hclae_ctx *ctx, const float *rows, const double *err, const 
     if (N == 0) return HCLAE_OK;
     if (!rows || !Cm || !rows_next || rows_next == rows)
         return fail(ctx, HCLAE_EINVAL, "hclae_beam_step: NULL or aliased rows");
+    if (misaligned(rows, Cm, rows_next)) return fail(ctx, HCLAE_EINVAL, "hclae_beam_step: float arrays must be 16-byte aligned");
     if (N * (int64_t)L >= ((int64_t)1 << 31)) return fail(ctx, HCLAE_EINVAL, "hclae_beam_step: N * L too large");
     if ((rc = beam_scratch(ctx, N, L, false)) != HCLAE_OK) return rc;
     return enqueue_beam_step(ctx, rows, err, Cm, N, Lc, beam_next_width(K, Lc, L), nullptr, nullptr, 0,
@@ -1196,6 +1213,7 @@ int hclae_encode_beam(hclae_ctx *ctx, const float *X, int64_t N, int D, const fl
     if (N == 0) return HCLAE_OK;
     if (!X || !C || !codes || !residue || residue == X)
         return fail(ctx, HCLAE_EINVAL, "hclae_encode_beam: NULL or aliased pointer");
+    if (misaligned(X, C, residue)) return fail(ctx, HCLAE_EINVAL, "hclae_encode_beam: float arrays must be 16-byte aligned");
     return enqueue_encode_beam(ctx, X, N, C, L, codes, residue, err);
 }
 
@@ -1259,6 +1277,7 @@ int hclae_rotate(hclae_ctx *ctx, const float *x, int64_t N, int D, const float *
     if (D != ctx->D) return fail(ctx, HCLAE_ESTATE, "D differs from hclae_create");
     if (N == 0) return HCLAE_OK;
     if (!x || !R || !out || x == out) return fail(ctx, HCLAE_EINVAL, "hclae_rotate: bad argument");
+    if (misaligned(x, R, out)) return fail(ctx, HCLAE_EINVAL, "hclae_rotate: float arrays must be 16-byte aligned");
     if ((rc = pca_scratch(ctx)) != HCLAE_OK) return rc;
     return launch_rotate(ctx, x, N, R, transpose, out);
 }
@@ -1270,6 +1289,7 @@ int hclae_covariance(hclae_ctx *ctx, const float *xp, int64_t N, int D, double *
     if (rc != HCLAE_OK) return fail(ctx, rc, "shape out of range");
     if (D != ctx->D) return fail(ctx, HCLAE_ESTATE, "D differs from hclae_create");
     if (N < 1 || !xp || !mean || !cov) return fail(ctx, HCLAE_EINVAL, "hclae_covariance: bad argument");
+    if (misaligned(xp)) return fail(ctx, HCLAE_EINVAL, "hclae_covariance: float arrays must be 16-byte aligned");
     if ((rc = pca_scratch(ctx)) != HCLAE_OK) return rc;
     Timed t_(ctx, HCLAE_T_MOMENTS);
     int ncol = (int)((N + 1023) / 1024);
@@ -1303,6 +1323,7 @@ int hclae_assign_prefix(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp
     if (m < 0 || m >= M || dact < 1 || dact > D) return fail(ctx, HCLAE_EINVAL, "hclae_assign_prefix: m or dact out of range");
     if (N == 0) return HCLAE_OK;
     if (!C || !codes || !xp) return fail(ctx, HCLAE_EINVAL, "hclae_assign_prefix: NULL pointer");
+    if (misaligned(C, xp)) return fail(ctx, HCLAE_EINVAL, "hclae_assign_prefix: float arrays must be 16-byte aligned");
     const float *Cm = C + (size_t)m * K * D;
     if ((rc = launch_norms(ctx, Cm, dact, D)) != HCLAE_OK) return rc;
     return launch_assign(ctx, m, N, xp, Cm, codes, dact, D);
@@ -1326,6 +1347,7 @@ int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, in
     if (N == 0) { if (stats) memset(stats, 0, sizeof(*stats)); return HCLAE_OK; }
     if (!C || !codes || !residue || !R || !xr || xr == residue)
         return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: NULL or aliased pointer");
+    if (misaligned(C, residue, R, xr)) return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: float arrays must be 16-byte aligned");
     if ((rc = pca_scratch(ctx)) != HCLAE_OK) return rc;
     float *Cm = C + (size_t)m * K * D;
     const size_t cbytes = (size_t)K * D * sizeof(float);
@@ -1385,6 +1407,7 @@ int hclae_reorder_by_variance(hclae_ctx *ctx, int64_t N, int D, float *C, int M,
     int rc = check_call(ctx, N, D, M, K);
     if (rc != HCLAE_OK) return rc;
     if (!C || (N > 0 && !codes)) return fail(ctx, HCLAE_EINVAL, "hclae_reorder_by_variance: NULL pointer");
+    if (misaligned(C)) return fail(ctx, HCLAE_EINVAL, "hclae_reorder_by_variance: float arrays must be 16-byte aligned");
     const size_t per = (size_t)K * D;
     double *dvar = nullptr;
     int *dorder = nullptr;

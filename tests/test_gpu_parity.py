@@ -406,6 +406,20 @@ def test_degenerate_shapes(oracle):
     assert L.hclae_heat(ctx._h, 0, 10, 32, None, 2, 4, None, None) == hclae.ESTATE
     assert L.hclae_heat(ctx._h, 0, 101, 16, None, 2, 4, None, None) == hclae.ESTATE
     assert L.hclae_heat(ctx._h, 2, 10, 16, None, 2, 4, None, None) == hclae.EINVAL
+    # a float array whose base is not 16-byte aligned is refused before anything is launched
+    flat = torch.zeros(10 * 16 + 4, dtype=torch.float32, device="cuda:0")
+    good, off = flat[:160].view(10, 16), flat[1:161].view(10, 16)
+    Cs = torch.zeros((2, 4, 16), dtype=torch.float32, device="cuda:0")
+    cs = torch.zeros((10, 2), dtype=torch.uint8, device="cuda:0")
+    assert off.data_ptr() % 16 == 4
+    with pytest.raises(hclae.HclaeError) as e:
+        ctx.heat(0, Cs, cs, off)
+    assert e.value.code == hclae.EINVAL and b"aligned" in L.hclae_last_error(ctx._h)
+    with pytest.raises(hclae.HclaeError):
+        ctx.sweep(Cs, cs, off, 1)
+    with pytest.raises(hclae.HclaeError):
+        ctx.encode(off, Cs, cs, good)
+    ctx.heat(0, Cs, cs, good)
     ctx.close()
 
 
