@@ -16,8 +16,7 @@
  *   Every float array (these, beam rows, R, rotated copies) is read and written four floats at a
  *   time: its base must be 16-byte aligned, else the call returns HCLAE_EINVAL.
  *   Values must be finite: the library does not scan its inputs, and with a NaN or an infinity in
- *   X, residue or C the codes, dictionaries and errors that come back are unspecified (every index
- *   it writes is still a valid one, and every call returns).
+ *   X, residue or C the behaviour is undefined.
  *   codes      : uint8_t [N][M]      (the paper's M-byte code; K <= 256)
  *
  * Ownership: every data pointer is caller-owned; the library neither allocates nor frees
