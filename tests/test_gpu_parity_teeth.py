@@ -10,14 +10,17 @@ import sys
 
 import pytest
 
+import test_gpu_beam as beam
 import test_gpu_parity as parity
+import test_gpu_pca as pca
 
 pytestmark = pytest.mark.gpu
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "da_oracle.c")
 
-# (name, text in da_oracle.c, replacement, the parity test that must object, run on the "tiny" case)
+# (name, text in da_oracle.c, replacement, the GPU test that must object: a name in test_gpu_parity.py, run on
+# its "tiny" case, or (module, name, arguments before the oracle))
 CASES = [
     ("heat_subtracts", "rn[d] = rn[d] + c[d];", "rn[d] = rn[d] - c[d];", "test_heat_and_cool_step"),
     ("distance_drops_first_coordinate",
@@ -28,7 +31,22 @@ CASES = [
     ("cool_adds", "xn[d] = xn[d] - c[d];", "xn[d] = xn[d] + c[d];", "test_encode"),
     ("argmin_prefers_the_second_best", "codes[n * M + m] = (uint8_t)ibest;",
      "codes[n * M + m] = (uint8_t)(isecond >= 0 ? isecond : ibest);", "test_lockstep_sweeps"),
+    # multi-path encoding (Sec. 3.3) and the rotation of the improved k-means (Sec. 3.2)
+    ("beam_error_adds_the_codeword", "const double t = (double)x[d] - a[d] - c[d];",
+     "const double t = (double)x[d] - a[d] + c[d];", (beam, "test_beam_step_locked", ("tiny", 3))),
+    ("beam_answer_is_the_last_path", "memcpy(codes + (size_t)n * M, pre + (size_t)n * Lc * M, (size_t)M);",
+     "memcpy(codes + (size_t)n * M, pre + ((size_t)n * Lc + (Lc - 1)) * M, (size_t)M);",
+     (beam, "test_encode_beam_against_oracle", ("tiny", 5))),
+    ("rotation_transposed", "(transpose ? R[(size_t)j * D + i] : R[(size_t)i * D + j])",
+     "(transpose ? R[(size_t)i * D + j] : R[(size_t)j * D + i])", (pca, "test_rotate", ("tiny",))),
 ]
+
+
+def _call(test, oracle):
+    if isinstance(test, str):
+        return getattr(parity, test)("tiny", oracle)
+    module, name, args = test
+    return getattr(module, name)(*args, oracle)
 
 
 def _oracle_from(tmp_path, name, text):
@@ -51,19 +69,21 @@ def _oracle_from(tmp_path, name, text):
 def _fresh_parity_state():
     """The parity module caches oracle states per case: what a planted mistake computes must neither come from
     that cache nor stay in it."""
-    saved, saved_contraction = parity._cache, parity._CONTRACTION
-    parity._cache, parity._CONTRACTION = {}, 0
+    saved, saved_contraction = parity._cache, [m._CONTRACTION for m in (parity, beam, pca)]
+    parity._cache = {}
+    parity._CONTRACTION = beam._CONTRACTION = pca._CONTRACTION = 0
     try:
         yield
     finally:
-        parity._cache, parity._CONTRACTION = saved, saved_contraction
+        parity._cache = saved
+        parity._CONTRACTION, beam._CONTRACTION, pca._CONTRACTION = saved_contraction
 
 
 def test_parity_slice_passes_against_a_faithful_copy(tmp_path):
     copy = _oracle_from(tmp_path, "faithful", open(SRC).read())
     with _fresh_parity_state():
         for case in CASES:
-            getattr(parity, case[3])("tiny", copy)
+            _call(case[3], copy)
 
 
 @pytest.mark.parametrize("name,old,new,test", CASES, ids=[c[0] for c in CASES])
@@ -73,5 +93,5 @@ def test_parity_objects_to_a_mistake_planted_in_the_oracle(tmp_path, name, old, 
     wrong = _oracle_from(tmp_path, name, text.replace(old, new, 1))
     with _fresh_parity_state():
         with pytest.raises(AssertionError):
-            getattr(parity, test)("tiny", wrong)
+            _call(test, wrong)
     sys.modules.pop("oracle_copy_" + name, None)
