@@ -345,8 +345,12 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     // Static tile schedule balanced per SIMD: waves w and w + 4 of a block share a SIMD (and its
     // matrix pipe), so tiles are dealt round-robin to the gridDim.x * 4 SIMD slots and the two
     // waves of a slot take alternate ones; no SIMD gets more than one tile above the average.
-    // rows of this launch: all N vectors, or the listed ones (PRUNE 2)
-    const int64_t rows = PRUNE == 2 ? (int64_t)*pa.active_count : N;
+    // rows of this launch: all N vectors, or the listed ones (PRUNE 2).  When nearly all are listed the launch
+    // takes all N in order instead: streaming rows beats gathering them, and a settled vector that is
+    // recomputed keeps its code (its bounds prove it) and gets fresh bounds.
+    const int64_t listed = PRUNE == 2 ? (int64_t)*pa.active_count : N;
+    const bool gather = PRUNE == 2 && listed * 32 < N * 31;
+    const int64_t rows = gather ? listed : N;
     const int64_t ntiles = (rows + kTileVec - 1) / kTileVec;
     const int64_t nslots = (int64_t)gridDim.x * 4;
     const int64_t tstride = 2 * nslots;
@@ -359,11 +363,11 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     auto vec_of = [&](int64_t tile) -> int64_t {
         const int64_t i = tile * kTileVec + r;
         if (i >= rows) return N;
-        return PRUNE == 2 ? (int64_t)pa.active[i] : i;
+        return gather ? (int64_t)pa.active[i] : i;
     };
     auto row_ptr = [&](int64_t tile) {
         int64_t n = vec_of(tile);
-        if (n >= N) n = PRUNE == 2 ? (int64_t)pa.active[rows - 1] : N - 1;   // tail columns re-read the last row
+        if (n >= N) n = gather ? (int64_t)pa.active[rows - 1] : N - 1;   // tail columns re-read the last row
         return xp + n * ld;
     };
 
@@ -495,7 +499,10 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
     const float cmax = sqrtf(2.f * hmax) * 1.000001f;
 
     // rows of this launch: all N vectors, or the listed ones (PRUNE 2; see PruneArgs)
-    const int64_t rows = PRUNE == 2 ? (int64_t)*pa.active_count : N;
+    // (nearly all listed: all N in order, as in k_assign_resident)
+    const int64_t listed = PRUNE == 2 ? (int64_t)*pa.active_count : N;
+    const bool gather = PRUNE == 2 && listed * 32 < N * 31;
+    const int64_t rows = gather ? listed : N;
     const int64_t nbt = (rows + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);   // block tiles
     float amax = 0.f;
     if ((int64_t)blockIdx.x < nbt) {
@@ -503,7 +510,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
         auto tile_row = [&](int64_t bt, int64_t &vec) -> const float * {
             const int64_t i = (bt * kAssignWaves + wave) * kTileVec + r;
             const int64_t ic = i < rows ? i : rows - 1;
-            const int64_t nrow = PRUNE == 2 ? (int64_t)pa.active[ic] : ic;
+            const int64_t nrow = gather ? (int64_t)pa.active[ic] : ic;
             vec = i < rows ? nrow : N;
             return xp + nrow * ld;
         };
@@ -542,9 +549,10 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_chunked(
 // of the list with one counter add (*count must be zero on entry; order is free).
 //
 // One codeword that moves far (a cluster of few members) costs every vector its lower bound.  When the
-// largest drift stands out from the (kVolatile+1)-th and the block has listed many of its vectors, it looks
-// at them again with the kVolatile codewords that moved most treated apart: the lower bound ages by the largest drift of the REST, and the distance to each of those
-// few is computed afresh from x' (expanded form in fp32 with its rounding bound) and joins the lower bound.
+// largest drift stands out from the (kVolatile+1)-th, the block looks again at those of its unsettled vectors
+// that the drift of the REST alone would leave settled (if they are many), with the kVolatile codewords that
+// moved most treated apart: the lower bound ages by the largest drift of the rest, and the distance to each of
+// those few is computed afresh from x' (expanded form in fp32 with its rounding bound) and joins the lower bound.
 // Vectors that this settles get their aged bounds and leave the list.  Eight lanes share a vector.
 // Dynamic LDS: kVolatile rows of D floats.
 constexpr int kBoundSpan = 4096;
@@ -579,6 +587,9 @@ __global__ __launch_bounds__(kBoundThreads) void k_bounds_step(
     top_drifts(sdrift, K, s_top, s_tk);
     const float d1 = s_top[0], d2 = s_top[1], drest = s_top[kVolatile];
     const int k1 = s_tk[0];
+    // The second look can only settle a vector whose upper bound stays below its lower bound aged by the drift
+    // of the rest: the others are kept without it (found: worth the second look; kept: to recompute).
+    const bool outlier = K > kVolatile + 1 && d1 > 3.0f * drest;
     {
 #pragma unroll
         for (int j = 0; j < U; ++j) {
@@ -589,20 +600,24 @@ __global__ __launch_bounds__(kBoundThreads) void k_bounds_step(
                 if (un < ln) {
                     bu[n] = un;
                     bl[n] = ln;
-                } else {
+                } else if (outlier && un < (l[j] - drest) * 0.999999f) {
                     found[atomicAdd(&nfound, 1u)] = (uint32_t)n;      // its bounds stay as they were
+                } else {
+                    kept[atomicAdd(&nkept, 1u)] = (uint32_t)n;        // likewise
                 }
             }
         }
     }
     __syncthreads();
     const unsigned nf = nfound;
-    // worth a gather of the listed rows of x'?
-    const bool apart = K > kVolatile + 1 && d1 > 3.0f * drest && nf * 8u > (unsigned)kBoundSpan;
+    // worth a gather of those rows of x'?
+    const bool apart = nf * 8u > (unsigned)kBoundSpan;
     if (!apart) {
-        if (threadIdx.x == 0 && nf) base = atomicAdd(count, nf);
+        const unsigned nk0 = nkept;
+        if (threadIdx.x == 0 && nf + nk0) base = atomicAdd(count, nf + nk0);
         __syncthreads();
-        for (unsigned i = threadIdx.x; i < nf; i += kBoundThreads) list[base + i] = found[i];
+        for (unsigned i = threadIdx.x; i < nk0; i += kBoundThreads) list[base + i] = kept[i];
+        for (unsigned i = threadIdx.x; i < nf; i += kBoundThreads) list[base + nk0 + i] = found[i];
         return;
     }
     for (int e = threadIdx.x; e < kVolatile * D; e += kBoundThreads) {

@@ -201,7 +201,9 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_split(
     const float cmax_eff = (cmax * 1.02f + split_bound / acc_bound) * 1.0001f;
 
     // rows of this launch: all N vectors, or the listed ones (PRUNE 2; see PruneArgs)
-    const int64_t rows = PRUNE == 2 ? (int64_t)*pa.active_count : N;
+    const int64_t listed = PRUNE == 2 ? (int64_t)*pa.active_count : N;
+    const bool gather = PRUNE == 2 && listed * 32 < N * 31;         // nearly all listed: all N in order
+    const int64_t rows = gather ? listed : N;
     const int64_t ntiles = (rows + kTileVec - 1) / kTileVec;
     const int64_t nslots = (int64_t)gridDim.x * 4;
     const int64_t tstride = 2 * nslots;
@@ -213,11 +215,11 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_split(
     auto vec_of = [&](int64_t tile) -> int64_t {
         const int64_t i = tile * kTileVec + r;
         if (i >= rows) return N;
-        return PRUNE == 2 ? (int64_t)pa.active[i] : i;
+        return gather ? (int64_t)pa.active[i] : i;
     };
     auto row_ptr = [&](int64_t tile) {
         int64_t n = vec_of(tile);
-        if (n >= N) n = PRUNE == 2 ? (int64_t)pa.active[rows - 1] : N - 1;
+        if (n >= N) n = gather ? (int64_t)pa.active[rows - 1] : N - 1;
         return xp + n * ld;
     };
 
@@ -407,14 +409,16 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_split_chunked(
     const float eps = 2.f * acc_bound;
     const float cmax_eff = (cmax * 1.02f + split_bound / acc_bound) * 1.0001f;
 
-    const int64_t rows = PRUNE == 2 ? (int64_t)*pa.active_count : N;
+    const int64_t listed = PRUNE == 2 ? (int64_t)*pa.active_count : N;
+    const bool gather = PRUNE == 2 && listed * 32 < N * 31;         // nearly all listed: all N in order
+    const int64_t rows = gather ? listed : N;
     const int64_t nbt = (rows + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);
     float amax = 0.f;
     if ((int64_t)blockIdx.x < nbt) {
         auto tile_row = [&](int64_t bt, int64_t &vec) -> const float * {
             const int64_t i = (bt * kAssignWaves + wave) * kTileVec + r;
             const int64_t ic = i < rows ? i : rows - 1;
-            const int64_t nrow = PRUNE == 2 ? (int64_t)pa.active[ic] : ic;
+            const int64_t nrow = gather ? (int64_t)pa.active[ic] : ic;
             vec = i < rows ? nrow : N;
             return xp + nrow * ld;
         };
