@@ -65,9 +65,12 @@ struct MovedArgs {
 // k < K; -inf for the padding rows up to kpad.
 // One wave per codeword.  Also resets the two counters the assign that follows will fill
 // (refine_count[0]: re-check entries, refine_count[1]: bits of max |x'|).
+// img (or nullptr): a copy of the dictionary in the LDS order of k_assign_resident (see stage_codebook), S = k-steps
+// of a row; written here in full, zero beyond K and D, and kept up to date by k_merge, so that the assignments
+// of a stage fill their LDS with one contiguous copy instead of a gather of 16-byte pieces.
 __global__ __launch_bounds__(256) void k_codeword_norms(
     const float *__restrict__ Cm, int K, int D, int ld, int kpad, float *__restrict__ hneg,
-    unsigned *__restrict__ refine_count, int keep_absmax)
+    unsigned *__restrict__ refine_count, int keep_absmax, float *__restrict__ img, int S)
 {
     const int lane = lane_id();
     const int k = blockIdx.x * (256 / kWave) + (threadIdx.x >> 6);
@@ -76,6 +79,8 @@ __global__ __launch_bounds__(256) void k_codeword_norms(
         if (!keep_absmax) refine_count[1] = 0u;    // bits of max |x'|
     }
     if (k >= kpad) return;
+    if (img)
+        for (int d = lane; d < 8 * S; d += kWave) img[image_float(k, d, S)] = (k < K && d < D) ? Cm[(size_t)k * ld + d] : 0.f;
     if (k >= K) {
         if (lane == 0) hneg[k] = -__builtin_inff();
         return;
@@ -318,12 +323,13 @@ __device__ __forceinline__ void decide(
 // the current one is contracted) and keeps all 32*KB scores of a vector in accumulators.
 // PREFIX (with PRUNE 0): the last 64-dim chunk stops after the 8-dim steps that hold coordinates below D
 // (assignments on a short prefix of the coordinates, Sec. 3.2: D = 2 costs one step, not eight).
-template <int KB, int PRUNE = 0, bool PREFIX = false>
+// IMG: the LDS is filled from the image of the dictionary in its own order (k_codeword_norms, k_merge).
+template <int KB, int PRUNE = 0, bool PREFIX = false, bool IMG = false>
 __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     const float *__restrict__ xp, const float *__restrict__ Cm, const float *__restrict__ hneg,
     int64_t N, int D, int ld, int K, int M, int m, int NC, float eps,
     uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count,
-    PruneArgs pa)
+    PruneArgs pa, const float4 *__restrict__ img = nullptr)
 {
     extern __shared__ float4 smem4[];
     const int S = 8 * NC;
@@ -334,7 +340,30 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_resident(
     const int h = lane >> 5;
     const int r = lane & 31;
 
-    stage_codebook(lds_c, Cm, K, D, ld, KB, S);
+    if (IMG) {                                                      // the image kept by k_codeword_norms / k_merge
+        // every block copies the same 16 * total bytes: each starts at a place of its own, so that the blocks of
+        // an XCD do not all ask the same L2 channel at the same time
+        constexpr int U = 8;
+        const int total = KB * S * kWave;
+        const int rot = (int)(blockIdx.x & 31u) * (total >> 5);
+        for (int e0 = threadIdx.x; e0 < total; e0 += U * blockDim.x) {
+            float4 v[U];
+            int at[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int e = e0 + u * blockDim.x;
+                at[u] = e + rot < total ? e + rot : e + rot - total;
+                v[u] = e < total ? img[at[u]] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int e = e0 + u * blockDim.x;
+                if (e < total) lds_c[at[u]] = v[u];
+            }
+        }
+    } else {
+        stage_codebook(lds_c, Cm, K, D, ld, KB, S);
+    }
     for (int k = threadIdx.x; k < 32 * KB; k += blockDim.x) lds_h[k] = hneg[k];
     __syncthreads();
     // largest ||c||^2/2 over the real codewords (every thread computes the same value)

@@ -44,6 +44,14 @@ __device__ __forceinline__ double block_sum(double v, double *scratch)
     return t;
 }
 
+// Float index of coordinate d of codeword k in the LDS order of the resident assign kernels: for row block b = k / 32,
+// k-step s = d / 8 (S steps a row) and lane l = 32 * (d / 4 % 2) + k % 32, the float4 at (b * S + s) * 64 + l holds
+// C[k][8 s + 4 h .. + 3].
+__device__ __forceinline__ size_t image_float(int k, int d, int S)
+{
+    return 4 * ((size_t)((k >> 5) * S + (d >> 3)) * kWave + 32 * ((d >> 2) & 1) + (k & 31)) + (d & 3);
+}
+
 // First column of the last 4-float piece of a row that starts below D: the clamp for unconditional row loads
 // whose out-of-range columns are zeroed at use.  D itself need not be a multiple of 4 (a prefix of the
 // coordinates); the row it lies in is, so the piece is inside the row.

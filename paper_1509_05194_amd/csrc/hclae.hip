@@ -43,6 +43,7 @@ struct hclae_ctx {
     // scratch (device)
     float *hneg;             // [32*kb]
     float4 *cb_image;        // [NC][kb*8*64] codebook in staging order (k_codebook_image; D-chunked shapes only)
+    float *lds_image;        // [kb*8*NC*64*4] dictionary of the running stage in the LDS order of the resident assign kernel
     float *split_norms;      // [K][2] split constants of the codebook in use (contraction 1)
     int contraction;         // 0: fp32 MFMA, 1: split-bf16 MFMA
     unsigned *refine_count;
@@ -203,14 +204,17 @@ int launch_heat_cool(hclae_ctx *ctx, int m, int64_t N, const float *C, const uin
 }
 
 // dact: leading coordinates that count (<= ld); ld: row stride of Cm.
-int launch_norms(hclae_ctx *ctx, const float *Cm, int dact = 0, int ld = 0, bool keep_absmax = false)
+// image: also write the dictionary in the LDS order of the resident assign kernel (the centroid updates that follow
+// keep it current; launch_assign then takes it when told so).
+int launch_norms(hclae_ctx *ctx, const float *Cm, int dact = 0, int ld = 0, bool keep_absmax = false, bool image = false)
 {
     if (dact <= 0) dact = ctx->D;
     if (ld <= 0) ld = ctx->D;
     const int kpad = 32 * ctx->kb;
     Timed t_(ctx, HCLAE_T_NORMS);
     hipLaunchKernelGGL(k_codeword_norms, dim3((kpad + 3) / 4), dim3(256), 0, ctx->stream,
-                       Cm, ctx->K, dact, ld, kpad, ctx->hneg, ctx->refine_count, keep_absmax ? 1 : 0);
+                       Cm, ctx->K, dact, ld, kpad, ctx->hneg, ctx->refine_count, keep_absmax ? 1 : 0,
+                       image && ctx->resident ? ctx->lds_image : (float *)nullptr, 8 * ctx->NC);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
@@ -219,7 +223,7 @@ int launch_norms(hclae_ctx *ctx, const float *Cm, int dact = 0, int ld = 0, bool
 // (over all D coordinates only; the caller checks).
 template <int KB>
 int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float *Cm, uint8_t *codes, int dact, int ld,
-                     int prune)
+                     int prune, bool use_image)
 {
     PruneArgs pa;
     pa.bu = ctx->bnd_u; pa.bl = ctx->bnd_l;
@@ -312,11 +316,24 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             attr_set_p = true;
         }
+        static bool attr_set_i = false;
+        if (use_image && !attr_set_i) {
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 0, false, true>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 1, false, true>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 2, false, true>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+            attr_set_i = true;
+        }
         auto kern = prefix ? &k_assign_resident<KB, 0, true>
+                  : use_image ? (prune == 1 ? &k_assign_resident<KB, 1, false, true>
+                                 : prune == 2 ? &k_assign_resident<KB, 2, false, true> : &k_assign_resident<KB, 0, false, true>)
                   : prune == 1 ? &k_assign_resident<KB, 1> : prune == 2 ? &k_assign_resident<KB, 2> : &k_assign_resident<KB, 0>;
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
                            xp, Cm, ctx->hneg, N, dact, ld, ctx->K, ctx->M, m, NC, eps,
-                           codes, ctx->refine_list, ctx->refine_count, pa);
+                           codes, ctx->refine_list, ctx->refine_count, pa,
+                           use_image && !prefix ? reinterpret_cast<const float4 *>(ctx->lds_image) : (const float4 *)nullptr);
     } else {
         // two slices of 64 dims in LDS: one block per CU
         const size_t lds = (size_t)2 * KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
@@ -352,17 +369,18 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
 }
 
 // Assumes hneg holds the norms of Cm (over the same dact coordinates) and the re-check counter is zero.
+// use_image: the dictionary image kept by launch_norms(image) and the centroid updates since is that of Cm.
 int launch_assign(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float *Cm, uint8_t *codes,
-                  int dact = 0, int ld = 0, int prune = 0)
+                  int dact = 0, int ld = 0, int prune = 0, bool use_image = false)
 {
     if (dact <= 0) dact = ctx->D;
     if (ld <= 0) ld = ctx->D;
-    if (dact != ctx->D || ld != ctx->D) prune = 0;
+    if (dact != ctx->D || ld != ctx->D) { prune = 0; use_image = false; }
     switch (ctx->kb) {
-    case 1: return launch_assign_kb<1>(ctx, m, N, xp, Cm, codes, dact, ld, prune);
-    case 2: return launch_assign_kb<2>(ctx, m, N, xp, Cm, codes, dact, ld, prune);
-    case 4: return launch_assign_kb<4>(ctx, m, N, xp, Cm, codes, dact, ld, prune);
-    default: return launch_assign_kb<8>(ctx, m, N, xp, Cm, codes, dact, ld, prune);
+    case 1: return launch_assign_kb<1>(ctx, m, N, xp, Cm, codes, dact, ld, prune, use_image);
+    case 2: return launch_assign_kb<2>(ctx, m, N, xp, Cm, codes, dact, ld, prune, use_image);
+    case 4: return launch_assign_kb<4>(ctx, m, N, xp, Cm, codes, dact, ld, prune, use_image);
+    default: return launch_assign_kb<8>(ctx, m, N, xp, Cm, codes, dact, ld, prune, use_image);
     }
 }
 
@@ -426,7 +444,8 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
                        online ? ctx->run_sum + (size_t)m * K * D : (double *)nullptr,
                        online ? ctx->run_cnt + (size_t)m * K : (long long *)nullptr,
                        keep_totals ? ctx->tot_sum : (long long *)nullptr, keep_totals ? ctx->tot_cnt : (int *)nullptr, 0,
-                       keep_totals ? ctx->moved_count : (unsigned *)nullptr, keep_totals ? ctx->drift : (float *)nullptr);
+                       keep_totals ? ctx->moved_count : (unsigned *)nullptr, keep_totals ? ctx->drift : (float *)nullptr,
+                       ctx->resident ? ctx->lds_image : (float *)nullptr, 8 * ctx->NC);
     HIP_TRY(ctx, hipGetLastError());
     if (keep_totals) {
         hipLaunchKernelGGL(k_save_column, dim3(stream_blocks(ctx, N, 256)), dim3(256), 0, ctx->stream,
@@ -461,7 +480,7 @@ int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float
     hipLaunchKernelGGL(k_merge, dim3(K), dim3(256), 0, ctx->stream,
                        ctx->partial, ctx->pcount, nb, K, D, D, Cm, ctx->hneg, ctx->nk, (int *)nullptr,
                        ctx->refine_count, (double *)nullptr, (long long *)nullptr, ctx->tot_sum, ctx->tot_cnt, 1,
-                       ctx->moved_count, ctx->drift);
+                       ctx->moved_count, ctx->drift, ctx->resident ? ctx->lds_image : (float *)nullptr, 8 * ctx->NC);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
@@ -497,7 +516,7 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
         hipLaunchKernelGGL(k_seed, dim3(K), dim3(256), 0, ctx->stream, residue, ctx->seed_idx, K, D, Cm);
         HIP_TRY(ctx, hipGetLastError());
     }
-    if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
+    if ((rc = launch_norms(ctx, Cm, 0, 0, false, true)) != HCLAE_OK) return rc;
     // x' stays as it is until the stage ends: the first centroid update sums all vectors and keeps the integer
     // totals, the others add only the vectors that changed cluster (exact, so the dictionaries are the same)
     // With pruning the first assignment stores distance bounds for every vector; after each centroid update
@@ -506,14 +525,14 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
     const bool prune = ctx->pruning && iters > 0;
     for (int t = 0; t < iters; ++t) {
         if (prune && t > 0 && (rc = launch_bounds_step(ctx, m, N, codes, residue, Cm)) != HCLAE_OK) return rc;
-        if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? (t == 0 ? 1 : 3) : 0)) != HCLAE_OK) return rc;
+        if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? (t == 0 ? 1 : 3) : 0, true)) != HCLAE_OK) return rc;
         rc = (t == 0 || !ctx->pruning)
                  ? launch_update(ctx, m, N, residue, Cm, codes, nullptr, true, false, 0, ctx->pruning && (iters > 1 || prune))
                  : launch_update_moved(ctx, m, N, residue, Cm);
         if (rc != HCLAE_OK) return rc;
     }
     if (prune && (rc = launch_bounds_step(ctx, m, N, codes, residue, Cm)) != HCLAE_OK) return rc;
-    if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? 2 : 0)) != HCLAE_OK) return rc;
+    if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? 2 : 0, true)) != HCLAE_OK) return rc;
     int pa;
     if (next < 0) {
         pa = launch_heat_cool<-1, true>(ctx, m, N, C, codes, residue, ctx->part_b);
@@ -622,6 +641,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
     struct { void **p; size_t bytes; } allocs[] = {
         {(void **)&ctx->hneg, sizeof(float) * 32 * ctx->kb},
         {(void **)&ctx->cb_image, ctx->resident ? 256 : sizeof(float4) * (size_t)ctx->NC * ctx->kb * 8 * kWave},
+        {(void **)&ctx->lds_image, ctx->resident ? sizeof(float4) * (size_t)ctx->NC * ctx->kb * 8 * kWave : 256},
         {(void **)&ctx->split_norms, sizeof(float) * 2 * HCLAE_MAX_K},
         {(void **)&ctx->refine_count, 256},
         {(void **)&ctx->refine_list, sizeof(RefineItem) * (size_t)N_max},
@@ -670,7 +690,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
 int hclae_destroy(hclae_ctx *ctx)
 {
     if (!ctx) return HCLAE_EINVAL;
-    void *dev[] = {ctx->hneg, ctx->cb_image, ctx->split_norms, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
+    void *dev[] = {ctx->hneg, ctx->cb_image, ctx->lds_image, ctx->split_norms, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
                    ctx->nk, ctx->tot_sum, ctx->tot_cnt, ctx->upd_col, ctx->moved_list, ctx->moved_count, ctx->bnd_u, ctx->bnd_l, ctx->drift, ctx->active, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
                    ctx->run_sum, ctx->run_cnt, ctx->n0_dev, ctx->pca_rt, ctx->pca_crot, ctx->pca_colpart,
                    ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32,
@@ -965,15 +985,15 @@ int hclae_online_chunk(hclae_ctx *ctx, const uint8_t *Xu8, int64_t n, int D, flo
     HIP_TRY(ctx, hipGetLastError());
     for (int m = 0; m < M; ++m) {
         float *Cm = C + (size_t)m * K * D;
-        if ((rc = launch_norms(ctx, Cm)) != HCLAE_OK) return rc;
-        if ((rc = launch_assign(ctx, m, n, residue, Cm, codes)) != HCLAE_OK) return rc;
+        if ((rc = launch_norms(ctx, Cm, 0, 0, false, true)) != HCLAE_OK) return rc;
+        if ((rc = launch_assign(ctx, m, n, residue, Cm, codes, 0, 0, 0, true)) != HCLAE_OK) return rc;
         if (codes_first) {
             hipLaunchKernelGGL(k_copy_column, dim3(stream_blocks(ctx, n, kFlatThreads)), dim3(kFlatThreads), 0, ctx->stream,
                                codes_first, codes, n, M, m);
             HIP_TRY(ctx, hipGetLastError());
         }
         if ((rc = launch_update(ctx, m, n, residue, Cm, codes, nullptr, true, true)) != HCLAE_OK) return rc;
-        if ((rc = launch_assign(ctx, m, n, residue, Cm, codes)) != HCLAE_OK) return rc;
+        if ((rc = launch_assign(ctx, m, n, residue, Cm, codes, 0, 0, 0, true)) != HCLAE_OK) return rc;
         const bool last = (m == M - 1) && err;
         const int b = last ? launch_heat_cool<-1, true>(ctx, m, n, C, codes, residue, ctx->part_b)
                            : launch_heat_cool<-1, false>(ctx, m, n, C, codes, residue, nullptr);

@@ -220,7 +220,7 @@ __global__ __launch_bounds__(256) void k_merge(
     int *__restrict__ counts_out, unsigned *__restrict__ refine_count,
     double *__restrict__ run_sum, long long *__restrict__ run_cnt,
     long long *__restrict__ tot_sum, int *__restrict__ tot_cnt, int delta, unsigned *__restrict__ moved_count,
-    float *__restrict__ drift)
+    float *__restrict__ drift, float *__restrict__ img = nullptr, int S = 0)
 {
     __shared__ double red[256 / kWave];
     __shared__ long long comb[kMergeGroups][kMergePairs][2];
@@ -316,6 +316,8 @@ __global__ __launch_bounds__(256) void k_merge(
                     moved2 += e0 * e0 + e1 * e1;
                 }
                 *dst = c;
+                // the copy in the LDS order of the assign kernel (k_codeword_norms): dims 2 pr, 2 pr + 1
+                if (img) *reinterpret_cast<float2 *>(img + image_float(k, 2 * pr, S)) = c;
             } else {
                 c = *dst;
             }
