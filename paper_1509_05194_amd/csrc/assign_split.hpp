@@ -43,11 +43,26 @@ __device__ __forceinline__ void split8(const float4 &u, const float4 &v, uint4 &
 // Per-codeword constants of the split over the first D coordinates (row stride ld), as fp32 rounded up:
 //   out[2k] = || cl_k ||  (low part),   out[2k + 1] = || c_k - ch_k - cl_k ||  (what two terms miss).
 // One wave per codeword; the assign kernel takes the maxima over k.
+// img (or nullptr; the grid then covers kpad rows): the split dictionary in the LDS order of k_assign_split (see
+// stage_codebook_split), T steps of 16 dims and kb row blocks, so that the kernel fills its LDS with one copy.
 __global__ __launch_bounds__(256) void k_split_norms(
-    const float *__restrict__ Cm, int K, int D, int ld, float *__restrict__ out)
+    const float *__restrict__ Cm, int K, int D, int ld, float *__restrict__ out,
+    uint4 *__restrict__ img = nullptr, int kb = 0, int T = 0)
 {
     const int lane = lane_id();
     const int k = blockIdx.x * (256 / kWave) + (threadIdx.x >> 6);
+    if (img && k < 32 * kb) {
+        for (int j = lane; j < 2 * T; j += kWave) {                // piece (t, g): dims 16 t + 8 g .. + 7
+            const int t = j >> 1, gg = j & 1, col = kSplitStep * t + 8 * gg;
+            const float4 u = load_row_piece(Cm, k, col, K, D, ld);
+            const float4 v = load_row_piece(Cm, k, col + 4, K, D, ld);
+            uint4 hi, lo;
+            split8(u, v, hi, lo);
+            const size_t tb = (size_t)t * kb + (k >> 5);
+            img[(tb * 2 + 0) * kWave + 32 * gg + (k & 31)] = hi;
+            img[(tb * 2 + 1) * kWave + 32 * gg + (k & 31)] = lo;
+        }
+    }
     if (k >= K) return;
     const float *c = Cm + (size_t)k * ld;
     double sl = 0.0, sd = 0.0;
@@ -161,7 +176,7 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_split(
     const float *__restrict__ split_norms,
     int64_t N, int D, int ld, int K, int M, int m, int NC, float acc_bound,
     uint8_t *__restrict__ codes, RefineItem *__restrict__ list, unsigned *__restrict__ refine_count,
-    PruneArgs pa)
+    PruneArgs pa, const uint4 *__restrict__ img)
 {
     extern __shared__ float4 smem4[];
     const int T = 4 * NC;                                                // 16-dim steps
@@ -172,7 +187,23 @@ __global__ __launch_bounds__(kAssignThreads) void k_assign_split(
     const int g = lane >> 5;
     const int r = lane & 31;
 
-    stage_codebook_split(lds_c, Cm, K, D, ld, KB, T);
+    {   // the split dictionary as k_split_norms has just laid it out: one contiguous copy
+        constexpr int U = 8;
+        const int total = KB * T * 2 * kWave;
+        for (int e0 = threadIdx.x; e0 < total; e0 += U * blockDim.x) {
+            uint4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int e = e0 + u * blockDim.x;
+                v[u] = e < total ? img[e] : make_uint4(0u, 0u, 0u, 0u);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int e = e0 + u * blockDim.x;
+                if (e < total) lds_c[e] = v[u];
+            }
+        }
+    }
     for (int k = threadIdx.x; k < 32 * KB; k += blockDim.x) lds_h[k] = hneg[k];
     __syncthreads();
     float hmax = 0.f;

@@ -44,6 +44,8 @@ struct hclae_ctx {
     float *hneg;             // [32*kb]
     float4 *cb_image;        // [NC][kb*8*64] codebook in staging order (k_codebook_image; D-chunked shapes only)
     float *lds_image;        // [kb*8*NC*64*4] dictionary of the running stage in the LDS order of the resident assign kernel
+    uint4 *split_image;      // [kb*4*NC*2*64] split dictionary in the LDS order of k_assign_split (written by k_split_norms)
+    size_t split_image_bytes;
     float *split_norms;      // [K][2] split constants of the codebook in use (contraction 1)
     int contraction;         // 0: fp32 MFMA, 1: split-bf16 MFMA
     unsigned *refine_count;
@@ -261,11 +263,14 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
         }
         // 3 MFMAs per 16 dims, each within 2^-21 of the magnitudes it adds; one more for the rounding of the norm
         const float acc_bound = (float)(3 * (dpad / kSplitStep) + 1) * 4.76837158203125e-7f;
-        hipLaunchKernelGGL(k_split_norms, dim3((ctx->K + 3) / 4), dim3(256), 0, ctx->stream, Cm, ctx->K, dact, ld, ctx->split_norms);
+        if ((size_t)KB * 4 * NC * 2 * kWave * sizeof(uint4) > ctx->split_image_bytes)
+            return fail(ctx, HCLAE_EINVAL, "assign: split dictionary image too small for this shape");
+        hipLaunchKernelGGL(k_split_norms, dim3((32 * KB + 3) / 4), dim3(256), 0, ctx->stream, Cm, ctx->K, dact, ld, ctx->split_norms,
+                           ctx->split_image, KB, 4 * NC);
         auto kern = prune == 1 ? &k_assign_split<KB, 1> : prune == 2 ? &k_assign_split<KB, 2> : &k_assign_split<KB, 0>;
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
                            xp, Cm, ctx->hneg, ctx->split_norms, N, dact, ld, ctx->K, ctx->M, m, NC, acc_bound,
-                           codes, ctx->refine_list, ctx->refine_count, pa);
+                           codes, ctx->refine_list, ctx->refine_count, pa, ctx->split_image);
     } else if (ctx->contraction == 1) {
         // D-chunked, split-bf16: two slices of 64 dims in LDS, one block per CU
         const size_t lds = (size_t)2 * KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
@@ -615,6 +620,10 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
     ctx->kb = K <= 32 ? 1 : K <= 64 ? 2 : K <= 128 ? 4 : 8;
     ctx->NC = (D + kChunkD - 1) / kChunkD;
     ctx->resident = (size_t)32 * ctx->kb * kChunkD * ctx->NC * sizeof(float) + 4096 <= (size_t)kLdsBudget;
+    {   // the split image serves every LDS-resident assignment, those on a prefix of a long row included
+        const int nc_res = (int)(((size_t)kLdsBudget - 4096) / ((size_t)32 * ctx->kb * kChunkD * sizeof(float)));
+        ctx->split_image_bytes = sizeof(uint4) * (size_t)ctx->kb * 4 * (ctx->NC < nc_res ? ctx->NC : nc_res) * 2 * kWave;
+    }
 
     hipError_t e = hipGetDevice(&ctx->device);
     hipDeviceProp_t prop;
@@ -642,6 +651,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
         {(void **)&ctx->hneg, sizeof(float) * 32 * ctx->kb},
         {(void **)&ctx->cb_image, ctx->resident ? 256 : sizeof(float4) * (size_t)ctx->NC * ctx->kb * 8 * kWave},
         {(void **)&ctx->lds_image, ctx->resident ? sizeof(float4) * (size_t)ctx->NC * ctx->kb * 8 * kWave : 256},
+        {(void **)&ctx->split_image, ctx->split_image_bytes},
         {(void **)&ctx->split_norms, sizeof(float) * 2 * HCLAE_MAX_K},
         {(void **)&ctx->refine_count, 256},
         {(void **)&ctx->refine_list, sizeof(RefineItem) * (size_t)N_max},
@@ -690,7 +700,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
 int hclae_destroy(hclae_ctx *ctx)
 {
     if (!ctx) return HCLAE_EINVAL;
-    void *dev[] = {ctx->hneg, ctx->cb_image, ctx->lds_image, ctx->split_norms, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
+    void *dev[] = {ctx->hneg, ctx->cb_image, ctx->lds_image, ctx->split_image, ctx->split_norms, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
                    ctx->nk, ctx->tot_sum, ctx->tot_cnt, ctx->upd_col, ctx->moved_list, ctx->moved_count, ctx->bnd_u, ctx->bnd_l, ctx->drift, ctx->active, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
                    ctx->run_sum, ctx->run_cnt, ctx->n0_dev, ctx->pca_rt, ctx->pca_crot, ctx->pca_colpart,
                    ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32,
