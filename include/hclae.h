@@ -182,9 +182,11 @@ int hclae_online_import(hclae_ctx *ctx, const double *run_sum, const int64_t *ru
 
 /*
  * Selects how the nearest-codeword kernels (Sec. 3.1 / 3.2 assignment; every entry point that assigns)
- * form the scores x'.c - ||c||^2/2.  Either way the scores only pre-select candidates within a rigorous
- * error margin and the decision is the fp64 direct-form re-check, so codes, dictionaries and residues do
- * not depend on the mode; only the number of vectors that take the re-check does.  Mode 1 applies to the
+ * form the scores x'.c - ||c||^2/2.  Either way the scores only pre-select candidates within an error margin
+ * (mode 0: a rigorous bound of the fp32 accumulation; mode 1: the dropped terms bounded rigorously, the
+ * accumulation of a bf16 MFMA by a measured constant with a fourfold allowance) and the decision is the fp64
+ * direct-form re-check, so codes, dictionaries and residues do not depend on the mode; only the number of
+ * vectors that take the re-check does.  Mode 1 applies to the
  * assignments and to the multi-path scoring (hclae_beam_step, hclae_encode_beam) of every shape.
  */
 int hclae_set_contraction(hclae_ctx *ctx, int mode);
@@ -237,9 +239,21 @@ int hclae_set_beam_width(hclae_ctx *ctx, int L);
 /* ---- improved k-means for high-dimensional residue (Sec. 3.2) --------------------------------- */
 
 /* Second moments of {x'} for its PCA: mean (DEVICE double[D]) and centred covariance (DEVICE
- * double[D][D], divided by N).  The eigen-decomposition itself is left to the caller: the rows of R
- * below are the principal axes, most variance first. */
+ * double[D][D], divided by N). */
 int hclae_covariance(hclae_ctx *ctx, const float *xp, int64_t N, int D, double *mean, double *cov);
+
+/* Step 1 of Sec. 3.2, the PCA space of {x'}: R (DEVICE float[D][D]) receives the principal axes of the N rows
+ * of xp as its rows, most variance first, each signed so that its entry of largest magnitude is positive;
+ * eigenvalues (HOST double[D], descending; may be NULL) the variances along them.  Second moments on the device
+ * (hclae_covariance), eigen-decomposition of the D x D matrix on the host in fp64 (Householder tridiagonal form,
+ * implicit-shift QR).  Synchronises the stream. */
+int hclae_pca_axes(hclae_ctx *ctx, const float *xp, int64_t N, int D, float *R, double *eigenvalues);
+
+/* The eigen-solver of hclae_pca_axes on its own; needs no device.  A: HOST double[n][n], symmetric, not
+ * modified.  w: HOST double[n], eigenvalues descending.  Vt: HOST double[n][n], row i = unit eigenvector of
+ * w[i] with its entry of largest magnitude positive.  1 <= n <= HCLAE_MAX_D.  HCLAE_ESTATE if the iteration
+ * does not converge. */
+int hclae_symmetric_eigen(const double *A, int n, double *w, double *Vt);
 
 /* Step 1 / step 3 of Sec. 3.2: out_n = R x_n (transpose == 0) or R^T x_n (transpose != 0) for the N rows
  * of x.  R: DEVICE float[D][D] row-major.  out: DEVICE float[N][D], must not alias x. */
@@ -256,8 +270,9 @@ int hclae_assign_prefix(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp
  *   for d in dims[0] < ... < dims[n_dims-1] = D: iters_per_dim Lloyd iterations whose assignment uses the
  *   first d coordinates and whose centroid update is the mean over all D coordinates;
  *   C_m = R^T C'; re-encode (assign in the original space); new residue.
- * R: DEVICE float[D][D].  dims: HOST int[n_dims].  xr: DEVICE float[N][D] scratch (caller-owned, holds
- * x^r on return).  Other arguments as hclae_anneal_stage.
+ * R: DEVICE float[D][D], the principal axes as rows; or NULL, in which case the stage computes them from
+ * its own x' (hclae_pca_axes; this synchronises the stream once).  dims: HOST int[n_dims].  xr: DEVICE
+ * float[N][D] scratch (caller-owned, holds x^r on return).  Other arguments as hclae_anneal_stage.
  */
 int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M, int K,
                            uint8_t *codes, float *residue, const float *R, const int *dims, int n_dims,
@@ -265,7 +280,7 @@ int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, in
 
 /* ---- dictionary order and code statistics (Sec. 3.3, Sec. 2.2) --------------------------------- */
 
-/* Sec. 3.3: "rearrange the dictionaries in the descending order of dictionary's elements variance".
+/* Sec. 3.3: dictionaries put in descending order of the variance of their codewords.
  * The variance of dictionary m is read as (1/K) sum_k ||c_m(k) - mean_k c_m||^2.  Writes var (HOST
  * double[M], variances in the OLD order) and order (HOST int[M]: new position j holds old dictionary
  * order[j]; ties keep the lower old index), then permutes C and the columns of codes accordingly, in place.

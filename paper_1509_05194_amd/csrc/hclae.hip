@@ -14,6 +14,7 @@
 #include "stream.hpp"
 #include "update.hpp"
 #include "pca.hpp"
+#include "eigen.hpp"
 #include "stats.hpp"
 #include "beam.hpp"
 #include <algorithm>
@@ -84,6 +85,8 @@ struct hclae_ctx {
     double *pca_grampart;    // [pca_ngram][D][D]
     double *pca_mean;        // [D]
     float *pca_mean32;       // [D]
+    double *pca_cov;         // [D][D] covariance of x' when the stage finds the principal axes itself
+    float *pca_R;            // [D][D] those axes (rows), fp32
     int pca_ncol, pca_ngram;
     // multi-path encoding scratch (allocated on first use, regrown when L or the batch grows)
     int64_t beam_cap;        // vectors per batch the buffers hold
@@ -703,7 +706,7 @@ int hclae_destroy(hclae_ctx *ctx)
     void *dev[] = {ctx->hneg, ctx->cb_image, ctx->lds_image, ctx->split_image, ctx->split_norms, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
                    ctx->nk, ctx->tot_sum, ctx->tot_cnt, ctx->upd_col, ctx->moved_list, ctx->moved_count, ctx->bnd_u, ctx->bnd_l, ctx->drift, ctx->active, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
                    ctx->run_sum, ctx->run_cnt, ctx->n0_dev, ctx->pca_rt, ctx->pca_crot, ctx->pca_colpart,
-                   ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32,
+                   ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32, ctx->pca_cov, ctx->pca_R,
                    ctx->beam_rows[0], ctx->beam_rows[1], ctx->beam_err[0], ctx->beam_err[1],
                    ctx->beam_pre[0], ctx->beam_pre[1], ctx->beam_mask};
     for (void *p : dev)
@@ -1265,6 +1268,8 @@ static int pca_scratch(hclae_ctx *ctx)
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->pca_grampart, (size_t)ng * D * D * sizeof(double));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->pca_mean, (size_t)D * sizeof(double));
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->pca_mean32, (size_t)D * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->pca_cov, (size_t)D * D * sizeof(double));
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->pca_R, (size_t)D * D * sizeof(float));
     if (e != hipSuccess) return fail(ctx, e == hipErrorOutOfMemory ? HCLAE_ENOMEM : HCLAE_EHIP, "hipMalloc (PCA scratch)", e);
     return HCLAE_OK;
 }
@@ -1312,15 +1317,9 @@ int hclae_rotate(hclae_ctx *ctx, const float *x, int64_t N, int D, const float *
     return launch_rotate(ctx, x, N, R, transpose, out);
 }
 
-int hclae_covariance(hclae_ctx *ctx, const float *xp, int64_t N, int D, double *mean, double *cov)
+static int enqueue_covariance(hclae_ctx *ctx, const float *xp, int64_t N, double *mean, double *cov)
 {
-    if (!ctx) return HCLAE_EINVAL;
-    int rc = hclae_check_shape(N, D, ctx->M, ctx->K);
-    if (rc != HCLAE_OK) return fail(ctx, rc, "shape out of range");
-    if (D != ctx->D) return fail(ctx, HCLAE_ESTATE, "D differs from hclae_create");
-    if (N < 1 || !xp || !mean || !cov) return fail(ctx, HCLAE_EINVAL, "hclae_covariance: bad argument");
-    if (misaligned(xp)) return fail(ctx, HCLAE_EINVAL, "hclae_covariance: float arrays must be 16-byte aligned");
-    if ((rc = pca_scratch(ctx)) != HCLAE_OK) return rc;
+    const int D = ctx->D;
     Timed t_(ctx, HCLAE_T_MOMENTS);
     int ncol = (int)((N + 1023) / 1024);
     if (ncol > ctx->pca_ncol) ncol = ctx->pca_ncol;
@@ -1343,6 +1342,63 @@ int hclae_covariance(hclae_ctx *ctx, const float *xp, int64_t N, int D, double *
                        ctx->pca_grampart, ng, N, D, mean, ctx->pca_mean32, cov);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
+}
+
+int hclae_covariance(hclae_ctx *ctx, const float *xp, int64_t N, int D, double *mean, double *cov)
+{
+    if (!ctx) return HCLAE_EINVAL;
+    int rc = hclae_check_shape(N, D, ctx->M, ctx->K);
+    if (rc != HCLAE_OK) return fail(ctx, rc, "shape out of range");
+    if (D != ctx->D) return fail(ctx, HCLAE_ESTATE, "D differs from hclae_create");
+    if (N < 1 || !xp || !mean || !cov) return fail(ctx, HCLAE_EINVAL, "hclae_covariance: bad argument");
+    if (misaligned(xp)) return fail(ctx, HCLAE_EINVAL, "hclae_covariance: float arrays must be 16-byte aligned");
+    if ((rc = pca_scratch(ctx)) != HCLAE_OK) return rc;
+    return enqueue_covariance(ctx, xp, N, mean, cov);
+}
+
+// Principal axes of the N rows of xp into R (DEVICE float [D][D], rows = axes, most variance first): second
+// moments on the device, eigen-decomposition on the host in fp64, axes rounded to fp32.  Synchronises the stream.
+static int compute_pca_axes(hclae_ctx *ctx, const float *xp, int64_t N, float *R, double *eigenvalues)
+{
+    const int D = ctx->D;
+    int rc = enqueue_covariance(ctx, xp, N, ctx->pca_mean, ctx->pca_cov);
+    if (rc != HCLAE_OK) return rc;
+    std::vector<double> cov((size_t)D * D), w(D), vt((size_t)D * D);
+    HIP_TRY(ctx, hipMemcpyAsync(cov.data(), ctx->pca_cov, cov.size() * sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    // the device result is symmetric up to the rounding order of the two triangles: take their mean
+    for (int i = 0; i < D; ++i)
+        for (int j = i + 1; j < D; ++j) {
+            const double a = 0.5 * (cov[(size_t)i * D + j] + cov[(size_t)j * D + i]);
+            cov[(size_t)i * D + j] = cov[(size_t)j * D + i] = a;
+        }
+    if (symmetric_eigen(cov.data(), D, w.data(), vt.data()) != 0)
+        return fail(ctx, HCLAE_EHIP, "eigen-decomposition of the covariance did not converge");
+    std::vector<float> r32((size_t)D * D);
+    for (size_t i = 0; i < r32.size(); ++i) r32[i] = (float)vt[i];
+    HIP_TRY(ctx, hipMemcpyAsync(R, r32.data(), r32.size() * sizeof(float), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));               // r32 is pageable host memory of this frame
+    if (eigenvalues) for (int i = 0; i < D; ++i) eigenvalues[i] = w[i];
+    return HCLAE_OK;
+}
+
+int hclae_symmetric_eigen(const double *A, int n, double *w, double *Vt)
+{
+    if (!A || !w || !Vt || n < 1 || n > HCLAE_MAX_D) return HCLAE_EINVAL;
+    std::vector<double> work(A, A + (size_t)n * n);
+    return symmetric_eigen(work.data(), n, w, Vt) == 0 ? HCLAE_OK : HCLAE_ESTATE;
+}
+
+int hclae_pca_axes(hclae_ctx *ctx, const float *xp, int64_t N, int D, float *R, double *eigenvalues)
+{
+    if (!ctx) return HCLAE_EINVAL;
+    int rc = hclae_check_shape(N, D, ctx->M, ctx->K);
+    if (rc != HCLAE_OK) return fail(ctx, rc, "shape out of range");
+    if (D != ctx->D) return fail(ctx, HCLAE_ESTATE, "D differs from hclae_create");
+    if (N < 1 || !xp || !R) return fail(ctx, HCLAE_EINVAL, "hclae_pca_axes: bad argument");
+    if (misaligned(xp, R)) return fail(ctx, HCLAE_EINVAL, "hclae_pca_axes: float arrays must be 16-byte aligned");
+    if ((rc = pca_scratch(ctx)) != HCLAE_OK) return rc;
+    return compute_pca_axes(ctx, xp, N, R, eigenvalues);
 }
 
 int hclae_assign_prefix(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, const float *C,
@@ -1375,7 +1431,7 @@ int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, in
         for (int i = 0; i < K; ++i)
             if (init_idx[i] < 0 || init_idx[i] >= N) return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: init_idx out of range");
     if (N == 0) { if (stats) memset(stats, 0, sizeof(*stats)); return HCLAE_OK; }
-    if (!C || !codes || !residue || !R || !xr || xr == residue)
+    if (!C || !codes || !residue || !xr || xr == residue)
         return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: NULL or aliased pointer");
     if (misaligned(C, residue, R, xr)) return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: float arrays must be 16-byte aligned");
     if ((rc = pca_scratch(ctx)) != HCLAE_OK) return rc;
@@ -1388,6 +1444,10 @@ int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, in
     if (init_idx) {
         hipLaunchKernelGGL(k_seed, dim3(K), dim3(256), 0, ctx->stream, residue, ctx->seed_idx, K, D, Cm);
         HIP_TRY(ctx, hipGetLastError());
+    }
+    if (!R) {                   // step 1 of Sec. 3.2 inside the library: the principal axes of this stage's x'
+        if ((rc = compute_pca_axes(ctx, residue, N, ctx->pca_R, nullptr)) != HCLAE_OK) return rc;
+        R = ctx->pca_R;
     }
     // into the PCA space: x^r = R x', C' = R C_m (C[m] holds C' until it is rotated back)
     if ((rc = launch_rotate(ctx, residue, N, R, 0, xr)) != HCLAE_OK) return rc;

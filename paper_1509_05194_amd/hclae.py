@@ -22,7 +22,7 @@ EXPORTS = (
     "hclae_heat", "hclae_cool", "hclae_assign", "hclae_update", "hclae_last_refined",
     "hclae_timing_enable", "hclae_timing_read", "hclae_online_begin", "hclae_online_chunk",
     "hclae_online_export", "hclae_online_import",
-    "hclae_covariance", "hclae_rotate", "hclae_assign_prefix", "hclae_anneal_stage_pca",
+    "hclae_covariance", "hclae_pca_axes", "hclae_symmetric_eigen", "hclae_rotate", "hclae_assign_prefix", "hclae_anneal_stage_pca",
     "hclae_reorder_by_variance", "hclae_code_stats",
     "hclae_beam_step", "hclae_encode_beam", "hclae_set_beam_width", "hclae_set_contraction", "hclae_set_pruning",
 )
@@ -86,6 +86,8 @@ def lib():
     L.hclae_online_export.argtypes = [vp, vp, vp]
     L.hclae_online_import.argtypes = [vp, vp, vp]
     L.hclae_covariance.argtypes = [vp, vp, i64, i32, vp, vp]
+    L.hclae_pca_axes.argtypes = [vp, vp, i64, i32, vp, vp]
+    L.hclae_symmetric_eigen.argtypes = [vp, i32, vp, vp]
     L.hclae_rotate.argtypes = [vp, vp, i64, i32, vp, i32, vp]
     L.hclae_assign_prefix.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, i32, vp]
     L.hclae_anneal_stage_pca.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, vp,
@@ -108,6 +110,20 @@ def lib():
 
 def check_shape(N, D, M, K):
     return lib().hclae_check_shape(N, D, M, K)
+
+
+def symmetric_eigen(A):
+    """(w float64 [n] descending, Vt float64 [n][n], rows = eigenvectors) of a symmetric host matrix; no device."""
+    A = np.ascontiguousarray(A, np.float64)
+    n = A.shape[0]
+    assert A.shape == (n, n)
+    w = np.zeros(n, np.float64)
+    Vt = np.zeros((n, n), np.float64)
+    rc = lib().hclae_symmetric_eigen(A.ctypes.data_as(ctypes.c_void_p), n, w.ctypes.data_as(ctypes.c_void_p),
+                                     Vt.ctypes.data_as(ctypes.c_void_p))
+    if rc != OK:
+        raise HclaeError(rc, "hclae_symmetric_eigen")
+    return w, Vt
 
 
 def _ptr(t, dtype_name, shape=None):
@@ -292,6 +308,16 @@ class Context:
                                          ctypes.c_void_p(mean.data_ptr()), ctypes.c_void_p(cov.data_ptr())))
         return mean, cov
 
+    def pca_axes(self, xp):
+        """(R float32 [D][D] CUDA tensor, rows = principal axes; eigenvalues float64 [D] NumPy, descending)."""
+        import torch
+        N = xp.shape[0]
+        R = torch.empty((self.D, self.D), dtype=torch.float32, device=xp.device)
+        w = np.zeros(self.D, np.float64)
+        self._chk(lib().hclae_pca_axes(self._h, _ptr(xp, "f32", (N, self.D)), N, self.D, _ptr(R, "f32"),
+                                       w.ctypes.data_as(ctypes.c_void_p)))
+        return R, w
+
     def rotate(self, x, R, out, transpose=False):
         N = x.shape[0]
         self._chk(lib().hclae_rotate(self._h, _ptr(x, "f32", (N, self.D)), N, self.D, _ptr(R, "f32", (self.D, self.D)),
@@ -312,7 +338,8 @@ class Context:
             assert idx.shape == (self.K,)
         stats = StageStats() if want_stats else None
         self._chk(lib().hclae_anneal_stage_pca(
-            self._h, m, N, self.D, pC, self.M, self.K, pcodes, pres, _ptr(R, "f32", (self.D, self.D)),
+            self._h, m, N, self.D, pC, self.M, self.K, pcodes, pres,
+            _ptr(R, "f32", (self.D, self.D)) if R is not None else None,
             dims.ctypes.data_as(ctypes.c_void_p), len(dims), iters_per_dim, _ptr(xr, "f32", (N, self.D)),
             idx.ctypes.data_as(ctypes.c_void_p) if idx is not None else None,
             ctypes.byref(stats) if want_stats else None))

@@ -1,0 +1,74 @@
+"""The host eigen-solver behind hclae_pca_axes (Sec. 3.2, step 1: the PCA space of {x'}), through the C ABI, without a
+GPU: against LAPACK (numpy.linalg.eigh), against closed forms, and against the oracle's axis conventions."""
+import numpy as np
+import pytest
+
+from paper_1509_05194_amd import hclae
+
+
+def _check(A, w, Vt, tol=1e-12):
+    n = A.shape[0]
+    scale = max(np.abs(A).max(), 1e-300)
+    ref = np.linalg.eigvalsh(A)[::-1]
+    assert np.all(np.diff(w) <= 0), "eigenvalues not descending"
+    assert np.abs(w - ref).max() <= tol * scale * n
+    assert np.abs(Vt @ Vt.T - np.eye(n)).max() <= tol * n
+    assert np.abs(A @ Vt.T - Vt.T * w[None, :]).max() <= tol * scale * n
+    for i in range(n):                                   # sign convention: the first largest-magnitude entry is positive
+        assert Vt[i, np.argmax(np.abs(Vt[i]))] > 0
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 7, 16, 128, 257])
+def test_random_symmetric_against_lapack(n):
+    g = np.random.default_rng(n)
+    B = g.standard_normal((n, n))
+    for A in (B + B.T, B @ B.T / n, (B + B.T) * 1e-9, (B @ B.T) * 1e9):
+        w, Vt = hclae.symmetric_eigen(A)
+        _check(A, w, Vt)
+
+
+def test_closed_forms():
+    # diagonal: nothing to do but sort
+    A = np.diag([3.0, -1.0, 7.0, 0.0])
+    w, Vt = hclae.symmetric_eigen(A)
+    np.testing.assert_array_equal(w, [7.0, 3.0, 0.0, -1.0])
+    np.testing.assert_array_equal(Vt, np.eye(4)[[2, 0, 3, 1]])
+    # 2 x 2: [[2, 1], [1, 2]] has eigenvalues 3, 1 with axes (1, 1)/sqrt 2 and (1, -1)/sqrt 2
+    w, Vt = hclae.symmetric_eigen(np.array([[2.0, 1.0], [1.0, 2.0]]))
+    np.testing.assert_allclose(w, [3.0, 1.0], rtol=1e-15)
+    np.testing.assert_allclose(Vt, np.array([[1.0, 1.0], [1.0, -1.0]]) / np.sqrt(2.0), atol=1e-15)
+    # second-difference matrix: eigenvalues 2 - 2 cos(k pi / (n + 1)), already tridiagonal
+    n = 50
+    A = 2.0 * np.eye(n) - np.eye(n, k=1) - np.eye(n, k=-1)
+    w, Vt = hclae.symmetric_eigen(A)
+    np.testing.assert_allclose(w, 2.0 - 2.0 * np.cos(np.arange(n, 0, -1) * np.pi / (n + 1)), rtol=1e-13)
+    _check(A, w, Vt)
+    # rank one plus identity: one eigenvalue 1 + ||u||^2 along u, the rest 1 (a repeated eigenvalue)
+    u = np.arange(1.0, 9.0)
+    A = np.eye(8) + np.outer(u, u)
+    w, Vt = hclae.symmetric_eigen(A)
+    np.testing.assert_allclose(w, [1.0 + u @ u] + [1.0] * 7, rtol=1e-13)
+    np.testing.assert_allclose(Vt[0], u / np.linalg.norm(u), atol=1e-14)
+    _check(A, w, Vt)
+    # zero matrix, and the argument checks
+    w, Vt = hclae.symmetric_eigen(np.zeros((5, 5)))
+    assert np.all(w == 0) and np.abs(Vt @ Vt.T - np.eye(5)).max() < 1e-15
+    L = hclae.lib()
+    assert L.hclae_symmetric_eigen(None, 3, None, None) == hclae.EINVAL
+    buf = np.zeros(4)
+    assert L.hclae_symmetric_eigen(buf.ctypes.data, 0, buf.ctypes.data, buf.ctypes.data) == hclae.EINVAL
+
+
+def test_axes_follow_the_oracles_conventions(oracle):
+    """Data with a clear spectrum: the solver applied to the covariance gives the oracle's principal axes -- same
+    order (most variance first), same signs -- to rounding."""
+    g = np.random.default_rng(5)
+    D = 24
+    Q = np.linalg.qr(g.standard_normal((D, D)))[0]
+    sig = 0.8 ** np.arange(D)                              # well separated variances (ratio 0.64 from one to the next)
+    X = (g.standard_normal((4000, D)) * sig) @ Q.T + 3.0
+    R_o = oracle.pca_axes(X)
+    cov = np.cov(X, rowvar=False, bias=True)
+    w, Vt = hclae.symmetric_eigen(cov)
+    np.testing.assert_allclose(Vt, R_o, atol=1e-8)
+    np.testing.assert_allclose(w, np.sort(np.linalg.eigvalsh(cov))[::-1], rtol=1e-10)

@@ -48,18 +48,18 @@ def test_fullsize_steps_sampled(data, oracle):
     assert np.all(np.abs(dm[same] - d1[same]) <= 2e-7 * d1[same])
     assert np.all(got[:, 1] == 0)
 
-    # --- centroid update at full N: every codeword against the plain fp64 mean of its members
+    # --- centroid update at full N: every codeword against the oracle's update of the same state
     counts = torch.zeros(K, dtype=torch.int32, device="cuda:0")
     C_before = C.clone()
     ctx.update(0, Xg, C, codes, counts)
-    col = codes[:, 0].long()
-    ref_cnt = torch.bincount(col, minlength=K)
-    assert torch.equal(ref_cnt.int(), counts)
-    sums = torch.zeros((K, D), dtype=torch.float64, device="cuda:0").index_add_(0, col, Xg.double())
-    ref = torch.where(ref_cnt[:, None] > 0, sums / ref_cnt.clamp(min=1)[:, None].double(), C_before[0].double())
-    err = (C[0].double() - ref).norm(dim=1) / (ref.norm() / K ** 0.5)
-    print("full-size update: max row error %.2e, empty %d" % (err.max().item(), int((ref_cnt == 0).sum())))
-    assert err.max().item() <= 1e-5
+    Cref = C_before.cpu().numpy().astype(np.float64)
+    cnt_o, empty_o = oracle.update(X.astype(np.float64), got, Cref, 0)
+    np.testing.assert_array_equal(counts.cpu().numpy().astype(np.int64), cnt_o)
+    Cn = C.cpu().numpy().astype(np.float64)
+    err = np.linalg.norm(Cn[0] - Cref[0], axis=1) / (np.linalg.norm(Cref[0]) / K ** 0.5)
+    print("full-size update: max row error %.2e, empty %d" % (err.max(), empty_o))
+    assert err.max() <= 1e-5
+    np.testing.assert_array_equal(Cn[1], Cref[1])          # the other dictionary untouched
     Cb = C_before.clone()
     ctx.update(0, Xg, Cb, codes, None)
     assert torch.equal(Cb, C)                              # bit-reproducible

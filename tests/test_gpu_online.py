@@ -151,3 +151,37 @@ def test_pipelined_host_chunks_give_identical_results():
     assert torch.equal(Ca, Cb)
     for a, b in zip(codes_a, codes_b):
         assert torch.equal(a, b)
+
+
+def test_online_chunks_free_running_against_oracle_online_chunk(oracle):
+    """Free-running: hclae_online_chunk and the oracle's own online_chunk each process the same chunks from the
+    same start, nothing exchanged in between.  The case has no near-tie that the two sides decide differently
+    (the codes must be EQUAL), so dictionaries, running sums, residues and E must agree to the fp32 bars."""
+    from paper_1509_05194_amd import hclae
+    n, nch = 6000 + 5, 3
+    chunks = [synth.sift_like(n, D=D, start=7_000_000 + i * n, dtype=np.uint8) for i in range(nch)]
+    C0 = _start_dictionaries(oracle, np.ascontiguousarray(synth.sift_like(CH, D=D, dtype=np.uint8)))
+    n0 = np.full((M, K), 40, np.int64)
+    ctx = hclae.Context(n, D, M, K)
+    Cg = to_dev(C0)
+    ctx.online_begin(Cg, n0)
+    Co = C0.astype(np.float64)
+    S = Co * n0[:, :, None]
+    cnt = n0.copy()
+    codes_g = torch.zeros((n, M), dtype=torch.uint8, device="cuda:0")
+    rg = torch.empty((n, D), dtype=torch.float32, device="cuda:0")
+    for i, ch in enumerate(chunks):
+        E_g = ctx.online_chunk(to_dev(ch), Cg, codes_g, rg, want_err=True)
+        codes_o, r_o, E_o = oracle.online_chunk(ch, Co, S, cnt)
+        ndiff = int((codes_g.cpu().numpy() != codes_o).sum())
+        print("free-running online chunk %d: %d codes differ, E gpu %.6f oracle %.6f, C err %.2e"
+              % (i, ndiff, E_g, E_o, rel_fro(Cg.cpu().numpy(), Co)))
+        assert ndiff == 0
+        assert abs(E_g - E_o) <= 1e-4 * E_o
+        assert rel_fro(rg.cpu().numpy(), r_o) <= 1e-4
+        for m in range(M):
+            assert rel_fro(Cg[m].cpu().numpy(), Co[m]) <= 1e-4
+    S_g, cnt_g = ctx.online_export()
+    np.testing.assert_array_equal(cnt_g, cnt)
+    assert rel_fro(S_g, S) <= 1e-6
+    ctx.close()

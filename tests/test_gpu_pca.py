@@ -201,3 +201,75 @@ def test_pca_stage_lockstep_and_entry_point(case, oracle):
     print("%s improved k-means: adopted %d near-ties; E after the stages %.6g" % (case, adopted, Eg))
     assert rel_fro(Cg.cpu().numpy(), C64) <= 1e-4
     ctx.close()
+
+
+@pytest.mark.parametrize("case", ["tiny", "sift"])
+def test_pca_stage_free_running_against_oracle_stage(case, oracle):
+    """Free-running: hclae_anneal_stage_pca (principal axes found inside the library) against the oracle's own
+    anneal_stage_pca with the oracle's axes, from the same start, nothing exchanged in between.  The cases have
+    no near-tie that the two sides decide differently: codes must be EQUAL, the rest within 1e-4."""
+    c = SHAPES[case]
+    N, D, M, K = c["N"], c["D"], c["M"], c["K"]
+    T = 2
+    X = _data(c)
+    idx = synth.init_indices(N, M, K)
+    dims = oracle.dimension_schedule(D, 10)
+    ctx = _ctx(c)
+    C64, codes64, r64 = fresh_state(X, M, K)
+    Cg = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+    codes_g = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+    rg = to_dev(X)
+    xr = torch.empty_like(rg)
+    for m in range(M):
+        R64 = oracle.pca_axes(r64)                                    # heat of a fresh stage is the identity
+        Eo = oracle.anneal_stage_pca(m, C64, codes64, r64, R64, dims, T, idx[m])
+        st = ctx.anneal_stage_pca(m, Cg, codes_g, rg, None, dims, T, xr, init_idx=idx[m])
+        ndiff = int((codes_g.cpu().numpy() != codes64).sum())
+        print("%s free-running improved k-means, stage %d: %d codes differ, E gpu %.6g oracle %.6g, C err %.2e"
+              % (case, m, ndiff, st["err_after"], Eo, rel_fro(Cg[m].cpu().numpy(), C64[m])))
+        assert ndiff == 0
+        assert abs(st["err_after"] - Eo) <= 1e-4 * Eo
+        assert rel_fro(Cg[m].cpu().numpy(), C64[m]) <= 1e-4
+        assert rel_fro(rg.cpu().numpy(), r64) <= 1e-4
+    ctx.close()
+
+
+def test_pca_axes_against_oracle_axes(oracle):
+    """hclae_pca_axes (second moments on the device, eigen-solver inside the library) against oracle.pca_axes
+    (NumPy covariance + LAPACK) on data with a clear spectrum: same axes in the same order with the same signs;
+    on the SIFT-shaped data, whose small eigenvalues are close to one another: the same invariant subspaces
+    (R diagonalises the oracle's covariance, eigenvalues descending and equal to LAPACK's)."""
+    from paper_1509_05194_amd import hclae
+    g = np.random.default_rng(11)
+    N, D = 30000 + 7, 32
+    Q = np.linalg.qr(g.standard_normal((D, D)))[0]
+    X = ((g.standard_normal((N, D)) * 0.8 ** np.arange(D)) @ Q.T + 2.0).astype(np.float32)
+    ctx = hclae.Context(N, D, 1, 16)
+    R, w = ctx.pca_axes(to_dev(X))
+    R = R.cpu().numpy().astype(np.float64)
+    R_o = oracle.pca_axes(X.astype(np.float64))
+    cov = np.cov(X.astype(np.float64), rowvar=False, bias=True)
+    w_o = np.linalg.eigvalsh(cov)[::-1]
+    print("clear spectrum: max axis error %.2e, max eigenvalue error %.2e of the largest"
+          % (np.abs(R - R_o).max(), np.abs(w - w_o).max() / w_o[0]))
+    assert np.abs(w - w_o).max() <= 1e-5 * w_o[0]          # the covariance comes from an fp32 matrix-core contraction
+    # an axis moves by about (error of the covariance) / (gap to the next eigenvalue)
+    gap = np.minimum(np.abs(np.diff(w_o, prepend=np.inf)), np.abs(np.diff(w_o, append=-np.inf)))
+    assert np.all(np.abs(R - R_o).max(axis=1) <= 2e-5 * w_o[0] / gap + 1e-6)
+    for i in range(D):
+        assert R[i, np.argmax(np.abs(R_o[i]))] > 0         # the oracle's sign convention
+    ctx.close()
+
+    c = SHAPES["sift"]
+    X = _data(c)
+    ctx = _ctx(c)
+    R, w = ctx.pca_axes(to_dev(X))
+    R = R.cpu().numpy().astype(np.float64)
+    cov = np.cov(X.astype(np.float64), rowvar=False, bias=True)
+    w_o = np.linalg.eigvalsh(cov)[::-1]
+    assert np.all(np.diff(w) <= 0) and np.abs(w - w_o).max() <= 1e-5 * w_o[0]
+    assert np.abs(R @ R.T - np.eye(c["D"])).max() <= 1e-6
+    T = R @ cov @ R.T
+    assert np.abs(T - np.diag(np.diag(T))).max() <= 2e-5 * w_o[0]
+    np.testing.assert_allclose(np.diag(T), w_o, atol=2e-5 * w_o[0])
+    ctx.close()

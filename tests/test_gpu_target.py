@@ -1,0 +1,197 @@
+"""The target itself, on ALL vectors: full DA sweeps (arXiv 1509.05194, Sec. 3.1) at the shapes of the paper's
+datasets (Sec. 5.1) against the oracle.
+
+  * SIFT1M shape, 64-bit codes: N = 1,000,000, D = 128, M = 8, K = 256, T = 10 -- a sweep from all-zero
+    dictionaries, then one annealing sweep;
+  * 128-bit codes: M = 16, two sweeps, N = 250,000 (what the oracle finishes in about two minutes);
+  * GIST1M shape: D = 960, M = 8, one sweep from all-zero dictionaries, N = 125,000.
+
+k-means is a chaotic iteration: one legitimate near-tie decided the other way moves a centroid, which moves
+other vectors in the next iteration.  Two free-running trajectories can therefore not be compared code by code
+after the first such tie, and at a million vectors and 88 assignments per sweep there are always some.  The
+comparison is therefore made in three parts, which together cover the product call bit for bit:
+
+  (1) hclae_sweep is called as a user calls it (one call per sweep, exact shortcuts on) and its outputs kept;
+  (2) the same sweeps are driven through the single-step entry points (hclae_heat / assign / update / cool, never
+      pruned) in lockstep with the oracle's primitives: after EVERY assignment all N codes are judged -- equal,
+      or an oracle near-tie (top-2 gap < 1e-5 relative) whose GPU choice is itself within 1e-5 of the best --
+      and the oracle adopts the exempt ones, so that both sides keep describing the same trajectory; after
+      every centroid update the dictionary, after every stage E, after every sweep the residues and all
+      dictionaries must agree within 1e-4 relative (tighter where stated);
+  (3) the outputs of (1) must equal the GPU state of (2) bit for bit.
+
+For the SIFT shape the oracle's own free-running sweep (oracle.sweep, no adoption) is run as well and compared
+with (1): E per stage within 1e-4, the share of differing codes reported, and the full bars applied when no
+code differs.
+"""
+import time
+
+import numpy as np
+import pytest
+
+from paper_1509_05194_amd import synth
+from parity_util import fresh_state, judge_codes, rel_fro, to_dev
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture
+def progress(capsys):
+    """Progress lines that reach the terminal while the test runs (a test of several minutes must not look hung)."""
+    t0 = time.perf_counter()
+
+    def say(msg):
+        with capsys.disabled():
+            print("  [%6.1f s] %s" % (time.perf_counter() - t0, msg), flush=True)
+    return say
+
+
+def _max_rel_row_error(got, ref):
+    """max_n ||got_n - ref_n|| / max(||ref_n||, rms_n ||ref||), in slices to bound the temporaries."""
+    rms = np.sqrt(_sq_mean(ref))
+    worst = 0.0
+    for a in range(0, ref.shape[0], 131072):
+        d = got[a:a + 131072].astype(np.float64) - ref[a:a + 131072]
+        nr = np.sqrt((ref[a:a + 131072] ** 2).sum(1))
+        worst = max(worst, float((np.sqrt((d ** 2).sum(1)) / np.maximum(nr, rms)).max()))
+    return worst
+
+
+def _sq_mean(r):
+    s = 0.0
+    for a in range(0, r.shape[0], 131072):
+        s += float((r[a:a + 131072] ** 2).sum())
+    return s / r.shape[0]
+
+
+def _sliced_rel_fro(got, ref):
+    num = den = 0.0
+    for a in range(0, ref.shape[0], 131072):
+        d = got[a:a + 131072].astype(np.float64) - ref[a:a + 131072]
+        num += float((d ** 2).sum())
+        den += float((ref[a:a + 131072] ** 2).sum())
+    return np.sqrt(num / max(den, 1e-300))
+
+
+def _target(oracle, say, X, M, K, T, sweeps, free_running):
+    from paper_1509_05194_amd import hclae
+    N, D = X.shape
+    idx = synth.init_indices(N, M, K)
+    Xg = to_dev(X)
+
+    # ---- (1) the product call
+    ctx = hclae.Context(N, D, M, K)
+    C1 = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+    codes1 = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+    r1 = Xg.clone()
+    product = []
+    for s in range(sweeps):
+        E = ctx.sweep(C1, codes1, r1, T, init_idx=idx if s == 0 else None)
+        product.append((C1.clone(), codes1.clone(), r1.clone(), E))
+        say("hclae_sweep %d: E per stage %s" % (s, np.array2string(E, precision=6)))
+    del C1, codes1, r1
+
+    # ---- (2) single steps in lockstep with the oracle, every code of every assignment judged
+    C64, codes64, r64 = fresh_state(X, M, K)
+    Cg = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+    codes_g = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+    rg = Xg.clone()
+    adopted = differing = 0
+    for s in range(sweeps):
+        E_lock = np.zeros(M)
+        for m in range(M):
+            ctx.heat(m, Cg, codes_g, rg)
+            oracle.heat(r64, codes64, C64, m)
+            if s == 0:                                                # seeding: a buffer copy on either side
+                Cg[m] = rg[torch.from_numpy(idx[m]).cuda()]
+                C64[m] = r64[idx[m]]
+            xmax = max(float(np.abs(r64[a:a + 131072]).max()) for a in range(0, N, 131072))
+            for t in range(T + 1):
+                ctx.assign(m, rg, Cg, codes_g)
+                d1, d2, _ = oracle.assign(r64, C64, codes64, m, top2=True)
+                got = codes_g[:, m].contiguous().cpu().numpy()
+                ndiff, nex, bad = judge_codes(oracle, r64, C64, m, got, codes64[:, m], d1, d2)
+                assert not bad, "sweep %d stage %d assignment %d: non-exempt code mismatches at %s" % (s, m, t, bad[:10])
+                differing += ndiff
+                adopted += nex
+                codes64[:, m] = got
+                if t < T:
+                    ctx.update(m, rg, Cg, codes_g)
+                    oracle.update(r64, codes64, C64, m)
+                    # 1e-5 of the dictionary's norm, plus half an fp32 ulp of the largest |x'| per element: the
+                    # GPU's x' is stored in fp32, the oracle's in fp64
+                    diff = np.linalg.norm(Cg[m].cpu().numpy().astype(np.float64) - C64[m])
+                    assert diff <= 1e-5 * np.linalg.norm(C64[m]) + np.sqrt(K * D) * xmax * 2.0 ** -24, \
+                        "sweep %d stage %d update %d: dictionary off by %.3g" % (s, m, t, diff)
+            ctx.cool(m, Cg, codes_g, rg)
+            oracle.cool(r64, codes64, C64, m)
+            Eg, Eo = ctx.quant_error(rg), oracle.quant_error(r64)
+            E_lock[m] = Eg
+            assert abs(Eg - Eo) <= 1e-4 * Eo, "sweep %d stage %d: E %r vs %r" % (s, m, Eg, Eo)
+            say("lockstep sweep %d stage %d: E gpu %.6f oracle %.6f (rel %.1e); near-ties adopted so far %d"
+                % (s, m, Eg, Eo, abs(Eg - Eo) / Eo, adopted))
+        # after the sweep: all dictionaries, all residues
+        Cn = Cg.cpu().numpy()
+        for m in range(M):
+            assert rel_fro(Cn[m], C64[m]) <= 1e-4, "sweep %d: dictionary %d" % (s, m)
+            scale = np.linalg.norm(C64[m]) / np.sqrt(K)
+            row = np.linalg.norm(Cn[m].astype(np.float64) - C64[m], axis=1).max()
+            assert row <= 1e-4 * scale, "sweep %d: a codeword of dictionary %d is off by %.3g" % (s, m, row)
+        rn = rg.cpu().numpy()
+        rf, rmax = _sliced_rel_fro(rn, r64), _max_rel_row_error(rn, r64)
+        say("lockstep sweep %d: residue error %.2e (Frobenius), %.2e (worst vector); dictionaries %.2e"
+            % (s, rf, rmax, rel_fro(Cn, C64)))
+        assert rf <= 1e-4 and rmax <= 1e-4
+        del rn
+        # x = sum_m C_m[i_m] + r on the GPU state, all vectors
+        recon = rg.clone()
+        for m in range(M):
+            recon += Cg[m][codes_g[:, m].long()]
+        assert float((recon - Xg).abs().max()) <= 1e-5 * max(float(np.abs(X).max()), 1.0) * max(1, M // 8)
+        del recon
+        # ---- (3) the product call gave these very bits
+        Cp, codesp, rp, Ep = product[s]
+        assert torch.equal(Cp, Cg), "sweep %d: hclae_sweep and the single steps differ in the dictionaries" % s
+        assert torch.equal(codesp, codes_g), "sweep %d: hclae_sweep and the single steps differ in the codes" % s
+        assert torch.equal(rp, rg), "sweep %d: hclae_sweep and the single steps differ in the residues" % s
+        np.testing.assert_allclose(Ep, E_lock, rtol=1e-12)
+        assert np.all(np.diff(Ep) <= 1e-7 * Ep[:-1]), "E rose inside sweep %d" % s
+    say("lockstep: %d codes differed over %d assignments of %d vectors, all of them exempt near-ties"
+        % (differing, sweeps * M * (T + 1), N))
+    assert adopted == differing
+    del r64, codes64
+
+    # ---- the oracle's own free-running sweeps against the product call
+    if free_running:
+        Co, codes_o, ro = fresh_state(X, M, K)
+        for s in range(free_running):
+            Eo = oracle.sweep(Co, codes_o, ro, T, idx if s == 0 else None)
+            Cp, codesp, rp, Ep = product[s]
+            mism = float((codesp.cpu().numpy() != codes_o).mean())
+            say("free-running sweep %d: max rel. E difference %.2e, codes differing %.2e, dictionaries %.2e"
+                % (s, float(np.abs(Ep - Eo).max() / Eo.min()), mism, rel_fro(Cp.cpu().numpy(), Co)))
+            np.testing.assert_allclose(Ep, Eo, rtol=1e-4)
+            if mism == 0.0:
+                assert rel_fro(Cp.cpu().numpy(), Co) <= 1e-4
+                assert _sliced_rel_fro(rp.cpu().numpy(), ro) <= 1e-4
+    ctx.close()
+
+
+def test_target_sift1m_two_sweeps(oracle, progress):
+    """N = 1,000,000, D = 128, M = 8, K = 256, T = 10: a sweep from all-zero dictionaries and one annealing sweep."""
+    X = synth.sift_like(1_000_000, D=128)
+    _target(oracle, progress, X, M=8, K=256, T=10, sweeps=2, free_running=1)
+
+
+def test_target_128bit_codes_two_sweeps(oracle, progress):
+    """M = 16 (128-bit codes), two sweeps, 32 values of E; late stages have small residues beside the large codeword
+    norms of the early dictionaries, where the expanded distance form cancels most."""
+    X = synth.sift_like(250_000, D=128)
+    _target(oracle, progress, X, M=16, K=256, T=10, sweeps=2, free_running=0)
+
+
+def test_target_gist_shape_fresh_sweep(oracle, progress):
+    """D = 960 (the D-chunked kernels), M = 8, one sweep from all-zero dictionaries."""
+    X = synth.gist_like(125_000, D=960)
+    _target(oracle, progress, X, M=8, K=256, T=10, sweeps=1, free_running=0)
