@@ -122,6 +122,22 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
  *   *out = (1/N) sum_n ||residue_n||^2, accumulated in fp64.  out: HOST.  N == 0 gives 0. */
 int hclae_quant_error(hclae_ctx *ctx, const float *residue, int64_t N, int D, double *out);
 
+/*
+ * hclae_quant_error for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Needs no hclae_ctx and calls no hipMalloc, hipFree or other allocating
+ * routine; its scratch (one fp64 partial sum per block of the reduction, 32 KB) is a static device array
+ * inside the library, which every GPU the library runs on holds until the process ends.
+ *   residue: DEVICE float[N][D], 16-byte aligned.  out: DEVICE double (8-byte aligned), receives
+ *   (1/N) sum_n ||residue_n||^2 (0 when N == 0) -- the same bits hclae_quant_error returns on a 256-CU device.
+ *   hip_stream: the hipStream_t the two kernels are enqueued on (NULL = the default stream); the call does
+ *   not synchronise.  The current device is used.
+ * Limits: 0 <= N < 2^31, 4 <= D <= 4096, D % 4 == 0; anything beyond is rejected with HCLAE_EINVAL before a
+ * launch (text via hclae_last_error(NULL)).  All calls on one GPU share that GPU's scratch: calls that may
+ * overlap on one GPU (different streams or threads) race and must be ordered by the caller.  Nothing in the
+ * scratch has to start at zero (every partial read has been written by the same call), so it is not cleared.
+ */
+int hclae_quant_error_noalloc(const float *residue, int64_t N, int D, double *out, void *hip_stream);
+
 /* ---- single steps of a stage (Sec. 3.1), exported so each can be checked on its own ---- */
 
 /* heat: residue_n += C[m][codes[n][m]] */

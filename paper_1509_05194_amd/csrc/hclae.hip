@@ -6,6 +6,7 @@
 #include <stdint.h>
 #include <stdio.h>
 #include <string.h>
+#include <mutex>
 #include <new>
 
 #include "../../include/hclae.h"
@@ -29,6 +30,39 @@ constexpr int kLdsBudget = 160 * 1024;   // LDS per workgroup on gfx950
 constexpr int kMaxTimed = 4096;          // event pairs kept between two hclae_timing_read calls
 
 thread_local char g_create_error[256] = "";
+
+}  // namespace
+
+// Scratch of hclae_quant_error_noalloc: one fp64 partial sum per block of the reduction (at most kFlatParts
+// blocks whatever the input size: the blocks stride over the array), 32 KB.  Every GPU the library runs on holds
+// its own copy of the array at its own address until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress: the address a kernel may use is the one that call returns, once per device.
+static __device__ __align__(256) double g_noalloc_scratch[kFlatParts];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+double *g_noalloc_ptr[kMaxDevices];      // device address of g_noalloc_scratch on device i, or null: not asked yet
+std::mutex g_noalloc_mutex;
+
+// Address of the current device's copy of g_noalloc_scratch (asked from the runtime on first use, then kept).
+hipError_t noalloc_scratch(double **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+    if (!g_noalloc_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_noalloc_scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_noalloc_ptr[dev] = static_cast<double *>(p);
+    }
+    *out = g_noalloc_ptr[dev];
+    return hipSuccess;
+}
 
 }  // namespace
 
@@ -637,6 +671,14 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
         return rc;
     }
     ctx->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    {   // this device's address of the static scratch of hclae_quant_error_noalloc, while allocation is still allowed
+        double *unused = nullptr;
+        if ((e = noalloc_scratch(&unused)) != hipSuccess) {
+            int rc = fail(nullptr, HCLAE_EHIP, "hipGetSymbolAddress (static scratch)", e);
+            delete ctx;
+            return rc;
+        }
+    }
     if ((size_t)prop.sharedMemPerBlock < 64 * 1024 && false) { /* LDS limit is raised per kernel below */ }
 
     // centroid partials: vector ranges x 64-dim windows fill the CUs once; int64 [ranges][K][D]
@@ -802,6 +844,32 @@ int hclae_quant_error(hclae_ctx *ctx, const float *residue, int64_t N, int D, do
     HIP_TRY(ctx, hipGetLastError());
     if ((rc = fetch_records(ctx, 1)) != HCLAE_OK) return rc;
     *out = ctx->rec_host[0].sum_after / (double)N;
+    return HCLAE_OK;
+}
+
+int hclae_quant_error_noalloc(const float *residue, int64_t N, int D, double *out, void *hip_stream)
+{
+    if (hclae_check_shape(N, D, 1, 1) != HCLAE_OK)
+        return fail(nullptr, HCLAE_EINVAL, "hclae_quant_error_noalloc: size beyond the limits (0 <= N < 2^31, 4 <= D <= 4096, D % 4 == 0)");
+    if (!out || (!residue && N > 0)) return fail(nullptr, HCLAE_EINVAL, "hclae_quant_error_noalloc: NULL pointer");
+    if (misaligned(residue) || (reinterpret_cast<uintptr_t>(out) & 7u))
+        return fail(nullptr, HCLAE_EINVAL, "hclae_quant_error_noalloc: residue must be 16-byte aligned, out 8-byte aligned");
+    double *scratch = nullptr;
+    hipError_t e = noalloc_scratch(&scratch);
+    if (e != hipSuccess) return fail(nullptr, HCLAE_EHIP, "hipGetSymbolAddress (static scratch)", e);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t n4 = N * (D / 4);
+    // the grid of hclae_quant_error on a 256-CU device, fixed here so that no device query is needed
+    int64_t blocks = (n4 + kFlatThreads * 4 - 1) / (kFlatThreads * 4);
+    if (blocks > 2048) blocks = 2048;
+    if (blocks < 1) blocks = 1;
+    if (N > 0) {
+        hipLaunchKernelGGL(k_sqnorm, dim3((unsigned)blocks), dim3(kFlatThreads), 0, stream,
+                           reinterpret_cast<const floatx4 *>(residue), n4, scratch);
+        if ((e = hipGetLastError()) != hipSuccess) return fail(nullptr, HCLAE_EHIP, "k_sqnorm", e);
+    }
+    hipLaunchKernelGGL(k_finish_mean, dim3(1), dim3(kFinishThreads), 0, stream, scratch, N > 0 ? (int)blocks : 0, N, out);
+    if ((e = hipGetLastError()) != hipSuccess) return fail(nullptr, HCLAE_EHIP, "k_finish_mean", e);
     return HCLAE_OK;
 }
 

@@ -290,4 +290,15 @@ __global__ __launch_bounds__(kFinishThreads) void k_finish_stage(
     }
 }
 
+// *out = (sum of the block partials) / N, the partials added in the order k_finish_stage adds them (N == 0: 0).
+__global__ __launch_bounds__(kFinishThreads) void k_finish_mean(
+    const double *__restrict__ part, int nparts, int64_t N, double *__restrict__ out)
+{
+    __shared__ double red[kFinishThreads / kWave];
+    double b = 0.0;
+    for (int i = threadIdx.x; i < nparts; i += kFinishThreads) b += part[i];
+    b = block_sum(b, red);
+    if (threadIdx.x == 0) *out = N > 0 ? b / (double)N : 0.0;
+}
+
 }  // namespace hclae

@@ -18,7 +18,7 @@ _ERRNAME = {0: "HCLAE_OK", -1: "HCLAE_EINVAL", -2: "HCLAE_ENOMEM", -3: "HCLAE_EH
 
 EXPORTS = (
     "hclae_check_shape", "hclae_create", "hclae_destroy", "hclae_last_error",
-    "hclae_encode", "hclae_anneal_stage", "hclae_sweep", "hclae_quant_error",
+    "hclae_encode", "hclae_anneal_stage", "hclae_sweep", "hclae_quant_error", "hclae_quant_error_noalloc",
     "hclae_heat", "hclae_cool", "hclae_assign", "hclae_update", "hclae_last_refined",
     "hclae_timing_enable", "hclae_timing_read", "hclae_online_begin", "hclae_online_chunk",
     "hclae_online_export", "hclae_online_import",
@@ -76,6 +76,7 @@ def lib():
     L.hclae_anneal_stage.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp, i32, vp, ctypes.POINTER(StageStats)]
     L.hclae_sweep.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp, i32, i32, vp, vp]
     L.hclae_quant_error.argtypes = [vp, vp, i64, i32, ctypes.POINTER(ctypes.c_double)]
+    L.hclae_quant_error_noalloc.argtypes = [vp, i64, i32, vp, vp]
     L.hclae_heat.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp]
     L.hclae_cool.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp]
     L.hclae_assign.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, vp, vp]
@@ -110,6 +111,18 @@ def lib():
 
 def check_shape(N, D, M, K):
     return lib().hclae_check_shape(N, D, M, K)
+
+
+def quant_error_noalloc(residue, out, stream=None):
+    """hclae_quant_error_noalloc: residue CUDA float32 [N][D], out CUDA float64 tensor of one element (written on
+    `stream`, default torch's current stream; no synchronisation)."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    N, D = residue.shape
+    rc = lib().hclae_quant_error_noalloc(_ptr(residue, "f32"), N, D, _ptr(out, "f64", (1,)), ctypes.c_void_p(stream))
+    if rc != OK:
+        raise HclaeError(rc, lib().hclae_last_error(None).decode())
 
 
 def symmetric_eigen(A):
