@@ -18,7 +18,10 @@ SEED_HELDOUT = 5195
 
 
 def _rng(seed, tag, block=0):
-    return np.random.Generator(np.random.Philox(key=[int(seed), int(tag)], counter=[int(block), 0, 0, 0]))
+    # The block id goes into the third 64-bit word of Philox's 256-bit counter: the streams of two blocks start
+    # 2^128 draws apart.  (In the lowest word they would start ONE counter step apart, each block's stream being
+    # the previous block's shifted by four draws.)
+    return np.random.Generator(np.random.Philox(key=[int(seed), int(tag)], counter=[0, 0, int(block), 0]))
 
 
 def _blocks(start, count):

@@ -207,9 +207,12 @@ def test_pca_stage_lockstep_and_entry_point(case, oracle):
 def test_pca_stage_free_running_against_oracle_stage(case, oracle):
     """Free-running: hclae_anneal_stage_pca (principal axes found inside the library) against the oracle's own
     anneal_stage_pca with the oracle's axes, from the same start, nothing exchanged in between.  The cases have
-    no near-tie that the two sides decide differently: codes must be EQUAL, the rest within 1e-4."""
+    no near-tie that the two sides decide differently: codes must be EQUAL, the rest within 1e-4.  (SIFT-shaped
+    data: the first stage only.  Seeds of a later stage can be rows whose residue is exactly zero -- sole members of
+    their clusters -- which tie exactly in the oracle and not on the GPU's fp32 state; the lockstep test covers those.)"""
     c = SHAPES[case]
     N, D, M, K = c["N"], c["D"], c["M"], c["K"]
+    stages = M if case == "tiny" else 1
     T = 2
     X = _data(c)
     idx = synth.init_indices(N, M, K)
@@ -220,7 +223,7 @@ def test_pca_stage_free_running_against_oracle_stage(case, oracle):
     codes_g = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
     rg = to_dev(X)
     xr = torch.empty_like(rg)
-    for m in range(M):
+    for m in range(stages):
         R64 = oracle.pca_axes(r64)                                    # heat of a fresh stage is the identity
         Eo = oracle.anneal_stage_pca(m, C64, codes64, r64, R64, dims, T, idx[m])
         st = ctx.anneal_stage_pca(m, Cg, codes_g, rg, None, dims, T, xr, init_idx=idx[m])
