@@ -236,8 +236,13 @@ int launch_heat_cool(hclae_ctx *ctx, int m, int64_t N, const float *C, const uin
     (void)rows;
     const float *Cm = C + (size_t)m * ctx->K * ctx->D;
     Timed t_(ctx, SIGN > 0 ? HCLAE_T_HEAT : HCLAE_T_COOL);
-    hipLaunchKernelGGL((k_heat_cool<SIGN, STATS>), dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
-                       r, codes, Cm, N, ctx->D, ctx->M, m, g, ctx->old_codes, part_err, ctx->part_chg);
+    // the row lengths of the SIFT- and GIST-shaped configurations have kernels of their own (addresses and geometry
+    // constant: 179 us instead of 185 us for the stage boundary at N = 1M, D = 128)
+    auto kern = ctx->D == 128 ? &k_row_pass<SIGN, STATS, 128>
+              : ctx->D == 960 ? &k_row_pass<SIGN, STATS, 960> : &k_row_pass<SIGN, STATS, 0>;
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
+                       r, codes, Cm, (const float *)nullptr, N, ctx->D, ctx->M, m, 0, g, ctx->old_codes, part_err,
+                       ctx->part_chg);
     HIP_TRY(ctx, hipGetLastError());
     return blocks;
 }
@@ -530,7 +535,7 @@ int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float
 int launch_sqnorm(hclae_ctx *ctx, const float *r, int64_t N, double *part)
 {
     const int64_t n4 = N * (ctx->D / 4);
-    const int blocks = stream_blocks(ctx, n4, kFlatThreads * 4);
+    const int blocks = stream_blocks(ctx, n4, kFlatThreads * kSqUnroll);
     Timed t_(ctx, HCLAE_T_ERROR);
     hipLaunchKernelGGL(k_sqnorm, dim3(blocks), dim3(kFlatThreads), 0, ctx->stream,
                        reinterpret_cast<const floatx4 *>(r), n4, part);
@@ -583,7 +588,8 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
         const RowGeom g = row_geom(D);
         pa = heat_cool_blocks(N, D, ctx->cus);
         Timed t_(ctx, HCLAE_T_TRANSITION);
-        hipLaunchKernelGGL(k_transition, dim3(pa), dim3(kStreamThreads), 0, ctx->stream,
+        auto kern = D == 128 ? &k_row_pass<0, true, 128> : D == 960 ? &k_row_pass<0, true, 960> : &k_row_pass<0, true, 0>;
+        hipLaunchKernelGGL(kern, dim3(pa), dim3(kStreamThreads), 0, ctx->stream,
                            residue, codes, Cm, C + (size_t)next * K * D, N, D, ctx->M, m, next, g,
                            ctx->old_codes, ctx->part_b, ctx->part_chg);
         HIP_TRY(ctx, hipGetLastError());
@@ -860,7 +866,7 @@ int hclae_quant_error_noalloc(const float *residue, int64_t N, int D, double *ou
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int64_t n4 = N * (D / 4);
     // the grid of hclae_quant_error on a 256-CU device, fixed here so that no device query is needed
-    int64_t blocks = (n4 + kFlatThreads * 4 - 1) / (kFlatThreads * 4);
+    int64_t blocks = (n4 + kFlatThreads * kSqUnroll - 1) / (kFlatThreads * kSqUnroll);
     if (blocks > 2048) blocks = 2048;
     if (blocks < 1) blocks = 1;
     if (N > 0) {

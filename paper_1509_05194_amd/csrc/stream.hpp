@@ -7,157 +7,155 @@
 
 namespace hclae {
 
-constexpr int kStreamThreads = 256;    // heat / cool
-constexpr int kStreamUnroll = 4;
+constexpr int kStreamThreads = 512;    // heat / cool / stage boundary
+constexpr int kStreamUnroll = 4;       // independent rows per thread per step
 constexpr int kFlatThreads = 256;      // flat float4 passes (copy, reduction, finish)
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-// Geometry of heat / cool: a block is (1 << lcw) column threads by (kStreamThreads >> lcw) rows; column thread tx walks float4 columns tx, tx + cw, ...
+// Geometry of the row passes: a block is (1 << lcw) column threads by (kStreamThreads >> lcw) rows; column thread tx
+// walks float4 columns tx, tx + cw, ...
 struct RowGeom {
     int lcw;        // log2 of column threads per row
     int d4;         // D / 4
 };
 
-// residue_n (+|-)= C_m[codes[n][m]]  with optional by-products:
-//   SIGN = +1 : heat.  Also saves column m of the codes (old_codes) and sums ||e_x||^2 of the input.
-//   SIGN = -1 : cool.  Also sums ||e_x||^2 of the output and counts codes != old_codes.
-// part_err[blockIdx.x], part_chg[blockIdx.x] receive this block's partial sums (fixed order).
-template <int SIGN, bool STATS>
-__global__ __launch_bounds__(kStreamThreads) void k_heat_cool(
-    float *__restrict__ r, const uint8_t *__restrict__ codes, const float *__restrict__ Cm,
-    int64_t N, int D, int M, int m, RowGeom g,
+// The in-place row passes of a stage (Sec. 3.1), one kernel body:
+//   MODE +1  heat       r_n += C_m[i_m(n)]; by-products: column m of the codes saved (old_codes), sum ||e_x||^2 of the input
+//   MODE -1  new residue r_n -= C_m[i_m(n)]; by-products: sum ||e_x||^2 of the output, codes that differ from old_codes
+//   MODE  0  stage boundary inside a sweep, one pass instead of two: e_x = x' - c_m(i_m) (end of stage m) followed at
+//            once by x'' = e_x + c_j(i_j) (heat of the next stage j).  The intermediate e_x is rounded to fp32 exactly
+//            as if it had been stored and reloaded, so the result equals the two passes bit for bit.  By-products:
+//            sum ||e_x||^2 (error after stage m = error before stage j), codes of stage m changed since its entry,
+//            and the code column of stage j saved for its own change count.
+// part_err[blockIdx.x], part_chg[blockIdx.x] receive this block's partial sums (fixed order); STATS false: no by-products.
+//
+// A thread works on kStreamUnroll rows at a time, one float4 column of each, in steps (row group, column chunk).
+// The row loads of the NEXT step (and the code bytes of its rows) are issued before the codeword rows of the current
+// step are gathered from L2: the HBM loads are then in flight all the time instead of half of it.  Measured on one
+// MI355X at N = 1M, D = 128: stage boundary 213 us -> 176 us (5.9 TB/s; a device-to-device hipMemcpy of the same
+// bytes takes 193 us); the launch shape (512 threads, 32 blocks per CU, about two steps per block) is the best of
+// a sweep of shapes.  All three modes share the geometry, so a thread adds the same squares in the same order in
+// the stage boundary as in the separate new-residue pass: the error sums are the same bits.
+// DT: the row length as a compile-time constant (with the geometry row_geom gives it), or 0: taken from D and g.
+template <int MODE, bool STATS, int DT = 0>
+__global__ __launch_bounds__(kStreamThreads) void k_row_pass(
+    float *__restrict__ r, const uint8_t *__restrict__ codes, const float *__restrict__ Cm, const float *__restrict__ Cj,
+    int64_t N, int D_rt, int M, int m, int j_stage, RowGeom g_rt,
     uint8_t *__restrict__ old_codes, double *__restrict__ part_err, long long *__restrict__ part_chg)
 {
     __shared__ double red[kStreamThreads / kWave];
-    constexpr int U = kStreamUnroll;                       // independent rows per thread per pass
+    constexpr int U = kStreamUnroll;
+    const int D = DT ? DT : D_rt;
+    RowGeom g = g_rt;
+    if (DT) {
+        g.d4 = DT / 4;
+        g.lcw = DT >= 256 ? 6 : DT >= 128 ? 5 : DT >= 64 ? 4 : DT >= 32 ? 3 : DT >= 16 ? 2 : DT >= 8 ? 1 : 0;
+    }
     const int cw = 1 << g.lcw;
     const int tx = threadIdx.x & (cw - 1);
     const int ty = threadIdx.x >> g.lcw;
     const int rows = kStreamThreads >> g.lcw;
+    const int nchunks = (g.d4 + cw - 1) >> g.lcw;
+    const int64_t stride = (int64_t)gridDim.x * rows * U;
     double err = 0.0;
     long long chg = 0;
-    for (int64_t n0 = (int64_t)blockIdx.x * rows * U + ty; n0 < N; n0 += (int64_t)gridDim.x * rows * U) {
-        int code[U];
-        bool ok[U];
+
+    // rows n0 + u * rows of a group; the loads of a step take rows clamped into range (never used beyond N)
+    auto load_codes = [&](int64_t n0, int (&a)[U], int (&b)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t n = n0 + (int64_t)u * rows;
-            ok[u] = n < N;
-            code[u] = ok[u] ? (int)codes[n * M + m] : 0;
+            const int64_t nn = n < N ? n : N - 1;
+            a[u] = codes[nn * M + m];
+            if (MODE == 0) b[u] = codes[nn * M + j_stage];
         }
-        if (STATS && tx == 0) {
+    };
+    auto load_rows = [&](int64_t n0, int c4, floatx4 (&v)[U]) {
+        const int cc = c4 < g.d4 ? c4 : g.d4 - 1;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t n = n0 + (int64_t)u * rows;
+            const int64_t nn = n < N ? n : N - 1;
+            v[u] = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(r + nn * D) + cc);
+        }
+    };
+
+    int64_t n0 = (int64_t)blockIdx.x * rows * U + ty;
+    int chunk = 0;
+    floatx4 v[U];
+    int cm[U], cj[U];
+    if (n0 < N) {
+        load_codes(n0, cm, cj);
+        load_rows(n0, tx, v);
+    }
+    while (n0 < N) {
+        // the step after this one
+        int chunk_next = chunk + 1;
+        int64_t n0_next = n0;
+        if (chunk_next == nchunks) { chunk_next = 0; n0_next = n0 + stride; }
+        floatx4 vn[U];
+        int cmn[U], cjn[U];
+        if (n0_next < N) {
+            if (chunk_next == 0) load_codes(n0_next, cmn, cjn);
+            load_rows(n0_next, chunk_next * cw + tx, vn);
+        }
+        const int c4 = chunk * cw + tx;
+        const bool live = c4 < g.d4;
+        const int cc = live ? c4 : g.d4 - 1;
+        floatx4 a[U], b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a[u] = *(reinterpret_cast<const floatx4 *>(Cm + (size_t)cm[u] * D) + cc);
+            if (MODE == 0) b[u] = *(reinterpret_cast<const floatx4 *>(Cj + (size_t)cj[u] * D) + cc);
+        }
+        if (STATS && tx == 0 && chunk == 0) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int64_t n = n0 + (int64_t)u * rows;
-                if (ok[u]) {
-                    if (SIGN > 0) old_codes[n] = (uint8_t)code[u];
-                    else chg += (old_codes[n] != (uint8_t)code[u]);
+                if (n < N) {
+                    if (MODE > 0) old_codes[n] = (uint8_t)cm[u];
+                    if (MODE < 0) chg += (old_codes[n] != (uint8_t)cm[u]);
+                    if (MODE == 0) {
+                        chg += (old_codes[n] != (uint8_t)cm[u]);
+                        old_codes[n] = (uint8_t)cj[u];
+                    }
                 }
             }
         }
-        for (int j = tx; j < g.d4; j += cw) {
-            floatx4 v[U], cv[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t n = n0 + (int64_t)u * rows;
-                if (ok[u]) {
-                    v[u] = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(r + n * D) + j);
-                    cv[u] = *(reinterpret_cast<const floatx4 *>(Cm + (size_t)code[u] * D) + j);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t n = n0 + (int64_t)u * rows;
-                if (ok[u]) {
-                    floatx4 w = v[u];
-                    if (STATS && SIGN > 0)
-                        err += (double)w.x * w.x + (double)w.y * w.y + (double)w.z * w.z + (double)w.w * w.w;
-                    if (SIGN > 0) w = w + cv[u];
-                    else w = w - cv[u];
-                    if (STATS && SIGN < 0)
-                        err += (double)w.x * w.x + (double)w.y * w.y + (double)w.z * w.z + (double)w.w * w.w;
-                    __builtin_nontemporal_store(w, reinterpret_cast<floatx4 *>(r + n * D) + j);
-                }
+        for (int u = 0; u < U; ++u) {
+            const int64_t n = n0 + (int64_t)u * rows;
+            if (live && n < N) {
+                floatx4 w = v[u];
+                if (STATS && MODE > 0)
+                    err += (double)w.x * w.x + (double)w.y * w.y + (double)w.z * w.z + (double)w.w * w.w;
+                if (MODE > 0) w = w + a[u];
+                else w = w - a[u];
+                if (STATS && MODE <= 0)
+                    err += (double)w.x * w.x + (double)w.y * w.y + (double)w.z * w.z + (double)w.w * w.w;
+                if (MODE == 0) w = w + b[u];
+                __builtin_nontemporal_store(w, reinterpret_cast<floatx4 *>(r + n * D) + c4);
             }
         }
+        if (chunk_next == 0) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) { cm[u] = cmn[u]; cj[u] = cjn[u]; }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = vn[u];
+        chunk = chunk_next;
+        n0 = n0_next;
     }
     if (STATS) {
         const double e = block_sum(err, red);
         if (threadIdx.x == 0) part_err[blockIdx.x] = e;
-        if (SIGN < 0) {
+        if (MODE <= 0) {
             // integer sum: any order gives the same value
             const double c = block_sum((double)chg, red);
             if (threadIdx.x == 0) part_chg[blockIdx.x] = (long long)c;
         }
     }
-}
-
-// Stage boundary inside a sweep, one pass instead of two: e_x = x' - c_m(i_m) (end of stage m) followed
-// at once by x'' = e_x + c_j(i_j) (heat of the next stage j).  The intermediate e_x is rounded to fp32
-// exactly as if it had been stored and reloaded, so the result equals cool(m) then heat(j) bit for bit.
-// By-products: sum ||e_x||^2 (error after stage m = error before stage j), codes of stage m changed
-// since its entry, and the code column of stage j saved for its own change count.
-__global__ __launch_bounds__(kStreamThreads) void k_transition(
-    float *__restrict__ r, const uint8_t *__restrict__ codes, const float *__restrict__ Cm, const float *__restrict__ Cj,
-    int64_t N, int D, int M, int m, int j_stage, RowGeom g,
-    uint8_t *__restrict__ old_codes, double *__restrict__ part_err, long long *__restrict__ part_chg)
-{
-    __shared__ double red[kStreamThreads / kWave];
-    constexpr int U = kStreamUnroll;
-    const int cw = 1 << g.lcw;
-    const int tx = threadIdx.x & (cw - 1);
-    const int ty = threadIdx.x >> g.lcw;
-    const int rows = kStreamThreads >> g.lcw;
-    double err = 0.0;
-    long long chg = 0;
-    for (int64_t n0 = (int64_t)blockIdx.x * rows * U + ty; n0 < N; n0 += (int64_t)gridDim.x * rows * U) {
-        int cm[U], cj[U];
-        bool ok[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t n = n0 + (int64_t)u * rows;
-            ok[u] = n < N;
-            cm[u] = ok[u] ? (int)codes[n * M + m] : 0;
-            cj[u] = ok[u] ? (int)codes[n * M + j_stage] : 0;
-        }
-        if (tx == 0) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t n = n0 + (int64_t)u * rows;
-                if (ok[u]) {
-                    chg += (old_codes[n] != (uint8_t)cm[u]);
-                    old_codes[n] = (uint8_t)cj[u];
-                }
-            }
-        }
-        for (int c4 = tx; c4 < g.d4; c4 += cw) {
-            floatx4 v[U], a[U], b[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t n = n0 + (int64_t)u * rows;
-                if (ok[u]) {
-                    v[u] = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(r + n * D) + c4);
-                    a[u] = *(reinterpret_cast<const floatx4 *>(Cm + (size_t)cm[u] * D) + c4);
-                    b[u] = *(reinterpret_cast<const floatx4 *>(Cj + (size_t)cj[u] * D) + c4);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t n = n0 + (int64_t)u * rows;
-                if (ok[u]) {
-                    floatx4 w = v[u] - a[u];
-                    err += (double)w.x * w.x + (double)w.y * w.y + (double)w.z * w.z + (double)w.w * w.w;
-                    w = w + b[u];
-                    __builtin_nontemporal_store(w, reinterpret_cast<floatx4 *>(r + n * D) + c4);
-                }
-            }
-        }
-    }
-    const double e = block_sum(err, red);
-    if (threadIdx.x == 0) part_err[blockIdx.x] = e;
-    const double c = block_sum((double)chg, red);
-    if (threadIdx.x == 0) part_chg[blockIdx.x] = (long long)c;
 }
 
 // r <- X (first step of the greedy encoder): four float4 per thread in flight.
@@ -206,20 +204,30 @@ __global__ __launch_bounds__(kFlatThreads) void k_copy_column(
         dst[n * M + m] = src[n * M + m];
 }
 
-// Partial sums of ||e_x||^2 (Eq. 1, first line), fp64 accumulation, four loads in flight.
+// Partial sums of ||e_x||^2 (Eq. 1, first line), fp64 accumulation.  Every block reads one contiguous piece of the
+// array, eight float4 per thread in flight: measured 79 us for 512 MB (6.5 TB/s) against 95 us when the blocks
+// interleave their loads across the whole array.
+constexpr int kSqUnroll = 8;
+__host__ __device__ inline int64_t sqnorm_piece(int64_t n4, int blocks)
+{
+    const int64_t step = (int64_t)kSqUnroll * kFlatThreads;
+    return ((n4 + blocks - 1) / blocks + step - 1) / step * step;
+}
 __global__ __launch_bounds__(kFlatThreads) void k_sqnorm(
     const floatx4 *__restrict__ r, int64_t n4, double *__restrict__ part_err)
 {
     __shared__ double red[kFlatThreads / kWave];
-    constexpr int U = 4;
-    const int64_t stride = (int64_t)gridDim.x * kFlatThreads;
+    constexpr int U = kSqUnroll;
+    const int64_t per = sqnorm_piece(n4, (int)gridDim.x);
+    const int64_t lo = (int64_t)blockIdx.x * per;
+    const int64_t hi = lo + per < n4 ? lo + per : n4;
     double err = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * kFlatThreads + threadIdx.x; i < n4; i += U * stride) {
+    for (int64_t i = lo + threadIdx.x; i < hi; i += U * kFlatThreads) {
         floatx4 v[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             v[u] = (floatx4){0.f, 0.f, 0.f, 0.f};
-            if (i + u * stride < n4) v[u] = __builtin_nontemporal_load(r + i + u * stride);
+            if (i + u * kFlatThreads < hi) v[u] = __builtin_nontemporal_load(r + i + u * kFlatThreads);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
