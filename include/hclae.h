@@ -301,7 +301,8 @@ int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, in
  * double[M], variances in the OLD order) and order (HOST int[M]: new position j holds old dictionary
  * order[j]; ties keep the lower old index), then permutes C and the columns of codes accordingly, in place.
  * The residue is unchanged (the sum of the selected codewords does not depend on their order).
- * var and order may be NULL.  Synchronises the stream. */
+ * var and order may be NULL.  Synchronises the stream.  Scratch (a copy of C) is allocated by the first call
+ * and kept by the ctx. */
 int hclae_reorder_by_variance(hclae_ctx *ctx, int64_t N, int D, float *C, int M, int K, uint8_t *codes,
                               double *var, int *order);
 

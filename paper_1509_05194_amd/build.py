@@ -8,7 +8,6 @@ LIB = os.path.join(HERE, "libhclae.so")
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-shared", "-fPIC",
-    "-munsafe-fp-atomics",                      # LDS float adds as ds_add_f32, not CAS loops
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]

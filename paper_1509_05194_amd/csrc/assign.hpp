@@ -44,6 +44,7 @@ struct PruneArgs {
     float *bu, *bl;                    // [N]
     const uint32_t *active;            // [*active_count] vector indices (PRUNE 2)
     const unsigned *active_count;
+    float slack;                       // rounding of ||x'||^2 and of the bound arithmetic, relative: grows with D
 };
 // Lower bound stored for a vector that goes to the fp64 re-check: no distance is negative, so the value
 // keeps the vector listed and tells it from all others.
@@ -287,9 +288,11 @@ __device__ __forceinline__ void decide(
     if (PRUNE) {
         // d^2 = ||x'||^2 - 2 score.  With E the rounding bound of a score (half the margin): the own codeword
         // has true score >= mx - E and every other one <= m2 + E.  A vector that goes to the re-check (or has
-        // no candidate) gets bounds that keep it active.  slack covers the fp32 evaluation of these lines.
+        // no candidate) gets bounds that keep it active.  slack covers the fp32 evaluation of these lines: x2 is a
+        // chain of D/2 fused multiply-adds per lane (relative error <= (D/2 + 1) 2^-24, all terms positive) and the
+        // few operations below add a handful of roundings of the magnitudes involved; pa.slack = (D/2 + 16) 2^-23.
         const float E = 0.5001f * margin;
-        const float slack = 2e-5f * (x2 + 2.f * fabsf(mx) + 2.f * fabsf(m2));
+        const float slack = pa.slack * (x2 + 2.f * fabsf(mx) + 2.f * fabsf(m2));
         float u = __builtin_inff(), l = cnt >= 2 ? kAmbiguousL : 0.f;
         if (cnt == 1) {
             u = sqrtf(fmaxf(0.f, (x2 - 2.f * (mx - E)) + slack)) * 1.00001f;

@@ -122,6 +122,11 @@ struct hclae_ctx {
     double *pca_cov;         // [D][D] covariance of x' when the stage finds the principal axes itself
     float *pca_R;            // [D][D] those axes (rows), fp32
     int pca_ncol, pca_ngram;
+    // dictionary order and code statistics (allocated on first use)
+    unsigned long long *stats_buf;   // [M][K] + [K][K] histogram counters
+    double *order_var;       // [M]
+    int *order_idx;          // [M]
+    float *order_tmp;        // [M][K][D] permuted dictionaries
     // multi-path encoding scratch (allocated on first use, regrown when L or the batch grows)
     int64_t beam_cap;        // vectors per batch the buffers hold
     int beam_L;              // beam width they were sized for
@@ -133,6 +138,9 @@ struct hclae_ctx {
     // optional per-kernel timing (HIP events on ctx->stream)
     uint32_t t_mask;
     int t_used;
+    // hipFuncSetAttribute (dynamic LDS limit) done by this ctx, one bit per call site: the attribute belongs to the
+    // device context a ctx was created on, so every ctx raises the limits it needs itself
+    uint64_t attr_done;
     hipEvent_t *t_beg, *t_end;   // [kMaxTimed] each, created on first enable
     uint8_t *t_cls;
     char err[256];
@@ -282,6 +290,7 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
     }
     const int NC = (dact + kChunkD - 1) / kChunkD;
     const int dpad = kChunkD * NC;
+    pa.slack = (float)(dpad / 2 + 16) * 1.1920929e-7f;
     const bool resident = (size_t)32 * KB * dpad * sizeof(float) + 4096 <= (size_t)kLdsBudget;
     // twice the worst-case rounding error of a score: (dpad + 1) roundings of relative size 2^-23
     // on partial sums bounded by h + ||x'|| ||c||, plus the rounding of h itself
@@ -293,15 +302,15 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
         const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
         int64_t blocks = (ntiles + 3) / 4;                      // few tiles: one per SIMD before any SIMD gets two
         if (blocks > ctx->cus) blocks = ctx->cus;
-        static bool attr_set = false;
-        if (!attr_set) {
+        const uint64_t attr_set = 1ull << 0;        // this call site's bit in ctx->attr_done
+        if (!(ctx->attr_done & attr_set)) {
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split<KB, 0>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split<KB, 1>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split<KB, 2>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
-            attr_set = true;
+            ctx->attr_done |= attr_set;
         }
         // 3 MFMAs per 16 dims, each within 2^-21 of the magnitudes it adds; one more for the rounding of the norm
         const float acc_bound = (float)(3 * (dpad / kSplitStep) + 1) * 4.76837158203125e-7f;
@@ -318,15 +327,15 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
         const size_t lds = (size_t)2 * KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t nbt = (N + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);
         int64_t blocks = nbt < ctx->cus ? nbt : ctx->cus;
-        static bool attr_set = false;
-        if (!attr_set) {
+        const uint64_t attr_set = 1ull << 1;        // this call site's bit in ctx->attr_done
+        if (!(ctx->attr_done & attr_set)) {
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split_chunked<KB, 0>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split_chunked<KB, 1>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_split_chunked<KB, 2>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
-            attr_set = true;
+            ctx->attr_done |= attr_set;
         }
         if (NC > ctx->NC || KB != ctx->kb)
             return fail(ctx, HCLAE_EINVAL, "assign: codebook image too small for this shape");
@@ -345,33 +354,33 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
         const int64_t ntiles = (N + kTileVec - 1) / kTileVec;
         int64_t blocks = (ntiles + 3) / 4;                      // few tiles: one per SIMD before any SIMD gets two
         if (blocks > ctx->cus) blocks = ctx->cus;
-        static bool attr_set = false;
-        if (!attr_set) {
+        const uint64_t attr_set = 1ull << 2;        // this call site's bit in ctx->attr_done
+        if (!(ctx->attr_done & attr_set)) {
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 0>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 1>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 2>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
-            attr_set = true;
+            ctx->attr_done |= attr_set;
         }
         // the last chunk holds fewer than eight 8-dim steps with coordinates that count: stop after them
         const bool prefix = prune == 0 && (dact % kChunkD) != 0 && (dact % kChunkD) <= kChunkD - 8;
-        static bool attr_set_p = false;
-        if (prefix && !attr_set_p) {
+        const uint64_t attr_set_p = 1ull << 3;        // this call site's bit in ctx->attr_done
+        if (prefix && !(ctx->attr_done & attr_set_p)) {
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 0, true>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
-            attr_set_p = true;
+            ctx->attr_done |= attr_set_p;
         }
-        static bool attr_set_i = false;
-        if (use_image && !attr_set_i) {
+        const uint64_t attr_set_i = 1ull << 4;        // this call site's bit in ctx->attr_done
+        if (use_image && !(ctx->attr_done & attr_set_i)) {
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 0, false, true>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 1, false, true>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_resident<KB, 2, false, true>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
-            attr_set_i = true;
+            ctx->attr_done |= attr_set_i;
         }
         auto kern = prefix ? &k_assign_resident<KB, 0, true>
                   : use_image ? (prune == 1 ? &k_assign_resident<KB, 1, false, true>
@@ -386,15 +395,15 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
         const size_t lds = (size_t)2 * KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t nbt = (N + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);
         int64_t blocks = nbt < ctx->cus ? nbt : ctx->cus;
-        static bool attr_set = false;
-        if (!attr_set) {
+        const uint64_t attr_set = 1ull << 5;        // this call site's bit in ctx->attr_done
+        if (!(ctx->attr_done & attr_set)) {
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_chunked<KB, 0>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_chunked<KB, 1>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_assign_chunked<KB, 2>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
-            attr_set = true;
+            ctx->attr_done |= attr_set;
         }
         if (NC > ctx->NC || KB != ctx->kb)
             return fail(ctx, HCLAE_EINVAL, "assign: codebook image too small for this shape");
@@ -436,11 +445,11 @@ int launch_assign(hclae_ctx *ctx, int m, int64_t N, const float *xp, const float
 int launch_bounds_step(hclae_ctx *ctx, int m, int64_t N, const uint8_t *codes, const float *xp, const float *Cm)
 {
     Timed t_(ctx, HCLAE_T_BOUNDS);
-    static bool attr_set = false;
-    if (!attr_set) {
+    const uint64_t attr_set = 1ull << 6;        // this call site's bit in ctx->attr_done
+    if (!(ctx->attr_done & attr_set)) {
         HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bounds_step),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget - 40 * 1024));
-        attr_set = true;
+        ctx->attr_done |= attr_set;
     }
     hipLaunchKernelGGL(k_bounds_step, dim3((unsigned)((N + kBoundSpan - 1) / kBoundSpan)), dim3(kBoundThreads),
                        (size_t)kVolatile * ctx->D * sizeof(float), ctx->stream,
@@ -465,11 +474,11 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
     if (nb < 1) nb = 1;
     int64_t rpb = (N + nb - 1) / nb;
     const size_t lds = upd_lds_bytes(K);
-    static bool attr_set = false;
-    if (!attr_set) {
+    const uint64_t attr_set = 1ull << 7;        // this call site's bit in ctx->attr_done
+    if (!(ctx->attr_done & attr_set)) {
         HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_accumulate),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
-        attr_set = true;
+        ctx->attr_done |= attr_set;
     }
     if (!have_absmax) {
         HIP_TRY(ctx, hipMemsetAsync(ctx->refine_count + 1, 0, sizeof(unsigned), ctx->stream));
@@ -510,11 +519,11 @@ int launch_update_moved(hclae_ctx *ctx, int m, int64_t N, const float *xp, float
     const int D = ctx->D, K = ctx->K;
     const int windows = (D + kUpdWindow - 1) / kUpdWindow;
     const int nb = ctx->upd_blocks;                  // upper bound; the kernels use as many as the list is worth
-    static bool attr_set = false;
-    if (!attr_set) {
+    const uint64_t attr_set = 1ull << 8;        // this call site's bit in ctx->attr_done
+    if (!(ctx->attr_done & attr_set)) {
         HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_accumulate_moved),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
-        attr_set = true;
+        ctx->attr_done |= attr_set;
     }
     {
         Timed t_(ctx, HCLAE_T_ACCUM_MOVED);
@@ -755,6 +764,7 @@ int hclae_destroy(hclae_ctx *ctx)
                    ctx->nk, ctx->tot_sum, ctx->tot_cnt, ctx->upd_col, ctx->moved_list, ctx->moved_count, ctx->bnd_u, ctx->bnd_l, ctx->drift, ctx->active, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
                    ctx->run_sum, ctx->run_cnt, ctx->n0_dev, ctx->pca_rt, ctx->pca_crot, ctx->pca_colpart,
                    ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32, ctx->pca_cov, ctx->pca_R,
+                   ctx->stats_buf, ctx->order_var, ctx->order_idx, ctx->order_tmp,
                    ctx->beam_rows[0], ctx->beam_rows[1], ctx->beam_err[0], ctx->beam_err[1],
                    ctx->beam_pre[0], ctx->beam_pre[1], ctx->beam_mask};
     for (void *p : dev)
@@ -1160,11 +1170,11 @@ static int launch_beam_score_kb(hclae_ctx *ctx, const float *rows, const double 
         const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         int64_t blocks = (ntiles + 3) / 4;                      // few tiles: one per SIMD before any SIMD gets two
         if (blocks > ctx->cus) blocks = ctx->cus;
-        static bool attr_set = false;
-        if (!attr_set) {
+        const uint64_t attr_set = 1ull << 9;        // this call site's bit in ctx->attr_done
+        if (!(ctx->attr_done & attr_set)) {
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_beam_score_split<KB>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
-            attr_set = true;
+            ctx->attr_done |= attr_set;
         }
         // accumulation bound of the split contraction (see launch_assign_kb) plus the roundings of the shift
         const float acc_bound = (float)(3 * (dpad / kSplitStep) + 9) * 4.76837158203125e-7f;
@@ -1176,11 +1186,11 @@ static int launch_beam_score_kb(hclae_ctx *ctx, const float *rows, const double 
         const size_t lds = (size_t)2 * KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t nbt = (ntiles + kAssignWaves - 1) / kAssignWaves;
         int64_t blocks = nbt < ctx->cus ? nbt : ctx->cus;
-        static bool attr_set = false;
-        if (!attr_set) {
+        const uint64_t attr_set = 1ull << 10;        // this call site's bit in ctx->attr_done
+        if (!(ctx->attr_done & attr_set)) {
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_beam_score_split_chunked<KB>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
-            attr_set = true;
+            ctx->attr_done |= attr_set;
         }
         if (NC > ctx->NC || KB != ctx->kb)
             return fail(ctx, HCLAE_EINVAL, "beam: codebook image too small for this shape");
@@ -1196,11 +1206,11 @@ static int launch_beam_score_kb(hclae_ctx *ctx, const float *rows, const double 
         const size_t lds = (size_t)KB * 8 * NC * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         int64_t blocks = (ntiles + 3) / 4;                      // few tiles: one per SIMD before any SIMD gets two
         if (blocks > ctx->cus) blocks = ctx->cus;
-        static bool attr_set = false;
-        if (!attr_set) {
+        const uint64_t attr_set = 1ull << 11;        // this call site's bit in ctx->attr_done
+        if (!(ctx->attr_done & attr_set)) {
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_beam_score_resident<KB>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
-            attr_set = true;
+            ctx->attr_done |= attr_set;
         }
         hipLaunchKernelGGL((k_beam_score_resident<KB>), dim3((unsigned)blocks), dim3(kAssignThreads), lds, ctx->stream,
                            rows, err, Cm, ctx->hneg, N, Lc, Ln, D, D, ctx->K, NC, gamma, masks);
@@ -1208,11 +1218,11 @@ static int launch_beam_score_kb(hclae_ctx *ctx, const float *rows, const double 
         const size_t lds = (size_t)2 * KB * 8 * kWave * sizeof(float4) + (32 * KB + 4) * sizeof(float);
         const int64_t nbt = (ntiles + kAssignWaves - 1) / kAssignWaves;
         int64_t blocks = nbt < ctx->cus ? nbt : ctx->cus;
-        static bool attr_set = false;
-        if (!attr_set) {
+        const uint64_t attr_set = 1ull << 12;        // this call site's bit in ctx->attr_done
+        if (!(ctx->attr_done & attr_set)) {
             HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_beam_score_chunked<KB>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
-            attr_set = true;
+            ctx->attr_done |= attr_set;
         }
         if (NC > ctx->NC || KB != ctx->kb)
             return fail(ctx, HCLAE_EINVAL, "beam: codebook image too small for this shape");
@@ -1353,11 +1363,11 @@ static int launch_project(hclae_ctx *ctx, const float *x, int64_t N, const float
 {
     const int D = ctx->D;
     const size_t lds = (size_t)8 * 8 * kWave * sizeof(float4);
-    static bool attr_set = false;
-    if (!attr_set) {
+    const uint64_t attr_set = 1ull << 13;        // this call site's bit in ctx->attr_done
+    if (!(ctx->attr_done & attr_set)) {
         HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_project),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
-        attr_set = true;
+        ctx->attr_done |= attr_set;
     }
     const int64_t nbt = (N + kTileVec * kAssignWaves - 1) / (kTileVec * kAssignWaves);
     const int groups = (D + 255) / 256;
@@ -1573,21 +1583,23 @@ int hclae_reorder_by_variance(hclae_ctx *ctx, int64_t N, int D, float *C, int M,
     if (!C || (N > 0 && !codes)) return fail(ctx, HCLAE_EINVAL, "hclae_reorder_by_variance: NULL pointer");
     if (misaligned(C)) return fail(ctx, HCLAE_EINVAL, "hclae_reorder_by_variance: float arrays must be 16-byte aligned");
     const size_t per = (size_t)K * D;
-    double *dvar = nullptr;
-    int *dorder = nullptr;
-    float *tmp = nullptr;
-    hipError_t e = hipMalloc((void **)&dvar, sizeof(double) * M);
-    if (e == hipSuccess) e = hipMalloc((void **)&dorder, sizeof(int) * M);
-    if (e == hipSuccess) e = hipMalloc((void **)&tmp, sizeof(float) * M * per);
-    auto cleanup = [&]() { if (dvar) (void)hipFree(dvar); if (dorder) (void)hipFree(dorder); if (tmp) (void)hipFree(tmp); };
-    if (e != hipSuccess) { cleanup(); return fail(ctx, HCLAE_ENOMEM, "hipMalloc (reorder scratch)", e); }
+    if (!ctx->order_tmp) {                  // scratch of this call, kept by the ctx from the first call on
+        hipError_t ea = hipMalloc((void **)&ctx->order_var, sizeof(double) * M);
+        if (ea == hipSuccess) ea = hipMalloc((void **)&ctx->order_idx, sizeof(int) * M);
+        if (ea == hipSuccess) ea = hipMalloc((void **)&ctx->order_tmp, sizeof(float) * M * per);
+        if (ea != hipSuccess) return fail(ctx, ea == hipErrorOutOfMemory ? HCLAE_ENOMEM : HCLAE_EHIP, "hipMalloc (reorder scratch)", ea);
+    }
+    double *dvar = ctx->order_var;
+    int *dorder = ctx->order_idx;
+    float *tmp = ctx->order_tmp;
+    hipError_t e = hipSuccess;
     std::vector<double> hv(M);
     std::vector<int> ho(M);
     hipLaunchKernelGGL(k_dictionary_variance, dim3(M), dim3(256), 0, ctx->stream, C, K, D, dvar);
     e = hipGetLastError();
     if (e == hipSuccess) e = hipMemcpyAsync(hv.data(), dvar, sizeof(double) * M, hipMemcpyDeviceToHost, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
-    if (e != hipSuccess) { cleanup(); return fail(ctx, HCLAE_EHIP, "dictionary variance", e); }
+    if (e != hipSuccess) return fail(ctx, HCLAE_EHIP, "dictionary variance", e);
     for (int j = 0; j < M; ++j) ho[j] = j;
     std::stable_sort(ho.begin(), ho.end(), [&](int x, int y) { return hv[x] > hv[y]; });
     e = hipMemcpyAsync(dorder, ho.data(), sizeof(int) * M, hipMemcpyHostToDevice, ctx->stream);
@@ -1603,7 +1615,6 @@ int hclae_reorder_by_variance(hclae_ctx *ctx, int64_t N, int D, float *C, int M,
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
-    cleanup();
     if (e != hipSuccess) return fail(ctx, HCLAE_EHIP, "reorder", e);
     if (var) for (int j = 0; j < M; ++j) var[j] = hv[j];
     if (order) for (int j = 0; j < M; ++j) order[j] = ho[j];
@@ -1618,9 +1629,12 @@ int hclae_code_stats(hclae_ctx *ctx, const uint8_t *codes, int64_t N, int M, int
     if (!hist || (N > 0 && !codes)) return fail(ctx, HCLAE_EINVAL, "hclae_code_stats: NULL pointer");
     if (joint && (a < 0 || a >= M || b < 0 || b >= M)) return fail(ctx, HCLAE_EINVAL, "hclae_code_stats: column out of range");
     const size_t nh = (size_t)M * K, nj = joint ? (size_t)K * K : 0;
-    unsigned long long *dev = nullptr;
-    hipError_t e = hipMalloc((void **)&dev, sizeof(unsigned long long) * (nh + nj));
-    if (e != hipSuccess) return fail(ctx, HCLAE_ENOMEM, "hipMalloc (code statistics)", e);
+    if (!ctx->stats_buf) {                  // sized for the joint histogram too; kept by the ctx from the first call on
+        hipError_t ea = hipMalloc((void **)&ctx->stats_buf, sizeof(unsigned long long) * (nh + (size_t)K * K));
+        if (ea != hipSuccess) return fail(ctx, ea == hipErrorOutOfMemory ? HCLAE_ENOMEM : HCLAE_EHIP, "hipMalloc (code statistics)", ea);
+    }
+    unsigned long long *dev = ctx->stats_buf;
+    hipError_t e = hipSuccess;
     hipLaunchKernelGGL(k_zero_u64, dim3(stream_blocks(ctx, (int64_t)(nh + nj), 256)), dim3(256), 0, ctx->stream, dev, nh + nj);
     e = hipGetLastError();
     if (e == hipSuccess && N > 0) {
@@ -1631,7 +1645,6 @@ int hclae_code_stats(hclae_ctx *ctx, const uint8_t *codes, int64_t N, int M, int
     if (e == hipSuccess) e = hipMemcpyAsync(hist, dev, sizeof(int64_t) * nh, hipMemcpyDeviceToHost, ctx->stream);
     if (e == hipSuccess && joint) e = hipMemcpyAsync(joint, dev + nh, sizeof(int64_t) * nj, hipMemcpyDeviceToHost, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
-    (void)hipFree(dev);
     if (e != hipSuccess) return fail(ctx, HCLAE_EHIP, "code statistics", e);
     return HCLAE_OK;
 }
