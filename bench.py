@@ -189,15 +189,29 @@ def sweep_bench(args, torch, hclae, synth, dev, gist, extras):
 
         # ---- where the time of the headline step goes: every kernel class bracketed by events, one more step
         st.restore("after_fresh")
+        ctx.work_counters(reset=True)
         ctx.timing_enable(hclae.KERNEL_CLASSES)
-        step()
+        ctx.sweep(st.C, st.codes, st.r, T, want_err=False)
+        n_assign, n_vec, n_refined = ctx.work_counters(reset=True)
+        ctx.encode(Xqg, st.C, qcodes, qres)
         ctx.timing_enable([])
         bt = ctx.timing_read()
         tot = sum(ms for ms, n in bt.values())
-        out["time_share"] = {"note": "share of the summed kernel time of one first_anneal_sweep step (events around "
-                                     "every launch; they lengthen the step itself)", "kernel_ms_total": tot,
-                             "classes": {c: {"share": ms / tot, "ms": ms, "launches": n}
-                                         for c, (ms, n) in bt.items() if n}}
+        share = {"note": "share of the summed kernel time of one first_anneal_sweep step (events around every launch; "
+                         "they lengthen the step itself)", "kernel_ms_total": tot,
+                 "classes": {c: {"share": ms / tot, "ms": ms, "launches": n} for c, (ms, n) in bt.items() if n}}
+        # what the exact shortcuts leave to the matrix cores, counted on the device (hclae_work_counters)
+        act_ms = bt["assign_active"][0]
+        act_vec = n_vec - M * N                               # beyond the first assignment of each stage
+        share["assignments"] = n_assign
+        share["vectors_recomputed"] = n_vec
+        share["vectors_recomputed_vs_unpruned"] = n_vec / float((T + 1) * M * N)
+        share["vectors_rechecked_fp64"] = n_refined
+        if act_ms > 0 and act_vec > 0:
+            tf = (3.0 if split else 1.0) * 2.0 * K * D * act_vec / (act_ms * 1e-3) / 1e12
+            share["assign_active_TFLOPs"] = tf
+            share["assign_active_frac_mfma"] = tf / peak
+        out["time_share"] = share
 
         # ---- every kernel class on its own terms: one converged-state sweep (fused stage boundaries), then the
         # same stages one by one so that heat and cool run as separate passes, then the error reduction

@@ -312,7 +312,14 @@ int hclae_reorder_by_variance(hclae_ctx *ctx, int64_t N, int D, float *C, int M,
 int hclae_code_stats(hclae_ctx *ctx, const uint8_t *codes, int64_t N, int M, int K,
                      int64_t *hist, int a, int b, int64_t *joint);
 
-/* ---- measurement: per-kernel durations from HIP events on the ctx's stream ------------- */
+/* ---- measurement: work done, and per-kernel durations from HIP events on the ctx's stream ------------- */
+
+/* Work since hclae_create or the last reset, counted on the device: out[0] = nearest-codeword assignments run
+ * (Sec. 3.1 cool-down and re-encode, Eq. 3 with one path), out[1] = vectors those assignments recomputed (all N
+ * of a full assignment, the listed ones of an assignment the distance bounds pruned), out[2] = vectors decided by
+ * the fp64 re-check.  out: HOST int64[3].  reset != 0 zeroes the counters.  Synchronises the stream. */
+int hclae_work_counters(hclae_ctx *ctx, int64_t *out, int reset);
+
 
 enum {
     HCLAE_T_HEAT = 0,   /* heat pass (Sec. 3.1, x' = e_x + c)                              */

@@ -732,11 +732,19 @@ constexpr int kRefineLanes = 4;
 __global__ __launch_bounds__(256) void k_refine(
     const float *__restrict__ xp, const float *__restrict__ Cm, int D, int ld, int M, int m,
     uint8_t *__restrict__ codes, const RefineItem *__restrict__ list,
-    const unsigned *__restrict__ refine_count, MovedArgs mv)
+    const unsigned *__restrict__ refine_count, MovedArgs mv,
+    unsigned long long *__restrict__ work, unsigned long long rows, const unsigned *__restrict__ rows_listed)
 {
     __shared__ unsigned long long found[kMovedSpan];
     __shared__ unsigned nfound, base;
     const unsigned count = *refine_count;
+    // Work counters of the ctx (read by hclae_work_counters): assignments run, vectors they recomputed, vectors that
+    // went to this re-check.  Launches on one stream follow one another, so one thread may add without atomics.
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        work[0] += 1ull;
+        work[1] += rows_listed ? (unsigned long long)*rows_listed : rows;
+        work[2] += count;
+    }
     // With the moved-vector list wanted, the two jobs run side by side: the first half of the blocks re-checks,
     // the second half scans the other recomputed vectors (below).
     const unsigned nr = mv.prev ? gridDim.x / 2 : gridDim.x;        // blocks that re-check

@@ -100,6 +100,7 @@ struct hclae_ctx {
     float *bnd_u, *bnd_l;    // [N_max]
     float *drift;            // [K]
     uint32_t *active;        // [N_max]: the vectors k_bounds_step lists for the next assignment
+    unsigned long long *work; // [4] work counters: assignments, vectors recomputed, vectors re-checked in fp64
     int64_t *seed_idx;       // [K]
     double *part_a, *part_b; // [nparts]
     long long *part_chg;     // [nparts]
@@ -419,7 +420,8 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
     HIP_TRY(ctx, hipGetLastError());
     Timed t_(ctx, HCLAE_T_REFINE);
     hipLaunchKernelGGL(k_refine, dim3(ctx->cus * 4), dim3(256), 0, ctx->stream,
-                       xp, Cm, dact, ld, ctx->M, m, codes, ctx->refine_list, ctx->refine_count, mv);
+                       xp, Cm, dact, ld, ctx->M, m, codes, ctx->refine_list, ctx->refine_count, mv,
+                       ctx->work, (unsigned long long)N, prune == 2 ? ctx->moved_count + 3 : (const unsigned *)nullptr);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
@@ -728,6 +730,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
         {(void **)&ctx->bnd_l, sizeof(float) * (size_t)N_max},
         {(void **)&ctx->drift, sizeof(float) * HCLAE_MAX_K},
         {(void **)&ctx->active, sizeof(uint32_t) * (size_t)N_max},
+        {(void **)&ctx->work, 256},
         {(void **)&ctx->seed_idx, sizeof(int64_t) * K},
         {(void **)&ctx->part_a, sizeof(double) * ctx->nparts},
         {(void **)&ctx->part_b, sizeof(double) * ctx->nparts},
@@ -747,6 +750,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
     if (e == hipSuccess) e = hipMemset(ctx->refine_count, 0, 256);
     if (e == hipSuccess) e = hipMemset(ctx->nk, 0, sizeof(int) * K);
     if (e == hipSuccess) e = hipMemset(ctx->moved_count, 0, 256);
+    if (e == hipSuccess) e = hipMemset(ctx->work, 0, 256);
     if (e != hipSuccess) {
         int rc = fail(nullptr, HCLAE_EHIP, "scratch initialisation", e);
         hclae_destroy(ctx);
@@ -761,7 +765,7 @@ int hclae_destroy(hclae_ctx *ctx)
 {
     if (!ctx) return HCLAE_EINVAL;
     void *dev[] = {ctx->hneg, ctx->cb_image, ctx->lds_image, ctx->split_image, ctx->split_norms, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
-                   ctx->nk, ctx->tot_sum, ctx->tot_cnt, ctx->upd_col, ctx->moved_list, ctx->moved_count, ctx->bnd_u, ctx->bnd_l, ctx->drift, ctx->active, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
+                   ctx->nk, ctx->tot_sum, ctx->tot_cnt, ctx->upd_col, ctx->moved_list, ctx->moved_count, ctx->bnd_u, ctx->bnd_l, ctx->drift, ctx->active, ctx->work, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
                    ctx->run_sum, ctx->run_cnt, ctx->n0_dev, ctx->pca_rt, ctx->pca_crot, ctx->pca_colpart,
                    ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32, ctx->pca_cov, ctx->pca_R,
                    ctx->stats_buf, ctx->order_var, ctx->order_idx, ctx->order_tmp,
@@ -1678,6 +1682,17 @@ int hclae_timing_read(hclae_ctx *ctx, hclae_kernel_times *out)
         out->launches[ctx->t_cls[i]] += 1;
     }
     ctx->t_used = 0;
+    return HCLAE_OK;
+}
+
+int hclae_work_counters(hclae_ctx *ctx, int64_t *out, int reset)
+{
+    if (!ctx || !out) return HCLAE_EINVAL;
+    unsigned long long v[3] = {0, 0, 0};
+    HIP_TRY(ctx, hipMemcpyAsync(v, ctx->work, sizeof(v), hipMemcpyDeviceToHost, ctx->stream));
+    if (reset) HIP_TRY(ctx, hipMemsetAsync(ctx->work, 0, sizeof(v), ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    for (int i = 0; i < 3; ++i) out[i] = (int64_t)v[i];
     return HCLAE_OK;
 }
 

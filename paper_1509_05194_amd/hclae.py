@@ -19,7 +19,7 @@ _ERRNAME = {0: "HCLAE_OK", -1: "HCLAE_EINVAL", -2: "HCLAE_ENOMEM", -3: "HCLAE_EH
 EXPORTS = (
     "hclae_check_shape", "hclae_create", "hclae_destroy", "hclae_last_error",
     "hclae_encode", "hclae_anneal_stage", "hclae_sweep", "hclae_quant_error", "hclae_quant_error_noalloc",
-    "hclae_heat", "hclae_cool", "hclae_assign", "hclae_update", "hclae_last_refined",
+    "hclae_heat", "hclae_cool", "hclae_assign", "hclae_update", "hclae_last_refined", "hclae_work_counters",
     "hclae_timing_enable", "hclae_timing_read", "hclae_online_begin", "hclae_online_chunk",
     "hclae_online_export", "hclae_online_import",
     "hclae_covariance", "hclae_pca_axes", "hclae_symmetric_eigen", "hclae_rotate", "hclae_assign_prefix", "hclae_anneal_stage_pca",
@@ -82,6 +82,7 @@ def lib():
     L.hclae_assign.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, vp, vp]
     L.hclae_update.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, vp, vp]
     L.hclae_last_refined.argtypes = [vp, ctypes.POINTER(i64)]
+    L.hclae_work_counters.argtypes = [vp, ctypes.POINTER(i64), i32]
     L.hclae_online_begin.argtypes = [vp, vp, i32, i32, i32, vp]
     L.hclae_online_chunk.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
     L.hclae_online_export.argtypes = [vp, vp, vp]
@@ -276,6 +277,12 @@ class Context:
         out = ctypes.c_int64()
         self._chk(lib().hclae_last_refined(self._h, ctypes.byref(out)))
         return out.value
+
+    def work_counters(self, reset=False):
+        """(assignments run, vectors they recomputed, vectors decided by the fp64 re-check) since the last reset."""
+        out = (ctypes.c_int64 * 3)()
+        self._chk(lib().hclae_work_counters(self._h, out, 1 if reset else 0))
+        return int(out[0]), int(out[1]), int(out[2])
 
     # ---- online learning -----------------------------------------------------------------
     def online_begin(self, C, n0=None):
