@@ -27,11 +27,11 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0    # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0             # MI355X HBM3E peak
 CONVERGED_AFTER = 8               # sweeps before the one `converged_sweep` times
 
-# HBM bytes per N=1M launch of the assign kernel from two rocprofv3 --pmc runs (FETCH_SIZE 250,684.0 KiB
-# x 2.000, WRITE_SIZE 20,701.9 KiB x 1.000; factors from a 512 MB device copy in the same runs), recorded
+# HBM bytes per N=1M launch of the assign kernel from two rocprofv3 --pmc runs (FETCH_SIZE 250,670.0 KiB
+# x 2.000, WRITE_SIZE 16,135.3 KiB x 1.000; factors from a 512 MB device copy in the same runs), recorded
 # in profiles/da_sweep_sift1m_counters.md: the launches that also store the distance bounds.  Algorithmic
 # bytes are 521e6 (x', codes, bounds).
-ASSIGN_TRAFFIC_BYTES = 5.346e8   # (250684.0 * 2.000 + 20701.9) KiB
+ASSIGN_TRAFFIC_BYTES = 5.299e8   # (250670.0 * 2.000 + 16135.3) KiB
 # the same for the D-chunked kernel at N=1M, D=960 (profiles/da_sweep_gist1m_counters.md); algorithmic 3.841e9
 ASSIGN_TRAFFIC_BYTES_GIST = 4.037e9   # (1962932.8 * 2.000 + 16579.8) KiB
 
