@@ -276,3 +276,31 @@ def test_pca_axes_against_oracle_axes(oracle):
     assert np.abs(T - np.diag(np.diag(T))).max() <= 2e-5 * w_o[0]
     np.testing.assert_allclose(np.diag(T), w_o, atol=2e-5 * w_o[0])
     ctx.close()
+
+
+@pytest.mark.parametrize("case", ["tiny", "d132", "gist"])
+def test_pca_stage_with_its_own_axes_equals_the_stage_given_them(case):
+    """hclae_anneal_stage_pca with R = NULL finds the principal axes of its own x' (hclae_pca_axes inside the call):
+    the result must be the very bits of the stage that is handed the axes hclae_pca_axes returns for that x'."""
+    c = SHAPES[case]
+    N, D, M, K = c["N"], c["D"], c["M"], c["K"]
+    X = _data(c)
+    idx = synth.init_indices(N, M, K)
+    dims = np.array([2, D // 3, D], np.int32)
+    ctx = _ctx(c)
+    out = []
+    for own in (True, False):
+        C = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+        codes = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+        r = to_dev(X)
+        xr = torch.empty_like(r)
+        for m in range(M):
+            if own:
+                ctx.anneal_stage_pca(m, C, codes, r, None, dims, 1, xr, init_idx=idx[m])
+            else:
+                R, w = ctx.pca_axes(r)                                # a fresh stage: x' is the residue
+                assert np.all(np.diff(w) <= 0) and w[-1] >= -1e-9 * w[0]
+                ctx.anneal_stage_pca(m, C, codes, r, R, dims, 1, xr, init_idx=idx[m])
+        out.append((C, codes, r))
+    assert torch.equal(out[0][0], out[1][0]) and torch.equal(out[0][1], out[1][1]) and torch.equal(out[0][2], out[1][2])
+    ctx.close()
