@@ -177,8 +177,8 @@ def sweep_bench(args, torch, hclae, synth, dev, gist, extras):
         t = timed_steps(torch, st, "zero", step_from_scratch, side_steps, 1)
         sweeps["fresh_sweep"] = {"ms_per_step": t * 1e3, "value": N * M / t, "steps": side_steps,
                                  "quant_error_after": ctx.quant_error(st.r),
-                                 "note": "from all-zero dictionaries; seeds copied from the host and one stream "
-                                         "synchronisation per stage are inside the call"}
+                                 "note": "from all-zero dictionaries; the copy of the seed rows from the host and one "
+                                         "stream synchronisation are inside the call"}
         t = timed_steps(torch, st, "converged", step, side_steps, 1)
         sweeps["converged_sweep"] = {"ms_per_step": t * 1e3, "value": N * M / t, "steps": side_steps,
                                      "quant_error_after": ctx.quant_error(st.r),

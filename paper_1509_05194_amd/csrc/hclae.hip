@@ -101,7 +101,7 @@ struct hclae_ctx {
     float *drift;            // [K]
     uint32_t *active;        // [N_max]: the vectors k_bounds_step lists for the next assignment
     unsigned long long *work; // [4] work counters: assignments, vectors recomputed, vectors re-checked in fp64
-    int64_t *seed_idx;       // [K]
+    int64_t *seed_idx;       // [M][K] seed rows of a sweep from all-zero dictionaries (a single stage uses row 0)
     double *part_a, *part_b; // [nparts]
     long long *part_chg;     // [nparts]
     int nparts;              // max(kFlatParts, heat/cool blocks at N_max)
@@ -559,19 +559,17 @@ int launch_sqnorm(hclae_ctx *ctx, const float *r, int64_t N, double *part)
 // stage ended with a fused transition).  next: >= 0 ends the stage with the fused transition into
 // that stage instead of the plain new-residue pass.
 int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, float *residue, int iters,
-                  const int64_t *init_idx, int slot, bool heated = false, int next = -1)
+                  const int64_t *seed_dev, int slot, bool heated = false, int next = -1)
 {
     const int D = ctx->D, K = ctx->K;
     float *Cm = C + (size_t)m * K * D;
     int rc;
-    if (init_idx)   // pageable host memory: the copy is staged before the call returns
-        HIP_TRY(ctx, hipMemcpyAsync(ctx->seed_idx, init_idx, sizeof(int64_t) * K, hipMemcpyHostToDevice, ctx->stream));
     if (!heated) {
         const int pb = launch_heat_cool<+1, true>(ctx, m, N, C, codes, residue, ctx->part_a);
         if (pb < 0) return pb;
     }
-    if (init_idx) {
-        hipLaunchKernelGGL(k_seed, dim3(K), dim3(256), 0, ctx->stream, residue, ctx->seed_idx, K, D, Cm);
+    if (seed_dev) {
+        hipLaunchKernelGGL(k_seed, dim3(K), dim3(256), 0, ctx->stream, residue, seed_dev, K, D, Cm);
         HIP_TRY(ctx, hipGetLastError());
     }
     if ((rc = launch_norms(ctx, Cm, 0, 0, false, true)) != HCLAE_OK) return rc;
@@ -731,7 +729,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
         {(void **)&ctx->drift, sizeof(float) * HCLAE_MAX_K},
         {(void **)&ctx->active, sizeof(uint32_t) * (size_t)N_max},
         {(void **)&ctx->work, 256},
-        {(void **)&ctx->seed_idx, sizeof(int64_t) * K},
+        {(void **)&ctx->seed_idx, sizeof(int64_t) * (size_t)M * K},
         {(void **)&ctx->part_a, sizeof(double) * ctx->nparts},
         {(void **)&ctx->part_b, sizeof(double) * ctx->nparts},
         {(void **)&ctx->part_chg, sizeof(long long) * ctx->nparts},
@@ -936,7 +934,9 @@ int hclae_anneal_stage(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M,
         if (stats) { memset(stats, 0, sizeof(*stats)); }
         return HCLAE_OK;
     }
-    if ((rc = enqueue_stage(ctx, m, N, C, codes, residue, iters, init_idx, 0)) != HCLAE_OK) return rc;
+    if (init_idx)
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->seed_idx, init_idx, sizeof(int64_t) * K, hipMemcpyHostToDevice, ctx->stream));
+    if ((rc = enqueue_stage(ctx, m, N, C, codes, residue, iters, init_idx ? ctx->seed_idx : nullptr, 0)) != HCLAE_OK) return rc;
     if (stats) {
         if ((rc = fetch_records(ctx, 1)) != HCLAE_OK) return rc;
         fill_stats(ctx->rec_host[0], N, iters, stats);
@@ -991,13 +991,14 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
         if (err_per_stage) for (int m = 0; m < M; ++m) err_per_stage[m] = 0.0;
         return HCLAE_OK;
     }
+    if (init_idx)   // all M x K seed rows at once; the caller's array is free again once the stream has passed the copy
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->seed_idx, init_idx, sizeof(int64_t) * (size_t)M * K, hipMemcpyHostToDevice, ctx->stream));
     for (int m = 0; m < M; ++m) {
-        const int64_t *idx = init_idx ? init_idx + (size_t)m * K : nullptr;
+        const int64_t *idx = init_idx ? ctx->seed_idx + (size_t)m * K : nullptr;
         // without the full re-encode, stage m ends and stage m+1 begins in one fused pass over the residue
         const bool fuse = (reencode_mode == 0);
         if ((rc = enqueue_stage(ctx, m, N, C, codes, residue, iters, idx, m, fuse && m > 0,
                                 (fuse && m + 1 < M) ? m + 1 : -1)) != HCLAE_OK) return rc;
-        if (idx) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));   // seed_idx scratch is reused by the next stage
         if (reencode_mode != 0) {
             rc = reencode_mode == 1 ? enqueue_encode(ctx, X, N, C, codes, residue)
                                     : enqueue_encode_beam(ctx, X, N, C, ctx->sweep_L, codes, residue, nullptr);
@@ -1015,6 +1016,9 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
     if (err_per_stage) {
         if ((rc = fetch_records(ctx, M)) != HCLAE_OK) return rc;
         for (int m = 0; m < M; ++m) err_per_stage[m] = ctx->rec_host[m].sum_after / (double)N;
+    } else if (init_idx) {
+        // the seed indices were read from caller memory by an asynchronous copy
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     }
     return HCLAE_OK;
 }
