@@ -72,3 +72,34 @@ def test_axes_follow_the_oracles_conventions(oracle):
     w, Vt = hclae.symmetric_eigen(cov)
     np.testing.assert_allclose(Vt, R_o, atol=1e-8)
     np.testing.assert_allclose(w, np.sort(np.linalg.eigvalsh(cov))[::-1], rtol=1e-10)
+
+
+def test_hard_spectra():
+    """Close pairs (Wilkinson's W21+), a graded matrix, many equal eigenvalues, and the size of the GIST-shaped
+    configuration (n = 960) against LAPACK."""
+    n = 21
+    W = np.diag(np.abs(np.arange(n) - 10.0)) + np.eye(n, k=1) + np.eye(n, k=-1)
+    w, Vt = hclae.symmetric_eigen(W)
+    _check(W, w, Vt)
+    assert w[0] - w[1] < 1e-10 and w[0] > 10.7          # the famous pair 10.746194182903...
+    g = np.random.default_rng(7)
+    # graded: entries from 1e8 down to 1e-8
+    s = 10.0 ** np.linspace(4, -4, 40)
+    B = g.standard_normal((40, 40))
+    A = (B + B.T) * np.outer(s, s)
+    w, Vt = hclae.symmetric_eigen(A)
+    _check(A, w, Vt)
+    # three eigenvalues only, each many times over
+    Q = np.linalg.qr(g.standard_normal((60, 60)))[0]
+    lam = np.repeat([5.0, 2.0, -1.0], 20)
+    A = (Q * lam) @ Q.T
+    A = 0.5 * (A + A.T)
+    w, Vt = hclae.symmetric_eigen(A)
+    np.testing.assert_allclose(w, lam, atol=1e-12)
+    _check(A, w, Vt)
+    # projector onto the eigenspace of 5 equals that of the construction
+    np.testing.assert_allclose(Vt[:20].T @ Vt[:20], Q[:, :20] @ Q[:, :20].T, atol=1e-12)
+    B = g.standard_normal((960, 960))
+    A = B @ B.T / 960
+    w, Vt = hclae.symmetric_eigen(A)
+    _check(A, w, Vt)
