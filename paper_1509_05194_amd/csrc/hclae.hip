@@ -215,6 +215,12 @@ RowGeom row_geom(int D);
 // 32 per CU measured best for the in-place read-modify-write stream, each looping a few times.
 int heat_cool_blocks(int64_t N, int D, int cus)
 {
+    if (D >= kWideMinD) {                  // k_row_pass_wide: a wave per kWideRows rows, 64 blocks per CU measured best
+        const int64_t per = (int64_t)(kStreamThreads / kWave) * kWideRows;
+        int64_t b = (N + per - 1) / per;
+        if (b > (int64_t)cus * 64) b = (int64_t)cus * 64;
+        return (int)(b < 1 ? 1 : b);
+    }
     const RowGeom g = row_geom(D);
     const int64_t per = (int64_t)(kStreamThreads >> g.lcw) * kStreamUnroll;
     int64_t b = (N + per - 1) / per;
@@ -245,10 +251,16 @@ int launch_heat_cool(hclae_ctx *ctx, int m, int64_t N, const float *C, const uin
     (void)rows;
     const float *Cm = C + (size_t)m * ctx->K * ctx->D;
     Timed t_(ctx, SIGN > 0 ? HCLAE_T_HEAT : HCLAE_T_COOL);
-    // the row lengths of the SIFT- and GIST-shaped configurations have kernels of their own (addresses and geometry
-    // constant: 179 us instead of 185 us for the stage boundary at N = 1M, D = 128)
-    auto kern = ctx->D == 128 ? &k_row_pass<SIGN, STATS, 128>
-              : ctx->D == 960 ? &k_row_pass<SIGN, STATS, 960> : &k_row_pass<SIGN, STATS, 0>;
+    // the row length of the SIFT-shaped configurations has a kernel of its own (addresses and geometry constant:
+    // 179 us instead of 185 us for the stage boundary at N = 1M, D = 128); long rows take k_row_pass_wide
+    if (ctx->D >= kWideMinD) {
+        hipLaunchKernelGGL((k_row_pass_wide<SIGN, STATS>), dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
+                           r, codes, Cm, (const float *)nullptr, N, ctx->D, ctx->M, m, 0, ctx->old_codes, part_err,
+                           ctx->part_chg);
+        HIP_TRY(ctx, hipGetLastError());
+        return blocks;
+    }
+    auto kern = ctx->D == 128 ? &k_row_pass<SIGN, STATS, 128> : &k_row_pass<SIGN, STATS, 0>;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
                        r, codes, Cm, (const float *)nullptr, N, ctx->D, ctx->M, m, 0, g, ctx->old_codes, part_err,
                        ctx->part_chg);
@@ -597,10 +609,16 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
         const RowGeom g = row_geom(D);
         pa = heat_cool_blocks(N, D, ctx->cus);
         Timed t_(ctx, HCLAE_T_TRANSITION);
-        auto kern = D == 128 ? &k_row_pass<0, true, 128> : D == 960 ? &k_row_pass<0, true, 960> : &k_row_pass<0, true, 0>;
-        hipLaunchKernelGGL(kern, dim3(pa), dim3(kStreamThreads), 0, ctx->stream,
-                           residue, codes, Cm, C + (size_t)next * K * D, N, D, ctx->M, m, next, g,
-                           ctx->old_codes, ctx->part_b, ctx->part_chg);
+        if (D >= kWideMinD) {
+            hipLaunchKernelGGL((k_row_pass_wide<0, true>), dim3(pa), dim3(kStreamThreads), 0, ctx->stream,
+                               residue, codes, Cm, C + (size_t)next * K * D, N, D, ctx->M, m, next,
+                               ctx->old_codes, ctx->part_b, ctx->part_chg);
+        } else {
+            auto kern = D == 128 ? &k_row_pass<0, true, 128> : &k_row_pass<0, true, 0>;
+            hipLaunchKernelGGL(kern, dim3(pa), dim3(kStreamThreads), 0, ctx->stream,
+                               residue, codes, Cm, C + (size_t)next * K * D, N, D, ctx->M, m, next, g,
+                               ctx->old_codes, ctx->part_b, ctx->part_chg);
+        }
         HIP_TRY(ctx, hipGetLastError());
     }
     hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFinishThreads), 0, ctx->stream,

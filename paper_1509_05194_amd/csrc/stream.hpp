@@ -158,6 +158,125 @@ __global__ __launch_bounds__(kStreamThreads) void k_row_pass(
     }
 }
 
+// The same passes for long rows (D >= kWideMinD): a wave owns whole rows.  Lane l takes float4 columns l, l + 64,
+// l + 128, l + 192 of a group of 256 columns (one contiguous kilobyte of the row per wave-instruction, up to 4 KB of
+// one row in flight), kWideRows rows per step, steps (row pair, column group) pipelined as in k_row_pass.  Measured at
+// N = 1M, D = 960 (3.84 GB each way): stage boundary 1.39 ms against 1.51 ms for k_row_pass, new residue 1.36 ms
+// against 1.43 ms.  Results are those of k_row_pass bit for bit (the same fp32 operations per element); the error
+// sums differ in their order of additions, which is the same in all three modes here too.
+constexpr int kWideMinD = 768;
+constexpr int kWideRows = 2;
+template <int MODE, bool STATS>
+__global__ __launch_bounds__(kStreamThreads) void k_row_pass_wide(
+    float *__restrict__ r, const uint8_t *__restrict__ codes, const float *__restrict__ Cm, const float *__restrict__ Cj,
+    int64_t N, int D, int M, int m, int j_stage,
+    uint8_t *__restrict__ old_codes, double *__restrict__ part_err, long long *__restrict__ part_chg)
+{
+    __shared__ double red[kStreamThreads / kWave];
+    constexpr int U = 4, R = kWideRows;
+    const int d4 = D >> 2;
+    const int ngroups = (d4 + U * kWave - 1) / (U * kWave);
+    const int lane = lane_id();
+    const int64_t stride = (int64_t)gridDim.x * (kStreamThreads / kWave) * R;
+    double err = 0.0;
+    long long chg = 0;
+
+    auto load_codes = [&](int64_t n0, int (&a)[R], int (&b)[R]) {
+#pragma unroll
+        for (int q = 0; q < R; ++q) {
+            const int64_t nn = n0 + q < N ? n0 + q : N - 1;
+            a[q] = codes[nn * M + m];
+            if (MODE == 0) b[q] = codes[nn * M + j_stage];
+        }
+    };
+    auto load_rows = [&](int64_t n0, int group, floatx4 (&v)[R][U]) {
+#pragma unroll
+        for (int q = 0; q < R; ++q) {
+            const int64_t nn = n0 + q < N ? n0 + q : N - 1;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = (group * U + u) * kWave + lane;
+                v[q][u] = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(r + nn * D) + (c < d4 ? c : d4 - 1));
+            }
+        }
+    };
+
+    int64_t n0 = ((int64_t)blockIdx.x * (kStreamThreads / kWave) + (threadIdx.x >> 6)) * R;
+    int group = 0;
+    floatx4 v[R][U];
+    int cm[R], cj[R];
+    if (n0 < N) {
+        load_codes(n0, cm, cj);
+        load_rows(n0, 0, v);
+    }
+    while (n0 < N) {
+        int group_next = group + 1;
+        int64_t n0_next = n0;
+        if (group_next == ngroups) { group_next = 0; n0_next = n0 + stride; }
+        floatx4 vn[R][U];
+        int cmn[R], cjn[R];
+        if (n0_next < N) {
+            if (group_next == 0) load_codes(n0_next, cmn, cjn);
+            load_rows(n0_next, group_next, vn);
+        }
+#pragma unroll
+        for (int q = 0; q < R; ++q) {
+            const int64_t n = n0 + q;
+            floatx4 a[U], b[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = (group * U + u) * kWave + lane;
+                const int cc = c < d4 ? c : d4 - 1;
+                a[u] = *(reinterpret_cast<const floatx4 *>(Cm + (size_t)cm[q] * D) + cc);
+                if (MODE == 0) b[u] = *(reinterpret_cast<const floatx4 *>(Cj + (size_t)cj[q] * D) + cc);
+            }
+            if (n < N) {
+                if (STATS && lane == 0 && group == 0) {
+                    if (MODE > 0) old_codes[n] = (uint8_t)cm[q];
+                    if (MODE < 0) chg += (old_codes[n] != (uint8_t)cm[q]);
+                    if (MODE == 0) {
+                        chg += (old_codes[n] != (uint8_t)cm[q]);
+                        old_codes[n] = (uint8_t)cj[q];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int c = (group * U + u) * kWave + lane;
+                    if (c < d4) {
+                        floatx4 w = v[q][u];
+                        if (STATS && MODE > 0)
+                            err += (double)w.x * w.x + (double)w.y * w.y + (double)w.z * w.z + (double)w.w * w.w;
+                        if (MODE > 0) w = w + a[u];
+                        else w = w - a[u];
+                        if (STATS && MODE <= 0)
+                            err += (double)w.x * w.x + (double)w.y * w.y + (double)w.z * w.z + (double)w.w * w.w;
+                        if (MODE == 0) w = w + b[u];
+                        __builtin_nontemporal_store(w, reinterpret_cast<floatx4 *>(r + n * D) + c);
+                    }
+                }
+            }
+        }
+        if (group_next == 0) {
+#pragma unroll
+            for (int q = 0; q < R; ++q) { cm[q] = cmn[q]; cj[q] = cjn[q]; }
+        }
+#pragma unroll
+        for (int q = 0; q < R; ++q)
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[q][u] = vn[q][u];
+        group = group_next;
+        n0 = n0_next;
+    }
+    if (STATS) {
+        const double e = block_sum(err, red);
+        if (threadIdx.x == 0) part_err[blockIdx.x] = e;
+        if (MODE <= 0) {
+            const double c = block_sum((double)chg, red);
+            if (threadIdx.x == 0) part_chg[blockIdx.x] = (long long)c;
+        }
+    }
+}
+
 // r <- X (first step of the greedy encoder): four float4 per thread in flight.
 __global__ __launch_bounds__(kFlatThreads) void k_copy(
     floatx4 *__restrict__ dst, const floatx4 *__restrict__ src, int64_t n4)
