@@ -357,9 +357,25 @@ def pca_stage_bench(torch, hclae, synth, ctx, st, idx, N, D, M, K):
             torch.cuda.synchronize()
             tt.append(time.perf_counter() - t0)
         res[kind] = {"ms_per_stage": min(tt) * 1e3, "vectors_per_s": N / min(tt), "quant_error_after": s["err_after"]}
+    # the whole sweep from all-zero dictionaries with either cool-down (hclae_set_cooldown): time and E after each stage
+    T = len(dims)
+    for kind in ("improved", "plain"):
+        ctx.set_cooldown(kind == "improved", 10)
+        tt = []
+        for _ in range(2):
+            st.restore("zero")
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            E = ctx.sweep(st.C, st.codes, st.r, T, init_idx=idx)
+            torch.cuda.synchronize()
+            tt.append(time.perf_counter() - t0)
+        res[kind]["sweep_ms"] = min(tt) * 1e3
+        res[kind]["sweep_quant_error_per_stage"] = [float(e) for e in E]
+    ctx.set_cooldown(False)
     res["note"] = ("stage 0 from all-zero dictionaries, %d Lloyd iterations either way; improved = covariance on the "
-                   "device, eigen-decomposition on the host (inside the call), rotation, prefixes %s, rotation back"
-                   % (len(dims), dims))
+                   "device, eigen-decomposition on the host (inside the call), rotation, prefixes %s, rotation back; "
+                   "sweep_*: the whole sweep from all-zero dictionaries (M stages) cooled either way, per-stage "
+                   "errors read back inside the timed call" % (len(dims), dims))
     return res
 
 

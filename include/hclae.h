@@ -110,7 +110,8 @@ int hclae_anneal_stage(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M,
  *                  hclae_set_beam_width (10 unless set).
  * init_idx: HOST int64[M][K] or NULL.  err_per_stage: HOST double[M] or NULL
  * (mean ||e_x||^2 after each stage).
- * With reencode_mode 0, init_idx == NULL and err_per_stage == NULL the call only enqueues kernels on the
+ * The k-means that cools each stage is the one hclae_set_cooldown chose (plain Lloyd iterations unless set).
+ * With the plain cool-down, reencode_mode 0, init_idx == NULL and err_per_stage == NULL the call only enqueues kernels on the
  * context's stream (no allocation, copy, memset or synchronisation; all data-dependent sizes are read on the
  * device), so it may be recorded into a HIP graph on that stream and replayed.
  */
@@ -293,6 +294,26 @@ int hclae_assign_prefix(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp
 int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M, int K,
                            uint8_t *codes, float *residue, const float *R, const int *dims, int n_dims,
                            int iters_per_dim, float *xr, const int64_t *init_idx, hclae_stage_stats *stats);
+
+/* The dimension schedule of Sec. 3.2: d_i = ceil(D^(i/phases)), i = 1..phases (the printed d^(i/I) is no integer:
+ * rounded up), equal values once, the last one D.  dims: HOST int[phases]; *n_dims: how many were written.
+ * Needs no device.  1 <= phases <= 64. */
+int hclae_dimension_schedule(int D, int phases, int *dims, int *n_dims);
+
+#define HCLAE_COOLDOWN_LLOYD    0   /* plain full-dimension Lloyd iterations (default)                       */
+#define HCLAE_COOLDOWN_IMPROVED 1   /* the improved k-means of Sec. 3.2                                       */
+
+/*
+ * Which k-means cools a dictionary in hclae_anneal_stage and hclae_sweep (Sec. 3.1 cools with "a k-means"; Sec. 3.2
+ * gives the improved one for high-dimensional residue).  With HCLAE_COOLDOWN_IMPROVED every stage runs as
+ * hclae_anneal_stage_pca does with R = NULL: principal axes of its own x', the schedule of `phases` prefixes
+ * (hclae_dimension_schedule; 10 in the paper), ceil(iters / prefixes) Lloyd iterations on each prefix -- `iters`
+ * being the argument of the stage or sweep call -- rotation back, re-encode in the original space.  Such a stage
+ * synchronises the stream once (the eigen-decomposition runs on the host), keeps heat and new residue as separate
+ * passes, and does not use the distance-bound shortcuts; x^r lives in scratch (N_max x D floats) that the first such
+ * stage allocates and the ctx keeps.  phases is ignored with HCLAE_COOLDOWN_LLOYD.
+ */
+int hclae_set_cooldown(hclae_ctx *ctx, int mode, int phases);
 
 /* ---- dictionary order and code statistics (Sec. 3.3, Sec. 2.2) --------------------------------- */
 

@@ -122,6 +122,9 @@ struct hclae_ctx {
     float *pca_mean32;       // [D]
     double *pca_cov;         // [D][D] covariance of x' when the stage finds the principal axes itself
     float *pca_R;            // [D][D] those axes (rows), fp32
+    float *pca_xr;           // [N_max][D] rotated data when the improved k-means is the ctx's cool-down
+    int cooldown;            // HCLAE_COOLDOWN_*
+    int cooldown_phases;     // prefixes of its dimension schedule before equal ones are merged (I of Sec. 3.2)
     int pca_ncol, pca_ngram;
     // dictionary order and code statistics (allocated on first use)
     unsigned long long *stats_buf;   // [M][K] + [K][K] histogram counters
@@ -687,6 +690,7 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
     ctx->stream = static_cast<hipStream_t>(hip_stream);
     ctx->sweep_L = 10;                       // the width the paper settles on (Sec. 3.3)
     ctx->pruning = 1;
+    ctx->cooldown_phases = 10;               // I = 10 (Sec. 3.2)
     ctx->kb = K <= 32 ? 1 : K <= 64 ? 2 : K <= 128 ? 4 : 8;
     ctx->NC = (D + kChunkD - 1) / kChunkD;
     ctx->resident = (size_t)32 * ctx->kb * kChunkD * ctx->NC * sizeof(float) + 4096 <= (size_t)kLdsBudget;
@@ -783,7 +787,7 @@ int hclae_destroy(hclae_ctx *ctx)
     void *dev[] = {ctx->hneg, ctx->cb_image, ctx->lds_image, ctx->split_image, ctx->split_norms, ctx->refine_count, ctx->refine_list, ctx->old_codes, ctx->partial, ctx->pcount,
                    ctx->nk, ctx->tot_sum, ctx->tot_cnt, ctx->upd_col, ctx->moved_list, ctx->moved_count, ctx->bnd_u, ctx->bnd_l, ctx->drift, ctx->active, ctx->work, ctx->seed_idx, ctx->part_a, ctx->part_b, ctx->part_chg, ctx->rec,
                    ctx->run_sum, ctx->run_cnt, ctx->n0_dev, ctx->pca_rt, ctx->pca_crot, ctx->pca_colpart,
-                   ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32, ctx->pca_cov, ctx->pca_R,
+                   ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32, ctx->pca_cov, ctx->pca_R, ctx->pca_xr,
                    ctx->stats_buf, ctx->order_var, ctx->order_idx, ctx->order_tmp,
                    ctx->beam_rows[0], ctx->beam_rows[1], ctx->beam_err[0], ctx->beam_err[1],
                    ctx->beam_pre[0], ctx->beam_pre[1], ctx->beam_mask};
@@ -937,6 +941,9 @@ static void fill_stats(const StageRecord &r, int64_t N, int iters, hclae_stage_s
     s->iters_run = iters;
 }
 
+static int enqueue_stage_cooldown_pca(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, float *residue,
+                                      int iters, const int64_t *seed_dev, int slot, int *iters_run_out);
+
 int hclae_anneal_stage(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M, int K,
                        uint8_t *codes, float *residue, int iters,
                        const int64_t *init_idx, hclae_stage_stats *stats)
@@ -954,10 +961,14 @@ int hclae_anneal_stage(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M,
     }
     if (init_idx)
         HIP_TRY(ctx, hipMemcpyAsync(ctx->seed_idx, init_idx, sizeof(int64_t) * K, hipMemcpyHostToDevice, ctx->stream));
-    if ((rc = enqueue_stage(ctx, m, N, C, codes, residue, iters, init_idx ? ctx->seed_idx : nullptr, 0)) != HCLAE_OK) return rc;
+    int iters_run = iters;
+    rc = ctx->cooldown == HCLAE_COOLDOWN_IMPROVED
+             ? enqueue_stage_cooldown_pca(ctx, m, N, C, codes, residue, iters, init_idx ? ctx->seed_idx : nullptr, 0, &iters_run)
+             : enqueue_stage(ctx, m, N, C, codes, residue, iters, init_idx ? ctx->seed_idx : nullptr, 0);
+    if (rc != HCLAE_OK) return rc;
     if (stats) {
         if ((rc = fetch_records(ctx, 1)) != HCLAE_OK) return rc;
-        fill_stats(ctx->rec_host[0], N, iters, stats);
+        fill_stats(ctx->rec_host[0], N, iters_run, stats);
     } else if (init_idx) {
         // the seed indices were read from caller memory by an asynchronous copy
         HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
@@ -1013,10 +1024,13 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
         HIP_TRY(ctx, hipMemcpyAsync(ctx->seed_idx, init_idx, sizeof(int64_t) * (size_t)M * K, hipMemcpyHostToDevice, ctx->stream));
     for (int m = 0; m < M; ++m) {
         const int64_t *idx = init_idx ? ctx->seed_idx + (size_t)m * K : nullptr;
-        // without the full re-encode, stage m ends and stage m+1 begins in one fused pass over the residue
-        const bool fuse = (reencode_mode == 0);
-        if ((rc = enqueue_stage(ctx, m, N, C, codes, residue, iters, idx, m, fuse && m > 0,
-                                (fuse && m + 1 < M) ? m + 1 : -1)) != HCLAE_OK) return rc;
+        // without the full re-encode, stage m ends and stage m+1 begins in one fused pass over the residue (plain
+        // Lloyd cool-down; the improved k-means rotates x' first and keeps the two passes apart)
+        const bool fuse = (reencode_mode == 0) && ctx->cooldown == HCLAE_COOLDOWN_LLOYD;
+        rc = ctx->cooldown == HCLAE_COOLDOWN_IMPROVED
+                 ? enqueue_stage_cooldown_pca(ctx, m, N, C, codes, residue, iters, idx, m, nullptr)
+                 : enqueue_stage(ctx, m, N, C, codes, residue, iters, idx, m, fuse && m > 0, (fuse && m + 1 < M) ? m + 1 : -1);
+        if (rc != HCLAE_OK) return rc;
         if (reencode_mode != 0) {
             rc = reencode_mode == 1 ? enqueue_encode(ctx, X, N, C, codes, residue)
                                     : enqueue_encode_beam(ctx, X, N, C, ctx->sweep_L, codes, residue, nullptr);
@@ -1525,34 +1539,35 @@ int hclae_assign_prefix(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp
     return launch_assign(ctx, m, N, xp, Cm, codes, dact, D);
 }
 
-int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M, int K,
-                           uint8_t *codes, float *residue, const float *R, const int *dims, int n_dims,
-                           int iters_per_dim, float *xr, const int64_t *init_idx, hclae_stage_stats *stats)
+// Prefixes of the coordinates for the improved k-means: d_i = ceil(D^(i/I)), i = 1..I (Sec. 3.2 prints d_i = d^(i/I)
+// with I = 10, which is no integer: rounded up), equal values once, the last one D.  Returns how many.
+static int dimension_schedule(int D, int I, int *dims)
 {
-    int rc = check_call(ctx, N, D, M, K);
-    if (rc != HCLAE_OK) return rc;
-    if (m < 0 || m >= M || iters_per_dim < 0 || n_dims < 1 || !dims)
-        return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: bad argument");
-    for (int i = 0; i < n_dims; ++i)
-        if (dims[i] < 1 || dims[i] > D || (i > 0 && dims[i] <= dims[i - 1]))
-            return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: dims must increase within [1, D]");
-    if (dims[n_dims - 1] != D) return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: the last prefix must be D");
-    if (init_idx)
-        for (int i = 0; i < K; ++i)
-            if (init_idx[i] < 0 || init_idx[i] >= N) return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: init_idx out of range");
-    if (N == 0) { if (stats) memset(stats, 0, sizeof(*stats)); return HCLAE_OK; }
-    if (!C || !codes || !residue || !xr || xr == residue)
-        return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: NULL or aliased pointer");
-    if (misaligned(C, residue, R, xr)) return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: float arrays must be 16-byte aligned");
-    if ((rc = pca_scratch(ctx)) != HCLAE_OK) return rc;
+    int n = 0;
+    for (int i = 1; i <= I; ++i) {
+        int d = (int)ceil(pow((double)D, (double)i / (double)I) - 1e-9);
+        if (d < 1) d = 1;
+        if (d > D) d = D;
+        if (n == 0 || d > dims[n - 1]) dims[n++] = d;
+    }
+    dims[n - 1] = D;
+    return n;
+}
+
+// Enqueues one stage whose cool-down is the improved k-means of Sec. 3.2; by-products land in ctx->rec[slot].
+// seed_dev: DEVICE seed rows or null.  R: DEVICE axes, or null: found from this stage's x' (synchronises once).
+static int enqueue_stage_pca(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, float *residue, const float *R,
+                             const int *dims, int n_dims, int iters_per_dim, float *xr, const int64_t *seed_dev,
+                             int slot, int *iters_run_out)
+{
+    const int D = ctx->D, K = ctx->K;
+    int rc;
     float *Cm = C + (size_t)m * K * D;
     const size_t cbytes = (size_t)K * D * sizeof(float);
-    if (init_idx)
-        HIP_TRY(ctx, hipMemcpyAsync(ctx->seed_idx, init_idx, sizeof(int64_t) * K, hipMemcpyHostToDevice, ctx->stream));
     const int pb = launch_heat_cool<+1, true>(ctx, m, N, C, codes, residue, ctx->part_a);
     if (pb < 0) return pb;
-    if (init_idx) {
-        hipLaunchKernelGGL(k_seed, dim3(K), dim3(256), 0, ctx->stream, residue, ctx->seed_idx, K, D, Cm);
+    if (seed_dev) {
+        hipLaunchKernelGGL(k_seed, dim3(K), dim3(256), 0, ctx->stream, residue, seed_dev, K, D, Cm);
         HIP_TRY(ctx, hipGetLastError());
     }
     if (!R) {                   // step 1 of Sec. 3.2 inside the library: the principal axes of this stage's x'
@@ -1588,8 +1603,74 @@ int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, in
     if (pa < 0) return pa;
     hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFinishThreads), 0, ctx->stream,
                        ctx->part_a, ctx->part_b, ctx->part_chg, pa, iters_run > 0 ? ctx->nk : nullptr, K,
-                       ctx->refine_count, ctx->rec);
+                       ctx->refine_count, ctx->rec + slot);
     HIP_TRY(ctx, hipGetLastError());
+    if (iters_run_out) *iters_run_out = iters_run;
+    return HCLAE_OK;
+}
+
+// The stage of a sweep (or of hclae_anneal_stage) when the improved k-means is the ctx's cool-down: the schedule
+// of hclae_set_cooldown, ceil(iters / prefixes) Lloyd iterations on each prefix, x^r in scratch the ctx keeps.
+static int enqueue_stage_cooldown_pca(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, float *residue,
+                                      int iters, const int64_t *seed_dev, int slot, int *iters_run_out)
+{
+    int rc = pca_scratch(ctx);
+    if (rc != HCLAE_OK) return rc;
+    if (!ctx->pca_xr) {
+        hipError_t e = hipMalloc((void **)&ctx->pca_xr, sizeof(float) * (size_t)ctx->N_max * ctx->D);
+        if (e != hipSuccess) return fail(ctx, e == hipErrorOutOfMemory ? HCLAE_ENOMEM : HCLAE_EHIP, "hipMalloc (rotated data)", e);
+    }
+    int dims[64];
+    const int n_dims = dimension_schedule(ctx->D, ctx->cooldown_phases, dims);
+    const int per = iters > 0 ? (iters + n_dims - 1) / n_dims : 0;
+    return enqueue_stage_pca(ctx, m, N, C, codes, residue, nullptr, dims, n_dims, per, ctx->pca_xr, seed_dev, slot,
+                             iters_run_out);
+}
+
+int hclae_dimension_schedule(int D, int phases, int *dims, int *n_dims)
+{
+    if (D < 1 || D > HCLAE_MAX_D || phases < 1 || phases > 64 || !dims || !n_dims) return HCLAE_EINVAL;
+    *n_dims = dimension_schedule(D, phases, dims);
+    return HCLAE_OK;
+}
+
+int hclae_set_cooldown(hclae_ctx *ctx, int mode, int phases)
+{
+    if (!ctx) return HCLAE_EINVAL;
+    if (mode != HCLAE_COOLDOWN_LLOYD && mode != HCLAE_COOLDOWN_IMPROVED)
+        return fail(ctx, HCLAE_EINVAL, "hclae_set_cooldown: unknown mode");
+    if (mode == HCLAE_COOLDOWN_IMPROVED && (phases < 1 || phases > 64))
+        return fail(ctx, HCLAE_EINVAL, "hclae_set_cooldown: need 1 <= phases <= 64");
+    ctx->cooldown = mode;
+    if (mode == HCLAE_COOLDOWN_IMPROVED) ctx->cooldown_phases = phases;
+    return HCLAE_OK;
+}
+
+int hclae_anneal_stage_pca(hclae_ctx *ctx, int m, int64_t N, int D, float *C, int M, int K,
+                           uint8_t *codes, float *residue, const float *R, const int *dims, int n_dims,
+                           int iters_per_dim, float *xr, const int64_t *init_idx, hclae_stage_stats *stats)
+{
+    int rc = check_call(ctx, N, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (m < 0 || m >= M || iters_per_dim < 0 || n_dims < 1 || !dims)
+        return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: bad argument");
+    for (int i = 0; i < n_dims; ++i)
+        if (dims[i] < 1 || dims[i] > D || (i > 0 && dims[i] <= dims[i - 1]))
+            return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: dims must increase within [1, D]");
+    if (dims[n_dims - 1] != D) return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: the last prefix must be D");
+    if (init_idx)
+        for (int i = 0; i < K; ++i)
+            if (init_idx[i] < 0 || init_idx[i] >= N) return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: init_idx out of range");
+    if (N == 0) { if (stats) memset(stats, 0, sizeof(*stats)); return HCLAE_OK; }
+    if (!C || !codes || !residue || !xr || xr == residue)
+        return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: NULL or aliased pointer");
+    if (misaligned(C, residue, R, xr)) return fail(ctx, HCLAE_EINVAL, "hclae_anneal_stage_pca: float arrays must be 16-byte aligned");
+    if ((rc = pca_scratch(ctx)) != HCLAE_OK) return rc;
+    if (init_idx)
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->seed_idx, init_idx, sizeof(int64_t) * K, hipMemcpyHostToDevice, ctx->stream));
+    int iters_run = 0;
+    if ((rc = enqueue_stage_pca(ctx, m, N, C, codes, residue, R, dims, n_dims, iters_per_dim, xr,
+                                init_idx ? ctx->seed_idx : nullptr, 0, &iters_run)) != HCLAE_OK) return rc;
     if (stats) {
         if ((rc = fetch_records(ctx, 1)) != HCLAE_OK) return rc;
         fill_stats(ctx->rec_host[0], N, iters_run, stats);

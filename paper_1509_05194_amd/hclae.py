@@ -22,7 +22,7 @@ EXPORTS = (
     "hclae_heat", "hclae_cool", "hclae_assign", "hclae_update", "hclae_last_refined", "hclae_work_counters",
     "hclae_timing_enable", "hclae_timing_read", "hclae_online_begin", "hclae_online_chunk",
     "hclae_online_export", "hclae_online_import",
-    "hclae_covariance", "hclae_pca_axes", "hclae_symmetric_eigen", "hclae_rotate", "hclae_assign_prefix", "hclae_anneal_stage_pca",
+    "hclae_covariance", "hclae_pca_axes", "hclae_symmetric_eigen", "hclae_rotate", "hclae_assign_prefix", "hclae_anneal_stage_pca", "hclae_dimension_schedule", "hclae_set_cooldown",
     "hclae_reorder_by_variance", "hclae_code_stats",
     "hclae_beam_step", "hclae_encode_beam", "hclae_set_beam_width", "hclae_set_contraction", "hclae_set_pruning",
 )
@@ -94,6 +94,8 @@ def lib():
     L.hclae_assign_prefix.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, i32, vp]
     L.hclae_anneal_stage_pca.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, vp,
                                          ctypes.POINTER(StageStats)]
+    L.hclae_dimension_schedule.argtypes = [i32, i32, vp, vp]
+    L.hclae_set_cooldown.argtypes = [vp, i32, i32]
     L.hclae_reorder_by_variance.argtypes = [vp, i64, i32, vp, i32, i32, vp, vp, vp]
     L.hclae_code_stats.argtypes = [vp, vp, i64, i32, i32, vp, i32, i32, vp]
     L.hclae_beam_step.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp]
@@ -124,6 +126,16 @@ def quant_error_noalloc(residue, out, stream=None):
     rc = lib().hclae_quant_error_noalloc(_ptr(residue, "f32"), N, D, _ptr(out, "f64", (1,)), ctypes.c_void_p(stream))
     if rc != OK:
         raise HclaeError(rc, lib().hclae_last_error(None).decode())
+
+
+def dimension_schedule(D, phases=10):
+    """The prefixes d_i = ceil(D^(i/phases)) of the improved k-means (Sec. 3.2), equal values once, the last one D."""
+    dims = np.zeros(phases, np.int32)
+    n = ctypes.c_int()
+    rc = lib().hclae_dimension_schedule(D, phases, dims.ctypes.data_as(ctypes.c_void_p), ctypes.byref(n))
+    if rc != OK:
+        raise HclaeError(rc, "hclae_dimension_schedule")
+    return dims[:n.value].copy()
 
 
 def symmetric_eigen(A):
@@ -211,6 +223,10 @@ class Context:
     def set_pruning(self, on):
         """Exact pruning of the Lloyd iterations of a stage (default on; same results either way)."""
         self._chk(lib().hclae_set_pruning(self._h, 1 if on else 0))
+
+    def set_cooldown(self, improved, phases=10):
+        """The k-means that cools a dictionary in anneal_stage / sweep: plain Lloyd, or the improved one of Sec. 3.2."""
+        self._chk(lib().hclae_set_cooldown(self._h, 1 if improved else 0, phases))
 
     def set_contraction(self, mode):
         """0: fp32 MFMA; 1: split-bf16 MFMA (same results, see hclae_set_contraction)."""

@@ -103,3 +103,21 @@ def test_hard_spectra():
     A = B @ B.T / 960
     w, Vt = hclae.symmetric_eigen(A)
     _check(A, w, Vt)
+
+
+def test_dimension_schedule(oracle):
+    """Sec. 3.2: d_i = d^(i/I), I = 10, read as rounded up: 128 dimensions give 2, 3, 5, 7, 12, 19, 30, 49, 79, 128; equal
+    prefixes are merged and the last one is D.  The library's schedule must be the oracle's for every row length."""
+    np.testing.assert_array_equal(hclae.dimension_schedule(128), [2, 3, 5, 7, 12, 19, 30, 49, 79, 128])
+    np.testing.assert_array_equal(hclae.dimension_schedule(4), [2, 3, 4])
+    np.testing.assert_array_equal(hclae.dimension_schedule(1024, 10), 2 ** np.arange(1, 11))      # exact powers
+    for D in list(range(4, 200, 4)) + [512, 960, 2052, 4096]:
+        for phases in (1, 3, 10, 17):
+            got = hclae.dimension_schedule(D, phases)
+            np.testing.assert_array_equal(got, oracle.dimension_schedule(D, phases))
+            assert got[-1] == D and np.all(np.diff(got) > 0)
+    L = hclae.lib()
+    buf = np.zeros(64, np.int32)
+    assert L.hclae_dimension_schedule(128, 0, buf.ctypes.data, buf.ctypes.data) == hclae.EINVAL
+    assert L.hclae_dimension_schedule(128, 65, buf.ctypes.data, buf.ctypes.data) == hclae.EINVAL
+    assert L.hclae_dimension_schedule(0, 10, buf.ctypes.data, buf.ctypes.data) == hclae.EINVAL
