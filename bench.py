@@ -25,7 +25,8 @@ import numpy as np
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
 PEAK_BF16_MFMA_TFLOPS = 2500.0    # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0             # MI355X HBM3E peak
-CONVERGED_AFTER = 8               # sweeps before the one `converged_sweep` times
+CONVERGED_AFTER = 8                # sweeps before the one `converged_sweep` times
+MANY_SWEEPS = 20                   # annealing sweeps of the hclae_anneal figure
 
 # HBM bytes per N=1M launch of the assign kernel from two rocprofv3 --pmc runs (FETCH_SIZE 250,670.0 KiB
 # x 2.000, WRITE_SIZE 16,135.3 KiB x 1.000; factors from a 512 MB device copy in the same runs), recorded
@@ -185,6 +186,34 @@ def sweep_bench(args, torch, hclae, synth, dev, gist, extras):
                                      "note": "the sweep after %d sweeps" % CONVERGED_AFTER}
         for v in sweeps.values():
             v["unit"] = "vectors/s per stage"
+        if not gist and not args.no_pruning:
+            # ---- a run of many annealing sweeps: one hclae_anneal call (every stage starts from the distance bounds
+            # its last visit kept) against the same sweeps as separate hclae_sweep calls; the same final state
+            def many(n):
+                st.restore("after_fresh")
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                ctx.anneal(st.C, st.codes, st.r, T, n, want_err=False)
+                torch.cuda.synchronize()
+                return time.perf_counter() - t0
+            t_all, t_head = many(MANY_SWEEPS), many(MANY_SWEEPS - 4)
+            t_all = min(t_all, many(MANY_SWEEPS))
+            e_many = ctx.quant_error(st.r)
+            st.restore("after_fresh")
+            torch.cuda.synchronize()
+            each = []
+            for _ in range(MANY_SWEEPS):
+                t0 = time.perf_counter()
+                ctx.sweep(st.C, st.codes, st.r, T, want_err=False)
+                torch.cuda.synchronize()
+                each.append(time.perf_counter() - t0)
+            assert ctx.quant_error(st.r) == e_many, "hclae_anneal ended at another quantization error"
+            sweeps["anneal_call"] = {
+                "sweeps": MANY_SWEEPS, "ms_total": t_all * 1e3, "ms_total_as_sweep_calls": sum(each) * 1e3,
+                "ms_per_sweep_last_4": (t_all - t_head) * 1e3 / 4, "ms_per_sweep_last_4_as_sweep_calls": sum(each[-4:]) * 1e3 / 4,
+                "value": N * M * MANY_SWEEPS / t_all, "unit": "vectors/s per stage", "quant_error_after": e_many,
+                "note": "annealing sweeps 1..%d after the sweep from all-zero dictionaries, in one hclae_anneal call; "
+                        "bit-identical to the separate calls" % MANY_SWEEPS}
         out["sweeps"] = sweeps
 
         # ---- where the time of the headline step goes: every kernel class bracketed by events, one more step

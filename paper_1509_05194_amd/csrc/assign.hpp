@@ -69,15 +69,26 @@ struct MovedArgs {
 // img (or nullptr): a copy of the dictionary in the LDS order of k_assign_resident (see stage_codebook), S = k-steps
 // of a row; written here in full, zero beyond K and D, and kept up to date by k_merge, so that the assignments
 // of a stage fill their LDS with one contiguous copy instead of a gather of 16-byte pieces.
+// keep_absmax 2: max |x'| was left by the row pass that wrote x', spread over amax_parts[0..64) (block_absmax): the
+// largest word becomes refine_count[1] and the words are cleared for the next such pass.
 __global__ __launch_bounds__(256) void k_codeword_norms(
     const float *__restrict__ Cm, int K, int D, int ld, int kpad, float *__restrict__ hneg,
-    unsigned *__restrict__ refine_count, int keep_absmax, float *__restrict__ img, int S)
+    unsigned *__restrict__ refine_count, int keep_absmax, float *__restrict__ img, int S,
+    unsigned *__restrict__ amax_parts = nullptr)
 {
     const int lane = lane_id();
     const int k = blockIdx.x * (256 / kWave) + (threadIdx.x >> 6);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         refine_count[0] = 0u;                      // re-check entries
         if (!keep_absmax) refine_count[1] = 0u;    // bits of max |x'|
+        if (keep_absmax == 2) {
+            unsigned mx = 0u;
+            for (int i = 0; i < 64; ++i) {
+                mx = max(mx, amax_parts[i]);
+                amax_parts[i] = 0u;
+            }
+            refine_count[1] = mx;
+        }
     }
     if (k >= kpad) return;
     if (img)
@@ -721,6 +732,105 @@ __global__ __launch_bounds__(kBoundThreads) void k_bounds_step(
     if (threadIdx.x == 0 && nk) base = atomicAdd(count, nk);
     __syncthreads();
     for (unsigned i = threadIdx.x; i < nk; i += kBoundThreads) list[base + i] = kept[i];
+}
+
+// ---- Distance bounds carried from one sweep to the next (several sweeps in one call, plain Lloyd cool-down) ----
+// When a sweep comes back to stage m, C_m and column m of the codes are as the stage's last visit left them
+// (Sec. 3.1: a stage changes its own dictionary and code only); x' alone has moved, in exact arithmetic by
+//   x'_new - x'_old = - sum over the stages j visited in between of d_j,   d_j = c_j,new(i_j,new) - c_j,old(i_j,old),
+// the change of stage j's part of the reconstruction.  The bounds the last visit ended with therefore still hold
+// once the upper one has grown and the lower one has shrunk by delta >= ||x'_new - x'_old||, and a vector they still
+// settle keeps its code without being assigned again.  delta is taken per vector as the sum of ||d_j|| (triangle
+// inequality), read from a K x K table per stage, plus a bound on the fp32 roundings of the passes in between:
+// 2M results of magnitude <= 2A per coordinate (A = largest |x'| or |codeword| coordinate seen), each off by at
+// most 2^-24 of itself, i.e. at most 3M 2^-24 sqrt(D) A in norm; (8M + 16) 2^-24 sqrt(D) A is used.
+
+// T[a][b] = ||C_now[b] - C_entry[a]||, rounded up: how far the reconstruction part of a vector moved whose code went
+// from a (dictionary as the stage found it) to b (as it leaves it).  One block per a; dynamic LDS: D floats.
+__global__ __launch_bounds__(256) void k_pair_table(
+    const float *__restrict__ Centry, const float *__restrict__ Cm, int K, int D, float *__restrict__ T)
+{
+    extern __shared__ float4 smem4[];
+    const int a = blockIdx.x;
+    const int d4 = D >> 2;
+    for (int d = threadIdx.x; d < d4; d += 256) smem4[d] = reinterpret_cast<const float4 *>(Centry + (size_t)a * D)[d];
+    __syncthreads();
+    // a thread per b: its row of the dictionary against the row in LDS (every lane reads the same LDS address)
+    for (int b = threadIdx.x; b < K; b += 256) {
+        const float4 *cb = reinterpret_cast<const float4 *>(Cm + (size_t)b * D);
+        double s0 = 0.0, s1 = 0.0;
+#pragma unroll 4
+        for (int d = 0; d < d4; ++d) {
+            const float4 x = cb[d], y = smem4[d];
+            const double t0 = (double)x.x - (double)y.x, t1 = (double)x.y - (double)y.y;
+            const double t2 = (double)x.z - (double)y.z, t3 = (double)x.w - (double)y.w;
+            s0 += t0 * t0 + t2 * t2;
+            s1 += t1 * t1 + t3 * t3;
+        }
+        T[(size_t)a * K + b] = (float)(sqrt(s0 + s1) * 1.000001);
+    }
+}
+
+// End of stage m: path[n] += T[code at entry][code now]; snap[n] = path[n] (the stage's mark on the running path
+// length: when it is visited again, path - snap is the sum of ||d_j|| over the stages in between).  Also folds the
+// stage's max |x'| (refine_count[1]) into the running maximum.
+__global__ __launch_bounds__(256) void k_path_step(
+    const uint8_t *__restrict__ entry, const uint8_t *__restrict__ codes, int64_t N, int M, int m,
+    const float *__restrict__ T, int K, double *__restrict__ path, double *__restrict__ snap,
+    unsigned *__restrict__ refine_count, unsigned *__restrict__ amax_run)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const unsigned a = refine_count[1];
+        if (a > *amax_run) *amax_run = a;
+    }
+    for (int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x; n < N; n += (int64_t)gridDim.x * 256) {
+        const double s = path[n] + (double)T[(size_t)entry[n] * K + codes[n * M + m]];
+        path[n] = s;
+        snap[n] = s;
+    }
+}
+
+// Entry of a stage whose bounds were kept: widen them by delta and list the vectors they no longer settle
+// (*count must be zero on entry; order is free), as k_bounds_step does after a centroid update.
+__global__ __launch_bounds__(kBoundThreads) void k_bounds_carry(
+    const double *__restrict__ path, const double *__restrict__ snap, int64_t N, double slack_unit,
+    const unsigned *__restrict__ amax_run, const unsigned *__restrict__ amax_now,
+    float *__restrict__ bu, float *__restrict__ bl, uint32_t *__restrict__ list, unsigned *__restrict__ count)
+{
+    __shared__ uint32_t kept[kBoundSpan];
+    __shared__ unsigned nkept, base;
+    if (threadIdx.x == 0) nkept = 0u;
+    __syncthreads();
+    const unsigned abits = max(*amax_run, *amax_now);
+    const double slack = slack_unit * (double)__uint_as_float(abits);
+    const int64_t n0 = (int64_t)blockIdx.x * kBoundSpan;
+    constexpr int U = kBoundSpan / kBoundThreads;
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+        const int64_t n = n0 + j * kBoundThreads + threadIdx.x;
+        if (n < N) {
+            const double delta = (path[n] - snap[n]) * (1.0 + 1e-9) + slack;
+            const float un = (float)((double)bu[n] + delta) * 1.000001f;    // rounded up
+            const float ln = (float)((double)bl[n] - delta) * 0.999999f;    // rounded down while positive
+            if (un < ln) {
+                bu[n] = un;
+                bl[n] = ln;
+            } else {
+                kept[atomicAdd(&nkept, 1u)] = (uint32_t)n;                  // its bounds stay; the assignment renews them
+            }
+        }
+    }
+    __syncthreads();
+    const unsigned nk = nkept;
+    if (threadIdx.x == 0 && nk) base = atomicAdd(count, nk);
+    __syncthreads();
+    for (unsigned i = threadIdx.x; i < nk; i += kBoundThreads) list[base + i] = kept[i];
+}
+
+__global__ void k_zero_words(unsigned *__restrict__ p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
 }
 
 constexpr int kMovedSpan = 1024;

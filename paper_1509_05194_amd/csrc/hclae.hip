@@ -100,6 +100,14 @@ struct hclae_ctx {
     float *bnd_u, *bnd_l;    // [N_max]
     float *drift;            // [K]
     uint32_t *active;        // [N_max]: the vectors k_bounds_step lists for the next assignment
+    float *cur_u, *cur_l;    // the bounds of the running stage: bnd_u / bnd_l, or the stage's own rows of carry_u / carry_l
+    // bounds carried from one sweep to the next (hclae_anneal; allocated on first use, see k_bounds_carry)
+    float *carry_u, *carry_l;    // [M][N_max] bounds each stage ended its last visit with
+    double *carry_path;          // [N_max] running sum of ||d_j||
+    double *carry_snap;          // [M][N_max] its value when stage m was last left
+    float *carry_Centry;         // [K][D] dictionary of the running stage as the stage found it
+    float *carry_T;              // [K][K] pair table of the running stage
+    unsigned *carry_amax;        // bits of the largest |x'| or |codeword| coordinate of the call so far
     unsigned long long *work; // [4] work counters: assignments, vectors recomputed, vectors re-checked in fp64
     int64_t *seed_idx;       // [M][K] seed rows of a sweep from all-zero dictionaries (a single stage uses row 0)
     double *part_a, *part_b; // [nparts]
@@ -244,9 +252,10 @@ RowGeom row_geom(int D)
 
 // ---- launches (all on ctx->stream) ------------------------------------------------------
 
+// amax (heat only): the pass also publishes max |x'| in refine_count[1] (see k_row_pass).
 template <int SIGN, bool STATS>
 int launch_heat_cool(hclae_ctx *ctx, int m, int64_t N, const float *C, const uint8_t *codes, float *r,
-                     double *part_err)
+                     double *part_err, bool amax = false)
 {
     const RowGeom g = row_geom(ctx->D);
     const int rows = kStreamThreads >> g.lcw;
@@ -256,17 +265,21 @@ int launch_heat_cool(hclae_ctx *ctx, int m, int64_t N, const float *C, const uin
     Timed t_(ctx, SIGN > 0 ? HCLAE_T_HEAT : HCLAE_T_COOL);
     // the row length of the SIFT-shaped configurations has a kernel of its own (addresses and geometry constant:
     // 179 us instead of 185 us for the stage boundary at N = 1M, D = 128); long rows take k_row_pass_wide
+    constexpr bool kCanAmax = SIGN > 0 && STATS;
+    if (amax && !kCanAmax) return fail(ctx, HCLAE_EINVAL, "row pass: max |x'| is a by-product of the heat pass only");
     if (ctx->D >= kWideMinD) {
-        hipLaunchKernelGGL((k_row_pass_wide<SIGN, STATS>), dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
+        auto kern = (amax && kCanAmax) ? &k_row_pass_wide<SIGN, STATS, kCanAmax> : &k_row_pass_wide<SIGN, STATS, false>;
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
                            r, codes, Cm, (const float *)nullptr, N, ctx->D, ctx->M, m, 0, ctx->old_codes, part_err,
-                           ctx->part_chg);
+                           ctx->part_chg, amax ? ctx->carry_amax + kAmaxSlots : (unsigned *)nullptr);
         HIP_TRY(ctx, hipGetLastError());
         return blocks;
     }
-    auto kern = ctx->D == 128 ? &k_row_pass<SIGN, STATS, 128> : &k_row_pass<SIGN, STATS, 0>;
+    auto kern = (amax && kCanAmax) ? (ctx->D == 128 ? &k_row_pass<SIGN, STATS, 128, kCanAmax> : &k_row_pass<SIGN, STATS, 0, kCanAmax>)
+                                   : (ctx->D == 128 ? &k_row_pass<SIGN, STATS, 128, false> : &k_row_pass<SIGN, STATS, 0, false>);
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(kStreamThreads), 0, ctx->stream,
                        r, codes, Cm, (const float *)nullptr, N, ctx->D, ctx->M, m, 0, g, ctx->old_codes, part_err,
-                       ctx->part_chg);
+                       ctx->part_chg, amax ? ctx->carry_amax + kAmaxSlots : (unsigned *)nullptr);
     HIP_TRY(ctx, hipGetLastError());
     return blocks;
 }
@@ -274,15 +287,18 @@ int launch_heat_cool(hclae_ctx *ctx, int m, int64_t N, const float *C, const uin
 // dact: leading coordinates that count (<= ld); ld: row stride of Cm.
 // image: also write the dictionary in the LDS order of the resident assign kernel (the centroid updates that follow
 // keep it current; launch_assign then takes it when told so).
-int launch_norms(hclae_ctx *ctx, const float *Cm, int dact = 0, int ld = 0, bool keep_absmax = false, bool image = false)
+// keep_absmax: 0 the counter of max |x'| is reset for the assignment that follows; 1 it stays; 2 it is taken from the
+// words the row pass that wrote x' left in carry_amax[64..128) (hclae_anneal).
+int launch_norms(hclae_ctx *ctx, const float *Cm, int dact = 0, int ld = 0, int keep_absmax = 0, bool image = false)
 {
     if (dact <= 0) dact = ctx->D;
     if (ld <= 0) ld = ctx->D;
     const int kpad = 32 * ctx->kb;
     Timed t_(ctx, HCLAE_T_NORMS);
     hipLaunchKernelGGL(k_codeword_norms, dim3((kpad + 3) / 4), dim3(256), 0, ctx->stream,
-                       Cm, ctx->K, dact, ld, kpad, ctx->hneg, ctx->refine_count, keep_absmax ? 1 : 0,
-                       image && ctx->resident ? ctx->lds_image : (float *)nullptr, 8 * ctx->NC);
+                       Cm, ctx->K, dact, ld, kpad, ctx->hneg, ctx->refine_count, keep_absmax,
+                       image && ctx->resident ? ctx->lds_image : (float *)nullptr, 8 * ctx->NC,
+                       keep_absmax == 2 ? ctx->carry_amax + kAmaxSlots : (unsigned *)nullptr);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
@@ -294,14 +310,14 @@ int launch_assign_kb(hclae_ctx *ctx, int m, int64_t N, const float *xp, const fl
                      int prune, bool use_image)
 {
     PruneArgs pa;
-    pa.bu = ctx->bnd_u; pa.bl = ctx->bnd_l;
+    pa.bu = ctx->cur_u; pa.bl = ctx->cur_l;
     pa.active = ctx->active; pa.active_count = ctx->moved_count + 3;
     // prune 3 = 2, and the re-check kernel lists the vectors that changed cluster (moved_count[0] is zero: the
     // merge of the previous centroid update of this stage reset it)
     MovedArgs mv = {};
     if (prune == 3) {
         mv.prev = ctx->upd_col; mv.list = ctx->moved_list; mv.count = ctx->moved_count;
-        mv.cand = ctx->active; mv.cand_count = ctx->moved_count + 3; mv.bl = ctx->bnd_l;
+        mv.cand = ctx->active; mv.cand_count = ctx->moved_count + 3; mv.bl = ctx->cur_l;
         prune = 2;
     }
     const int NC = (dact + kChunkD - 1) / kChunkD;
@@ -470,7 +486,7 @@ int launch_bounds_step(hclae_ctx *ctx, int m, int64_t N, const uint8_t *codes, c
     }
     hipLaunchKernelGGL(k_bounds_step, dim3((unsigned)((N + kBoundSpan - 1) / kBoundSpan)), dim3(kBoundThreads),
                        (size_t)kVolatile * ctx->D * sizeof(float), ctx->stream,
-                       codes, N, ctx->M, m, ctx->drift, ctx->K, ctx->bnd_u, ctx->bnd_l,
+                       codes, N, ctx->M, m, ctx->drift, ctx->K, ctx->cur_u, ctx->cur_l,
                        ctx->active, ctx->moved_count + 3, xp, ctx->D, Cm);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
@@ -498,7 +514,8 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
         ctx->attr_done |= attr_set;
     }
     if (!have_absmax) {
-        HIP_TRY(ctx, hipMemsetAsync(ctx->refine_count + 1, 0, sizeof(unsigned), ctx->stream));
+        // a fill kernel, not a memset: the call may be recorded into a HIP graph
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, ctx->stream, ctx->refine_count + 1, 1);
         const int64_t n4 = N * (D / 4);
         hipLaunchKernelGGL(k_absmax, dim3(stream_blocks(ctx, n4, 256 * 4)), dim3(256), 0, ctx->stream,
                            reinterpret_cast<const float4 *>(xp), n4, ctx->refine_count + 1);
@@ -573,21 +590,45 @@ int launch_sqnorm(hclae_ctx *ctx, const float *r, int64_t N, double *part)
 // heated: residue already holds x' of this stage and ctx->part_a its entry error (the previous
 // stage ended with a fused transition).  next: >= 0 ends the stage with the fused transition into
 // that stage instead of the plain new-residue pass.
+// carry (several sweeps in one call; needs pruning, iters > 0, no seeding; the caller has allocated the carry arrays):
+// 1 = the stage keeps its final bounds in its own rows of carry_u / carry_l and marks the path length; 2 = it also
+// starts from the bounds its last visit kept (k_bounds_carry) instead of an assignment over all vectors.  With
+// either, max |x'| comes from the row pass that wrote x' (the first assignment may not read every row).
 int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, float *residue, int iters,
-                  const int64_t *seed_dev, int slot, bool heated = false, int next = -1)
+                  const int64_t *seed_dev, int slot, bool heated = false, int next = -1, int carry = 0)
 {
     const int D = ctx->D, K = ctx->K;
     float *Cm = C + (size_t)m * K * D;
     int rc;
+    if (carry && (!ctx->pruning || iters <= 0 || seed_dev || !ctx->carry_u))
+        return fail(ctx, HCLAE_ESTATE, "stage: carried bounds need pruning, iters > 0 and no seeding");
+    ctx->cur_u = carry ? ctx->carry_u + (size_t)m * ctx->N_max : ctx->bnd_u;
+    ctx->cur_l = carry ? ctx->carry_l + (size_t)m * ctx->N_max : ctx->bnd_l;
     if (!heated) {
-        const int pb = launch_heat_cool<+1, true>(ctx, m, N, C, codes, residue, ctx->part_a);
+        const int pb = launch_heat_cool<+1, true>(ctx, m, N, C, codes, residue, ctx->part_a, carry != 0);
         if (pb < 0) return pb;
     }
     if (seed_dev) {
         hipLaunchKernelGGL(k_seed, dim3(K), dim3(256), 0, ctx->stream, residue, seed_dev, K, D, Cm);
         HIP_TRY(ctx, hipGetLastError());
     }
-    if ((rc = launch_norms(ctx, Cm, 0, 0, false, true)) != HCLAE_OK) return rc;
+    if ((rc = launch_norms(ctx, Cm, 0, 0, carry ? 2 : 0, true)) != HCLAE_OK) return rc;
+    if (carry) {
+        const int64_t c4 = (int64_t)K * D / 4;
+        hipLaunchKernelGGL(k_copy, dim3(stream_blocks(ctx, c4, kFlatThreads * 4)), dim3(kFlatThreads), 0, ctx->stream,
+                           reinterpret_cast<floatx4 *>(ctx->carry_Centry), reinterpret_cast<const floatx4 *>(Cm), c4);
+        HIP_TRY(ctx, hipGetLastError());
+    }
+    if (carry == 2) {
+        Timed t_(ctx, HCLAE_T_BOUNDS);
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, ctx->stream, ctx->moved_count + 3, 1);
+        // (8M + 16) 2^-24 sqrt(D), times the largest coordinate seen: the roundings of the passes since the last visit
+        const double slack_unit = (8.0 * ctx->M + 16.0) * 5.9604644775390625e-8 * sqrt((double)D);
+        hipLaunchKernelGGL(k_bounds_carry, dim3((unsigned)((N + kBoundSpan - 1) / kBoundSpan)), dim3(kBoundThreads), 0,
+                           ctx->stream, ctx->carry_path, ctx->carry_snap + (size_t)m * ctx->N_max, N, slack_unit,
+                           ctx->carry_amax, ctx->refine_count + 1, ctx->cur_u, ctx->cur_l, ctx->active, ctx->moved_count + 3);
+        HIP_TRY(ctx, hipGetLastError());
+    }
     // x' stays as it is until the stage ends: the first centroid update sums all vectors and keeps the integer
     // totals, the others add only the vectors that changed cluster (exact, so the dictionaries are the same)
     // With pruning the first assignment stores distance bounds for every vector; after each centroid update
@@ -596,7 +637,7 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
     const bool prune = ctx->pruning && iters > 0;
     for (int t = 0; t < iters; ++t) {
         if (prune && t > 0 && (rc = launch_bounds_step(ctx, m, N, codes, residue, Cm)) != HCLAE_OK) return rc;
-        if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? (t == 0 ? 1 : 3) : 0, true)) != HCLAE_OK) return rc;
+        if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? (t == 0 ? (carry == 2 ? 2 : 1) : 3) : 0, true)) != HCLAE_OK) return rc;
         rc = (t == 0 || !ctx->pruning)
                  ? launch_update(ctx, m, N, residue, Cm, codes, nullptr, true, false, 0, ctx->pruning && (iters > 1 || prune))
                  : launch_update_moved(ctx, m, N, residue, Cm);
@@ -604,6 +645,15 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
     }
     if (prune && (rc = launch_bounds_step(ctx, m, N, codes, residue, Cm)) != HCLAE_OK) return rc;
     if ((rc = launch_assign(ctx, m, N, residue, Cm, codes, 0, 0, prune ? 2 : 0, true)) != HCLAE_OK) return rc;
+    if (carry) {
+        // how far this visit moved every vector's part of the reconstruction (old_codes still holds the column as the
+        // stage found it: the row pass below is the one that replaces it)
+        hipLaunchKernelGGL(k_pair_table, dim3(K), dim3(256), sizeof(float) * D, ctx->stream, ctx->carry_Centry, Cm, K, D, ctx->carry_T);
+        hipLaunchKernelGGL(k_path_step, dim3(stream_blocks(ctx, N, 256 * 4)), dim3(256), 0, ctx->stream,
+                           ctx->old_codes, codes, N, ctx->M, m, ctx->carry_T, K, ctx->carry_path,
+                           ctx->carry_snap + (size_t)m * ctx->N_max, ctx->refine_count, ctx->carry_amax);
+        HIP_TRY(ctx, hipGetLastError());
+    }
     int pa;
     if (next < 0) {
         pa = launch_heat_cool<-1, true>(ctx, m, N, C, codes, residue, ctx->part_b);
@@ -613,17 +663,23 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
         pa = heat_cool_blocks(N, D, ctx->cus);
         Timed t_(ctx, HCLAE_T_TRANSITION);
         if (D >= kWideMinD) {
-            hipLaunchKernelGGL((k_row_pass_wide<0, true>), dim3(pa), dim3(kStreamThreads), 0, ctx->stream,
+            auto kern = carry ? &k_row_pass_wide<0, true, true> : &k_row_pass_wide<0, true, false>;
+            hipLaunchKernelGGL(kern, dim3(pa), dim3(kStreamThreads), 0, ctx->stream,
                                residue, codes, Cm, C + (size_t)next * K * D, N, D, ctx->M, m, next,
-                               ctx->old_codes, ctx->part_b, ctx->part_chg);
+                               ctx->old_codes, ctx->part_b, ctx->part_chg,
+                               carry ? ctx->carry_amax + kAmaxSlots : (unsigned *)nullptr);
         } else {
-            auto kern = D == 128 ? &k_row_pass<0, true, 128> : &k_row_pass<0, true, 0>;
+            auto kern = carry ? (D == 128 ? &k_row_pass<0, true, 128, true> : &k_row_pass<0, true, 0, true>)
+                              : (D == 128 ? &k_row_pass<0, true, 128, false> : &k_row_pass<0, true, 0, false>);
             hipLaunchKernelGGL(kern, dim3(pa), dim3(kStreamThreads), 0, ctx->stream,
                                residue, codes, Cm, C + (size_t)next * K * D, N, D, ctx->M, m, next, g,
-                               ctx->old_codes, ctx->part_b, ctx->part_chg);
+                               ctx->old_codes, ctx->part_b, ctx->part_chg,
+                               carry ? ctx->carry_amax + kAmaxSlots : (unsigned *)nullptr);
         }
         HIP_TRY(ctx, hipGetLastError());
     }
+    ctx->cur_u = ctx->bnd_u;
+    ctx->cur_l = ctx->bnd_l;
     hipLaunchKernelGGL(k_finish_stage, dim3(1), dim3(kFinishThreads), 0, ctx->stream,
                        ctx->part_a, ctx->part_b, ctx->part_chg, pa, iters > 0 ? ctx->nk : nullptr, K,
                        ctx->refine_count, ctx->rec + slot);
@@ -776,6 +832,8 @@ int hclae_create(hclae_ctx **out, int64_t N_max, int D, int M, int K, void *hip_
         hclae_destroy(ctx);
         return rc;
     }
+    ctx->cur_u = ctx->bnd_u;
+    ctx->cur_l = ctx->bnd_l;
     snprintf(ctx->err, sizeof(ctx->err), "ok");
     *out = ctx;
     return HCLAE_OK;
@@ -789,6 +847,7 @@ int hclae_destroy(hclae_ctx *ctx)
                    ctx->run_sum, ctx->run_cnt, ctx->n0_dev, ctx->pca_rt, ctx->pca_crot, ctx->pca_colpart,
                    ctx->pca_grampart, ctx->pca_mean, ctx->pca_mean32, ctx->pca_cov, ctx->pca_R, ctx->pca_xr,
                    ctx->stats_buf, ctx->order_var, ctx->order_idx, ctx->order_tmp,
+                   ctx->carry_u, ctx->carry_l, ctx->carry_path, ctx->carry_snap, ctx->carry_Centry, ctx->carry_T, ctx->carry_amax,
                    ctx->beam_rows[0], ctx->beam_rows[1], ctx->beam_err[0], ctx->beam_err[1],
                    ctx->beam_pre[0], ctx->beam_pre[1], ctx->beam_mask};
     for (void *p : dev)
@@ -862,7 +921,10 @@ int hclae_update(hclae_ctx *ctx, int m, int64_t N, int D, const float *xp, float
     if (N > 0 && (!C || !codes || !xp)) return fail(ctx, HCLAE_EINVAL, "hclae_update: NULL pointer");
     if (misaligned(C, xp)) return fail(ctx, HCLAE_EINVAL, "hclae_update: float arrays must be 16-byte aligned");
     if (N == 0) {
-        if (counts) HIP_TRY(ctx, hipMemsetAsync(counts, 0, sizeof(int32_t) * K, ctx->stream));
+        if (counts) {
+            hipLaunchKernelGGL(k_zero_words, dim3((K + 255) / 256), dim3(256), 0, ctx->stream, reinterpret_cast<unsigned *>(counts), K);
+            HIP_TRY(ctx, hipGetLastError());
+        }
         return HCLAE_OK;
     }
     return launch_update(ctx, m, N, xp, C + (size_t)m * K * D, codes, counts, false);
@@ -1051,6 +1113,79 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
     } else if (init_idx) {
         // the seed indices were read from caller memory by an asynchronous copy
         HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    }
+    return HCLAE_OK;
+}
+
+// Arrays of the bounds carried between sweeps (hclae_anneal), allocated once per ctx.
+static int carry_scratch(hclae_ctx *ctx)
+{
+    if (ctx->carry_u) return HCLAE_OK;
+    const size_t n = (size_t)ctx->N_max, M = (size_t)ctx->M, K = (size_t)ctx->K, D = (size_t)ctx->D;
+    struct { void **p; size_t bytes; } allocs[] = {
+        {(void **)&ctx->carry_l, sizeof(float) * M * n},
+        {(void **)&ctx->carry_path, sizeof(double) * n},
+        {(void **)&ctx->carry_snap, sizeof(double) * M * n},
+        {(void **)&ctx->carry_Centry, sizeof(float) * K * D},
+        {(void **)&ctx->carry_T, sizeof(float) * K * K},
+        {(void **)&ctx->carry_amax, sizeof(unsigned) * 2 * kAmaxSlots},    // [0] running maximum, [64..128) words of the row passes
+        {(void **)&ctx->carry_u, sizeof(float) * M * n},        // last: its presence says that all are there
+    };
+    for (auto &a : allocs) {
+        hipError_t e = hipMalloc(a.p, a.bytes);
+        if (e != hipSuccess) {
+            for (auto &b : allocs) {
+                if (*b.p) (void)hipFree(*b.p);
+                *b.p = nullptr;
+            }
+            return fail(ctx, e == hipErrorOutOfMemory ? HCLAE_ENOMEM : HCLAE_EHIP, "hipMalloc (carried bounds)", e);
+        }
+    }
+    return HCLAE_OK;
+}
+
+int hclae_anneal(hclae_ctx *ctx, int64_t N, int D, float *C, int M, int K, uint8_t *codes, float *residue,
+                 int iters, int n_sweeps, double *err_per_stage)
+{
+    int rc = check_call(ctx, N, D, M, K);
+    if (rc != HCLAE_OK) return rc;
+    if (iters < 0 || n_sweeps < 0 || (N > 0 && (!C || !codes || !residue)))
+        return fail(ctx, HCLAE_EINVAL, "hclae_anneal: bad argument");
+    if (misaligned(C, residue)) return fail(ctx, HCLAE_EINVAL, "hclae_anneal: float arrays must be 16-byte aligned");
+    if (N == 0 || n_sweeps == 0) {
+        if (err_per_stage) for (int i = 0; i < n_sweeps * M; ++i) err_per_stage[i] = 0.0;
+        return HCLAE_OK;
+    }
+    const bool lloyd = ctx->cooldown == HCLAE_COOLDOWN_LLOYD;
+    const bool carry = lloyd && ctx->pruning && iters > 0 && n_sweeps > 1;
+    if (carry) {
+        if ((rc = carry_scratch(ctx)) != HCLAE_OK) return rc;
+        // path lengths start at zero; the running maximum starts at the largest dictionary coordinate (a codeword
+        // nobody is assigned to keeps a value the data of this call need not reach)
+        hipLaunchKernelGGL(k_zero_u64, dim3(stream_blocks(ctx, N, 256)), dim3(256), 0, ctx->stream,
+                           reinterpret_cast<unsigned long long *>(ctx->carry_path), (size_t)N);
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(2 * kAmaxSlots), 0, ctx->stream, ctx->carry_amax, 2 * kAmaxSlots);
+        const int64_t c4 = (int64_t)M * K * D / 4;
+        hipLaunchKernelGGL(k_absmax, dim3(stream_blocks(ctx, c4, 256 * 4)), dim3(256), 0, ctx->stream,
+                           reinterpret_cast<const float4 *>(C), c4, ctx->carry_amax);
+        HIP_TRY(ctx, hipGetLastError());
+    }
+    for (int s = 0; s < n_sweeps; ++s) {
+        for (int m = 0; m < M; ++m) {
+            if (lloyd) {
+                // every stage but the very last ends in the fused pass into the next one, across sweeps too
+                const bool last = s == n_sweeps - 1 && m == M - 1;
+                rc = enqueue_stage(ctx, m, N, C, codes, residue, iters, nullptr, m, !(s == 0 && m == 0),
+                                   last ? -1 : (m + 1) % M, carry ? (s == 0 ? 1 : 2) : 0);
+            } else {
+                rc = enqueue_stage_cooldown_pca(ctx, m, N, C, codes, residue, iters, nullptr, m, nullptr);
+            }
+            if (rc != HCLAE_OK) return rc;
+        }
+        if (err_per_stage) {
+            if ((rc = fetch_records(ctx, M)) != HCLAE_OK) return rc;
+            for (int m = 0; m < M; ++m) err_per_stage[(size_t)s * M + m] = ctx->rec_host[m].sum_after / (double)N;
+        }
     }
     return HCLAE_OK;
 }

@@ -20,6 +20,24 @@ struct RowGeom {
     int d4;         // D / 4
 };
 
+// max |x'| of a block merged into one of kAmaxSlots words (bits of a non-negative float: integer max is float max):
+// one atomic per block, spread over the words so that thousands of blocks do not queue on one address; the reader
+// (k_codeword_norms) takes the largest word and clears them.  scratch: kStreamThreads / kWave floats of LDS.
+constexpr int kAmaxSlots = 64;
+__device__ __forceinline__ void block_absmax(float amax, float *scratch, unsigned *__restrict__ slots)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, kWave));
+    __syncthreads();                                                // the scratch may still be read by a block_sum
+    if (lane_id() == 0) scratch[threadIdx.x >> 6] = amax;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float mx = scratch[0];
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) mx = fmaxf(mx, scratch[w]);
+        atomicMax(slots + (blockIdx.x & (kAmaxSlots - 1)), __float_as_uint(mx));
+    }
+}
+
 // The in-place row passes of a stage (Sec. 3.1), one kernel body:
 //   MODE +1  heat       r_n += C_m[i_m(n)]; by-products: column m of the codes saved (old_codes), sum ||e_x||^2 of the input
 //   MODE -1  new residue r_n -= C_m[i_m(n)]; by-products: sum ||e_x||^2 of the output, codes that differ from old_codes
@@ -38,11 +56,14 @@ struct RowGeom {
 // a sweep of shapes.  All three modes share the geometry, so a thread adds the same squares in the same order in
 // the stage boundary as in the separate new-residue pass: the error sums are the same bits.
 // DT: the row length as a compile-time constant (with the geometry row_geom gives it), or 0: taken from D and g.
-template <int MODE, bool STATS, int DT = 0>
+// AMAX (MODE +1 and 0): max |x'| over everything written is merged into absmax_slot[0..kAmaxSlots) (block_absmax), for
+// a stage whose first assignment does not read every row and so cannot provide it.
+template <int MODE, bool STATS, int DT = 0, bool AMAX = false>
 __global__ __launch_bounds__(kStreamThreads) void k_row_pass(
     float *__restrict__ r, const uint8_t *__restrict__ codes, const float *__restrict__ Cm, const float *__restrict__ Cj,
     int64_t N, int D_rt, int M, int m, int j_stage, RowGeom g_rt,
-    uint8_t *__restrict__ old_codes, double *__restrict__ part_err, long long *__restrict__ part_chg)
+    uint8_t *__restrict__ old_codes, double *__restrict__ part_err, long long *__restrict__ part_chg,
+    unsigned *__restrict__ absmax_slot = nullptr)
 {
     __shared__ double red[kStreamThreads / kWave];
     constexpr int U = kStreamUnroll;
@@ -60,6 +81,7 @@ __global__ __launch_bounds__(kStreamThreads) void k_row_pass(
     const int64_t stride = (int64_t)gridDim.x * rows * U;
     double err = 0.0;
     long long chg = 0;
+    float amax = 0.f;
 
     // rows n0 + u * rows of a group; the loads of a step take rows clamped into range (never used beyond N)
     auto load_codes = [&](int64_t n0, int (&a)[U], int (&b)[U]) {
@@ -135,6 +157,10 @@ __global__ __launch_bounds__(kStreamThreads) void k_row_pass(
                 if (STATS && MODE <= 0)
                     err += (double)w.x * w.x + (double)w.y * w.y + (double)w.z * w.z + (double)w.w * w.w;
                 if (MODE == 0) w = w + b[u];
+                if (AMAX && MODE >= 0) {
+                    amax = fmaxf(fmaxf(amax, fabsf(w.x)), fabsf(w.y));
+                    amax = fmaxf(fmaxf(amax, fabsf(w.z)), fabsf(w.w));
+                }
                 __builtin_nontemporal_store(w, reinterpret_cast<floatx4 *>(r + n * D) + c4);
             }
         }
@@ -156,6 +182,7 @@ __global__ __launch_bounds__(kStreamThreads) void k_row_pass(
             if (threadIdx.x == 0) part_chg[blockIdx.x] = (long long)c;
         }
     }
+    if (AMAX && MODE >= 0) block_absmax(amax, reinterpret_cast<float *>(red), absmax_slot);
 }
 
 // The same passes for long rows (D >= kWideMinD): a wave owns whole rows.  Lane l takes float4 columns l, l + 64,
@@ -166,11 +193,12 @@ __global__ __launch_bounds__(kStreamThreads) void k_row_pass(
 // sums differ in their order of additions, which is the same in all three modes here too.
 constexpr int kWideMinD = 768;
 constexpr int kWideRows = 2;
-template <int MODE, bool STATS>
+template <int MODE, bool STATS, bool AMAX = false>
 __global__ __launch_bounds__(kStreamThreads) void k_row_pass_wide(
     float *__restrict__ r, const uint8_t *__restrict__ codes, const float *__restrict__ Cm, const float *__restrict__ Cj,
     int64_t N, int D, int M, int m, int j_stage,
-    uint8_t *__restrict__ old_codes, double *__restrict__ part_err, long long *__restrict__ part_chg)
+    uint8_t *__restrict__ old_codes, double *__restrict__ part_err, long long *__restrict__ part_chg,
+    unsigned *__restrict__ absmax_slot = nullptr)
 {
     __shared__ double red[kStreamThreads / kWave];
     constexpr int U = 4, R = kWideRows;
@@ -180,6 +208,7 @@ __global__ __launch_bounds__(kStreamThreads) void k_row_pass_wide(
     const int64_t stride = (int64_t)gridDim.x * (kStreamThreads / kWave) * R;
     double err = 0.0;
     long long chg = 0;
+    float amax = 0.f;
 
     auto load_codes = [&](int64_t n0, int (&a)[R], int (&b)[R]) {
 #pragma unroll
@@ -251,6 +280,10 @@ __global__ __launch_bounds__(kStreamThreads) void k_row_pass_wide(
                         if (STATS && MODE <= 0)
                             err += (double)w.x * w.x + (double)w.y * w.y + (double)w.z * w.z + (double)w.w * w.w;
                         if (MODE == 0) w = w + b[u];
+                        if (AMAX && MODE >= 0) {
+                            amax = fmaxf(fmaxf(amax, fabsf(w.x)), fabsf(w.y));
+                            amax = fmaxf(fmaxf(amax, fabsf(w.z)), fabsf(w.w));
+                        }
                         __builtin_nontemporal_store(w, reinterpret_cast<floatx4 *>(r + n * D) + c);
                     }
                 }
@@ -275,6 +308,7 @@ __global__ __launch_bounds__(kStreamThreads) void k_row_pass_wide(
             if (threadIdx.x == 0) part_chg[blockIdx.x] = (long long)c;
         }
     }
+    if (AMAX && MODE >= 0) block_absmax(amax, reinterpret_cast<float *>(red), absmax_slot);
 }
 
 // r <- X (first step of the greedy encoder): four float4 per thread in flight.

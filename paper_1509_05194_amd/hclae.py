@@ -18,7 +18,7 @@ _ERRNAME = {0: "HCLAE_OK", -1: "HCLAE_EINVAL", -2: "HCLAE_ENOMEM", -3: "HCLAE_EH
 
 EXPORTS = (
     "hclae_check_shape", "hclae_create", "hclae_destroy", "hclae_last_error",
-    "hclae_encode", "hclae_anneal_stage", "hclae_sweep", "hclae_quant_error", "hclae_quant_error_noalloc",
+    "hclae_encode", "hclae_anneal_stage", "hclae_sweep", "hclae_anneal", "hclae_quant_error", "hclae_quant_error_noalloc",
     "hclae_heat", "hclae_cool", "hclae_assign", "hclae_update", "hclae_last_refined", "hclae_work_counters",
     "hclae_timing_enable", "hclae_timing_read", "hclae_online_begin", "hclae_online_chunk",
     "hclae_online_export", "hclae_online_import",
@@ -75,6 +75,7 @@ def lib():
     L.hclae_encode.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp]
     L.hclae_anneal_stage.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp, i32, vp, ctypes.POINTER(StageStats)]
     L.hclae_sweep.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp, i32, i32, vp, vp]
+    L.hclae_anneal.argtypes = [vp, i64, i32, vp, i32, i32, vp, vp, i32, i32, vp]
     L.hclae_quant_error.argtypes = [vp, vp, i64, i32, ctypes.POINTER(ctypes.c_double)]
     L.hclae_quant_error_noalloc.argtypes = [vp, i64, i32, vp, vp]
     L.hclae_heat.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp]
@@ -260,6 +261,14 @@ class Context:
                                     iters, reencode_mode,
                                     idx.ctypes.data_as(ctypes.c_void_p) if idx is not None else None,
                                     err.ctypes.data_as(ctypes.c_void_p) if want_err else None))
+        return err
+
+    def anneal(self, C, codes, residue, iters, n_sweeps, want_err=True):
+        N = residue.shape[0]
+        pC, pcodes, pres = self._shapes(N, C, codes, residue)
+        err = np.zeros((n_sweeps, self.M), np.float64) if want_err else None
+        self._chk(lib().hclae_anneal(self._h, N, self.D, pC, self.M, self.K, pcodes, pres, iters, n_sweeps,
+                                     err.ctypes.data_as(ctypes.c_void_p) if want_err else None))
         return err
 
     def quant_error(self, residue):
