@@ -47,3 +47,41 @@ def test_captured_sweep_replays_like_the_eager_call(contraction):
             E = ctx.quant_error(r)
             assert np.isfinite(E)
         ctx.close()
+
+
+def test_captured_anneal_call_replays_like_the_eager_call():
+    """hclae_anneal without the errors: once the carried-bounds arrays exist (first call), a call is kernel launches
+    only; a captured call of six sweeps, replayed from restored states, gives the bits of the eager one."""
+    from paper_1509_05194_amd import hclae
+    N, D, M, K, T, sweeps = 30000 + 7, 128, 3, 256, 4, 6
+    X = synth.sift_like(N, D=D)
+    idx = synth.init_indices(N, M, K)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        Xg = torch.from_numpy(X).cuda()
+        ctx = hclae.Context(N, D, M, K)
+        C = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+        codes = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+        r = Xg.clone()
+        ctx.sweep(C, codes, r, T, init_idx=idx, want_err=False)
+        torch.cuda.synchronize()
+        start = (C.clone(), codes.clone(), r.clone())
+        ctx.anneal(C, codes, r, T, sweeps, want_err=False)        # eager; allocates the carried-bounds arrays
+        torch.cuda.synchronize()
+        want = (C.clone(), codes.clone(), r.clone())
+        C.copy_(start[0]); codes.copy_(start[1]); r.copy_(start[2])
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            ctx.anneal(C, codes, r, T, sweeps, want_err=False)
+        torch.cuda.synchronize()
+        assert torch.equal(C, start[0]) and torch.equal(r, start[2])
+        for i in range(3):
+            g.replay()
+            torch.cuda.synchronize()
+            for got, w, name in zip((C, codes, r), want, ("C", "codes", "residue")):
+                assert torch.equal(got, w), "replay %d: %s" % (i, name)
+            assert np.isfinite(ctx.quant_error(r))
+            C.copy_(start[0]); codes.copy_(start[1]); r.copy_(start[2])
+            torch.cuda.synchronize()
+        ctx.close()
