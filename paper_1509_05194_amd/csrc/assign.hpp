@@ -71,10 +71,13 @@ struct MovedArgs {
 // of a stage fill their LDS with one contiguous copy instead of a gather of 16-byte pieces.
 // keep_absmax 2: max |x'| was left by the row pass that wrote x', spread over amax_parts[0..64) (block_absmax): the
 // largest word becomes refine_count[1] and the words are cleared for the next such pass.
+// entry_copy (or nullptr): receives the K x D dictionary as it is now (the carried bounds price a stage by how far
+// it moves from here); zero_word (or nullptr): a counter cleared for the kernel that follows.
 __global__ __launch_bounds__(256) void k_codeword_norms(
     const float *__restrict__ Cm, int K, int D, int ld, int kpad, float *__restrict__ hneg,
     unsigned *__restrict__ refine_count, int keep_absmax, float *__restrict__ img, int S,
-    unsigned *__restrict__ amax_parts = nullptr)
+    unsigned *__restrict__ amax_parts = nullptr, float *__restrict__ entry_copy = nullptr,
+    unsigned *__restrict__ zero_word = nullptr)
 {
     const int lane = lane_id();
     const int k = blockIdx.x * (256 / kWave) + (threadIdx.x >> 6);
@@ -89,6 +92,7 @@ __global__ __launch_bounds__(256) void k_codeword_norms(
             }
             refine_count[1] = mx;
         }
+        if (zero_word) *zero_word = 0u;
     }
     if (k >= kpad) return;
     if (img)
@@ -99,7 +103,11 @@ __global__ __launch_bounds__(256) void k_codeword_norms(
     }
     const float *c = Cm + (size_t)k * ld;
     double s = 0.0;
-    for (int d = lane; d < D; d += kWave) s += (double)c[d] * (double)c[d];
+    for (int d = lane; d < D; d += kWave) {
+        const float v = c[d];
+        s += (double)v * (double)v;
+        if (entry_copy) entry_copy[(size_t)k * D + d] = v;
+    }
     s = wave_sum(s);
     if (lane == 0) hneg[k] = -(float)(0.5 * s);
 }

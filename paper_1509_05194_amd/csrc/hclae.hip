@@ -289,6 +289,8 @@ int launch_heat_cool(hclae_ctx *ctx, int m, int64_t N, const float *C, const uin
 // keep it current; launch_assign then takes it when told so).
 // keep_absmax: 0 the counter of max |x'| is reset for the assignment that follows; 1 it stays; 2 it is taken from the
 // words the row pass that wrote x' left in carry_amax[64..128) (hclae_anneal).
+// With keep_absmax 2 the kernel also copies the dictionary to carry_Centry and clears the list counter of
+// k_bounds_carry (moved_count[3]).
 int launch_norms(hclae_ctx *ctx, const float *Cm, int dact = 0, int ld = 0, int keep_absmax = 0, bool image = false)
 {
     if (dact <= 0) dact = ctx->D;
@@ -298,7 +300,9 @@ int launch_norms(hclae_ctx *ctx, const float *Cm, int dact = 0, int ld = 0, int 
     hipLaunchKernelGGL(k_codeword_norms, dim3((kpad + 3) / 4), dim3(256), 0, ctx->stream,
                        Cm, ctx->K, dact, ld, kpad, ctx->hneg, ctx->refine_count, keep_absmax,
                        image && ctx->resident ? ctx->lds_image : (float *)nullptr, 8 * ctx->NC,
-                       keep_absmax == 2 ? ctx->carry_amax + kAmaxSlots : (unsigned *)nullptr);
+                       keep_absmax == 2 ? ctx->carry_amax + kAmaxSlots : (unsigned *)nullptr,
+                       keep_absmax == 2 ? ctx->carry_Centry : (float *)nullptr,
+                       keep_absmax == 2 ? ctx->moved_count + 3 : (unsigned *)nullptr);
     HIP_TRY(ctx, hipGetLastError());
     return HCLAE_OK;
 }
@@ -524,7 +528,8 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
     {
         Timed t_(ctx, HCLAE_T_ACCUM);
         hipLaunchKernelGGL(k_accumulate, dim3((unsigned)nb, (unsigned)windows), dim3(kUpdThreads), lds, ctx->stream,
-                           xp, codes, N, D, K, ctx->M, m, rpb, ctx->refine_count + 1, ctx->partial, ctx->pcount);
+                           xp, codes, N, D, K, ctx->M, m, rpb, ctx->refine_count + 1, ctx->partial, ctx->pcount,
+                           keep_totals ? ctx->upd_col : (uint8_t *)nullptr);
     }
     HIP_TRY(ctx, hipGetLastError());
     Timed t_(ctx, HCLAE_T_MERGE);
@@ -537,11 +542,6 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
                        keep_totals ? ctx->moved_count : (unsigned *)nullptr, keep_totals ? ctx->drift : (float *)nullptr,
                        ctx->resident ? ctx->lds_image : (float *)nullptr, 8 * ctx->NC);
     HIP_TRY(ctx, hipGetLastError());
-    if (keep_totals) {
-        hipLaunchKernelGGL(k_save_column, dim3(stream_blocks(ctx, N, 256)), dim3(256), 0, ctx->stream,
-                           codes, N, ctx->M, m, ctx->upd_col);
-        HIP_TRY(ctx, hipGetLastError());
-    }
     return HCLAE_OK;
 }
 
@@ -613,15 +613,8 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
         HIP_TRY(ctx, hipGetLastError());
     }
     if ((rc = launch_norms(ctx, Cm, 0, 0, carry ? 2 : 0, true)) != HCLAE_OK) return rc;
-    if (carry) {
-        const int64_t c4 = (int64_t)K * D / 4;
-        hipLaunchKernelGGL(k_copy, dim3(stream_blocks(ctx, c4, kFlatThreads * 4)), dim3(kFlatThreads), 0, ctx->stream,
-                           reinterpret_cast<floatx4 *>(ctx->carry_Centry), reinterpret_cast<const floatx4 *>(Cm), c4);
-        HIP_TRY(ctx, hipGetLastError());
-    }
     if (carry == 2) {
         Timed t_(ctx, HCLAE_T_BOUNDS);
-        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, ctx->stream, ctx->moved_count + 3, 1);
         // (8M + 16) 2^-24 sqrt(D), times the largest coordinate seen: the roundings of the passes since the last visit
         const double slack_unit = (8.0 * ctx->M + 16.0) * 5.9604644775390625e-8 * sqrt((double)D);
         hipLaunchKernelGGL(k_bounds_carry, dim3((unsigned)((N + kBoundSpan - 1) / kBoundSpan)), dim3(kBoundThreads), 0,
