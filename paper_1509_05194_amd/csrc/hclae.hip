@@ -528,8 +528,7 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
     {
         Timed t_(ctx, HCLAE_T_ACCUM);
         hipLaunchKernelGGL(k_accumulate, dim3((unsigned)nb, (unsigned)windows), dim3(kUpdThreads), lds, ctx->stream,
-                           xp, codes, N, D, K, ctx->M, m, rpb, ctx->refine_count + 1, ctx->partial, ctx->pcount,
-                           keep_totals ? ctx->upd_col : (uint8_t *)nullptr);
+                           xp, codes, N, D, K, ctx->M, m, rpb, ctx->refine_count + 1, ctx->partial, ctx->pcount);
     }
     HIP_TRY(ctx, hipGetLastError());
     Timed t_(ctx, HCLAE_T_MERGE);
@@ -542,6 +541,11 @@ int launch_update(hclae_ctx *ctx, int m, int64_t N, const float *xp, float *Cm, 
                        keep_totals ? ctx->moved_count : (unsigned *)nullptr, keep_totals ? ctx->drift : (float *)nullptr,
                        ctx->resident ? ctx->lds_image : (float *)nullptr, 8 * ctx->NC);
     HIP_TRY(ctx, hipGetLastError());
+    if (keep_totals) {
+        hipLaunchKernelGGL(k_save_column, dim3(stream_blocks(ctx, N, 256)), dim3(256), 0, ctx->stream,
+                           codes, N, ctx->M, m, ctx->upd_col);
+        HIP_TRY(ctx, hipGetLastError());
+    }
     return HCLAE_OK;
 }
 

@@ -36,12 +36,10 @@ __device__ __forceinline__ int fixed_point_shift(unsigned xmax_bits)
 }
 
 // grid: (vector ranges, 64-dim windows).  partial: int64 [gridDim.x][K][D] (sum of q); pcount: int [gridDim.x][K].
-// save_col (or nullptr): receives column m of the codes as this pass saw it (the blocks of the first window write it),
-// the reference against which later passes find the vectors that changed cluster.
 __global__ __launch_bounds__(kUpdThreads) void k_accumulate(
     const float *__restrict__ xp, const uint8_t *__restrict__ codes,
     int64_t N, int D, int K, int M, int m, int64_t rows_per_block, const unsigned *__restrict__ xmax_bits,
-    long long *__restrict__ partial, int *__restrict__ pcount, uint8_t *__restrict__ save_col = nullptr)
+    long long *__restrict__ partial, int *__restrict__ pcount)
 {
     extern __shared__ float4 smem4[];
     unsigned long long *acc = reinterpret_cast<unsigned long long *>(smem4);   // [K][64]
@@ -71,7 +69,6 @@ __global__ __launch_bounds__(kUpdThreads) void k_accumulate(
             const int nrow = min(kUpdDepth, segn - r0);              // uniform
             // lane u < nrow fetches the code of row r0 + u; values reach the scalar unit by readlane
             const int cvec = (lane < nrow) ? (int)segc[(unsigned)(r0 + lane) * (unsigned)M] : 0;
-            if (counting && save_col && lane < nrow) save_col[seg0 + r0 + lane] = (uint8_t)cvec;
             float v[kUpdDepth];
 #pragma unroll
             for (int u = 0; u < kUpdDepth; ++u) {
@@ -108,6 +105,16 @@ __global__ __launch_bounds__(kUpdThreads) void k_accumulate(
     }
     if (counting)
         for (int k = threadIdx.x; k < K; k += kUpdThreads) pcount[blockIdx.x * K + k] = (int)cnt[k];
+}
+
+// prev[n] = codes[n][m]: the column as the full centroid pass saw it.  (A kernel of its own: as a by-product of
+// k_accumulate the byte stores sat in the row loop of the blocks of the first window and made those blocks, and with
+// them the pass, 18 % slower at D = 960.)
+__global__ __launch_bounds__(256) void k_save_column(
+    const uint8_t *__restrict__ codes, int64_t N, int M, int m, uint8_t *__restrict__ prev)
+{
+    for (int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x; n < N; n += (int64_t)gridDim.x * 256)
+        prev[n] = codes[n * M + m];
 }
 
 // Blocks (of the x dimension) that the pass over `total` moved vectors uses: 160 rows per block measured best
