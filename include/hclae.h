@@ -120,21 +120,23 @@ int hclae_sweep(hclae_ctx *ctx, const float *X, int64_t N, int D, float *C, int 
                 const int64_t *init_idx, double *err_per_stage);
 
 /*
- * Sec. 3.1, "multiple iterations" of the whole method: n_sweeps sweeps over the dictionaries as they are
- * (hclae_sweep with reencode_mode 0 and init_idx NULL, n_sweeps times).  C, codes and residue end with the very
+ * Sec. 3.1, "multiple iterations" of the whole method: n_sweeps sweeps over the dictionaries
+ * (hclae_sweep with reencode_mode 0, n_sweeps times; init_idx, if given, seeds the all-zero dictionaries of the
+ * first sweep as it does there, NULL for the others).  C, codes and residue end with the very
  * bits those calls give; what the single call adds is speed in late sweeps: every stage but the last passes
  * into the next through the fused row pass, from one sweep to the next as well, and (plain Lloyd cool-down with
- * the exact shortcuts on, iters > 0, n_sweeps > 1) each stage keeps the distance bounds it ends with and starts
- * its next visit from them, widened by how far x' has moved since, so that the first assignment of a stage also
- * runs only over the vectors the bounds cannot settle.  The arrays this needs (20 * M + 8 bytes per vector of
- * N_max) are allocated at the first such call and kept by the ctx.
+ * the exact shortcuts on, iters > 0, at least two sweeps that do not seed) each stage keeps the distance bounds it
+ * ends with and starts its next visit from them, widened by how far x' has moved since, so that the first assignment
+ * of a stage also runs only over the vectors the bounds cannot settle.  The arrays this needs (16 * M + 8 bytes per
+ * vector of N_max) are allocated at the first such call and kept by the ctx.
  *   C: DEVICE float[M][K][D], codes: DEVICE uint8[N][M], residue: DEVICE float[N][D], all updated in place.
  *   Precondition: residue == X - sum_j C[j][codes[:,j]].
- *   err_per_stage: HOST double[n_sweeps][M] (mean ||e_x||^2 after each stage; the stream is synchronised once per
- *   sweep) or NULL (the call only enqueues, apart from that first allocation).
+ *   init_idx: HOST int64[M][K] or NULL.  err_per_stage: HOST double[n_sweeps][M] (mean ||e_x||^2 after each stage;
+ *   the stream is synchronised once per sweep) or NULL (without init_idx the call then only enqueues, apart from
+ *   that first allocation; with it, it synchronises once at the end).
  */
 int hclae_anneal(hclae_ctx *ctx, int64_t N, int D, float *C, int M, int K, uint8_t *codes, float *residue,
-                 int iters, int n_sweeps, double *err_per_stage);
+                 int iters, int n_sweeps, const int64_t *init_idx, double *err_per_stage);
 
 /* Eq. 1, first line, averaged over the vectors (Table 1 reports such means):
  *   *out = (1/N) sum_n ||residue_n||^2, accumulated in fp64.  out: HOST.  N == 0 gives 0. */

@@ -598,8 +598,10 @@ int launch_sqnorm(hclae_ctx *ctx, const float *r, int64_t N, double *part)
 // 1 = the stage keeps its final bounds in its own rows of carry_u / carry_l and marks the path length; 2 = it also
 // starts from the bounds its last visit kept (k_bounds_carry) instead of an assignment over all vectors.  With
 // either, max |x'| comes from the row pass that wrote x' (the first assignment may not read every row).
+// next_amax: the fused pass into the next stage takes max |x'| for it (that stage runs with carry != 0).
 int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, float *residue, int iters,
-                  const int64_t *seed_dev, int slot, bool heated = false, int next = -1, int carry = 0)
+                  const int64_t *seed_dev, int slot, bool heated = false, int next = -1, int carry = 0,
+                  bool next_amax = false)
 {
     const int D = ctx->D, K = ctx->K;
     float *Cm = C + (size_t)m * K * D;
@@ -660,18 +662,18 @@ int enqueue_stage(hclae_ctx *ctx, int m, int64_t N, float *C, uint8_t *codes, fl
         pa = heat_cool_blocks(N, D, ctx->cus);
         Timed t_(ctx, HCLAE_T_TRANSITION);
         if (D >= kWideMinD) {
-            auto kern = carry ? &k_row_pass_wide<0, true, true> : &k_row_pass_wide<0, true, false>;
+            auto kern = next_amax ? &k_row_pass_wide<0, true, true> : &k_row_pass_wide<0, true, false>;
             hipLaunchKernelGGL(kern, dim3(pa), dim3(kStreamThreads), 0, ctx->stream,
                                residue, codes, Cm, C + (size_t)next * K * D, N, D, ctx->M, m, next,
                                ctx->old_codes, ctx->part_b, ctx->part_chg,
-                               carry ? ctx->carry_amax + kAmaxSlots : (unsigned *)nullptr);
+                               next_amax ? ctx->carry_amax + kAmaxSlots : (unsigned *)nullptr);
         } else {
-            auto kern = carry ? (D == 128 ? &k_row_pass<0, true, 128, true> : &k_row_pass<0, true, 0, true>)
-                              : (D == 128 ? &k_row_pass<0, true, 128, false> : &k_row_pass<0, true, 0, false>);
+            auto kern = next_amax ? (D == 128 ? &k_row_pass<0, true, 128, true> : &k_row_pass<0, true, 0, true>)
+                                  : (D == 128 ? &k_row_pass<0, true, 128, false> : &k_row_pass<0, true, 0, false>);
             hipLaunchKernelGGL(kern, dim3(pa), dim3(kStreamThreads), 0, ctx->stream,
                                residue, codes, Cm, C + (size_t)next * K * D, N, D, ctx->M, m, next, g,
                                ctx->old_codes, ctx->part_b, ctx->part_chg,
-                               carry ? ctx->carry_amax + kAmaxSlots : (unsigned *)nullptr);
+                               next_amax ? ctx->carry_amax + kAmaxSlots : (unsigned *)nullptr);
         }
         HIP_TRY(ctx, hipGetLastError());
     }
@@ -1142,40 +1144,55 @@ static int carry_scratch(hclae_ctx *ctx)
 }
 
 int hclae_anneal(hclae_ctx *ctx, int64_t N, int D, float *C, int M, int K, uint8_t *codes, float *residue,
-                 int iters, int n_sweeps, double *err_per_stage)
+                 int iters, int n_sweeps, const int64_t *init_idx, double *err_per_stage)
 {
     int rc = check_call(ctx, N, D, M, K);
     if (rc != HCLAE_OK) return rc;
     if (iters < 0 || n_sweeps < 0 || (N > 0 && (!C || !codes || !residue)))
         return fail(ctx, HCLAE_EINVAL, "hclae_anneal: bad argument");
     if (misaligned(C, residue)) return fail(ctx, HCLAE_EINVAL, "hclae_anneal: float arrays must be 16-byte aligned");
+    if (init_idx && check_init_idx(init_idx, M * K, N) != HCLAE_OK)
+        return fail(ctx, HCLAE_EINVAL, "hclae_anneal: init_idx out of range");
     if (N == 0 || n_sweeps == 0) {
         if (err_per_stage) for (int i = 0; i < n_sweeps * M; ++i) err_per_stage[i] = 0.0;
         return HCLAE_OK;
     }
     const bool lloyd = ctx->cooldown == HCLAE_COOLDOWN_LLOYD;
-    const bool carry = lloyd && ctx->pruning && iters > 0 && n_sweeps > 1;
+    // a sweep that seeds its dictionaries stands apart: its stages start from other dictionaries than they were left with
+    const int first_kept = init_idx ? 1 : 0;                 // first sweep whose stages keep their bounds
+    const bool carry = lloyd && ctx->pruning && iters > 0 && n_sweeps - first_kept > 1;
+    if (init_idx)
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->seed_idx, init_idx, sizeof(int64_t) * (size_t)M * K, hipMemcpyHostToDevice, ctx->stream));
     if (carry) {
         if ((rc = carry_scratch(ctx)) != HCLAE_OK) return rc;
-        // path lengths start at zero; the running maximum starts at the largest dictionary coordinate (a codeword
-        // nobody is assigned to keeps a value the data of this call need not reach)
-        hipLaunchKernelGGL(k_zero_u64, dim3(stream_blocks(ctx, N, 256)), dim3(256), 0, ctx->stream,
-                           reinterpret_cast<unsigned long long *>(ctx->carry_path), (size_t)N);
+        // the running maximum and the words the row passes leave max |x'| in start empty
         hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(2 * kAmaxSlots), 0, ctx->stream, ctx->carry_amax, 2 * kAmaxSlots);
-        const int64_t c4 = (int64_t)M * K * D / 4;
-        hipLaunchKernelGGL(k_absmax, dim3(stream_blocks(ctx, c4, 256 * 4)), dim3(256), 0, ctx->stream,
-                           reinterpret_cast<const float4 *>(C), c4, ctx->carry_amax);
         HIP_TRY(ctx, hipGetLastError());
     }
     for (int s = 0; s < n_sweeps; ++s) {
+        if (carry && s == first_kept) {
+            // path lengths start at zero; the running maximum starts at the largest coordinate of the dictionaries as
+            // they are now (a codeword nobody is assigned to keeps a value the data from here on need not reach)
+            hipLaunchKernelGGL(k_zero_u64, dim3(stream_blocks(ctx, N, 256)), dim3(256), 0, ctx->stream,
+                               reinterpret_cast<unsigned long long *>(ctx->carry_path), (size_t)N);
+            const int64_t c4 = (int64_t)M * K * D / 4;
+            hipLaunchKernelGGL(k_absmax, dim3(stream_blocks(ctx, c4, 256 * 4)), dim3(256), 0, ctx->stream,
+                               reinterpret_cast<const float4 *>(C), c4, ctx->carry_amax);
+            HIP_TRY(ctx, hipGetLastError());
+        }
         for (int m = 0; m < M; ++m) {
+            const int64_t *seeds = (init_idx && s == 0) ? ctx->seed_idx + (size_t)m * K : nullptr;
             if (lloyd) {
-                // every stage but the very last ends in the fused pass into the next one, across sweeps too
+                // every stage but the very last ends in the fused pass into the next one, across sweeps too; the pass
+                // into a stage that keeps bounds also takes max |x'| for it
                 const bool last = s == n_sweeps - 1 && m == M - 1;
-                rc = enqueue_stage(ctx, m, N, C, codes, residue, iters, nullptr, m, !(s == 0 && m == 0),
-                                   last ? -1 : (m + 1) % M, carry ? (s == 0 ? 1 : 2) : 0);
+                const int mode = !carry || s < first_kept ? 0 : s == first_kept ? 1 : 2;
+                const int s_next = m + 1 < M ? s : s + 1;
+                const bool next_kept = carry && !last && s_next >= first_kept;
+                rc = enqueue_stage(ctx, m, N, C, codes, residue, iters, seeds, m, !(s == 0 && m == 0),
+                                   last ? -1 : (m + 1) % M, mode, next_kept);
             } else {
-                rc = enqueue_stage_cooldown_pca(ctx, m, N, C, codes, residue, iters, nullptr, m, nullptr);
+                rc = enqueue_stage_cooldown_pca(ctx, m, N, C, codes, residue, iters, seeds, m, nullptr);
             }
             if (rc != HCLAE_OK) return rc;
         }
@@ -1184,6 +1201,8 @@ int hclae_anneal(hclae_ctx *ctx, int64_t N, int D, float *C, int M, int K, uint8
             for (int m = 0; m < M; ++m) err_per_stage[(size_t)s * M + m] = ctx->rec_host[m].sum_after / (double)N;
         }
     }
+    // the seed indices were read from caller memory by an asynchronous copy
+    if (init_idx && !err_per_stage) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     return HCLAE_OK;
 }
 

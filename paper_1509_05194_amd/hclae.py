@@ -75,7 +75,7 @@ def lib():
     L.hclae_encode.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp]
     L.hclae_anneal_stage.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp, i32, vp, ctypes.POINTER(StageStats)]
     L.hclae_sweep.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp, i32, i32, vp, vp]
-    L.hclae_anneal.argtypes = [vp, i64, i32, vp, i32, i32, vp, vp, i32, i32, vp]
+    L.hclae_anneal.argtypes = [vp, i64, i32, vp, i32, i32, vp, vp, i32, i32, vp, vp]
     L.hclae_quant_error.argtypes = [vp, vp, i64, i32, ctypes.POINTER(ctypes.c_double)]
     L.hclae_quant_error_noalloc.argtypes = [vp, i64, i32, vp, vp]
     L.hclae_heat.argtypes = [vp, i32, i64, i32, vp, i32, i32, vp, vp]
@@ -263,11 +263,16 @@ class Context:
                                     err.ctypes.data_as(ctypes.c_void_p) if want_err else None))
         return err
 
-    def anneal(self, C, codes, residue, iters, n_sweeps, want_err=True):
+    def anneal(self, C, codes, residue, iters, n_sweeps, init_idx=None, want_err=True):
         N = residue.shape[0]
         pC, pcodes, pres = self._shapes(N, C, codes, residue)
+        idx = None
+        if init_idx is not None:
+            idx = np.ascontiguousarray(init_idx, np.int64)
+            assert idx.shape == (self.M, self.K)
         err = np.zeros((n_sweeps, self.M), np.float64) if want_err else None
         self._chk(lib().hclae_anneal(self._h, N, self.D, pC, self.M, self.K, pcodes, pres, iters, n_sweeps,
+                                     idx.ctypes.data_as(ctypes.c_void_p) if idx is not None else None,
                                      err.ctypes.data_as(ctypes.c_void_p) if want_err else None))
         return err
 

@@ -105,7 +105,7 @@ def test_anneal_twice_and_with_a_larger_context():
     ctx = hclae.Context(3 * N, D, M, K)
     C, codes, r = _fresh(ctx, X, M, K, T)
     assert ctx.anneal(C, codes, r, T, 5, want_err=False) is None
-    # something else in between: the dictionaries re-ordered and put back, an encode of other data
+    # something else in between on the same ctx: an encode of other data
     other = torch.from_numpy(synth.sift_like(5000, D=D, start=10 ** 6)).cuda()
     oc = torch.zeros((5000, M), dtype=torch.uint8, device="cuda:0")
     orr = torch.empty_like(other)
@@ -131,3 +131,36 @@ def test_anneal_fullsize_ten_sweeps():
     print("N = 1M: vectors recomputed %d in ten sweep calls, %d in one call (%.1f %%)"
           % (a[4][1], b[4][1], 100.0 * b[4][1] / a[4][1]))
     assert b[4][1] < a[4][1]
+
+
+@pytest.mark.parametrize("name", ["sift_resident", "gist_chunked"])
+def test_anneal_from_zero_dictionaries_in_one_call(name):
+    """init_idx: the call's first sweep seeds the all-zero dictionaries (as hclae_sweep does), the others anneal and
+    carry their bounds; the whole training in one call equals the sweep calls bit for bit."""
+    from paper_1509_05194_amd import hclae
+    kind, N, D, M, K, T, sweeps = SHAPES[name]
+    X = torch.from_numpy(_data(kind, N, D)).cuda()
+    idx = synth.init_indices(N, M, K)
+    out = []
+    for one_call in (False, True):
+        ctx = hclae.Context(N, D, M, K)
+        C = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+        codes = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+        r = X.clone()
+        if one_call:
+            E = ctx.anneal(C, codes, r, T, sweeps + 1, init_idx=idx)
+        else:
+            E = np.stack([ctx.sweep(C, codes, r, T, init_idx=idx if s == 0 else None) for s in range(sweeps + 1)])
+        torch.cuda.synchronize()
+        out.append((C.clone(), codes.clone(), r.clone(), E, ctx.work_counters()))
+        ctx.close()
+    _assert_same(out[0], out[1])
+    assert out[1][4][1] < out[0][4][1]
+    # without the errors the call synchronises once at the end (the seed indices are read asynchronously)
+    ctx = hclae.Context(N, D, M, K)
+    C = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+    codes = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+    r = X.clone()
+    assert ctx.anneal(C, codes, r, T, 2, init_idx=idx, want_err=False) is None
+    ctx.sweep(C, codes, r, T, want_err=False)
+    ctx.close()
