@@ -56,6 +56,9 @@ SHAPES = {
     "padded_d": ("gmm", 12000 + 3, 20, 3, 50, 3, 7),
     "gist_chunked": ("gist", 6000 + 9, 960, 2, 256, 3, 6),
     "one_dictionary": ("sift", 15000 + 1, 128, 1, 256, 4, 6),
+    "codes_128bit": ("sift", 30000 + 3, 128, 16, 256, 2, 5),
+    "one_codeword": ("gmm", 5000 + 1, 16, 2, 1, 2, 4),
+    "few_vectors": ("sift", 100, 128, 2, 64, 3, 6),
 }
 
 
@@ -76,7 +79,7 @@ def test_anneal_equals_repeated_sweeps(name):
     # the same number of assignments, fewer vectors recomputed: the first assignment of a stage was pruned too
     assert a[4][0] == b[4][0] == sweeps * M * (T + 1)
     print("%s: vectors recomputed %d in %d sweep calls, %d in one call" % (name, a[4][1], sweeps, b[4][1]))
-    assert b[4][1] < a[4][1]
+    assert b[4][1] <= a[4][1] if name in ("one_codeword", "few_vectors") else b[4][1] < a[4][1]
     assert np.all(np.diff(b[3].reshape(-1)) <= 1e-7 * b[3].reshape(-1)[:-1])
 
 
