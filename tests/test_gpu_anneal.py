@@ -167,3 +167,27 @@ def test_anneal_from_zero_dictionaries_in_one_call(name):
     assert ctx.anneal(C, codes, r, T, 2, init_idx=idx, want_err=False) is None
     ctx.sweep(C, codes, r, T, want_err=False)
     ctx.close()
+
+
+def test_anneal_with_the_improved_kmeans_cooldown():
+    """With the cool-down of Sec. 3.2 chosen (hclae_set_cooldown) nothing is carried and no pass is fused: the call is
+    the loop over the sweeps, equal to the separate calls bit for bit."""
+    from paper_1509_05194_amd import hclae
+    N, D, M, K, T, sweeps = 8000 + 3, 32, 3, 64, 10, 3
+    X = torch.from_numpy(synth.sift_like(N, D=D)).cuda()
+    idx = synth.init_indices(N, M, K)
+    out = []
+    for one_call in (False, True):
+        ctx = hclae.Context(N, D, M, K)
+        ctx.set_cooldown(True, 10)
+        C = torch.zeros((M, K, D), dtype=torch.float32, device="cuda:0")
+        codes = torch.zeros((N, M), dtype=torch.uint8, device="cuda:0")
+        r = X.clone()
+        if one_call:
+            E = ctx.anneal(C, codes, r, T, sweeps, init_idx=idx)
+        else:
+            E = np.stack([ctx.sweep(C, codes, r, T, init_idx=idx if s == 0 else None) for s in range(sweeps)])
+        torch.cuda.synchronize()
+        out.append((C.clone(), codes.clone(), r.clone(), E))
+        ctx.close()
+    _assert_same(out[0], out[1])
