@@ -28,13 +28,13 @@ PEAK_HBM_GBS = 8000.0             # MI355X HBM3E peak
 CONVERGED_AFTER = 8                # sweeps before the one `converged_sweep` times
 MANY_SWEEPS = 20                   # annealing sweeps of the hclae_anneal figure
 
-# HBM bytes per N=1M launch of the assign kernel from two rocprofv3 --pmc runs (FETCH_SIZE 250,670.0 KiB
-# x 2.000, WRITE_SIZE 16,135.3 KiB x 1.000; factors from a 512 MB device copy in the same runs), recorded
+# HBM bytes per N=1M launch of the assign kernel from two rocprofv3 --pmc runs (FETCH_SIZE 250,672.6 KiB
+# x 2.000, WRITE_SIZE 16,135.5 KiB x 1.000; factors from a 512 MB device copy in the same runs), recorded
 # in profiles/da_sweep_sift1m_counters.md: the launches that also store the distance bounds.  Algorithmic
 # bytes are 521e6 (x', codes, bounds).
-ASSIGN_TRAFFIC_BYTES = 5.299e8   # (250670.0 * 2.000 + 16135.3) KiB
+ASSIGN_TRAFFIC_BYTES = 5.299e8   # (250672.6 * 2.000 + 16135.5) KiB
 # the same for the D-chunked kernel at N=1M, D=960 (profiles/da_sweep_gist1m_counters.md); algorithmic 3.841e9
-ASSIGN_TRAFFIC_BYTES_GIST = 4.037e9   # (1962932.8 * 2.000 + 16579.8) KiB
+ASSIGN_TRAFFIC_BYTES_GIST = 4.035e9   # (1962277.4 * 2.000 + 16313.4) KiB
 
 
 class State:
