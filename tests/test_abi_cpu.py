@@ -54,6 +54,7 @@ def test_null_ctx_is_einval():
     assert L.hclae_encode(None, None, 1, 16, None, 4, 16, None, None) == hclae.EINVAL
     assert L.hclae_anneal_stage(None, 0, 1, 16, None, 4, 16, None, None, 1, None, None) == hclae.EINVAL
     assert L.hclae_sweep(None, None, 1, 16, None, 4, 16, None, None, 1, 0, None, None) == hclae.EINVAL
+    assert L.hclae_anneal(None, 1, 16, None, 4, 16, None, None, 1, 2, None, None) == hclae.EINVAL
     assert L.hclae_heat(None, 0, 1, 16, None, 4, 16, None, None) == hclae.EINVAL
     assert L.hclae_cool(None, 0, 1, 16, None, 4, 16, None, None) == hclae.EINVAL
     assert L.hclae_assign(None, 0, 1, 16, None, None, 4, 16, None, None) == hclae.EINVAL
